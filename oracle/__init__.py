@@ -1,0 +1,159 @@
+"""ctypes front end of the CPU oracle (sadj_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg.  The product package never imports this module and
+this module never imports the product package.
+
+Every function takes and returns NumPy float64 arrays in C order with the slowest
+axis first (shape (nz,ny,nx), (ny,nx) or (n,)); float32 inputs are widened to
+double first, which is how the fp32 workloads are checked: same rounded inputs,
+fp64 arithmetic.  See sadj_oracle.c for what each routine computes and which
+passage of the paper it follows.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sadj_oracle.c")
+_LIB = os.path.join(_HERE, "libsadj_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc -O2 (no fast-math, no OpenMP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-Wall", "-Wextra",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+    return _lib
+
+
+_P = ctypes.c_void_p
+_L = ctypes.c_long
+_I = ctypes.c_int
+_D = ctypes.c_double
+
+
+def _f64(a, writable=False):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    if writable and not a.flags.writeable:
+        a = a.copy()
+    return a
+
+
+def _ptr(a):
+    return _P(a.ctypes.data) if a is not None else _P(0)
+
+
+def _dims(shape):
+    shape = tuple(int(s) for s in shape)
+    ndim = len(shape)
+    if ndim == 1:
+        return ndim, shape[0], 1, 1
+    if ndim == 2:
+        return ndim, shape[1], shape[0], 1
+    if ndim == 3:
+        return ndim, shape[2], shape[1], shape[0]
+    raise ValueError("1-, 2- or 3-D grids only")
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError("oracle %s: bad argument (rc=%d)" % (what, rc))
+
+
+def star_weights(radius: int) -> np.ndarray:
+    w = np.zeros(5)
+    _check(_load().oracle_star_weights(_I(radius), _ptr(w)), "star_weights")
+    return w[: radius + 1].copy()
+
+
+def wave_primal(u, u_prev, c, radius: int, r_init=None) -> np.ndarray:
+    """r = 2u - u_prev + c*Lap_w(u) on the primal interior; elsewhere r keeps r_init
+    (zeros if not given)."""
+    u, u_prev, c = _f64(u), _f64(u_prev), _f64(c)
+    ndim, nx, ny, nz = _dims(u.shape)
+    r = np.zeros_like(u) if r_init is None else _f64(r_init).copy()
+    fn = _load().oracle_wave_primal
+    _check(fn(_I(ndim), _I(radius), _L(nx), _L(ny), _L(nz), _ptr(u), _ptr(u_prev), _ptr(c), _ptr(r)),
+           "wave_primal")
+    return r
+
+
+def wave_tangent(c, u_dot, u_prev_dot, radius: int) -> np.ndarray:
+    c, u_dot, u_prev_dot = _f64(c), _f64(u_dot), _f64(u_prev_dot)
+    ndim, nx, ny, nz = _dims(c.shape)
+    r_dot = np.zeros_like(c)
+    fn = _load().oracle_wave_tangent
+    _check(fn(_I(ndim), _I(radius), _L(nx), _L(ny), _L(nz), _ptr(c), _ptr(u_dot), _ptr(u_prev_dot),
+              _ptr(r_dot)), "wave_tangent")
+    return r_dot
+
+
+def wave_adjoint(c, r_bar, u_bar, radius: int, u_prev_bar=None, want_scale: bool = False):
+    """Returns (u_bar_out, u_prev_bar_out or None, scale or None).  The inputs are
+    not modified.  scale[j] = sum of |contribution| that reached index j."""
+    c, r_bar = _f64(c), _f64(r_bar)
+    ndim, nx, ny, nz = _dims(c.shape)
+    ub = _f64(u_bar).copy()
+    upb = _f64(u_prev_bar).copy() if u_prev_bar is not None else None
+    scale = np.zeros_like(ub) if want_scale else None
+    fn = _load().oracle_wave_adjoint
+    _check(fn(_I(ndim), _I(radius), _L(nx), _L(ny), _L(nz), _ptr(c), _ptr(r_bar), _ptr(ub),
+              _ptr(upb), _ptr(scale)), "wave_adjoint")
+    return ub, upb, scale
+
+
+def burgers_primal(u, C: float, D: float, r_init=None) -> np.ndarray:
+    u = _f64(u)
+    r = np.zeros_like(u) if r_init is None else _f64(r_init).copy()
+    _check(_load().oracle_burgers_primal(_L(u.size), _D(C), _D(D), _ptr(u), _ptr(r)), "burgers_primal")
+    return r
+
+
+def burgers_tangent(u, u_dot, C: float, D: float) -> np.ndarray:
+    u, u_dot = _f64(u), _f64(u_dot)
+    r_dot = np.zeros_like(u)
+    _check(_load().oracle_burgers_tangent(_L(u.size), _D(C), _D(D), _ptr(u), _ptr(u_dot), _ptr(r_dot)),
+           "burgers_tangent")
+    return r_dot
+
+
+def burgers_adjoint(u, r_bar, u_bar, C: float, D: float, want_scale: bool = False):
+    """Returns (u_bar_out, scale or None)."""
+    u, r_bar = _f64(u), _f64(r_bar)
+    ub = _f64(u_bar).copy()
+    scale = np.zeros_like(ub) if want_scale else None
+    _check(_load().oracle_burgers_adjoint(_L(u.size), _D(C), _D(D), _ptr(u), _ptr(r_bar), _ptr(ub),
+                                          _ptr(scale)), "burgers_adjoint")
+    return ub, scale
+
+
+def lin3_primal(c, u, lo: int, hi: int, wm: float, w0: float, wp: float) -> np.ndarray:
+    c, u = _f64(c), _f64(u)
+    r = np.zeros_like(u)
+    _check(_load().oracle_lin3_primal(_L(u.size), _L(lo), _L(hi), _D(wm), _D(w0), _D(wp), _ptr(c),
+                                      _ptr(u), _ptr(r)), "lin3_primal")
+    return r
+
+
+def lin3_adjoint(c, r_bar, u_bar, lo: int, hi: int, wm: float, w0: float, wp: float) -> np.ndarray:
+    c, r_bar = _f64(c), _f64(r_bar)
+    ub = _f64(u_bar).copy()
+    _check(_load().oracle_lin3_adjoint(_L(ub.size), _L(lo), _L(hi), _D(wm), _D(w0), _D(wp), _ptr(c),
+                                       _ptr(r_bar), _ptr(ub)), "lin3_adjoint")
+    return ub
+

@@ -1,0 +1,252 @@
+/*
+ * sadj_oracle.c -- plain, slow, single-threaded CPU oracle for the adjoint of a
+ * stencil loop.  TEST INFRASTRUCTURE ONLY: it may be built and called from tests/,
+ * from the smoke check and from the benchmark's cpu_baseline leg, never from the
+ * product path.  It shares no code, header, table or helper with the HIP library.
+ *
+ * What it computes (paper Section 3.2, first two listings, and Section 3.3.1):
+ * the conventional reverse-mode adjoint of a gather stencil loop
+ *     for i in I:  r[i] = f(u[i+o_1], ..., u[i+o_M], passive data)
+ * is the scatter loop
+ *     for i in I:  for each read offset o:  u_bar[i+o] += (df_i/du_{i+o}) * r_bar[i]
+ * i.e. u_bar_out = u_bar_in + J^T r_bar with J the Jacobian of the primal loop.
+ * The oracle is that scatter written out.  It contains no gather form, no index
+ * shifting, no core/remainder split and no boundary rule: what happens at the
+ * boundary emerges from the primal iteration space I alone.
+ *
+ * Stencils:
+ *  - linear variable-coefficient wave step in 1, 2 or 3 dimensions with a star
+ *    Laplacian of radius R (paper Section 4.1 for R=1 in 3-D; the script in its
+ *    first figure defines r = 2u - u_prev + c*D*(u_xx+u_yy+u_zz); D is folded
+ *    into c here):        r[i] = 2 u[i] - u_prev[i] + c[i] * sum_o w_o u[i+o]
+ *  - 1-D upwinded Burgers step (paper Section 4.2, its generating script):
+ *    r[i] = u[i] - C*(max(u[i],0)*(u[i]-u[i-1]) + min(u[i],0)*(u[i+1]-u[i]))
+ *                + D*(u[i-1] - 2u[i] + u[i+1])
+ *  - the 1-D worked example of paper Section 3.2 with arbitrary, possibly
+ *    asymmetric, three-point weights:  r[i] = c[i]*(wm*u[i-1] + w0*u[i] + wp*u[i+1])
+ *
+ * Conventions: arrays are dense, x fastest: index = x + nx*(y + ny*z).  The primal
+ * iteration space is I = prod_d [R, n_d-1-R] over the first `ndim` axes (paper:
+ * bounds [1,n-2] for R=1); unused axes must have extent 1.  Loops run in ascending
+ * lexicographic order (z outer, x inner); per iteration the reads are visited
+ * centre first, then offsets -R..-1,+1..+R along x, then y, then z.  Everything is
+ * fp64.  `scale`, when non-NULL, receives sum |contribution| per output index: the
+ * magnitude against which a differently ordered summation may be compared.
+ *
+ * Pins (tests/test_oracle_*.py): polynomial exactness of the weights, a library
+ * correlation for the primal, dot-product test against the tangent loops, central
+ * finite differences, an assembled dense Jacobian transposed by a library mat-vec,
+ * the paper's printed 1-D remainder statements and merged core loop, the paper's
+ * printed Burgers and 3-D wave gather core loops, the symmetric constant-c case,
+ * the conservation sum, zero rows of J^T, NaN poisoning, and brute force over all
+ * sizes 2R+1..4R+3.
+ */
+#include <math.h>
+#include <stddef.h>
+
+#define ORACLE_OK 0
+#define ORACLE_BAD_ARG 1
+
+/* Standard central finite-difference weights of the second derivative on a unit
+ * grid, w[0] centre, w[k] at distance k (orders 2, 4, 6, 8). */
+static int star_weights(int R, double w[5])
+{
+    switch (R) {
+    case 1: w[0] = -2.0;          w[1] = 1.0; return 0;
+    case 2: w[0] = -5.0 / 2.0;    w[1] = 4.0 / 3.0; w[2] = -1.0 / 12.0; return 0;
+    case 3: w[0] = -49.0 / 18.0;  w[1] = 3.0 / 2.0; w[2] = -3.0 / 20.0; w[3] = 1.0 / 90.0; return 0;
+    case 4: w[0] = -205.0 / 72.0; w[1] = 8.0 / 5.0; w[2] = -1.0 / 5.0;  w[3] = 8.0 / 315.0;
+            w[4] = -1.0 / 560.0; return 0;
+    default: return 1;
+    }
+}
+
+int oracle_star_weights(int R, double *w) { return star_weights(R, w) ? ORACLE_BAD_ARG : ORACLE_OK; }
+
+typedef struct { long n[3]; long stride[3]; long lo[3], hi[3]; int ndim; int R; double w[5]; } grid_t;
+
+static int grid_init(grid_t *g, int ndim, int R, long nx, long ny, long nz)
+{
+    if (ndim < 1 || ndim > 3) return 1;
+    if (star_weights(R, g->w)) return 1;
+    g->ndim = ndim; g->R = R;
+    g->n[0] = nx; g->n[1] = ny; g->n[2] = nz;
+    g->stride[0] = 1; g->stride[1] = nx; g->stride[2] = nx * ny;
+    for (int d = 0; d < 3; ++d) {
+        if (g->n[d] < 1) return 1;
+        if (d < ndim) {
+            if (g->n[d] < 2 * R + 1) return 1;       /* empty primal interior */
+            g->lo[d] = R; g->hi[d] = g->n[d] - 1 - R;
+        } else {
+            if (g->n[d] != 1) return 1;
+            g->lo[d] = 0; g->hi[d] = 0;
+        }
+    }
+    return 0;
+}
+
+/* ---------------------------------------------------------------- wave: primal */
+/* r[i] = 2u[i] - u_prev[i] + c[i]*Lap_w(u)[i] for i in I; r outside I untouched.
+ * (Section 4.1; the listing there prints "+=", the script says lhs = rhs: assign.) */
+int oracle_wave_primal(int ndim, int R, long nx, long ny, long nz,
+                       const double *u, const double *u_prev, const double *c, double *r)
+{
+    grid_t g;
+    if (!u || !u_prev || !c || !r || grid_init(&g, ndim, R, nx, ny, nz)) return ORACLE_BAD_ARG;
+    for (long z = g.lo[2]; z <= g.hi[2]; ++z)
+    for (long y = g.lo[1]; y <= g.hi[1]; ++y)
+    for (long x = g.lo[0]; x <= g.hi[0]; ++x) {
+        long i = x + nx * (y + ny * z);
+        double lap = (double)ndim * g.w[0] * u[i];
+        for (int d = 0; d < ndim; ++d) {
+            for (int k = -R; k <= R; ++k) {
+                if (k == 0) continue;
+                lap += g.w[k < 0 ? -k : k] * u[i + k * g.stride[d]];
+            }
+        }
+        r[i] = 2.0 * u[i] - u_prev[i] + c[i] * lap;
+    }
+    return ORACLE_OK;
+}
+
+/* Forward-mode (tangent) loop: r_dot = J_u u_dot + J_uprev u_prev_dot.  The wave
+ * stencil is linear in (u, u_prev), so the tangent has the primal's form. */
+int oracle_wave_tangent(int ndim, int R, long nx, long ny, long nz, const double *c,
+                        const double *u_dot, const double *u_prev_dot, double *r_dot)
+{
+    grid_t g;
+    if (!u_dot || !u_prev_dot || !c || !r_dot || grid_init(&g, ndim, R, nx, ny, nz)) return ORACLE_BAD_ARG;
+    for (long z = g.lo[2]; z <= g.hi[2]; ++z)
+    for (long y = g.lo[1]; y <= g.hi[1]; ++y)
+    for (long x = g.lo[0]; x <= g.hi[0]; ++x) {
+        long i = x + nx * (y + ny * z);
+        double d_centre = 2.0 + c[i] * (double)ndim * g.w[0];
+        double acc = d_centre * u_dot[i];
+        for (int d = 0; d < ndim; ++d)
+            for (int k = -R; k <= R; ++k) {
+                if (k == 0) continue;
+                acc += (c[i] * g.w[k < 0 ? -k : k]) * u_dot[i + k * g.stride[d]];
+            }
+        r_dot[i] = acc - u_prev_dot[i];
+    }
+    return ORACLE_OK;
+}
+
+/* --------------------------------------------------------------- wave: adjoint */
+/* Scatter adjoint (Section 3.2 second listing; Section 4.1 third listing without
+ * the atomics):  for i in I:
+ *     u_bar[i]      += (2 + c[i]*ndim*w_0) * r_bar[i]
+ *     u_bar[i+o]    += (c[i]*w_o) * r_bar[i]            for every off-centre read o
+ *     u_prev_bar[i] -= r_bar[i]                          (if u_prev_bar != NULL)
+ * c is passive: no c_bar.  r_bar is read only. */
+int oracle_wave_adjoint(int ndim, int R, long nx, long ny, long nz,
+                        const double *c, const double *r_bar,
+                        double *u_bar, double *u_prev_bar, double *scale)
+{
+    grid_t g;
+    if (!c || !r_bar || !u_bar || grid_init(&g, ndim, R, nx, ny, nz)) return ORACLE_BAD_ARG;
+    for (long z = g.lo[2]; z <= g.hi[2]; ++z)
+    for (long y = g.lo[1]; y <= g.hi[1]; ++y)
+    for (long x = g.lo[0]; x <= g.hi[0]; ++x) {
+        long i = x + nx * (y + ny * z);
+        double rb = r_bar[i];
+        double t = (2.0 + c[i] * (double)ndim * g.w[0]) * rb;
+        u_bar[i] += t;
+        if (scale) scale[i] += fabs(t);
+        for (int d = 0; d < ndim; ++d)
+            for (int k = -R; k <= R; ++k) {
+                if (k == 0) continue;
+                long j = i + k * g.stride[d];
+                t = (c[i] * g.w[k < 0 ? -k : k]) * rb;
+                u_bar[j] += t;
+                if (scale) scale[j] += fabs(t);
+            }
+        if (u_prev_bar) u_prev_bar[i] -= rb;
+    }
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------ Burgers 1-D */
+static double pos(double a) { return a > 0.0 ? a : 0.0; }   /* max(a,0) */
+static double neg(double a) { return a < 0.0 ? a : 0.0; }   /* min(a,0) */
+
+/* r[i] for i in [1, n-2] (Section 4.2, the upwind formula and the script). */
+int oracle_burgers_primal(long n, double C, double D, const double *u, double *r)
+{
+    if (!u || !r || n < 3) return ORACLE_BAD_ARG;
+    for (long i = 1; i <= n - 2; ++i) {
+        double conv = pos(u[i]) * (u[i] - u[i - 1]) + neg(u[i]) * (u[i + 1] - u[i]);
+        r[i] = u[i] - C * conv + D * (u[i - 1] - 2.0 * u[i] + u[i + 1]);
+    }
+    return ORACLE_OK;
+}
+
+/* Partial derivatives of one Burgers iteration with respect to its three reads.
+ * d max(a,0)/da and d min(a,0)/da are both taken as 1 at a == 0, which is what
+ * the paper's printed adjoint does ((u>=0)?1:0 and (-u>=0)?1:0). */
+static void burgers_partials(double C, double D, double um, double u0, double up,
+                             double *dm, double *d0, double *dp)
+{
+    double dpos = (u0 >= 0.0) ? 1.0 : 0.0;
+    double dneg = (-u0 >= 0.0) ? 1.0 : 0.0;
+    *dm = C * pos(u0) + D;
+    *dp = -C * neg(u0) + D;
+    *d0 = 1.0 - C * (dpos * (u0 - um) + pos(u0) + dneg * (up - u0) - neg(u0)) - 2.0 * D;
+}
+
+int oracle_burgers_tangent(long n, double C, double D, const double *u,
+                           const double *u_dot, double *r_dot)
+{
+    if (!u || !u_dot || !r_dot || n < 3) return ORACLE_BAD_ARG;
+    for (long i = 1; i <= n - 2; ++i) {
+        double dm, d0, dp;
+        burgers_partials(C, D, u[i - 1], u[i], u[i + 1], &dm, &d0, &dp);
+        r_dot[i] = dm * u_dot[i - 1] + d0 * u_dot[i] + dp * u_dot[i + 1];
+    }
+    return ORACLE_OK;
+}
+
+/* Scatter adjoint; the stencil is nonlinear so the primal u is read (Section 3.1). */
+int oracle_burgers_adjoint(long n, double C, double D, const double *u,
+                           const double *r_bar, double *u_bar, double *scale)
+{
+    if (!u || !r_bar || !u_bar || n < 3) return ORACLE_BAD_ARG;
+    for (long i = 1; i <= n - 2; ++i) {
+        double dm, d0, dp;
+        burgers_partials(C, D, u[i - 1], u[i], u[i + 1], &dm, &d0, &dp);
+        double rb = r_bar[i];
+        u_bar[i]     += d0 * rb;
+        u_bar[i - 1] += dm * rb;
+        u_bar[i + 1] += dp * rb;
+        if (scale) {
+            scale[i]     += fabs(d0 * rb);
+            scale[i - 1] += fabs(dm * rb);
+            scale[i + 1] += fabs(dp * rb);
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* --------------------------------------- 1-D three-point example, general weights */
+/* Primal r[i] = c[i]*(wm*u[i-1] + w0*u[i] + wp*u[i+1]) for i in [lo,hi], arrays of
+ * length len (Section 3.2: weights (2,-3,4), i in [1,n-1], arrays of length n+1). */
+int oracle_lin3_primal(long len, long lo, long hi, double wm, double w0, double wp,
+                       const double *c, const double *u, double *r)
+{
+    if (!c || !u || !r || lo < 1 || hi > len - 2 || lo > hi) return ORACLE_BAD_ARG;
+    for (long i = lo; i <= hi; ++i)
+        r[i] = c[i] * (wm * u[i - 1] + w0 * u[i] + wp * u[i + 1]);
+    return ORACLE_OK;
+}
+
+int oracle_lin3_adjoint(long len, long lo, long hi, double wm, double w0, double wp,
+                        const double *c, const double *r_bar, double *u_bar)
+{
+    if (!c || !r_bar || !u_bar || lo < 1 || hi > len - 2 || lo > hi) return ORACLE_BAD_ARG;
+    for (long i = lo; i <= hi; ++i) {
+        u_bar[i - 1] += wm * c[i] * r_bar[i];
+        u_bar[i]     += w0 * c[i] * r_bar[i];
+        u_bar[i + 1] += wp * c[i] * r_bar[i];
+    }
+    return ORACLE_OK;
+}
