@@ -1,0 +1,135 @@
+/*
+ * sadj.h -- C ABI of libsadj: primal stencil loops and their gather-form adjoints
+ * on one AMD MI355X (gfx950).
+ *
+ * Problem statement (paper Sections 3.2 and 3.3): a primal stencil loop computes
+ *     r[i] = f(u[i+o_1], ..., u[i+o_M]; passive data)        for i in I
+ * on a dense 1-, 2- or 3-D grid.  Its reverse-mode adjoint is
+ *     u_bar += (dr/du)^T r_bar .
+ * Conventional AD writes that as a scatter u_bar[i+o] += ... over i in I, which
+ * races when parallelised.  Every sadj_adjoint_* call instead evaluates the
+ * index-shifted gather form (Section 3.3.2): each element of u_bar is produced by
+ * exactly one GPU thread, which sums the terms (df_{j-o}/du_j) * r_bar[j-o] over the
+ * offsets o whose primal iteration j-o exists (j-o in I).  No atomics are used and
+ * the result is bitwise reproducible from run to run (Section 3.5).  The grid is
+ * covered by a core region, where all terms exist (Section 3.3.3), and by boundary /
+ * remainder regions, where a subset exists (Section 3.3.4); the regions are
+ * disjoint, so they need no ordering among themselves.
+ *
+ * General conventions
+ *  - Every array argument is a DEVICE pointer owned by the caller; it must stay valid
+ *    until the work queued on `stream` has finished.  The library allocates nothing
+ *    and keeps no reference after the work has run.
+ *  - Arrays are dense with x fastest: element (x,y,z) lives at x + nx*(y + ny*z);
+ *    every array of a call has nx*ny*nz elements of the call's dtype.
+ *  - Primal iteration space: I = prod_d [R, n_d-1-R] with R the stencil radius
+ *    (the paper's loop bounds [1,n-2] for R=1).  Every extent must be >= 2R+1,
+ *    otherwise SADJ_ERR_SIZE.  Grids whose core region is empty (n_d < 4R+1) are valid.
+ *    Limits: nx*ny <= 2^30 elements and every extent <= 2^30.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *    are asynchronous: they enqueue kernels and return.
+ *  - Primal calls ASSIGN r on I and leave r outside I untouched.
+ *  - Adjoint calls ACCUMULATE into u_bar (and u_prev_bar) over the whole grid;
+ *    r_bar is read only; values of r_bar, c (and u_prev) outside I never influence
+ *    the result, not even when they are NaN.  c is passive: there is no c_bar.
+ *  - An output array must not overlap any input array of the same call (Section 3.4:
+ *    read and write sets are disjoint) -> SADJ_ERR_ALIAS.
+ *  - Errors are return codes; argument checks happen before anything is enqueued, so
+ *    a failed call has no effect.  No function throws or aborts.
+ *  - Calls are thread-safe; one GPU (the current HIP device of the calling thread).
+ *
+ * Star Laplacian weights: R=1: (-2, 1); R=4: the 8th-order central weights
+ * (-205/72, 8/5, -1/5, 8/315, -1/560) per axis; the centre weight is multiplied by
+ * the number of dimensions.  Grid spacing and time step are folded into c.
+ */
+#ifndef SADJ_H
+#define SADJ_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SADJ_OK = 0,
+    SADJ_ERR_NULL = 1,        /* a required pointer is NULL                              */
+    SADJ_ERR_SIZE = 2,        /* an extent is < 2R+1 or above the documented limits      */
+    SADJ_ERR_ALIAS = 3,       /* an output array overlaps an input array                 */
+    SADJ_ERR_UNSUPPORTED = 4, /* dtype or radius not built, unknown option               */
+    SADJ_ERR_DEVICE = 5       /* HIP reported an error when enqueueing                   */
+} sadj_status;
+
+typedef enum { SADJ_F32 = 0, SADJ_F64 = 1 } sadj_dtype;
+
+/* Static, NUL-terminated description of a status code (never NULL). */
+const char *sadj_status_string(sadj_status status);
+
+/* Library version as a static string, e.g. "0.1.0". */
+const char *sadj_version(void);
+
+/* ---- linear variable-coefficient wave step ---------------------------------------
+ * Primal (paper Section 4.1, the generating script):
+ *     r[i] = 2 u[i] - u_prev[i] + c[i] * sum_o w_o u[i+o]            for i in I
+ * Adjoint (Section 4.1, gather listing, generalised to radius R and merged into one
+ * update per index as in the last listing of Section 3.2):
+ *     u_bar[j]      += 2 r_bar[j] [j in I] + sum_o w_o * c[j-o] r_bar[j-o] [j-o in I]
+ *     u_prev_bar[j] -= r_bar[j] [j in I]            (skipped when u_prev_bar is NULL)
+ * The linear stencil's adjoint does not need the primal u (Section 3.1).
+ * 1-D and 2-D: radius 1 (3- and 5-point).  3-D: radius 1 (7-point) or 4 (25-point).
+ */
+sadj_status sadj_primal_wave1d(sadj_dtype dtype, long n,
+                               const void *u, const void *u_prev, const void *c, void *r,
+                               void *stream);
+sadj_status sadj_adjoint_wave1d(sadj_dtype dtype, long n,
+                                const void *c, const void *r_bar,
+                                void *u_bar, void *u_prev_bar /* nullable */, void *stream);
+
+sadj_status sadj_primal_wave2d(sadj_dtype dtype, long nx, long ny,
+                               const void *u, const void *u_prev, const void *c, void *r,
+                               void *stream);
+sadj_status sadj_adjoint_wave2d(sadj_dtype dtype, long nx, long ny,
+                                const void *c, const void *r_bar,
+                                void *u_bar, void *u_prev_bar /* nullable */, void *stream);
+
+sadj_status sadj_primal_wave3d(sadj_dtype dtype, int radius, long nx, long ny, long nz,
+                               const void *u, const void *u_prev, const void *c, void *r,
+                               void *stream);
+sadj_status sadj_adjoint_wave3d(sadj_dtype dtype, int radius, long nx, long ny, long nz,
+                                const void *c, const void *r_bar,
+                                void *u_bar, void *u_prev_bar /* nullable */, void *stream);
+
+/* ---- 1-D upwinded Burgers step -----------------------------------------------------
+ * Primal (paper Section 4.2, upwind formula and generating script), i in [1, n-2]:
+ *     r[i] = u[i] - C*(max(u[i],0)*(u[i]-u[i-1]) + min(u[i],0)*(u[i+1]-u[i]))
+ *                 + D*(u[i-1] - 2u[i] + u[i+1])
+ * Adjoint (Section 4.2, gather listing): nonlinear, so the primal u is read, at
+ * shifted indices (Section 3.3.2); with g_-(i), g_0(i), g_+(i) the partial derivatives
+ * of iteration i with respect to u[i-1], u[i], u[i+1],
+ *     u_bar[j] += g_-(j+1) r_bar[j+1] [j+1 in I] + g_0(j) r_bar[j] [j in I]
+ *               + g_+(j-1) r_bar[j-1] [j-1 in I]
+ * d max(a,0)/da and d min(a,0)/da are both 1 at a == 0, as in the paper's listing.
+ * C and D are converted to dtype before use.
+ */
+sadj_status sadj_primal_burgers1d(sadj_dtype dtype, long n, double C, double D,
+                                  const void *u, void *r, void *stream);
+sadj_status sadj_adjoint_burgers1d(sadj_dtype dtype, long n, double C, double D,
+                                   const void *u, const void *r_bar, void *u_bar,
+                                   void *stream);
+
+/* ---- launch options -------------------------------------------------------------------
+ * Process-wide integer options that select among equivalent launch strategies; they
+ * never change what is computed, only how the regions are mapped to kernels.
+ *   "wave3d.fused"   1 (default): core and remainder regions in one dispatch;
+ *                    0: one dispatch for the core region and one per remainder slab
+ *                    (Section 3.3.4: the regions are disjoint, either is valid).
+ *   "wave3d.zchunk"  planes of output per workgroup along z (default 0 = automatic).
+ *   "wave3d.variant" tile-shape variant index (default 0 = automatic).
+ * Unknown names or out-of-range values give SADJ_ERR_UNSUPPORTED and change nothing.
+ * sadj_get_option returns SADJ_OK and stores the value, or SADJ_ERR_UNSUPPORTED.
+ */
+sadj_status sadj_set_option(const char *name, long value);
+sadj_status sadj_get_option(const char *name, long *value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SADJ_H */

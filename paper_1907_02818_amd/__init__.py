@@ -1,0 +1,159 @@
+"""Python binding of libsadj (include/sadj.h): argument marshalling only.
+
+Every function has the name of the C entry point it calls and takes torch tensors
+that live on the GPU; torch is used for device memory and streams, nothing else.
+All arithmetic happens in the HIP kernels of libsadj.so.  There is no CPU path: if
+the shared library has not been built, importing a symbol raises.
+
+Tensor layout: C-contiguous, slowest axis first, x last -- shape (n,), (ny, nx) or
+(nz, ny, nx) -- which is the "x fastest" layout of the C ABI.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+__all__ = [
+    "SadjError", "lib_path", "load", "set_option", "get_option", "version",
+    "sadj_primal_wave1d", "sadj_adjoint_wave1d", "sadj_primal_wave2d", "sadj_adjoint_wave2d",
+    "sadj_primal_wave3d", "sadj_adjoint_wave3d", "sadj_primal_burgers1d", "sadj_adjoint_burgers1d",
+]
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsadj.so")
+_lib = None
+
+SADJ_F32, SADJ_F64 = 0, 1
+
+
+class SadjError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("libsadj status %d: %s" % (status, message))
+        self.status = status
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Load libsadj.so (built by `python -m paper_1907_02818_amd.build`)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("libsadj.so is not built: run `python -m paper_1907_02818_amd.build` "
+                          "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    P, L, I, D = ctypes.c_void_p, ctypes.c_long, ctypes.c_int, ctypes.c_double
+    lib.sadj_status_string.restype = ctypes.c_char_p
+    lib.sadj_status_string.argtypes = [I]
+    lib.sadj_version.restype = ctypes.c_char_p
+    lib.sadj_version.argtypes = []
+    lib.sadj_set_option.argtypes = [ctypes.c_char_p, L]
+    lib.sadj_get_option.argtypes = [ctypes.c_char_p, ctypes.POINTER(L)]
+    lib.sadj_primal_wave1d.argtypes = [I, L, P, P, P, P, P]
+    lib.sadj_adjoint_wave1d.argtypes = [I, L, P, P, P, P, P]
+    lib.sadj_primal_wave2d.argtypes = [I, L, L, P, P, P, P, P]
+    lib.sadj_adjoint_wave2d.argtypes = [I, L, L, P, P, P, P, P]
+    lib.sadj_primal_wave3d.argtypes = [I, I, L, L, L, P, P, P, P, P]
+    lib.sadj_adjoint_wave3d.argtypes = [I, I, L, L, L, P, P, P, P, P]
+    lib.sadj_primal_burgers1d.argtypes = [I, L, D, D, P, P, P]
+    lib.sadj_adjoint_burgers1d.argtypes = [I, L, D, D, P, P, P, P]
+    for name in ("sadj_set_option", "sadj_get_option", "sadj_primal_wave1d", "sadj_adjoint_wave1d",
+                 "sadj_primal_wave2d", "sadj_adjoint_wave2d", "sadj_primal_wave3d", "sadj_adjoint_wave3d",
+                 "sadj_primal_burgers1d", "sadj_adjoint_burgers1d"):
+        getattr(lib, name).restype = I
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise SadjError(status, load().sadj_status_string(status).decode())
+
+
+def version() -> str:
+    return load().sadj_version().decode()
+
+
+def set_option(name: str, value: int) -> None:
+    _check(load().sadj_set_option(name.encode(), int(value)))
+
+
+def get_option(name: str) -> int:
+    v = ctypes.c_long(0)
+    _check(load().sadj_get_option(name.encode(), ctypes.byref(v)))
+    return v.value
+
+
+def _marshal(tensors, ndim, optional=()):
+    """Common checks: same device/dtype/shape, contiguous, on the GPU.  Returns
+    (dtype code, shape, pointers, stream handle)."""
+    import torch
+
+    ref = next(t for t in tensors if t is not None)
+    if ref.dim() != ndim:
+        raise ValueError("expected %d-D tensors" % ndim)
+    if ref.dtype == torch.float64:
+        code = SADJ_F64
+    elif ref.dtype == torch.float32:
+        code = SADJ_F32
+    else:
+        raise TypeError("float32 or float64 tensors only")
+    ptrs = []
+    for i, t in enumerate(tensors):
+        if t is None:
+            if i not in optional:
+                raise ValueError("tensor %d is required" % i)
+            ptrs.append(None)
+            continue
+        if not t.is_cuda:
+            raise ValueError("libsadj works on GPU memory only (no CPU path)")
+        if t.dtype != ref.dtype or t.shape != ref.shape or t.device != ref.device:
+            raise ValueError("all tensors of a call share dtype, shape and device")
+        if not t.is_contiguous():
+            raise ValueError("tensors must be C-contiguous (x fastest)")
+        ptrs.append(ctypes.c_void_p(t.data_ptr()))
+    stream = ctypes.c_void_p(torch.cuda.current_stream(ref.device).cuda_stream)
+    return code, tuple(ref.shape), ptrs, stream
+
+
+def sadj_primal_wave1d(u, u_prev, c, r) -> None:
+    code, (n,), p, s = _marshal([u, u_prev, c, r], 1)
+    _check(load().sadj_primal_wave1d(code, n, *p, s))
+
+
+def sadj_adjoint_wave1d(c, r_bar, u_bar, u_prev_bar=None) -> None:
+    code, (n,), p, s = _marshal([c, r_bar, u_bar, u_prev_bar], 1, optional=(3,))
+    _check(load().sadj_adjoint_wave1d(code, n, *p, s))
+
+
+def sadj_primal_wave2d(u, u_prev, c, r) -> None:
+    code, (ny, nx), p, s = _marshal([u, u_prev, c, r], 2)
+    _check(load().sadj_primal_wave2d(code, nx, ny, *p, s))
+
+
+def sadj_adjoint_wave2d(c, r_bar, u_bar, u_prev_bar=None) -> None:
+    code, (ny, nx), p, s = _marshal([c, r_bar, u_bar, u_prev_bar], 2, optional=(3,))
+    _check(load().sadj_adjoint_wave2d(code, nx, ny, *p, s))
+
+
+def sadj_primal_wave3d(radius: int, u, u_prev, c, r) -> None:
+    code, (nz, ny, nx), p, s = _marshal([u, u_prev, c, r], 3)
+    _check(load().sadj_primal_wave3d(code, int(radius), nx, ny, nz, *p, s))
+
+
+def sadj_adjoint_wave3d(radius: int, c, r_bar, u_bar, u_prev_bar=None) -> None:
+    code, (nz, ny, nx), p, s = _marshal([c, r_bar, u_bar, u_prev_bar], 3, optional=(3,))
+    _check(load().sadj_adjoint_wave3d(code, int(radius), nx, ny, nz, *p, s))
+
+
+def sadj_primal_burgers1d(C: float, D: float, u, r) -> None:
+    code, (n,), p, s = _marshal([u, r], 1)
+    _check(load().sadj_primal_burgers1d(code, n, float(C), float(D), *p, s))
+
+
+def sadj_adjoint_burgers1d(C: float, D: float, u, r_bar, u_bar) -> None:
+    code, (n,), p, s = _marshal([u, r_bar, u_bar], 1)
+    _check(load().sadj_adjoint_burgers1d(code, n, float(C), float(D), *p, s))

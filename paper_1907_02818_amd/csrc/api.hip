@@ -1,0 +1,216 @@
+// C ABI of libsadj: argument validation and dispatch.  See include/sadj.h for the
+// contract of every entry point.
+#include "../../include/sadj.h"
+#include "launch.hpp"
+
+#include <atomic>
+#include <cstdint>
+#include <cstring>
+
+namespace {
+
+std::atomic<long> g_fused{1}, g_zchunk{0}, g_variant{0};
+
+sadj::LaunchOptions current_options()
+{
+    sadj::LaunchOptions o;
+    o.fused = g_fused.load();
+    o.zchunk = g_zchunk.load();
+    o.variant = g_variant.load();
+    return o;
+}
+
+constexpr long kMaxExtent = 1L << 30;
+constexpr long kMaxPlane = 1L << 28;   // elements; keeps in-plane byte offsets below 2^32
+
+struct Span { const void *p; size_t bytes; };
+
+bool overlaps(const Span &a, const Span &b)
+{
+    if (!a.p || !b.p || a.bytes == 0 || b.bytes == 0) return false;
+    const uintptr_t a0 = (uintptr_t)a.p, b0 = (uintptr_t)b.p;
+    return a0 < b0 + b.bytes && b0 < a0 + a.bytes;
+}
+
+bool dtype_ok(sadj_dtype d) { return d == SADJ_F32 || d == SADJ_F64; }
+size_t elem(sadj_dtype d) { return d == SADJ_F64 ? 8 : 4; }
+
+// Outputs must not overlap inputs, nor each other.
+template <size_t NI, size_t NO>
+bool any_alias(const Span (&in)[NI], const Span (&out)[NO])
+{
+    for (size_t o = 0; o < NO; ++o) {
+        for (size_t i = 0; i < NI; ++i)
+            if (overlaps(out[o], in[i])) return true;
+        for (size_t o2 = o + 1; o2 < NO; ++o2)
+            if (overlaps(out[o], out[o2])) return true;
+    }
+    return false;
+}
+
+sadj_status check_extents(int radius, long nx, long ny, long nz, int ndim)
+{
+    const long n[3] = {nx, ny, nz};
+    for (int d = 0; d < ndim; ++d)
+        if (n[d] < 2L * radius + 1 || n[d] > kMaxExtent) return SADJ_ERR_SIZE;
+    if (ndim >= 2 && nx * ny > kMaxPlane) return SADJ_ERR_SIZE;
+    return SADJ_OK;
+}
+
+sadj_status from_hip(hipError_t e) { return e == hipSuccess ? SADJ_OK : SADJ_ERR_DEVICE; }
+
+}  // namespace
+
+extern "C" {
+
+const char *sadj_status_string(sadj_status s)
+{
+    switch (s) {
+    case SADJ_OK: return "ok";
+    case SADJ_ERR_NULL: return "a required pointer is NULL";
+    case SADJ_ERR_SIZE: return "grid extent below 2*radius+1 or above the supported limit";
+    case SADJ_ERR_ALIAS: return "an output array overlaps an input array";
+    case SADJ_ERR_UNSUPPORTED: return "unsupported dtype, radius or option";
+    case SADJ_ERR_DEVICE: return "HIP error while enqueueing";
+    }
+    return "unknown status";
+}
+
+const char *sadj_version(void) { return "0.1.0"; }
+
+sadj_status sadj_set_option(const char *name, long value)
+{
+    if (!name) return SADJ_ERR_NULL;
+    if (!std::strcmp(name, "wave3d.fused")) {
+        if (value != 0 && value != 1) return SADJ_ERR_UNSUPPORTED;
+        g_fused = value;
+        return SADJ_OK;
+    }
+    if (!std::strcmp(name, "wave3d.zchunk")) {
+        if (value < 0 || value > kMaxExtent) return SADJ_ERR_UNSUPPORTED;
+        g_zchunk = value;
+        return SADJ_OK;
+    }
+    if (!std::strcmp(name, "wave3d.variant")) {
+        if (value < 0 || value > 15) return SADJ_ERR_UNSUPPORTED;
+        g_variant = value;
+        return SADJ_OK;
+    }
+    return SADJ_ERR_UNSUPPORTED;
+}
+
+sadj_status sadj_get_option(const char *name, long *value)
+{
+    if (!name || !value) return SADJ_ERR_NULL;
+    if (!std::strcmp(name, "wave3d.fused")) { *value = g_fused; return SADJ_OK; }
+    if (!std::strcmp(name, "wave3d.zchunk")) { *value = g_zchunk; return SADJ_OK; }
+    if (!std::strcmp(name, "wave3d.variant")) { *value = g_variant; return SADJ_OK; }
+    return SADJ_ERR_UNSUPPORTED;
+}
+
+// ---------------------------------------------------------------------------- wave
+static sadj_status primal_wave(int ndim, sadj_dtype dtype, int radius, long nx, long ny, long nz,
+                               const void *u, const void *u_prev, const void *c, void *r, void *stream)
+{
+    if (!dtype_ok(dtype)) return SADJ_ERR_UNSUPPORTED;
+    if (!u || !u_prev || !c || !r) return SADJ_ERR_NULL;
+    sadj_status s = check_extents(radius, nx, ny, nz, ndim);
+    if (s != SADJ_OK) return s;
+    const size_t bytes = (size_t)nx * ny * nz * elem(dtype);
+    const Span in[3] = {{u, bytes}, {u_prev, bytes}, {c, bytes}};
+    const Span out[1] = {{r, bytes}};
+    if (any_alias(in, out)) return SADJ_ERR_ALIAS;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int f64 = dtype == SADJ_F64;
+    switch (ndim) {
+    case 1: return from_hip(sadj::launch_primal_wave1d(f64, nx, u, u_prev, c, r, st));
+    case 2: return from_hip(sadj::launch_primal_wave2d(f64, (int)nx, (int)ny, u, u_prev, c, r, st));
+    default: return from_hip(sadj::launch_primal_wave3d(f64, radius, (int)nx, (int)ny, (int)nz, u, u_prev, c, r,
+                                                        current_options(), st));
+    }
+}
+
+static sadj_status adjoint_wave(int ndim, sadj_dtype dtype, int radius, long nx, long ny, long nz,
+                                const void *c, const void *r_bar, void *u_bar, void *u_prev_bar,
+                                void *stream)
+{
+    if (!dtype_ok(dtype)) return SADJ_ERR_UNSUPPORTED;
+    if (!c || !r_bar || !u_bar) return SADJ_ERR_NULL;
+    sadj_status s = check_extents(radius, nx, ny, nz, ndim);
+    if (s != SADJ_OK) return s;
+    const size_t bytes = (size_t)nx * ny * nz * elem(dtype);
+    const Span in[2] = {{c, bytes}, {r_bar, bytes}};
+    const Span out[2] = {{u_bar, bytes}, {u_prev_bar, u_prev_bar ? bytes : 0}};
+    if (any_alias(in, out)) return SADJ_ERR_ALIAS;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int f64 = dtype == SADJ_F64;
+    switch (ndim) {
+    case 1: return from_hip(sadj::launch_adjoint_wave1d(f64, nx, c, r_bar, u_bar, u_prev_bar, st));
+    case 2: return from_hip(sadj::launch_adjoint_wave2d(f64, (int)nx, (int)ny, c, r_bar, u_bar, u_prev_bar, st));
+    default: return from_hip(sadj::launch_adjoint_wave3d(f64, radius, (int)nx, (int)ny, (int)nz, c, r_bar, u_bar,
+                                                         u_prev_bar, current_options(), st));
+    }
+}
+
+sadj_status sadj_primal_wave1d(sadj_dtype dtype, long n, const void *u, const void *u_prev, const void *c,
+                               void *r, void *stream)
+{
+    return primal_wave(1, dtype, 1, n, 1, 1, u, u_prev, c, r, stream);
+}
+sadj_status sadj_adjoint_wave1d(sadj_dtype dtype, long n, const void *c, const void *r_bar, void *u_bar,
+                                void *u_prev_bar, void *stream)
+{
+    return adjoint_wave(1, dtype, 1, n, 1, 1, c, r_bar, u_bar, u_prev_bar, stream);
+}
+sadj_status sadj_primal_wave2d(sadj_dtype dtype, long nx, long ny, const void *u, const void *u_prev,
+                               const void *c, void *r, void *stream)
+{
+    return primal_wave(2, dtype, 1, nx, ny, 1, u, u_prev, c, r, stream);
+}
+sadj_status sadj_adjoint_wave2d(sadj_dtype dtype, long nx, long ny, const void *c, const void *r_bar,
+                                void *u_bar, void *u_prev_bar, void *stream)
+{
+    return adjoint_wave(2, dtype, 1, nx, ny, 1, c, r_bar, u_bar, u_prev_bar, stream);
+}
+sadj_status sadj_primal_wave3d(sadj_dtype dtype, int radius, long nx, long ny, long nz, const void *u,
+                               const void *u_prev, const void *c, void *r, void *stream)
+{
+    if (radius != 1 && radius != 4) return SADJ_ERR_UNSUPPORTED;
+    return primal_wave(3, dtype, radius, nx, ny, nz, u, u_prev, c, r, stream);
+}
+sadj_status sadj_adjoint_wave3d(sadj_dtype dtype, int radius, long nx, long ny, long nz, const void *c,
+                                const void *r_bar, void *u_bar, void *u_prev_bar, void *stream)
+{
+    if (radius != 1 && radius != 4) return SADJ_ERR_UNSUPPORTED;
+    return adjoint_wave(3, dtype, radius, nx, ny, nz, c, r_bar, u_bar, u_prev_bar, stream);
+}
+
+// ------------------------------------------------------------------------- Burgers
+sadj_status sadj_primal_burgers1d(sadj_dtype dtype, long n, double C, double D, const void *u, void *r,
+                                  void *stream)
+{
+    if (!dtype_ok(dtype)) return SADJ_ERR_UNSUPPORTED;
+    if (!u || !r) return SADJ_ERR_NULL;
+    if (n < 3 || n > kMaxExtent) return SADJ_ERR_SIZE;
+    const size_t bytes = (size_t)n * elem(dtype);
+    const Span in[1] = {{u, bytes}};
+    const Span out[1] = {{r, bytes}};
+    if (any_alias(in, out)) return SADJ_ERR_ALIAS;
+    return from_hip(sadj::launch_primal_burgers1d(dtype == SADJ_F64, n, C, D, u, r, static_cast<hipStream_t>(stream)));
+}
+
+sadj_status sadj_adjoint_burgers1d(sadj_dtype dtype, long n, double C, double D, const void *u,
+                                   const void *r_bar, void *u_bar, void *stream)
+{
+    if (!dtype_ok(dtype)) return SADJ_ERR_UNSUPPORTED;
+    if (!u || !r_bar || !u_bar) return SADJ_ERR_NULL;
+    if (n < 3 || n > kMaxExtent) return SADJ_ERR_SIZE;
+    const size_t bytes = (size_t)n * elem(dtype);
+    const Span in[2] = {{u, bytes}, {r_bar, bytes}};
+    const Span out[1] = {{u_bar, bytes}};
+    if (any_alias(in, out)) return SADJ_ERR_ALIAS;
+    return from_hip(sadj::launch_adjoint_burgers1d(dtype == SADJ_F64, n, C, D, u, r_bar, u_bar,
+                                                   static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

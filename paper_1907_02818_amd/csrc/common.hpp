@@ -1,0 +1,83 @@
+// Shared device/host helpers of libsadj (HIP, gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sadj {
+
+// Central finite-difference weights of the second derivative on a unit grid
+// (orders 2 and 8), the nearest double of each rational; w(0) is the per-axis
+// centre weight.
+template <int R> __host__ __device__ constexpr double star_w(int k);
+template <> __host__ __device__ constexpr double star_w<1>(int k) { return k == 0 ? -2.0 : 1.0; }
+template <> __host__ __device__ constexpr double star_w<4>(int k)
+{
+    return k == 0 ? -205.0 / 72.0
+         : k == 1 ? 8.0 / 5.0
+         : k == 2 ? -1.0 / 5.0
+         : k == 3 ? 8.0 / 315.0
+                  : -1.0 / 560.0;
+}
+
+// Workgroups are dealt to the 8 XCDs round-robin by their linear id, and each XCD
+// has its own L2.  Map the hardware id to a logical id such that every XCD works
+// on one contiguous range of logical ids (so that neighbouring tiles, which share
+// halo cells, meet in the same L2).  Bijective for any total.
+__device__ __forceinline__ int xcd_contiguous_id(int hw_id, int total)
+{
+    constexpr int NXCD = 8;
+    const int xcd = hw_id % NXCD;
+    const int idx = hw_id / NXCD;
+    const int base = total / NXCD;
+    const int rem = total % NXCD;
+    const int start = xcd * base + (xcd < rem ? xcd : rem);
+    return start + idx;
+}
+
+struct Box { int x0, x1, y0, y1, z0, z1; };   // half-open index ranges
+
+// One rectangular region of output indices with its own tiling.
+struct Region {
+    Box box;
+    int ntx, nty, ntz;     // tiles along x, y and z-chunks
+    int first_block;       // logical id of the region's first workgroup
+};
+
+constexpr int kMaxRegions = 8;
+
+template <class T> __device__ __forceinline__ T ld_off(const T *base, uint32_t byte_off)
+{
+    return *reinterpret_cast<const T *>(reinterpret_cast<const char *>(base) + byte_off);
+}
+template <class T> __device__ __forceinline__ void st_off(T *base, uint32_t byte_off, T v)
+{
+    *reinterpret_cast<T *>(reinterpret_cast<char *>(base) + byte_off) = v;
+}
+
+
+// N consecutive elements moved with one (up to 16-byte) memory instruction.
+template <class T, int N> struct alignas(sizeof(T) * N) Vec { T v[N]; };
+
+template <class T, int N> __device__ __forceinline__ Vec<T, N> ld_vec(const T *p)
+{
+    return *reinterpret_cast<const Vec<T, N> *>(p);
+}
+template <class T, int N> __device__ __forceinline__ void st_vec(T *p, const Vec<T, N> &v)
+{
+    *reinterpret_cast<Vec<T, N> *>(p) = v;
+}
+
+// Neighbour exchange inside a 64-lane wave whose lanes own PX consecutive elements
+// each: left = element just before this lane's first, right = element just after
+// its last.  `halo` holds, in lane 0, the element before the wave's segment and, in
+// lane 63, the element after it.
+template <class T, int PX>
+__device__ __forceinline__ void wave_neighbours(const T (&v)[PX], T halo, int lane, T &left, T &right)
+{
+    left = __shfl_up(v[PX - 1], 1);
+    right = __shfl_down(v[0], 1);
+    if (lane == 0) left = halo;
+    if (lane == 63) right = halo;
+}
+
+}  // namespace sadj

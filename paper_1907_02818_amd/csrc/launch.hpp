@@ -1,0 +1,35 @@
+// Internal launcher interface between the C ABI (api.hip) and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace sadj {
+
+struct LaunchOptions {
+    long fused = 1;      // wave3d: 1 = all regions in one dispatch
+    long zchunk = 0;     // wave3d: output planes per workgroup (0 = automatic)
+    long variant = 0;    // wave3d: tile-shape variant
+};
+
+hipError_t launch_adjoint_wave3d(int is_f64, int radius, int nx, int ny, int nz, const void *c,
+                                 const void *r_bar, void *u_bar, void *u_prev_bar,
+                                 const LaunchOptions &opt, hipStream_t stream);
+hipError_t launch_primal_wave3d(int is_f64, int radius, int nx, int ny, int nz, const void *u,
+                                const void *u_prev, const void *c, void *r,
+                                const LaunchOptions &opt, hipStream_t stream);
+
+hipError_t launch_adjoint_wave2d(int is_f64, int nx, int ny, const void *c, const void *r_bar,
+                                 void *u_bar, void *u_prev_bar, hipStream_t stream);
+hipError_t launch_primal_wave2d(int is_f64, int nx, int ny, const void *u, const void *u_prev,
+                                const void *c, void *r, hipStream_t stream);
+
+hipError_t launch_adjoint_wave1d(int is_f64, long n, const void *c, const void *r_bar, void *u_bar,
+                                 void *u_prev_bar, hipStream_t stream);
+hipError_t launch_primal_wave1d(int is_f64, long n, const void *u, const void *u_prev, const void *c,
+                                void *r, hipStream_t stream);
+
+hipError_t launch_adjoint_burgers1d(int is_f64, long n, double C, double D, const void *u,
+                                    const void *r_bar, void *u_bar, hipStream_t stream);
+hipError_t launch_primal_burgers1d(int is_f64, long n, double C, double D, const void *u, void *r,
+                                   hipStream_t stream);
+
+}  // namespace sadj

@@ -1,0 +1,322 @@
+// 1-D stencils: linear 3-point wave step and upwinded Burgers step, primal and
+// gather-form adjoint (paper Sections 3.2, 4.1 in one dimension, and 4.2).
+//
+// Mapping to CDNA4.  A 64-lane wave owns a segment of 64*PX consecutive cells, PX
+// cells (16 bytes) per lane.  Neighbour values travel between lanes with wave
+// shuffles; the two cells beside the segment are loaded by lanes 0 and 63.  No LDS,
+// no barrier, no atomics: each output cell is written by exactly one lane.
+//
+// Regions (Sections 3.3.3, 3.3.4).  The core launch covers the segments whose reads
+// all lie in the primal iteration space I = [1, n-2]; it is compiled without any
+// guard.  The remainder launch covers the first and the last segment(s) with the
+// guarded instantiation: a term is kept iff its primal iteration exists, unused
+// values are replaced by zero with a select (never multiplied by zero), and loads
+// are element-wise and clamped into the array.
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace sadj {
+
+struct Args1d {
+    const void *a0, *a1, *a2;   // inputs (meaning depends on the kernel)
+    void *o0, *o1;              // outputs
+    long n;
+    double C, D;
+    long seg_first;             // core launch: first segment
+    long seg_count;             // number of segments (= waves) of this launch
+    long seg_jump_after;        // remainder launch: local index 0 -> segment 0, k>0 -> seg_jump_after + k
+    int remainder;              // 0: core launch, 1: remainder launch
+};
+
+constexpr int kWaves1d = 4;
+
+__device__ __forceinline__ long segment_of(const Args1d &a, long local)
+{
+    if (!a.remainder) return a.seg_first + local;
+    return local == 0 ? 0 : a.seg_jump_after + local;
+}
+
+// Load PX consecutive cells starting at x.  Unguarded: one vector load.  Guarded:
+// element-wise, indices clamped to [0, n-1].
+template <class T, int PX, bool GUARD>
+__device__ __forceinline__ void load_cells(const T *p, long x, long n, T (&v)[PX])
+{
+    if (!GUARD) {
+        const Vec<T, PX> t = ld_vec<T, PX>(p + x);
+#pragma unroll
+        for (int e = 0; e < PX; ++e) v[e] = t.v[e];
+    } else {
+#pragma unroll
+        for (int e = 0; e < PX; ++e) {
+            const long i = x + e < n ? x + e : n - 1;
+            v[e] = p[i];
+        }
+    }
+}
+template <class T, bool GUARD> __device__ __forceinline__ T load_cell(const T *p, long i, long n)
+{
+    if (GUARD) i = i < 0 ? 0 : (i > n - 1 ? n - 1 : i);
+    return p[i];
+}
+template <class T, int PX, bool GUARD>
+__device__ __forceinline__ void store_cells(T *p, long x, long n, const T (&v)[PX], const bool (&ok)[PX])
+{
+    if (!GUARD) {
+        Vec<T, PX> t;
+#pragma unroll
+        for (int e = 0; e < PX; ++e) t.v[e] = v[e];
+        st_vec<T, PX>(p + x, t);
+    } else {
+#pragma unroll
+        for (int e = 0; e < PX; ++e)
+            if (ok[e]) p[x + e] = v[e];
+    }
+}
+
+// ------------------------------------------------------------------- wave, adjoint
+// u_bar[j] += 2 r_bar[j] [j in I] + q[j-1] - 2 q[j] + q[j+1],  q = c*r_bar on I, else 0.
+template <class T, int PX, bool GUARD, bool UPREV>
+__device__ __forceinline__ void adj_wave1d_segment(const Args1d &a, long xs, int lane)
+{
+    constexpr int W = 64 * PX;
+    const long n = a.n;
+    const T *cg = static_cast<const T *>(a.a0);
+    const T *rg = static_cast<const T *>(a.a1);
+    T *ug = static_cast<T *>(a.o0);
+    T *pg = static_cast<T *>(a.o1);
+    const long x = xs + (long)lane * PX;
+    const long hx = lane < 32 ? xs - 1 : xs + W;
+    T cv[PX], rv[PX], uv[PX], pv[PX];
+    load_cells<T, PX, GUARD>(cg, x, n, cv);
+    load_cells<T, PX, GUARD>(rg, x, n, rv);
+    load_cells<T, PX, GUARD>(ug, x, n, uv);
+    if (UPREV) load_cells<T, PX, GUARD>(pg, x, n, pv);
+    const T hc = load_cell<T, GUARD>(cg, hx, n), hr = load_cell<T, GUARD>(rg, hx, n);
+    T q[PX], rr[PX];
+    bool ok[PX];
+#pragma unroll
+    for (int e = 0; e < PX; ++e) {
+        const bool in = GUARD ? (x + e >= 1 && x + e <= n - 2) : true;
+        ok[e] = GUARD ? (x + e < n) : true;
+        rr[e] = in ? rv[e] : T(0);
+        q[e] = in ? cv[e] * rv[e] : T(0);
+    }
+    const bool hin = GUARD ? (hx >= 1 && hx <= n - 2) : true;
+    const T qh = hin ? hc * hr : T(0);
+    T left, right;
+    wave_neighbours<T, PX>(q, qh, lane, left, right);
+    T out[PX], pout[PX];
+#pragma unroll
+    for (int e = 0; e < PX; ++e) {
+        const T l = e == 0 ? left : q[e - 1];
+        const T r = e == PX - 1 ? right : q[e + 1];
+        out[e] = uv[e] + ((T(-2) * q[e] + (l + r)) + T(2) * rr[e]);
+        if (UPREV) pout[e] = pv[e] - rr[e];
+    }
+    store_cells<T, PX, GUARD>(ug, x, n, out, ok);
+    if (UPREV) store_cells<T, PX, GUARD>(pg, x, n, pout, ok);
+}
+
+// -------------------------------------------------------------------- wave, primal
+// r[i] = 2u[i] - u_prev[i] + c[i]*(u[i-1] - 2u[i] + u[i+1]) for i in I.
+template <class T, int PX, bool GUARD>
+__device__ __forceinline__ void pri_wave1d_segment(const Args1d &a, long xs, int lane)
+{
+    constexpr int W = 64 * PX;
+    const long n = a.n;
+    const T *ug = static_cast<const T *>(a.a0);
+    const T *pg = static_cast<const T *>(a.a1);
+    const T *cg = static_cast<const T *>(a.a2);
+    T *rg = static_cast<T *>(a.o0);
+    const long x = xs + (long)lane * PX;
+    const long hx = lane < 32 ? xs - 1 : xs + W;
+    T uv[PX], pv[PX], cv[PX];
+    load_cells<T, PX, GUARD>(ug, x, n, uv);
+    load_cells<T, PX, GUARD>(pg, x, n, pv);
+    load_cells<T, PX, GUARD>(cg, x, n, cv);
+    const T uh = load_cell<T, GUARD>(ug, hx, n);
+    T left, right;
+    wave_neighbours<T, PX>(uv, uh, lane, left, right);
+    T out[PX];
+    bool ok[PX];
+#pragma unroll
+    for (int e = 0; e < PX; ++e) {
+        const T l = e == 0 ? left : uv[e - 1];
+        const T r = e == PX - 1 ? right : uv[e + 1];
+        ok[e] = GUARD ? (x + e >= 1 && x + e <= n - 2) : true;
+        out[e] = T(2) * uv[e] - pv[e] + cv[e] * (T(-2) * uv[e] + (l + r));
+    }
+    store_cells<T, PX, GUARD>(rg, x, n, out, ok);
+}
+
+// ----------------------------------------------------------------- Burgers, primal
+template <class T> __device__ __forceinline__ T pos_part(T v) { return v > T(0) ? v : T(0); }
+template <class T> __device__ __forceinline__ T neg_part(T v) { return v < T(0) ? v : T(0); }
+
+template <class T, int PX, bool GUARD>
+__device__ __forceinline__ void pri_burgers_segment(const Args1d &a, long xs, int lane)
+{
+    constexpr int W = 64 * PX;
+    const long n = a.n;
+    const T C = (T)a.C, D = (T)a.D;
+    const T *ug = static_cast<const T *>(a.a0);
+    T *rg = static_cast<T *>(a.o0);
+    const long x = xs + (long)lane * PX;
+    const long hx = lane < 32 ? xs - 1 : xs + W;
+    T uv[PX];
+    load_cells<T, PX, GUARD>(ug, x, n, uv);
+    const T uh = load_cell<T, GUARD>(ug, hx, n);
+    T left, right;
+    wave_neighbours<T, PX>(uv, uh, lane, left, right);
+    T out[PX];
+    bool ok[PX];
+#pragma unroll
+    for (int e = 0; e < PX; ++e) {
+        const T um = e == 0 ? left : uv[e - 1];
+        const T up = e == PX - 1 ? right : uv[e + 1];
+        const T u0 = uv[e];
+        ok[e] = GUARD ? (x + e >= 1 && x + e <= n - 2) : true;
+        const T conv = pos_part(u0) * (u0 - um) + neg_part(u0) * (up - u0);
+        out[e] = u0 - C * conv + D * (um - T(2) * u0 + up);
+    }
+    store_cells<T, PX, GUARD>(rg, x, n, out, ok);
+}
+
+// ---------------------------------------------------------------- Burgers, adjoint
+// u_bar[j] += g_-(j+1) r_bar[j+1] [j+1 in I] + g_0(j) r_bar[j] [j in I] + g_+(j-1) r_bar[j-1] [j-1 in I]
+//   g_-(i) = C max(u_i,0) + D,  g_+(i) = -C min(u_i,0) + D,
+//   g_0(i) = 1 - 2D - C( [u_i>=0](u_i-u_{i-1}) + max(u_i,0) + [-u_i>=0](u_{i+1}-u_i) - min(u_i,0) )
+// The primal u is read at j-1, j, j+1 (shifted reads, Section 3.3.2).
+template <class T, int PX, bool GUARD>
+__device__ __forceinline__ void adj_burgers_segment(const Args1d &a, long xs, int lane)
+{
+    constexpr int W = 64 * PX;
+    const long n = a.n;
+    const T C = (T)a.C, D = (T)a.D;
+    const T *ug = static_cast<const T *>(a.a0);
+    const T *rg = static_cast<const T *>(a.a1);
+    T *bg = static_cast<T *>(a.o0);
+    const long x = xs + (long)lane * PX;
+    const long hx = lane < 32 ? xs - 1 : xs + W;
+    T uv[PX], rv[PX], bv[PX];
+    load_cells<T, PX, GUARD>(ug, x, n, uv);
+    load_cells<T, PX, GUARD>(rg, x, n, rv);
+    load_cells<T, PX, GUARD>(bg, x, n, bv);
+    const T uh = load_cell<T, GUARD>(ug, hx, n);
+    T rh = load_cell<T, GUARD>(rg, hx, n);
+    bool ok[PX], in[PX];
+#pragma unroll
+    for (int e = 0; e < PX; ++e) {
+        in[e] = GUARD ? (x + e >= 1 && x + e <= n - 2) : true;
+        ok[e] = GUARD ? (x + e < n) : true;
+        rv[e] = in[e] ? rv[e] : T(0);       // r_bar outside I is never used
+    }
+    if (GUARD) rh = (hx >= 1 && hx <= n - 2) ? rh : T(0);
+    T ul, ur, rl, rr;
+    wave_neighbours<T, PX>(uv, uh, lane, ul, ur);
+    wave_neighbours<T, PX>(rv, rh, lane, rl, rr);
+    T out[PX];
+#pragma unroll
+    for (int e = 0; e < PX; ++e) {
+        const T um = e == 0 ? ul : uv[e - 1];
+        const T up = e == PX - 1 ? ur : uv[e + 1];
+        const T rm = e == 0 ? rl : rv[e - 1];
+        const T rp = e == PX - 1 ? rr : rv[e + 1];
+        const T u0 = uv[e];
+        const T dpos = u0 >= T(0) ? T(1) : T(0);
+        const T dneg = -u0 >= T(0) ? T(1) : T(0);
+        const T g0 = T(1) - C * (dpos * (u0 - um) + pos_part(u0) + dneg * (up - u0) - neg_part(u0)) - T(2) * D;
+        const T from_right = (C * pos_part(up) + D) * rp;      // iteration j+1 read u[j] as its left cell
+        const T from_left = (-C * neg_part(um) + D) * rm;      // iteration j-1 read u[j] as its right cell
+        out[e] = bv[e] + (from_right + (in[e] ? g0 * rv[e] : T(0)) + from_left);
+    }
+    store_cells<T, PX, GUARD>(bg, x, n, out, ok);
+}
+
+// -------------------------------------------------------------------------- kernels
+enum Op1d { OP_ADJ_WAVE, OP_ADJ_WAVE_UPREV, OP_PRI_WAVE, OP_PRI_BURGERS, OP_ADJ_BURGERS };
+
+template <class T, int PX, bool GUARD, int OP>
+__global__ __launch_bounds__(64 * kWaves1d) void stencil1d_kernel(Args1d a)
+{
+    constexpr int W = 64 * PX;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long local = (long)blockIdx.x * kWaves1d + wave;
+    if (local >= a.seg_count) return;              // wave-uniform; no barrier in this kernel
+    const long xs = segment_of(a, local) * W;
+    if (OP == OP_ADJ_WAVE) adj_wave1d_segment<T, PX, GUARD, false>(a, xs, lane);
+    else if (OP == OP_ADJ_WAVE_UPREV) adj_wave1d_segment<T, PX, GUARD, true>(a, xs, lane);
+    else if (OP == OP_PRI_WAVE) pri_wave1d_segment<T, PX, GUARD>(a, xs, lane);
+    else if (OP == OP_PRI_BURGERS) pri_burgers_segment<T, PX, GUARD>(a, xs, lane);
+    else adj_burgers_segment<T, PX, GUARD>(a, xs, lane);
+}
+
+// Core launch: segments [1, s_hi] (all reads inside I, whole vectors inside the
+// array).  Remainder launch: segment 0 and segments s_hi+1 .. nseg-1.
+template <class T, int PX, int OP>
+static hipError_t launch_1d(Args1d a, hipStream_t stream)
+{
+    constexpr int W = 64 * PX;
+    const long n = a.n;
+    const long nseg = (n + W - 1) / W;
+    long s_hi = (n - 2) / W - 1;                  // last segment with xs + W <= n-2
+    if (s_hi < 1) s_hi = 0;                       // no core segment
+    if (s_hi >= 1) {
+        a.remainder = 0;
+        a.seg_first = 1;
+        a.seg_count = s_hi;                       // segments 1..s_hi
+        dim3 grid((unsigned)((a.seg_count + kWaves1d - 1) / kWaves1d));
+        hipLaunchKernelGGL((stencil1d_kernel<T, PX, false, OP>), grid, dim3(64 * kWaves1d), 0, stream, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    a.remainder = 1;
+    a.seg_first = 0;
+    a.seg_jump_after = s_hi;
+    a.seg_count = 1 + (nseg - 1 - s_hi);          // segment 0 and segments s_hi+1 .. nseg-1
+    dim3 grid((unsigned)((a.seg_count + kWaves1d - 1) / kWaves1d));
+    hipLaunchKernelGGL((stencil1d_kernel<T, PX, true, OP>), grid, dim3(64 * kWaves1d), 0, stream, a);
+    return hipGetLastError();
+}
+
+static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+template <int OP>
+static hipError_t dispatch_1d(int is_f64, const Args1d &a, hipStream_t stream)
+{
+    const bool al = aligned16(a.a0) && aligned16(a.a1) && aligned16(a.a2) && aligned16(a.o0) && aligned16(a.o1);
+    if (is_f64) return al ? launch_1d<double, 2, OP>(a, stream) : launch_1d<double, 1, OP>(a, stream);
+    return al ? launch_1d<float, 4, OP>(a, stream) : launch_1d<float, 1, OP>(a, stream);
+}
+
+hipError_t launch_adjoint_wave1d(int is_f64, long n, const void *c, const void *r_bar, void *u_bar,
+                                 void *u_prev_bar, hipStream_t stream)
+{
+    Args1d a{};
+    a.a0 = c; a.a1 = r_bar; a.o0 = u_bar; a.o1 = u_prev_bar; a.n = n;
+    return u_prev_bar ? dispatch_1d<OP_ADJ_WAVE_UPREV>(is_f64, a, stream)
+                      : dispatch_1d<OP_ADJ_WAVE>(is_f64, a, stream);
+}
+hipError_t launch_primal_wave1d(int is_f64, long n, const void *u, const void *u_prev, const void *c,
+                                void *r, hipStream_t stream)
+{
+    Args1d a{};
+    a.a0 = u; a.a1 = u_prev; a.a2 = c; a.o0 = r; a.n = n;
+    return dispatch_1d<OP_PRI_WAVE>(is_f64, a, stream);
+}
+hipError_t launch_adjoint_burgers1d(int is_f64, long n, double C, double D, const void *u,
+                                    const void *r_bar, void *u_bar, hipStream_t stream)
+{
+    Args1d a{};
+    a.a0 = u; a.a1 = r_bar; a.o0 = u_bar; a.n = n; a.C = C; a.D = D;
+    return dispatch_1d<OP_ADJ_BURGERS>(is_f64, a, stream);
+}
+hipError_t launch_primal_burgers1d(int is_f64, long n, double C, double D, const void *u, void *r,
+                                   hipStream_t stream)
+{
+    Args1d a{};
+    a.a0 = u; a.o0 = r; a.n = n; a.C = C; a.D = D;
+    return dispatch_1d<OP_PRI_BURGERS>(is_f64, a, stream);
+}
+
+}  // namespace sadj

@@ -1,0 +1,285 @@
+// 2-D linear wave stencil, 5-point star (radius 1): primal and gather-form adjoint.
+//
+// Adjoint: with q = c*r_bar on I and 0 elsewhere,
+//     u_bar[j] += 2 r_bar[j] [j in I] + q[j-ex] + q[j+ex] + q[j-ey] + q[j+ey] - 4 q[j]
+// (paper Section 4.1 gather listing reduced to two dimensions; Sections 3.3.2-3.3.4).
+//
+// Mapping to CDNA4.  Each 64-lane wave owns a strip of 64*PX columns (PX elements
+// = 16 bytes per lane, x is unit stride) and marches down y.  An arriving row of q
+// contributes its x-neighbours and centre to the running sum of the same output row
+// and q itself to the sums of the rows above and below, so a lane keeps three
+// running sums per owned column; x-neighbours travel between lanes with wave
+// shuffles and the two cells beside the strip are loaded by lanes 0 and 63.  There
+// is no LDS and no barrier; waves are independent.  Waves whose reads all lie in I
+// run the unguarded instantiation (core); waves touching the first/last columns or
+// rows run the guarded one, where unused cells are replaced by zero with a select
+// (the if-guarded remainder variant of Section 3.3.4).
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace sadj {
+
+struct Wave2dArgs {
+    const void *c, *r_bar;
+    void *u_bar, *u_prev_bar;
+    const void *u, *u_prev;
+    void *r;
+    int nx, ny;
+    int ychunk;
+};
+
+constexpr int kWavesPerBlock2d = 4;
+
+template <class T, int PX, bool GUARD, bool UPREV>
+__device__ __forceinline__ void adj2d_strip(const Wave2dArgs &a, int xs, int ys, int ye, int lane)
+{
+    constexpr int W = 64 * PX;
+    using V = Vec<T, PX>;
+    const int nx = a.nx, ny = a.ny;
+    const T *__restrict__ cg = static_cast<const T *>(a.c);
+    const T *__restrict__ rg = static_cast<const T *>(a.r_bar);
+    T *__restrict__ ug = static_cast<T *>(a.u_bar);
+    T *__restrict__ pg = static_cast<T *>(a.u_prev_bar);
+
+    const int x = xs + lane * PX;
+    const bool active = GUARD ? (x < nx) : true;
+    const int xc = active ? x : xs;
+    bool xin[PX];
+#pragma unroll
+    for (int e = 0; e < PX; ++e) xin[e] = GUARD ? (x + e >= 1 && x + e <= nx - 2) : true;
+    const int hx = lane < 32 ? xs - 1 : xs + W;
+    const bool hin = GUARD ? (hx >= 1 && hx <= nx - 2) : true;
+    const int hxc = hin ? hx : xs;
+
+    T acc[PX][3];
+#pragma unroll
+    for (int e = 0; e < PX; ++e) acc[e][0] = acc[e][1] = acc[e][2] = T(0);
+    V ncv{}, nrv{}, nuv{}, npv{};
+    T nhc = T(0), nhr = T(0);
+
+    auto row_in_I = [&](int y) { return GUARD ? (y >= 1 && y <= ny - 2) : true; };
+    auto load_row = [&](int y) {
+        const T *cp = cg + (size_t)y * nx;
+        const T *rp = rg + (size_t)y * nx;
+        ncv = ld_vec<T, PX>(cp + xc);
+        nrv = ld_vec<T, PX>(rp + xc);
+        nhc = cp[hxc];
+        nhr = rp[hxc];
+        if (UPREV) {
+            if (y >= ys && y < ye) npv = ld_vec<T, PX>(pg + (size_t)y * nx + xc);
+        }
+    };
+    const int yi0 = ys - 1, yi1 = ye;
+    if (row_in_I(yi0)) load_row(yi0);
+    for (int yi = yi0; yi <= yi1; ++yi) {
+        const bool rin = row_in_I(yi);
+        const int yo = yi - 1;
+        T q[PX], rr[PX], qh = T(0);
+        if (rin) {
+#pragma unroll
+            for (int e = 0; e < PX; ++e) {
+                rr[e] = GUARD ? (xin[e] ? nrv.v[e] : T(0)) : nrv.v[e];
+                q[e] = GUARD ? (xin[e] ? ncv.v[e] * nrv.v[e] : T(0)) : ncv.v[e] * nrv.v[e];
+            }
+            qh = GUARD ? (hin ? nhc * nhr : T(0)) : nhc * nhr;
+            if (UPREV) {
+                if (yi >= ys && yi < ye && active) {
+                    V o;
+#pragma unroll
+                    for (int e = 0; e < PX; ++e) o.v[e] = npv.v[e] - rr[e];
+                    st_vec<T, PX>(pg + (size_t)yi * nx + x, o);
+                }
+            }
+        }
+        const V cu = nuv;
+        if (yi + 1 <= yi1) {
+            if (row_in_I(yi + 1)) load_row(yi + 1);
+            if (yo + 1 >= ys) nuv = ld_vec<T, PX>(ug + (size_t)(yo + 1) * nx + xc);
+        }
+        if (rin) {
+            T left, right;
+            wave_neighbours<T, PX>(q, qh, lane, left, right);
+#pragma unroll
+            for (int e = 0; e < PX; ++e) {
+                const T l = e == 0 ? left : q[e - 1];
+                const T r = e == PX - 1 ? right : q[e + 1];
+                acc[e][1] += (T(-4) * q[e] + (l + r)) + T(2) * rr[e];
+                acc[e][0] += q[e];
+                acc[e][2] += q[e];
+            }
+        }
+        if (yo >= ys && active) {
+            V o;
+#pragma unroll
+            for (int e = 0; e < PX; ++e) o.v[e] = cu.v[e] + acc[e][0];
+            st_vec<T, PX>(ug + (size_t)yo * nx + x, o);
+        }
+#pragma unroll
+        for (int e = 0; e < PX; ++e) {
+            acc[e][0] = acc[e][1];
+            acc[e][1] = acc[e][2];
+            acc[e][2] = T(0);
+        }
+    }
+}
+
+template <class T, int PX, bool UPREV>
+__global__ __launch_bounds__(64 * kWavesPerBlock2d) void adj_wave2d_kernel(Wave2dArgs a)
+{
+    constexpr int W = 64 * PX;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int xs = (blockIdx.x * kWavesPerBlock2d + wave) * W;
+    if (xs >= a.nx) return;                     // wave-uniform; the kernel has no barrier
+    const int ys = blockIdx.y * a.ychunk;
+    const int ye = min(ys + a.ychunk, a.ny);
+    const bool core = xs >= 2 && xs + W <= a.nx - 2 && ys >= 2 && ye <= a.ny - 2;
+    if (core) adj2d_strip<T, PX, false, UPREV>(a, xs, ys, ye, lane);
+    else      adj2d_strip<T, PX, true, UPREV>(a, xs, ys, ye, lane);
+}
+
+// ------------------------------------------------------------------------- primal
+// r = 2u - u_prev + c*(u[x-1]+u[x+1]+u[y-1]+u[y+1]-4u) on I (paper Section 4.1 in two
+// dimensions).  Same march applied to u; u of the completing row is kept in a
+// two-deep register queue.  Only cells of I are stored.
+template <class T, int PX>
+__global__ __launch_bounds__(64 * kWavesPerBlock2d) void primal_wave2d_kernel(Wave2dArgs a)
+{
+    constexpr int W = 64 * PX;
+    using V = Vec<T, PX>;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nx = a.nx, ny = a.ny;
+    const int xs = (blockIdx.x * kWavesPerBlock2d + wave) * W;
+    if (xs >= nx) return;
+    const int ys = 1 + blockIdx.y * a.ychunk;             // output rows cover [1, ny-1)
+    const int ye = min(ys + a.ychunk, ny - 1);
+    const T *__restrict__ ug = static_cast<const T *>(a.u);
+    const T *__restrict__ pg = static_cast<const T *>(a.u_prev);
+    const T *__restrict__ cg = static_cast<const T *>(a.c);
+    T *__restrict__ rg = static_cast<T *>(a.r);
+
+    const int x = xs + lane * PX;
+    const bool active = x < nx;
+    const int xc = active ? x : xs;
+    bool xin[PX], all_in = true;
+#pragma unroll
+    for (int e = 0; e < PX; ++e) { xin[e] = x + e >= 1 && x + e <= nx - 2; all_in = all_in && xin[e]; }
+    const int hx = lane < 32 ? xs - 1 : xs + W;
+    const int hxc = (hx >= 0 && hx < nx) ? hx : xs;
+
+    T acc[PX][3], uq[PX][2];
+#pragma unroll
+    for (int e = 0; e < PX; ++e) { acc[e][0] = acc[e][1] = acc[e][2] = T(0); uq[e][0] = uq[e][1] = T(0); }
+    V nuv = ld_vec<T, PX>(ug + (size_t)(ys - 1) * nx + xc);
+    T nh = ug[(size_t)(ys - 1) * nx + hxc];
+    V ncv{}, npv{};
+    for (int yi = ys - 1; yi <= ye; ++yi) {
+        const int yo = yi - 1;
+        T u0[PX];
+#pragma unroll
+        for (int e = 0; e < PX; ++e) u0[e] = nuv.v[e];
+        const T uh = nh;
+        const V cc = ncv, pp = npv;
+        if (yi + 1 <= ye) {
+            nuv = ld_vec<T, PX>(ug + (size_t)(yi + 1) * nx + xc);
+            nh = ug[(size_t)(yi + 1) * nx + hxc];
+            if (yo + 1 >= ys) {
+                ncv = ld_vec<T, PX>(cg + (size_t)(yo + 1) * nx + xc);
+                npv = ld_vec<T, PX>(pg + (size_t)(yo + 1) * nx + xc);
+            }
+        }
+        T left, right;
+        wave_neighbours<T, PX>(u0, uh, lane, left, right);
+#pragma unroll
+        for (int e = 0; e < PX; ++e) {
+            const T l = e == 0 ? left : u0[e - 1];
+            const T r = e == PX - 1 ? right : u0[e + 1];
+            acc[e][1] += T(-4) * u0[e] + (l + r);
+            acc[e][0] += u0[e];
+            acc[e][2] += u0[e];
+            uq[e][1] = u0[e];
+        }
+        if (yo >= ys && active) {
+            V o;
+#pragma unroll
+            for (int e = 0; e < PX; ++e) o.v[e] = T(2) * uq[e][0] - pp.v[e] + cc.v[e] * acc[e][0];
+            T *rp = rg + (size_t)yo * nx + x;
+            if (all_in) {
+                st_vec<T, PX>(rp, o);
+            } else {
+#pragma unroll
+                for (int e = 0; e < PX; ++e)
+                    if (xin[e]) rp[e] = o.v[e];
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < PX; ++e) {
+            acc[e][0] = acc[e][1];
+            acc[e][1] = acc[e][2];
+            acc[e][2] = T(0);
+            uq[e][0] = uq[e][1];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------ launchers
+static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+template <class T, int PX>
+static hipError_t launch_adj2d(const Wave2dArgs &a0, hipStream_t stream)
+{
+    Wave2dArgs a = a0;
+    a.ychunk = 64;
+    constexpr int W = 64 * PX;
+    const int nstrips = (a.nx + W - 1) / W;
+    dim3 grid((nstrips + kWavesPerBlock2d - 1) / kWavesPerBlock2d, (a.ny + a.ychunk - 1) / a.ychunk);
+    dim3 block(64 * kWavesPerBlock2d);
+    if (a.u_prev_bar) hipLaunchKernelGGL((adj_wave2d_kernel<T, PX, true>), grid, block, 0, stream, a);
+    else              hipLaunchKernelGGL((adj_wave2d_kernel<T, PX, false>), grid, block, 0, stream, a);
+    return hipGetLastError();
+}
+
+template <class T, int PX>
+static hipError_t launch_pri2d(const Wave2dArgs &a0, hipStream_t stream)
+{
+    Wave2dArgs a = a0;
+    a.ychunk = 64;
+    constexpr int W = 64 * PX;
+    const int nstrips = (a.nx + W - 1) / W;
+    const int rows = a.ny - 2;
+    dim3 grid((nstrips + kWavesPerBlock2d - 1) / kWavesPerBlock2d, (rows + a.ychunk - 1) / a.ychunk);
+    dim3 block(64 * kWavesPerBlock2d);
+    hipLaunchKernelGGL((primal_wave2d_kernel<T, PX>), grid, block, 0, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_adjoint_wave2d(int is_f64, int nx, int ny, const void *c, const void *r_bar,
+                                 void *u_bar, void *u_prev_bar, hipStream_t stream)
+{
+    Wave2dArgs a{};
+    a.c = c; a.r_bar = r_bar; a.u_bar = u_bar; a.u_prev_bar = u_prev_bar;
+    a.nx = nx; a.ny = ny;
+    const bool al = aligned16(c) && aligned16(r_bar) && aligned16(u_bar) && aligned16(u_prev_bar);
+    if (is_f64) {
+        if (al && nx % 2 == 0) return launch_adj2d<double, 2>(a, stream);
+        return launch_adj2d<double, 1>(a, stream);
+    }
+    if (al && nx % 4 == 0) return launch_adj2d<float, 4>(a, stream);
+    return launch_adj2d<float, 1>(a, stream);
+}
+
+hipError_t launch_primal_wave2d(int is_f64, int nx, int ny, const void *u, const void *u_prev,
+                                const void *c, void *r, hipStream_t stream)
+{
+    Wave2dArgs a{};
+    a.u = u; a.u_prev = u_prev; a.c = c; a.r = r;
+    a.nx = nx; a.ny = ny;
+    const bool al = aligned16(u) && aligned16(u_prev) && aligned16(c) && aligned16(r);
+    if (is_f64) {
+        if (al && nx % 2 == 0) return launch_pri2d<double, 2>(a, stream);
+        return launch_pri2d<double, 1>(a, stream);
+    }
+    if (al && nx % 4 == 0) return launch_pri2d<float, 4>(a, stream);
+    return launch_pri2d<float, 1>(a, stream);
+}
+
+}  // namespace sadj

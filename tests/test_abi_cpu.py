@@ -1,0 +1,103 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_1907_02818_amd as sadj
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "sadj.h")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(sadj.lib_path()),
+                                reason="libsadj.so not built (python -m paper_1907_02818_amd.build)")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sadj_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    names = _declared_functions()
+    for n in ("sadj_primal_wave1d", "sadj_adjoint_wave1d", "sadj_primal_wave2d", "sadj_adjoint_wave2d",
+              "sadj_primal_wave3d", "sadj_adjoint_wave3d", "sadj_primal_burgers1d",
+              "sadj_adjoint_burgers1d", "sadj_status_string", "sadj_version", "sadj_set_option",
+              "sadj_get_option"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol():
+    lib = sadj.load()
+    for name in _declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_binding_has_the_same_names():
+    for name in _declared_functions():
+        if name in ("sadj_status_string", "sadj_version", "sadj_set_option", "sadj_get_option"):
+            continue
+        assert callable(getattr(sadj, name))
+
+
+def test_status_strings_and_version():
+    lib = sadj.load()
+    assert lib.sadj_status_string(0) == b"ok"
+    seen = {lib.sadj_status_string(i) for i in range(6)}
+    assert len(seen) == 6 and all(seen)
+    assert lib.sadj_status_string(99)
+    assert re.match(r"^\d+\.\d+\.\d+$", sadj.version())
+
+
+def test_options_roundtrip_and_reject_unknown():
+    assert sadj.get_option("wave3d.fused") in (0, 1)
+    old = sadj.get_option("wave3d.zchunk")
+    sadj.set_option("wave3d.zchunk", 32)
+    assert sadj.get_option("wave3d.zchunk") == 32
+    sadj.set_option("wave3d.zchunk", old)
+    with pytest.raises(sadj.SadjError) as e:
+        sadj.set_option("no.such.option", 1)
+    assert e.value.status == 4
+    with pytest.raises(sadj.SadjError):
+        sadj.set_option("wave3d.fused", 7)
+
+
+P = ctypes.c_void_p
+A, B, C_, D_ = (P(0x10000000), P(0x20000000), P(0x30000000), P(0x40000000))  # never dereferenced
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    lib = sadj.load()
+    F64 = 1
+    # null pointers
+    assert lib.sadj_adjoint_wave3d(F64, 4, 32, 32, 32, None, B, C_, None, None) == 1
+    assert lib.sadj_adjoint_wave3d(F64, 4, 32, 32, 32, A, B, None, None, None) == 1
+    assert lib.sadj_primal_wave3d(F64, 4, 32, 32, 32, A, B, C_, None, None) == 1
+    assert lib.sadj_adjoint_burgers1d(F64, 100, 0.1, 0.05, A, None, C_, None) == 1
+    # sizes: every extent must be at least 2R+1
+    assert lib.sadj_adjoint_wave3d(F64, 4, 8, 32, 32, A, B, C_, None, None) == 2
+    assert lib.sadj_adjoint_wave3d(F64, 1, 32, 2, 32, A, B, C_, None, None) == 2
+    assert lib.sadj_adjoint_wave2d(F64, 2, 32, A, B, C_, None, None) == 2
+    assert lib.sadj_adjoint_wave1d(F64, 2, A, B, C_, None, None) == 2
+    assert lib.sadj_primal_burgers1d(F64, 2, 0.1, 0.05, A, B, None) == 2
+    assert lib.sadj_adjoint_wave2d(F64, 1 << 20, 1 << 20, A, B, C_, None, None) == 2
+    # aliasing: an output overlapping an input, or two outputs overlapping
+    assert lib.sadj_adjoint_wave3d(F64, 1, 16, 16, 16, A, B, A, None, None) == 3
+    assert lib.sadj_adjoint_wave3d(F64, 1, 16, 16, 16, A, B, P(0x20000000 + 8), None, None) == 3
+    assert lib.sadj_adjoint_wave3d(F64, 1, 16, 16, 16, A, B, C_, C_, None) == 3
+    assert lib.sadj_primal_wave1d(F64, 64, A, B, C_, B, None) == 3
+    assert lib.sadj_adjoint_burgers1d(F64, 64, 0.1, 0.05, A, B, A, None) == 3
+    # unsupported radius / dtype
+    assert lib.sadj_adjoint_wave3d(F64, 2, 32, 32, 32, A, B, C_, None, None) == 4
+    assert lib.sadj_adjoint_wave3d(7, 4, 32, 32, 32, A, B, C_, None, None) == 4
+    assert lib.sadj_primal_wave2d(-1, 32, 32, A, B, C_, D_, None) == 4
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    t = torch.zeros(16, dtype=torch.float64)
+    with pytest.raises(ValueError):
+        sadj.sadj_adjoint_wave1d(t, t.clone(), t.clone())

@@ -1,0 +1,191 @@
+"""GPU parity for the 1-D and 2-D stencils (wave 3-point, wave 5-point, Burgers):
+HIP path through the C ABI binding vs the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+import inputs
+import oracle
+from jacobians import interior_mask
+from parity import assert_close, to_gpu, to_host
+
+pytestmark = pytest.mark.gpu
+
+C, D = 0.1, 0.05
+
+
+@pytest.fixture(scope="module")
+def sadj():
+    import paper_1907_02818_amd as lib
+    lib.load()
+    return lib
+
+
+def _sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------------- 1-D wave
+N1D = [3, 4, 5, 7, 63, 64, 65, 127, 128, 129, 130, 131, 255, 256, 257, 258, 259, 260, 511, 1000,
+       4096, 4097, 100003]
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("n", N1D)
+def test_wave1d_adjoint_and_primal(sadj, n, dtype):
+    d = inputs.wave_inputs((n,), 0.01, 0.25, seed=n, dtype=dtype)
+    for with_prev in (False, True):
+        ub = to_gpu(d["u_bar"])
+        upb = to_gpu(d["u_prev_bar"]) if with_prev else None
+        sadj.sadj_adjoint_wave1d(to_gpu(d["c"]), to_gpu(d["r_bar"]), ub, upb)
+        _sync()
+        want, wantp, scale = oracle.wave_adjoint(d["c"], d["r_bar"], d["u_bar"], 1,
+                                                 u_prev_bar=d["u_prev_bar"] if with_prev else None,
+                                                 want_scale=True)
+        assert_close(to_host(ub), want, scale + np.abs(d["u_bar"].astype(np.float64)), dtype, "wave1d n=%d" % n)
+        if with_prev:
+            sp = np.abs(d["u_prev_bar"].astype(np.float64)) + np.abs(d["r_bar"].astype(np.float64))
+            assert_close(to_host(upb), wantp, sp, dtype, "wave1d u_prev_bar n=%d" % n)
+            assert to_host(upb)[0] == d["u_prev_bar"][0] and to_host(upb)[-1] == d["u_prev_bar"][-1]
+    r0 = inputs.uniform(1, "aux", (n,), -1, 1).astype(dtype)
+    r = to_gpu(r0)
+    sadj.sadj_primal_wave1d(to_gpu(d["u"]), to_gpu(d["u_prev"]), to_gpu(d["c"]), r)
+    _sync()
+    want = oracle.wave_primal(d["u"], d["u_prev"], d["c"], 1, r_init=r0)
+    got = to_host(r)
+    assert got[0] == r0[0] and got[-1] == r0[-1]
+    u = np.abs(d["u"].astype(np.float64))
+    sc = 2 * u + np.abs(d["u_prev"].astype(np.float64))
+    sc[1:-1] += np.abs(d["c"].astype(np.float64))[1:-1] * (u[:-2] + 2 * u[1:-1] + u[2:])
+    assert_close(got, want, sc, dtype, "wave1d primal n=%d" % n)
+
+
+def test_wave1d_unaligned_pointers_and_nan_outside_interior(sadj):
+    import torch
+    n = 1001
+    d = inputs.wave_inputs((n,), 0.01, 0.25, seed=2)
+    d["c"][0] = d["c"][-1] = np.nan
+    d["r_bar"][0] = d["r_bar"][-1] = np.nan
+    # views that start 8 bytes into an allocation: not 16-byte aligned
+    def off(a):
+        t = torch.empty(n + 1, dtype=torch.float64, device="cuda")
+        t[1:] = torch.from_numpy(a).cuda()
+        return t[1:]
+    ub = off(d["u_bar"])
+    sadj.sadj_adjoint_wave1d(off(d["c"]), off(d["r_bar"]), ub)
+    _sync()
+    want, _, scale = oracle.wave_adjoint(d["c"], d["r_bar"], d["u_bar"], 1, want_scale=True)
+    assert np.isfinite(to_host(ub)).all()
+    assert_close(to_host(ub), want, scale + np.abs(d["u_bar"]), np.float64, "unaligned 1-D")
+
+
+# ----------------------------------------------------------------------- Burgers
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("n", N1D + [1 << 20])
+def test_burgers_adjoint_and_primal(sadj, n, dtype):
+    d = inputs.burgers_inputs(n, seed=n, dtype=dtype)
+    u = d["u"].copy()
+    if n > 300:
+        u[[5, 100, 101, 200]] = 0.0             # exact zeros: the kink convention
+    ub = to_gpu(d["u_bar"])
+    sadj.sadj_adjoint_burgers1d(C, D, to_gpu(u), to_gpu(d["r_bar"]), ub)
+    _sync()
+    Cd, Dd = (float(np.float32(C)), float(np.float32(D))) if dtype == np.float32 else (C, D)
+    want, scale = oracle.burgers_adjoint(u, d["r_bar"], d["u_bar"], Cd, Dd, want_scale=True)
+    # the centre partial is itself a cancelling sum of O(1) terms: add |r_bar| to the scale
+    sc = scale + np.abs(d["u_bar"].astype(np.float64)) + np.abs(d["r_bar"].astype(np.float64))
+    assert_close(to_host(ub), want, sc, dtype, "burgers adjoint n=%d" % n)
+    r0 = inputs.uniform(1, "aux", (n,), -1, 1).astype(dtype)
+    r = to_gpu(r0)
+    sadj.sadj_primal_burgers1d(C, D, to_gpu(u), r)
+    _sync()
+    want = oracle.burgers_primal(u, Cd, Dd, r_init=r0)
+    got = to_host(r)
+    assert got[0] == r0[0] and got[-1] == r0[-1]
+    assert_close(got, want, np.abs(want) + 1.0, dtype, "burgers primal n=%d" % n)
+
+
+def test_burgers_nan_in_r_bar_outside_interior_and_reproducible(sadj):
+    n = 5000
+    d = inputs.burgers_inputs(n, seed=3)
+    rb = d["r_bar"].copy()
+    rb[0] = rb[-1] = np.nan
+    outs = []
+    for _ in range(2):
+        ub = to_gpu(d["u_bar"])
+        sadj.sadj_adjoint_burgers1d(C, D, to_gpu(d["u"]), to_gpu(rb), ub)
+        _sync()
+        outs.append(to_host(ub))
+    assert np.isfinite(outs[0]).all()
+    assert np.array_equal(outs[0], outs[1])
+
+
+def test_burgers_full_size(sadj):
+    n = 1 << 24
+    d = inputs.config_inputs("burgers1d")
+    ub = to_gpu(d["u_bar"])
+    sadj.sadj_adjoint_burgers1d(C, D, to_gpu(d["u"]), to_gpu(d["r_bar"]), ub)
+    _sync()
+    want, scale = oracle.burgers_adjoint(d["u"], d["r_bar"], d["u_bar"], C, D, want_scale=True)
+    assert_close(to_host(ub), want, scale + np.abs(d["u_bar"]) + np.abs(d["r_bar"]), np.float64,
+                 "burgers n=2^24")
+
+
+# ---------------------------------------------------------------------- 2-D wave
+SHAPES2D = [(3, 3), (3, 200), (200, 3), (5, 7), (66, 130), (67, 131), (130, 256), (129, 258),
+            (200, 513), (70, 1030), (300, 300)]
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("shape", SHAPES2D)
+def test_wave2d_adjoint_and_primal(sadj, shape, dtype):
+    d = inputs.wave_inputs(shape, 0.01, 0.2, seed=sum(shape), dtype=dtype)
+    m = interior_mask(shape, 1)
+    for with_prev in (False, True):
+        ub = to_gpu(d["u_bar"])
+        upb = to_gpu(d["u_prev_bar"]) if with_prev else None
+        sadj.sadj_adjoint_wave2d(to_gpu(d["c"]), to_gpu(d["r_bar"]), ub, upb)
+        _sync()
+        want, wantp, scale = oracle.wave_adjoint(d["c"], d["r_bar"], d["u_bar"], 1,
+                                                 u_prev_bar=d["u_prev_bar"] if with_prev else None,
+                                                 want_scale=True)
+        assert_close(to_host(ub), want, scale + np.abs(d["u_bar"].astype(np.float64)), dtype,
+                     "wave2d %s" % (shape,))
+        if with_prev:
+            sp = np.abs(d["u_prev_bar"].astype(np.float64)) + np.abs(d["r_bar"].astype(np.float64))
+            assert_close(to_host(upb), wantp, sp, dtype, "wave2d u_prev_bar %s" % (shape,))
+            assert np.array_equal(to_host(upb)[~m], d["u_prev_bar"][~m])
+    r0 = inputs.uniform(1, "aux", shape, -1, 1).astype(dtype)
+    r = to_gpu(r0)
+    sadj.sadj_primal_wave2d(to_gpu(d["u"]), to_gpu(d["u_prev"]), to_gpu(d["c"]), r)
+    _sync()
+    want = oracle.wave_primal(d["u"], d["u_prev"], d["c"], 1, r_init=r0)
+    got = to_host(r)
+    assert np.array_equal(got[~m], r0[~m])
+    assert_close(got[m], want[m], np.abs(want[m]) + 3.0, dtype, "wave2d primal %s" % (shape,))
+
+
+def test_wave2d_nan_outside_interior_and_reproducible(sadj):
+    shape = (150, 390)
+    d = inputs.wave_inputs(shape, 0.01, 0.2, seed=4)
+    m = interior_mask(shape, 1)
+    c = np.where(m, d["c"], np.nan)
+    rb = np.where(m, d["r_bar"], np.nan)
+    outs = []
+    for _ in range(2):
+        ub = to_gpu(d["u_bar"])
+        sadj.sadj_adjoint_wave2d(to_gpu(c), to_gpu(rb), ub)
+        _sync()
+        outs.append(to_host(ub))
+    assert np.isfinite(outs[0]).all() and np.array_equal(outs[0], outs[1])
+    want, _, scale = oracle.wave_adjoint(d["c"], d["r_bar"], d["u_bar"], 1, want_scale=True)
+    assert_close(outs[0], want, scale + np.abs(d["u_bar"]), np.float64, "wave2d NaN-poisoned")
+
+
+def test_wave2d_full_size(sadj):
+    d = inputs.config_inputs("wave2d")
+    ub = to_gpu(d["u_bar"])
+    sadj.sadj_adjoint_wave2d(to_gpu(d["c"]), to_gpu(d["r_bar"]), ub)
+    _sync()
+    want, _, scale = oracle.wave_adjoint(d["c"], d["r_bar"], d["u_bar"], 1, want_scale=True)
+    assert_close(to_host(ub), want, scale + np.abs(d["u_bar"]), np.float64, "wave2d 8192^2")
