@@ -1,0 +1,210 @@
+#!/usr/bin/env python3
+"""Benchmark of the adjoint-stencil hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--all] [--no-cpu-baseline]
+
+A step is one call of sadj_adjoint_wave3d (core region + remainder regions) on the
+headline workload: 3-D variable-coefficient wave stencil, 25-point star (radius 4),
+512^3 grid, fp64, u_bar accumulated, inputs already resident in HBM.  Prints ONE
+JSON line.  `value` = grid points of u_bar updated per second (Gpoints/s).
+
+roofline: HBM-bound.  achieved = algorithmic bytes per call / mean kernel time
+measured with HIP events on the launch stream; algorithmic bytes = read c and r_bar
+once on the primal interior, read and write u_bar once on the whole grid
+(16 N + 16 |I| bytes in fp64).  peak = 8000 GB/s (MI355X HBM3E).
+
+cpu_baseline: the CPU oracle (scatter adjoint, one core, gcc -O2) timed on the
+first 192 z-planes of the same arrays.
+
+With --all the same JSON line carries an "others" object with the remaining
+workloads (fp32, radius 1, primal, 2-D, Burgers, 1-D), each timed the same way.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+METRIC = "adjoint stencil Gpoints/s + % of peak HBM GB/s, 3D wave r=4 512^3 fp64"
+
+
+def interior_points(shape, radius):
+    n = 1
+    for s in shape:
+        n *= s - 2 * radius
+    return n
+
+
+def wave_adjoint_bytes(shape, radius, esize, with_prev=False):
+    N = int(np.prod(shape))
+    I = interior_points(shape, radius)
+    b = 2 * esize * N + 2 * esize * I
+    if with_prev:
+        b += 2 * esize * I
+    return b
+
+
+def time_calls(fn, steps, warmup):
+    """Returns (wall ms per step, mean HIP-event ms per call).  Events are recorded
+    on torch's current stream, which is the stream the binding launches on."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        starts[i].record()
+        fn()
+        stops[i].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ev = [s.elapsed_time(e) for s, e in zip(starts, stops)]
+    return (t1 - t0) * 1e3 / steps, float(np.mean(ev)), float(np.min(ev))
+
+
+def read_traffic(name):
+    """HBM bytes per launch derived from rocprofv3 --pmc runs, kept as text under
+    profiles/ (line 'traffic_bytes_per_launch: N'); None when not recorded."""
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        with open(path) as fh:
+            for ln in fh:
+                if ln.startswith("traffic_bytes_per_launch:"):
+                    return float(ln.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--all", action="store_true", help="also time the other workloads")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--size", type=int, default=512, help="grid edge of the headline workload")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the hot path is a single-GPU kernel "
+              "library; see DESIGN.md for how it would shard); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import inputs
+    import paper_1907_02818_amd as sadj
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    sadj.load()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    n = args.size
+    shape = (n, n, n)
+    R = 4
+    d = inputs.config_inputs("wave3d_r4", shape=shape, fields=("c", "r_bar", "u_bar"))
+    c, rb, ub = (torch.from_numpy(d[k]).to(dev) for k in ("c", "r_bar", "u_bar"))
+    torch.cuda.synchronize()
+
+    wall_ms, ev_ms, ev_min = time_calls(lambda: sadj.sadj_adjoint_wave3d(R, c, rb, ub), args.steps, args.warmup)
+    N = n ** 3
+    alg_bytes = wave_adjoint_bytes(shape, R, 8)
+    achieved = alg_bytes / (ev_ms * 1e-3) / 1e9
+    out = {
+        "metric": METRIC,
+        "value": N / (wall_ms * 1e-3) / 1e9,
+        "unit": "Gpoints/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall_ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": "wave3d adjoint, 25-point star r=4, %d^3, fp64, u_bar only" % n,
+                   "variant": sadj.get_option("wave3d.variant"),
+                   "zchunk": sadj.get_option("wave3d.zchunk")},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": read_traffic("adjoint_wave3d_r4_f64_512_pmc.txt") if n == 512 else None,
+                     "kernel_ms_mean": ev_ms, "kernel_ms_min": ev_min, "algorithmic_bytes": alg_bytes},
+    }
+
+    others = {}
+
+    def add(name, fn, points, nbytes, dtype):
+        w, e, emin = time_calls(fn, max(5, args.steps // 2), 3)
+        others[name] = {"Gpoints/s": points / (w * 1e-3) / 1e9, "ms": w, "kernel_ms_mean": e,
+                        "GB/s": nbytes / (e * 1e-3) / 1e9, "frac": nbytes / (e * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                        "dtype": dtype}
+
+    # fp32 run of the same workload (same draws rounded to float)
+    c32, rb32, ub32 = c.float(), rb.float(), ub.float()
+    add("wave3d_r4_f32_adjoint", lambda: sadj.sadj_adjoint_wave3d(R, c32, rb32, ub32), N,
+        wave_adjoint_bytes(shape, R, 4), "f32")
+    del c32, rb32, ub32
+
+    if args.all:
+        upb = torch.from_numpy(inputs.config_inputs("wave3d_r4", shape=shape, fields=("u_prev_bar",))["u_prev_bar"]).to(dev)
+        add("wave3d_r4_f64_adjoint_with_u_prev_bar", lambda: sadj.sadj_adjoint_wave3d(R, c, rb, ub, upb), N,
+            wave_adjoint_bytes(shape, R, 8, True), "f64")
+        # primal: reads u, u_prev, c, writes r (u_bar/u_prev_bar buffers reused as u/u_prev)
+        r = torch.empty_like(ub)
+        I = interior_points(shape, R)
+        add("wave3d_r4_f64_primal", lambda: sadj.sadj_primal_wave3d(R, ub, upb, c, r), N, 8 * N + 24 * I, "f64")
+        add("wave3d_r1_f64_adjoint", lambda: sadj.sadj_adjoint_wave3d(1, c, rb, ub), N,
+            wave_adjoint_bytes(shape, 1, 8), "f64")
+        add("wave3d_r1_f64_primal", lambda: sadj.sadj_primal_wave3d(1, ub, upb, c, r), N,
+            8 * N + 24 * interior_points(shape, 1), "f64")
+        del upb, r
+        # 2-D 8192^2
+        s2 = (8192, 8192)
+        c2, rb2, ub2 = (t.reshape(-1)[: s2[0] * s2[1]].reshape(s2) for t in (c, rb, ub))
+        add("wave2d_f64_adjoint", lambda: sadj.sadj_adjoint_wave2d(c2, rb2, ub2), s2[0] * s2[1],
+            wave_adjoint_bytes(s2, 1, 8), "f64")
+        # Burgers 2^24, rotating three buffer sets so the arrays do not stay in the 256 MB last-level cache
+        nb = 1 << 24
+        sets = [tuple(t.reshape(-1)[k * nb:(k + 1) * nb] for t in (rb, c, ub)) for k in range(3)]
+        state = {"i": 0}
+
+        def burg():
+            u_, r_, b_ = sets[state["i"] % 3]
+            state["i"] += 1
+            sadj.sadj_adjoint_burgers1d(0.1, 0.05, u_, r_, b_)
+        add("burgers1d_f64_adjoint", burg, nb, 32 * nb, "f64")
+        n1 = 4096
+        c1, rb1, ub1 = (t.reshape(-1)[:n1] for t in (c, rb, ub))
+        add("wave1d_f64_adjoint_n4096_latency", lambda: sadj.sadj_adjoint_wave1d(c1, rb1, ub1), n1, 32 * n1, "f64")
+    out["others"] = others
+
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        nzs = min(192, n)
+        sl = (slice(0, nzs),)
+        t0 = time.perf_counter()
+        oracle.wave_adjoint(d["c"][sl], d["r_bar"][sl], d["u_bar"][sl], R)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": nzs * n * n / dt / 1e9, "unit": "Gpoints/s", "cores": 1, "kind": "oracle",
+                               "sample": "first %d z-planes of the same %d^3 arrays (%d x %d x %d grid), one run, "
+                                         "%.1f s" % (nzs, n, n, n, nzs, dt),
+                               "host_cpus": os.cpu_count()}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -25,7 +25,7 @@
  *  - Primal iteration space: I = prod_d [R, n_d-1-R] with R the stencil radius
  *    (the paper's loop bounds [1,n-2] for R=1).  Every extent must be >= 2R+1,
  *    otherwise SADJ_ERR_SIZE.  Grids whose core region is empty (n_d < 4R+1) are valid.
- *    Limits: nx*ny <= 2^30 elements and every extent <= 2^30.
+ *    Limits: nx*ny <= 2^28 elements and every extent <= 2^30.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *    are asynchronous: they enqueue kernels and return.
  *  - Primal calls ASSIGN r on I and leave r outside I untouched.
@@ -65,6 +65,10 @@ const char *sadj_status_string(sadj_status status);
 
 /* Library version as a static string, e.g. "0.1.0". */
 const char *sadj_version(void);
+
+/* HIP's description of the error behind the calling thread's most recent
+ * SADJ_ERR_DEVICE ("no error" if there was none).  Static string, never NULL. */
+const char *sadj_last_device_error(void);
 
 /* ---- linear variable-coefficient wave step ---------------------------------------
  * Primal (paper Section 4.1, the generating script):
@@ -118,9 +122,6 @@ sadj_status sadj_adjoint_burgers1d(sadj_dtype dtype, long n, double C, double D,
 /* ---- launch options -------------------------------------------------------------------
  * Process-wide integer options that select among equivalent launch strategies; they
  * never change what is computed, only how the regions are mapped to kernels.
- *   "wave3d.fused"   1 (default): core and remainder regions in one dispatch;
- *                    0: one dispatch for the core region and one per remainder slab
- *                    (Section 3.3.4: the regions are disjoint, either is valid).
  *   "wave3d.zchunk"  planes of output per workgroup along z (default 0 = automatic).
  *   "wave3d.variant" tile-shape variant index (default 0 = automatic).
  * Unknown names or out-of-range values give SADJ_ERR_UNSUPPORTED and change nothing.

@@ -46,20 +46,37 @@ def _key(seed: int, stream: int) -> np.uint64:
     return k
 
 
+def _unit_chunk(out, key, start, lo, hi):
+    with np.errstate(over="ignore"):
+        k = np.arange(start + lo, start + hi, dtype=np.uint64)
+        k *= _GOLDEN
+        k += key
+        k ^= k >> np.uint64(30)
+        k *= _M1
+        k ^= k >> np.uint64(27)
+        k *= _M2
+        k ^= k >> np.uint64(31)
+        k >>= np.uint64(11)
+        np.multiply(k, 2.0 ** -53, out=out[lo:hi])
+
+
 def unit(seed: int, stream: int, count: int, start: int = 0) -> np.ndarray:
-    """`count` doubles in [0,1) for counters start..start+count-1 of (seed, stream)."""
+    """`count` doubles in [0,1) for counters start..start+count-1 of (seed, stream).
+    Large requests are filled chunk by chunk on a few threads; the values do not
+    depend on the chunking."""
     out = np.empty(count, dtype=np.float64)
     key = _key(seed, stream)
-    chunk = 1 << 22
-    with np.errstate(over="ignore"):
-        for lo in range(0, count, chunk):
-            hi = min(count, lo + chunk)
-            k = np.arange(start + lo, start + hi, dtype=np.uint64)
-            k *= _GOLDEN
-            k += key
-            z = _mix(k)
-            z >>= np.uint64(11)
-            out[lo:hi] = z.astype(np.float64) * (2.0 ** -53)
+    chunk = 1 << 20
+    spans = [(lo, min(count, lo + chunk)) for lo in range(0, count, chunk)]
+    if len(spans) <= 4:
+        for lo, hi in spans:
+            _unit_chunk(out, key, start, lo, hi)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        import os
+        workers = max(1, min(8, (os.cpu_count() or 1)))
+        with ThreadPoolExecutor(workers) as ex:
+            list(ex.map(lambda s: _unit_chunk(out, key, start, s[0], s[1]), spans))
     return out
 
 
@@ -102,16 +119,24 @@ def _round_dtype(arrs: dict, dtype) -> dict:
     return {k: v.astype(dtype) for k, v in arrs.items()}
 
 
+WAVE_FIELDS = ("u", "u_prev", "r_bar", "u_bar", "u_prev_bar", "c")
+
+
 def wave_inputs(shape, c_lo: float, c_hi: float, seed: int = 0, dtype=np.float64,
-                c_mode: str = "iid", nlayers: int = 16, blend: int = 4) -> dict:
+                c_mode: str = "iid", nlayers: int = 16, blend: int = 4,
+                fields=WAVE_FIELDS) -> dict:
     """Fields of a linear variable-coefficient wave workload on a grid `shape`
     (slowest axis first, x last).  u, u_prev, r_bar, u_bar, u_prev_bar ~ U(-1,1) iid.
     c_mode "iid": c ~ U(c_lo,c_hi) iid.  c_mode "layered": c depends only on the
-    slowest axis through `layered_profile` (layered in z for 3-D, in y for 2-D)."""
+    slowest axis through `layered_profile` (layered in z for 3-D, in y for 2-D).
+    `fields` selects which arrays are produced (each array's values do not depend on
+    which others are requested)."""
     shape = tuple(int(s) for s in shape)
     out = {name: uniform(seed, name, shape, -1.0, 1.0)
-           for name in ("u", "u_prev", "r_bar", "u_bar", "u_prev_bar")}
-    if c_mode == "iid":
+           for name in ("u", "u_prev", "r_bar", "u_bar", "u_prev_bar") if name in fields}
+    if "c" not in fields:
+        pass
+    elif c_mode == "iid":
         out["c"] = uniform(seed, "c", shape, c_lo, c_hi)
     elif c_mode == "layered":
         prof = layered_profile(seed, shape[0], nlayers, blend, c_lo, c_hi)
@@ -148,7 +173,7 @@ CONFIGS = {
 
 
 def config_inputs(name: str, shape=None, seed: int = 0, dtype=np.float64,
-                  c_mode: str | None = None) -> dict:
+                  c_mode: str | None = None, fields=WAVE_FIELDS) -> dict:
     """Inputs of benchmark workload `name`, optionally on a smaller `shape`."""
     cfg = CONFIGS[name]
     shape = tuple(shape) if shape is not None else cfg["shape"]
@@ -156,4 +181,4 @@ def config_inputs(name: str, shape=None, seed: int = 0, dtype=np.float64,
         return burgers_inputs(shape[0], seed=seed, dtype=dtype)
     return wave_inputs(shape, cfg["c"][0], cfg["c"][1], seed=seed, dtype=dtype,
                        c_mode=c_mode or cfg["c_mode"],
-                       nlayers=cfg.get("nlayers", 16), blend=cfg.get("blend", 4))
+                       nlayers=cfg.get("nlayers", 16), blend=cfg.get("blend", 4), fields=fields)

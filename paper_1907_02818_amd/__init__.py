@@ -41,6 +41,10 @@ def load() -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
+    # torch ships its own HIP runtime under the same soname as the system one; it
+    # must be in the process first so that libsadj binds to the runtime that owns
+    # torch's streams and allocations (two runtimes in one process cannot share them).
+    import torch  # noqa: F401
     if not os.path.exists(_LIB_PATH):
         raise ImportError("libsadj.so is not built: run `python -m paper_1907_02818_amd.build` "
                           "(there is no fallback path)")
@@ -50,6 +54,8 @@ def load() -> ctypes.CDLL:
     lib.sadj_status_string.argtypes = [I]
     lib.sadj_version.restype = ctypes.c_char_p
     lib.sadj_version.argtypes = []
+    lib.sadj_last_device_error.restype = ctypes.c_char_p
+    lib.sadj_last_device_error.argtypes = []
     lib.sadj_set_option.argtypes = [ctypes.c_char_p, L]
     lib.sadj_get_option.argtypes = [ctypes.c_char_p, ctypes.POINTER(L)]
     lib.sadj_primal_wave1d.argtypes = [I, L, P, P, P, P, P]
@@ -70,7 +76,10 @@ def load() -> ctypes.CDLL:
 
 def _check(status: int) -> None:
     if status != 0:
-        raise SadjError(status, load().sadj_status_string(status).decode())
+        msg = load().sadj_status_string(status).decode()
+        if status == 5:
+            msg += " (" + load().sadj_last_device_error().decode() + ")"
+        raise SadjError(status, msg)
 
 
 def version() -> str:

@@ -9,12 +9,11 @@
 
 namespace {
 
-std::atomic<long> g_fused{1}, g_zchunk{0}, g_variant{0};
+std::atomic<long> g_zchunk{0}, g_variant{0};
 
 sadj::LaunchOptions current_options()
 {
     sadj::LaunchOptions o;
-    o.fused = g_fused.load();
     o.zchunk = g_zchunk.load();
     o.variant = g_variant.load();
     return o;
@@ -57,7 +56,18 @@ sadj_status check_extents(int radius, long nx, long ny, long nz, int ndim)
     return SADJ_OK;
 }
 
-sadj_status from_hip(hipError_t e) { return e == hipSuccess ? SADJ_OK : SADJ_ERR_DEVICE; }
+thread_local hipError_t g_last_hip_error = hipSuccess;
+
+sadj_status from_hip(hipError_t e)
+{
+    if (e == hipSuccess) return SADJ_OK;
+    g_last_hip_error = e;
+    return SADJ_ERR_DEVICE;
+}
+
+// An earlier, unrelated HIP call of this thread may have left a sticky error code
+// behind; drop it so that the check after our launch reports our launch only.
+void clear_stale_hip_error() { (void)hipGetLastError(); }
 
 }  // namespace
 
@@ -78,14 +88,11 @@ const char *sadj_status_string(sadj_status s)
 
 const char *sadj_version(void) { return "0.1.0"; }
 
+const char *sadj_last_device_error(void) { return hipGetErrorString(g_last_hip_error); }
+
 sadj_status sadj_set_option(const char *name, long value)
 {
     if (!name) return SADJ_ERR_NULL;
-    if (!std::strcmp(name, "wave3d.fused")) {
-        if (value != 0 && value != 1) return SADJ_ERR_UNSUPPORTED;
-        g_fused = value;
-        return SADJ_OK;
-    }
     if (!std::strcmp(name, "wave3d.zchunk")) {
         if (value < 0 || value > kMaxExtent) return SADJ_ERR_UNSUPPORTED;
         g_zchunk = value;
@@ -96,13 +103,13 @@ sadj_status sadj_set_option(const char *name, long value)
         g_variant = value;
         return SADJ_OK;
     }
+
     return SADJ_ERR_UNSUPPORTED;
 }
 
 sadj_status sadj_get_option(const char *name, long *value)
 {
     if (!name || !value) return SADJ_ERR_NULL;
-    if (!std::strcmp(name, "wave3d.fused")) { *value = g_fused; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.zchunk")) { *value = g_zchunk; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.variant")) { *value = g_variant; return SADJ_OK; }
     return SADJ_ERR_UNSUPPORTED;
@@ -122,6 +129,7 @@ static sadj_status primal_wave(int ndim, sadj_dtype dtype, int radius, long nx, 
     if (any_alias(in, out)) return SADJ_ERR_ALIAS;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int f64 = dtype == SADJ_F64;
+    clear_stale_hip_error();
     switch (ndim) {
     case 1: return from_hip(sadj::launch_primal_wave1d(f64, nx, u, u_prev, c, r, st));
     case 2: return from_hip(sadj::launch_primal_wave2d(f64, (int)nx, (int)ny, u, u_prev, c, r, st));
@@ -144,6 +152,7 @@ static sadj_status adjoint_wave(int ndim, sadj_dtype dtype, int radius, long nx,
     if (any_alias(in, out)) return SADJ_ERR_ALIAS;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int f64 = dtype == SADJ_F64;
+    clear_stale_hip_error();
     switch (ndim) {
     case 1: return from_hip(sadj::launch_adjoint_wave1d(f64, nx, c, r_bar, u_bar, u_prev_bar, st));
     case 2: return from_hip(sadj::launch_adjoint_wave2d(f64, (int)nx, (int)ny, c, r_bar, u_bar, u_prev_bar, st));
@@ -196,6 +205,7 @@ sadj_status sadj_primal_burgers1d(sadj_dtype dtype, long n, double C, double D, 
     const Span in[1] = {{u, bytes}};
     const Span out[1] = {{r, bytes}};
     if (any_alias(in, out)) return SADJ_ERR_ALIAS;
+    clear_stale_hip_error();
     return from_hip(sadj::launch_primal_burgers1d(dtype == SADJ_F64, n, C, D, u, r, static_cast<hipStream_t>(stream)));
 }
 
@@ -209,6 +219,7 @@ sadj_status sadj_adjoint_burgers1d(sadj_dtype dtype, long n, double C, double D,
     const Span in[2] = {{u, bytes}, {r_bar, bytes}};
     const Span out[1] = {{u_bar, bytes}};
     if (any_alias(in, out)) return SADJ_ERR_ALIAS;
+    clear_stale_hip_error();
     return from_hip(sadj::launch_adjoint_burgers1d(dtype == SADJ_F64, n, C, D, u, r_bar, u_bar,
                                                    static_cast<hipStream_t>(stream)));
 }

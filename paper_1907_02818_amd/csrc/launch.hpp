@@ -5,7 +5,6 @@
 namespace sadj {
 
 struct LaunchOptions {
-    long fused = 1;      // wave3d: 1 = all regions in one dispatch
     long zchunk = 0;     // wave3d: output planes per workgroup (0 = automatic)
     long variant = 0;    // wave3d: tile-shape variant
 };

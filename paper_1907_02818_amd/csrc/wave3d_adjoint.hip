@@ -1,0 +1,350 @@
+// 3-D linear wave stencil of radius R: gather-form adjoint kernel.
+//
+// What is computed (paper Section 4.1, gather listing, generalised to radius R;
+// Sections 3.3.2-3.3.4 for index shifting, core and remainder).  With
+//     q[i] = c[i]*r_bar[i] for i in I,   q[i] = 0 elsewhere,
+//     u_bar[j] += 2 r_bar[j] [j in I] + sum_o w_o q[j-o]
+// i.e. the same star applied to q, because the weights are symmetric; the product
+// c*r_bar is formed once per staged element instead of once per term.  Optionally
+// u_prev_bar[j] -= r_bar[j] for j in I.
+//
+// Mapping to CDNA4.  The x-y plane is cut into tiles of TX x TY outputs; a workgroup
+// owns one tile and marches along z.  Each arriving plane of q is staged in LDS
+// (tile + halo of width R, no corners: a star never reads them) and contributes
+//   - its in-plane star to the running sum of the same output plane,
+//   - w_k * q(x,y) to the running sums of the output planes z-k and z+k,
+// so a thread keeps 2R+1 running sums per owned point in registers and LDS holds
+// only the plane that has just arrived (two buffers, one barrier per plane).  An
+// output plane is complete R steps after its own plane arrived; u_bar is then
+// read-modify-written once.  x is the unit-stride direction of memory and lanes.
+//
+// Memory pipeline.  Global loads run D planes ahead of the arithmetic: the values of
+// plane z+D (c and r_bar on tile and halo, u_bar of plane z+D-R) are requested as
+// soon as the registers of plane z have been consumed, so D planes are in flight
+// per workgroup.  The z loop is unrolled D times; the stage index is a compile-time
+// constant, hence no register copies.
+//
+// HBM traffic.  The chip is bound by traffic that misses the 4 MB L2 of an XCD, so
+// halo cells must be found in L2.  Workgroup ids are mapped such that each XCD owns
+// a compact patch of neighbouring tiles, and the grid is sized to one resident wave
+// of workgroups; all of them start together, do identical work per plane and hence
+// move through z in near lockstep: a halo cell is fetched from memory by whichever
+// tile asks first and is an L2 hit for its neighbour.  u_bar is streamed with
+// non-temporal loads and stores so that it does not displace c and r_bar from L2.
+//
+// Regions (Section 3.3.4).  Tiles whose reads in x and y all lie in I run the
+// unguarded instantiation (core): every staged element is loaded and used
+// unconditionally.  Tiles that touch the first/last 2R columns or rows run the
+// guarded instantiation (remainder): an element is used iff it lies in I, otherwise
+// it is replaced by zero with a select -- never by a multiplication, so NaN outside
+// I cannot leak.  Along z the same rule is applied per plane with a wave-uniform
+// (scalar) test in both instantiations: planes outside I are skipped.  The regions
+// are disjoint and need no ordering, so they share one dispatch.
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace sadj {
+
+struct AdjWave3dArgs {
+    const void *c, *r_bar;
+    void *u_bar, *u_prev_bar;
+    int nx, ny, nz;
+    int ntx, nty, ntz;      // tiles along x and y, chunks along z
+    int zchunk;             // output planes per chunk
+    int total_blocks;
+};
+
+template <class T, int R, int BX, int BY, int PY>
+struct AdjTile {
+    static constexpr int TX = BX, TY = BY * PY, NT = BX * BY;
+    static constexpr int LX = TX + 2 * R, LY = TY + 2 * R;
+    static constexpr int NH = 2 * R * TX + 2 * R * TY;     // halo cells without corners
+    static constexpr int HS = (NH + NT - 1) / NT;          // halo slots per thread
+    static constexpr int LDS_ELEMS = 2 * LY * LX;
+};
+
+template <class T, bool NT> __device__ __forceinline__ T ld_stream(const T *base, uint32_t byte_off)
+{
+    const T *p = reinterpret_cast<const T *>(reinterpret_cast<const char *>(base) + byte_off);
+    return NT ? __builtin_nontemporal_load(p) : *p;
+}
+template <class T, bool NT> __device__ __forceinline__ void st_stream(T *base, uint32_t byte_off, T v)
+{
+    T *p = reinterpret_cast<T *>(reinterpret_cast<char *>(base) + byte_off);
+    if (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+template <class T, int R, int BX, int BY, int PY, int D, bool NTU, bool GUARD, bool UPREV>
+__device__ __forceinline__ void adj3d_march(const AdjWave3dArgs &a, int tix, int tiy, int tiz,
+                                            T *__restrict__ sq)
+{
+    using G = AdjTile<T, R, BX, BY, PY>;
+    constexpr int TX = G::TX, TY = G::TY, NT = G::NT, LX = G::LX, LY = G::LY, NH = G::NH, HS = G::HS;
+    constexpr int NACC = 2 * R + 1;
+    const int tid = threadIdx.x;
+    const int tx = tid % BX, ty = tid / BX;
+    const int nx = a.nx, ny = a.ny, nz = a.nz;
+    const size_t plane = (size_t)nx * ny;
+    const int x0 = tix * TX, y0 = tiy * TY;
+    const int zs = tiz * a.zchunk;
+    const int ze = min(zs + a.zchunk, nz);
+
+    const T *__restrict__ cg = static_cast<const T *>(a.c);
+    const T *__restrict__ rg = static_cast<const T *>(a.r_bar);
+    T *__restrict__ ug = static_cast<T *>(a.u_bar);
+    T *__restrict__ upg = static_cast<T *>(a.u_prev_bar);
+
+    // A cell that is always inside the grid: unused slots load it and discard it.
+    const uint32_t dummy = (uint32_t)((size_t)y0 * nx + x0) * sizeof(T);
+
+    // ---- owned points: x = x0+tx, y = y0 + ty*PY + p
+    uint32_t ooff[PY];
+    bool ouse[PY], ostore[PY];
+    const int x = x0 + tx;
+#pragma unroll
+    for (int p = 0; p < PY; ++p) {
+        const int y = y0 + ty * PY + p;
+        if (GUARD) {
+            ouse[p] = x >= R && x < nx - R && y >= R && y < ny - R;
+            ostore[p] = x < nx && y < ny;
+        } else {
+            ouse[p] = true;
+            ostore[p] = true;
+        }
+        ooff[p] = ostore[p] ? (uint32_t)((size_t)y * nx + x) * sizeof(T) : dummy;
+    }
+    // ---- halo slots
+    uint32_t hoff[HS];
+    int hlds[HS];
+    bool huse[HS];
+#pragma unroll
+    for (int s = 0; s < HS; ++s) {
+        const int h = tid + s * NT;
+        int lx, ly;
+        if (h < 2 * R * TX) {
+            const int row = h / TX;
+            lx = R + h % TX;
+            ly = row < R ? row : row + TY;
+        } else {
+            const int h2 = h - 2 * R * TX;
+            const int k = h2 % (2 * R);
+            lx = k < R ? k : k + TX;
+            ly = R + h2 / (2 * R);
+        }
+        const int gx = x0 - R + lx, gy = y0 - R + ly;
+        bool use = h < NH;
+        if (GUARD) use = use && gx >= R && gx < nx - R && gy >= R && gy < ny - R;
+        huse[s] = use;
+        hoff[s] = use ? (uint32_t)((size_t)gy * nx + gx) * sizeof(T) : dummy;
+        hlds[s] = h < NH ? ly * LX + lx : 0;      // cell (0,0) is a corner nobody reads
+    }
+
+    T acc[PY][NACC];
+#pragma unroll
+    for (int p = 0; p < PY; ++p)
+#pragma unroll
+        for (int k = 0; k < NACC; ++k) acc[p][k] = T(0);
+
+    // D stages of values in flight
+    T sc[D][PY], sr[D][PY], shc[D][HS], shr[D][HS], su[D][PY], sp[D][PY];
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+#pragma unroll
+        for (int p = 0; p < PY; ++p) { sc[d][p] = sr[d][p] = su[d][p] = sp[d][p] = T(0); }
+#pragma unroll
+        for (int s = 0; s < HS; ++s) { shc[d][s] = shr[d][s] = T(0); }
+    }
+
+    const int zi0 = zs - R, zi1 = ze - 1 + R;     // input planes that reach outputs [zs, ze)
+    auto plane_in_I = [&](int z) { return z >= R && z < nz - R; };
+
+    // Request everything step `z` will consume into stage d.
+    auto issue = [&](int z, int d) {
+        if (z > zi1) return;
+        if (plane_in_I(z)) {
+            const T *cp = cg + (size_t)z * plane;
+            const T *rp = rg + (size_t)z * plane;
+#pragma unroll
+            for (int p = 0; p < PY; ++p) { sc[d][p] = ld_off(cp, ooff[p]); sr[d][p] = ld_off(rp, ooff[p]); }
+#pragma unroll
+            for (int s = 0; s < HS; ++s) { shc[d][s] = ld_off(cp, hoff[s]); shr[d][s] = ld_off(rp, hoff[s]); }
+            if (UPREV) {
+                if (z >= zs && z < ze) {
+                    const T *pp = upg + (size_t)z * plane;
+#pragma unroll
+                    for (int p = 0; p < PY; ++p) sp[d][p] = ld_stream<T, NTU>(pp, ooff[p]);
+                }
+            }
+        }
+        const int zo = z - R;
+        if (zo >= zs) {                            // zo <= ze-1 because z <= zi1
+            const T *up = ug + (size_t)zo * plane;
+#pragma unroll
+            for (int p = 0; p < PY; ++p) su[d][p] = ld_stream<T, NTU>(up, ooff[p]);
+        }
+    };
+
+    int buf = 0;
+    auto step = [&](int zi, int d) {
+        const bool zin = plane_in_I(zi);
+        const int zo = zi - R;
+        T *sb = sq + buf * (LY * LX);
+        T qo[PY], ro[PY], cu[PY];
+#pragma unroll
+        for (int p = 0; p < PY; ++p) cu[p] = su[d][p];
+        if (zin) {
+#pragma unroll
+            for (int p = 0; p < PY; ++p) {
+                const T rr = GUARD ? (ouse[p] ? sr[d][p] : T(0)) : sr[d][p];
+                const T qq = GUARD ? (ouse[p] ? sc[d][p] * sr[d][p] : T(0)) : sc[d][p] * sr[d][p];
+                ro[p] = rr;
+                qo[p] = qq;
+                sb[(R + ty * PY + p) * LX + R + tx] = qq;
+            }
+#pragma unroll
+            for (int s = 0; s < HS; ++s) {
+                const T qq = GUARD ? (huse[s] ? shc[d][s] * shr[d][s] : T(0)) : shc[d][s] * shr[d][s];
+                sb[hlds[s]] = qq;
+            }
+            if (UPREV) {
+                if (zi >= zs && zi < ze) {
+                    T *pp = upg + (size_t)zi * plane;
+#pragma unroll
+                    for (int p = 0; p < PY; ++p)
+                        if (!GUARD || ouse[p]) st_stream<T, NTU>(pp, ooff[p], sp[d][p] - ro[p]);
+                }
+            }
+        }
+        // the registers of stage d are free again: request plane zi+D
+        issue(zi + D, d);
+        if (zin) {
+            __syncthreads();
+            T col[PY + 2 * R];
+#pragma unroll
+            for (int i = 0; i < PY + 2 * R; ++i) col[i] = sb[(ty * PY + i) * LX + R + tx];
+#pragma unroll
+            for (int p = 0; p < PY; ++p) {
+                const T *row = sb + (R + ty * PY + p) * LX + R + tx;
+                T s = T(3.0 * star_w<R>(0)) * qo[p];
+#pragma unroll
+                for (int k = 1; k <= R; ++k) s += T(star_w<R>(k)) * (row[-k] + row[k]);
+#pragma unroll
+                for (int k = 1; k <= R; ++k) s += T(star_w<R>(k)) * (col[R + p - k] + col[R + p + k]);
+                acc[p][R] += s + T(2) * ro[p];
+#pragma unroll
+                for (int k = 1; k <= R; ++k) {
+                    acc[p][R - k] += T(star_w<R>(k)) * qo[p];
+                    acc[p][R + k] += T(star_w<R>(k)) * qo[p];
+                }
+            }
+            buf ^= 1;
+        }
+        if (zo >= zs) {
+            T *up = ug + (size_t)zo * plane;
+#pragma unroll
+            for (int p = 0; p < PY; ++p)
+                if (!GUARD || ostore[p]) st_stream<T, NTU>(up, ooff[p], cu[p] + acc[p][0]);
+        }
+#pragma unroll
+        for (int p = 0; p < PY; ++p) {
+#pragma unroll
+            for (int k = 0; k < NACC - 1; ++k) acc[p][k] = acc[p][k + 1];
+            acc[p][NACC - 1] = T(0);
+        }
+    };
+
+#pragma unroll
+    for (int d = 0; d < D; ++d) issue(zi0 + d, d);
+    for (int zb = zi0; zb <= zi1; zb += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d)
+            if (zb + d <= zi1) step(zb + d, d);
+    }
+}
+
+template <class T, int R, int BX, int BY, int PY, int D, bool NTU, bool UPREV>
+__global__ __launch_bounds__(BX *BY) void adj_wave3d_kernel(AdjWave3dArgs a)
+{
+    using G = AdjTile<T, R, BX, BY, PY>;
+    __shared__ T sq[G::LDS_ELEMS];
+    const int L = xcd_contiguous_id(blockIdx.x, a.total_blocks);
+    const int tix = L % a.ntx;
+    const int t = L / a.ntx;
+    const int tiy = t % a.nty;
+    const int tiz = t / a.nty;
+    // core tile: own cells and halo cells all inside I in x and y
+    const int x0 = tix * G::TX, y0 = tiy * G::TY;
+    const bool core = x0 >= 2 * R && x0 + G::TX + 2 * R <= a.nx && y0 >= 2 * R && y0 + G::TY + 2 * R <= a.ny;
+    if (core) adj3d_march<T, R, BX, BY, PY, D, NTU, false, UPREV>(a, tix, tiy, tiz, sq);
+    else      adj3d_march<T, R, BX, BY, PY, D, NTU, true, UPREV>(a, tix, tiy, tiz, sq);
+}
+
+static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+template <class T, int R, int BX, int BY, int PY, int D, bool NTU>
+static hipError_t launch_cfg(AdjWave3dArgs a, const LaunchOptions &opt, hipStream_t stream)
+{
+    using G = AdjTile<T, R, BX, BY, PY>;
+    a.ntx = cdiv(a.nx, G::TX);
+    a.nty = cdiv(a.ny, G::TY);
+    int zchunk = (int)opt.zchunk;
+    if (zchunk <= 0) {
+        // one resident wave of workgroups: as few z-chunks as still give every CU work
+        int dev = 0, ncu = 256;
+        if (hipGetDevice(&dev) == hipSuccess) {
+            int v = 0;
+            if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) ncu = v;
+        }
+        const int tiles = a.ntx * a.nty;
+        const int chunks = tiles >= ncu ? 1 : cdiv(ncu, tiles);
+        zchunk = cdiv(a.nz, chunks);
+        if (zchunk < 4 * R) zchunk = 4 * R;          // keep the re-read of 2R planes per chunk below 50 %
+    }
+    if (zchunk > a.nz) zchunk = a.nz;
+    a.zchunk = zchunk;
+    a.ntz = cdiv(a.nz, zchunk);
+    a.total_blocks = a.ntx * a.nty * a.ntz;
+    dim3 grid(a.total_blocks), block(G::NT);
+    if (a.u_prev_bar) hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, D, NTU, true>), grid, block, 0, stream, a);
+    else              hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, D, NTU, false>), grid, block, 0, stream, a);
+    return hipGetLastError();
+}
+
+template <class T, int R>
+static hipError_t launch_T(const AdjWave3dArgs &a, const LaunchOptions &opt, hipStream_t stream)
+{
+    switch (opt.variant) {
+    default:
+    case 0: return launch_cfg<T, R, 64, 8, 4, 2, true>(a, opt, stream);
+    case 1: return launch_cfg<T, R, 64, 4, 4, 1, false>(a, opt, stream);
+    case 2: return launch_cfg<T, R, 64, 4, 4, 1, true>(a, opt, stream);
+    case 3: return launch_cfg<T, R, 64, 4, 4, 2, true>(a, opt, stream);
+    case 4: return launch_cfg<T, R, 64, 8, 4, 1, true>(a, opt, stream);
+    case 5: return launch_cfg<T, R, 64, 8, 2, 2, true>(a, opt, stream);
+    case 6: return launch_cfg<T, R, 64, 8, 4, 2, false>(a, opt, stream);
+    case 7: return launch_cfg<T, R, 128, 4, 4, 2, true>(a, opt, stream);
+    case 8: return launch_cfg<T, R, 64, 4, 8, 2, true>(a, opt, stream);
+    case 9: return launch_cfg<T, R, 64, 4, 8, 1, true>(a, opt, stream);
+    case 10: return launch_cfg<T, R, 64, 16, 2, 1, true>(a, opt, stream);
+    case 11: return launch_cfg<T, R, 128, 8, 2, 1, true>(a, opt, stream);
+    case 12: return launch_cfg<T, R, 32, 16, 4, 2, true>(a, opt, stream);
+    }
+}
+
+hipError_t launch_adjoint_wave3d(int is_f64, int radius, int nx, int ny, int nz, const void *c,
+                                 const void *r_bar, void *u_bar, void *u_prev_bar,
+                                 const LaunchOptions &opt, hipStream_t stream)
+{
+    AdjWave3dArgs a{};
+    a.c = c; a.r_bar = r_bar; a.u_bar = u_bar; a.u_prev_bar = u_prev_bar;
+    a.nx = nx; a.ny = ny; a.nz = nz;
+    if (is_f64) {
+        if (radius == 1) return launch_T<double, 1>(a, opt, stream);
+        return launch_T<double, 4>(a, opt, stream);
+    }
+    if (radius == 1) return launch_T<float, 1>(a, opt, stream);
+    return launch_T<float, 4>(a, opt, stream);
+}
+
+}  // namespace sadj

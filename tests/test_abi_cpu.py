@@ -26,7 +26,7 @@ def test_header_declares_the_expected_entry_points():
     for n in ("sadj_primal_wave1d", "sadj_adjoint_wave1d", "sadj_primal_wave2d", "sadj_adjoint_wave2d",
               "sadj_primal_wave3d", "sadj_adjoint_wave3d", "sadj_primal_burgers1d",
               "sadj_adjoint_burgers1d", "sadj_status_string", "sadj_version", "sadj_set_option",
-              "sadj_get_option"):
+              "sadj_get_option", "sadj_last_device_error"):
         assert n in names
 
 
@@ -38,7 +38,8 @@ def test_library_exports_every_declared_symbol():
 
 def test_binding_has_the_same_names():
     for name in _declared_functions():
-        if name in ("sadj_status_string", "sadj_version", "sadj_set_option", "sadj_get_option"):
+        if name in ("sadj_status_string", "sadj_version", "sadj_set_option", "sadj_get_option",
+                    "sadj_last_device_error"):
             continue
         assert callable(getattr(sadj, name))
 
@@ -53,7 +54,6 @@ def test_status_strings_and_version():
 
 
 def test_options_roundtrip_and_reject_unknown():
-    assert sadj.get_option("wave3d.fused") in (0, 1)
     old = sadj.get_option("wave3d.zchunk")
     sadj.set_option("wave3d.zchunk", 32)
     assert sadj.get_option("wave3d.zchunk") == 32
@@ -62,7 +62,7 @@ def test_options_roundtrip_and_reject_unknown():
         sadj.set_option("no.such.option", 1)
     assert e.value.status == 4
     with pytest.raises(sadj.SadjError):
-        sadj.set_option("wave3d.fused", 7)
+        sadj.set_option("wave3d.variant", -1)
 
 
 P = ctypes.c_void_p
