@@ -14,7 +14,7 @@ once on the primal interior, read and write u_bar once on the whole grid
 (16 N + 16 |I| bytes in fp64).  peak = 8000 GB/s (MI355X HBM3E).
 
 cpu_baseline: the CPU oracle (scatter adjoint, one core, gcc -O2) timed on the
-first 192 z-planes of the same arrays.
+leading z-planes of the same arrays (about 15 s of work, at most the whole grid).
 
 With --all the same JSON line carries an "others" object with the remaining
 workloads (fp32, radius 1, primal, 2-D, Burgers, 1-D), each timed the same way.
@@ -89,11 +89,14 @@ def read_traffic(name):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--all", action="store_true", help="also time the other workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--size", type=int, default=512, help="grid edge of the headline workload")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="after the timed region run one plain device copy of a whole array (the known-size "
+                         "reference that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the hot path is a single-GPU kernel "
@@ -147,7 +150,7 @@ def main():
     others = {}
 
     def add(name, fn, points, nbytes, dtype):
-        w, e, emin = time_calls(fn, max(5, args.steps // 2), 3)
+        w, e, emin = time_calls(fn, max(5, args.steps // 4), max(3, args.warmup // 4))
         others[name] = {"Gpoints/s": points / (w * 1e-3) / 1e9, "ms": w, "kernel_ms_mean": e,
                         "GB/s": nbytes / (e * 1e-3) / 1e9, "frac": nbytes / (e * 1e-3) / 1e9 / HBM_PEAK_GBS,
                         "dtype": dtype}
@@ -190,15 +193,24 @@ def main():
         c1, rb1, ub1 = (t.reshape(-1)[:n1] for t in (c, rb, ub))
         add("wave1d_f64_adjoint_n4096_latency", lambda: sadj.sadj_adjoint_wave1d(c1, rb1, ub1), n1, 32 * n1, "f64")
     out["others"] = others
+    if args.copy_probe:
+        ub.copy_(c)
+        torch.cuda.synchronize()
 
     if not args.no_cpu_baseline:
         import oracle
         oracle.build()
-        nzs = min(192, n)
-        sl = (slice(0, nzs),)
-        t0 = time.perf_counter()
-        oracle.wave_adjoint(d["c"][sl], d["r_bar"][sl], d["u_bar"][sl], R)
-        dt = time.perf_counter() - t0
+
+        def run_oracle(nzs):
+            sl = (slice(0, nzs),)
+            t0 = time.perf_counter()
+            oracle.wave_adjoint(d["c"][sl], d["r_bar"][sl], d["u_bar"][sl], R)
+            return time.perf_counter() - t0
+
+        probe = min(n, 32)
+        rate = probe / run_oracle(probe)                 # planes per second on this host
+        nzs = int(min(n, max(probe, rate * 15.0)))      # about 15 s of CPU work, at most the whole grid
+        dt = run_oracle(nzs)
         out["cpu_baseline"] = {"value": nzs * n * n / dt / 1e9, "unit": "Gpoints/s", "cores": 1, "kind": "oracle",
                                "sample": "first %d z-planes of the same %d^3 arrays (%d x %d x %d grid), one run, "
                                          "%.1f s" % (nzs, n, n, n, nzs, dt),

@@ -311,24 +311,24 @@ static hipError_t launch_cfg(AdjWave3dArgs a, const LaunchOptions &opt, hipStrea
     return hipGetLastError();
 }
 
+// Tile shapes.  Variant 0 picks the measured best per dtype: rows of 512 bytes per
+// tile (64 doubles / 128 floats), 32 x 16 rows, one workgroup per CU.
 template <class T, int R>
 static hipError_t launch_T(const AdjWave3dArgs &a, const LaunchOptions &opt, hipStream_t stream)
 {
     switch (opt.variant) {
     default:
-    case 0: return launch_cfg<T, R, 64, 8, 4, 2, true>(a, opt, stream);
-    case 1: return launch_cfg<T, R, 64, 4, 4, 1, false>(a, opt, stream);
-    case 2: return launch_cfg<T, R, 64, 4, 4, 1, true>(a, opt, stream);
-    case 3: return launch_cfg<T, R, 64, 4, 4, 2, true>(a, opt, stream);
-    case 4: return launch_cfg<T, R, 64, 8, 4, 1, true>(a, opt, stream);
+    case 0:
+        if (sizeof(T) == 8) return launch_cfg<T, R, 64, 8, 4, 1, true>(a, opt, stream);
+        return launch_cfg<T, R, 128, 8, 2, 1, true>(a, opt, stream);
+    case 1: return launch_cfg<T, R, 64, 8, 4, 1, true>(a, opt, stream);
+    case 2: return launch_cfg<T, R, 128, 8, 2, 1, true>(a, opt, stream);
+    case 3: return launch_cfg<T, R, 64, 8, 4, 2, true>(a, opt, stream);
+    case 4: return launch_cfg<T, R, 64, 4, 4, 1, true>(a, opt, stream);
     case 5: return launch_cfg<T, R, 64, 8, 2, 2, true>(a, opt, stream);
-    case 6: return launch_cfg<T, R, 64, 8, 4, 2, false>(a, opt, stream);
-    case 7: return launch_cfg<T, R, 128, 4, 4, 2, true>(a, opt, stream);
-    case 8: return launch_cfg<T, R, 64, 4, 8, 2, true>(a, opt, stream);
-    case 9: return launch_cfg<T, R, 64, 4, 8, 1, true>(a, opt, stream);
-    case 10: return launch_cfg<T, R, 64, 16, 2, 1, true>(a, opt, stream);
-    case 11: return launch_cfg<T, R, 128, 8, 2, 1, true>(a, opt, stream);
-    case 12: return launch_cfg<T, R, 32, 16, 4, 2, true>(a, opt, stream);
+    case 6: return launch_cfg<T, R, 64, 8, 4, 1, false>(a, opt, stream);
+    case 7: return launch_cfg<T, R, 64, 16, 2, 1, true>(a, opt, stream);
+    case 8: return launch_cfg<T, R, 32, 16, 4, 1, true>(a, opt, stream);
     }
 }
 
