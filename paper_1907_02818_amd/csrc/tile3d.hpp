@@ -1,0 +1,82 @@
+// Geometry shared by the 3-D marching kernels: an x-y tile of TX x TY cells owned by a
+// workgroup of BX x BY threads (PY consecutive rows per thread), staged in LDS with a
+// halo of width R on all four sides (corners omitted: a star never reads them).
+#pragma once
+#include "common.hpp"
+
+namespace sadj {
+
+template <class T, int R, int BX, int BY, int PY>
+struct Tile3d {
+    static constexpr int TX = BX, TY = BY * PY, NT = BX * BY;
+    static constexpr int LX = TX + 2 * R, LY = TY + 2 * R;      // LDS plane extents
+    static constexpr int PLANE = LX * LY;
+    static constexpr int NH = 2 * R * TX + 2 * R * TY;          // halo cells without corners
+    static constexpr int HS = (NH + NT - 1) / NT;               // halo slots per thread
+
+    // Halo slot s of thread tid -> LDS coordinates (lx, ly); false if the slot is unused.
+    // Slots 0 .. 2R*TX-1 are the R rows above and below the tile (x fastest), the rest
+    // are the R columns left and right of it.
+    __device__ static __forceinline__ bool halo_cell(int tid, int s, int &lx, int &ly)
+    {
+        const int h = tid + s * NT;
+        if (h < 2 * R * TX) {
+            const int row = h / TX;
+            lx = R + h % TX;
+            ly = row < R ? row : row + TY;
+        } else {
+            const int h2 = h - 2 * R * TX;
+            const int k = h2 % (2 * R);
+            lx = k < R ? k : k + TX;
+            ly = R + h2 / (2 * R);
+        }
+        return h < NH;
+    }
+};
+
+struct March3dArgs {
+    const void *in0, *in1, *in2;   // adjoint: c, r_bar, -      primal: u, u_prev, c
+    void *out0, *out1;             // adjoint: u_bar, u_prev_bar (nullable)   primal: r, -
+    int nx, ny, nz;
+    int ntx, nty, ntz;             // tiles along x and y, chunks along z
+    int zchunk;                    // output planes per chunk
+    int total_blocks;
+};
+
+static inline int cdiv_i(int a, int b) { return (a + b - 1) / b; }
+
+// One resident wave of workgroups: as few z-chunks as still give every CU a workgroup.
+static inline void plan_march(March3dArgs &a, int TX, int TY, int R, long zchunk_opt)
+{
+    a.ntx = cdiv_i(a.nx, TX);
+    a.nty = cdiv_i(a.ny, TY);
+    int zchunk = (int)zchunk_opt;
+    if (zchunk <= 0) {
+        int dev = 0, ncu = 256, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            ncu = v;
+        const int tiles = a.ntx * a.nty;
+        const int chunks = tiles >= ncu ? 1 : cdiv_i(ncu, tiles);
+        zchunk = cdiv_i(a.nz, chunks);
+        if (zchunk < 4 * R) zchunk = 4 * R;      // keep the 2R re-read planes per chunk below 50 %
+    }
+    if (zchunk > a.nz) zchunk = a.nz;
+    a.zchunk = zchunk;
+    a.ntz = cdiv_i(a.nz, zchunk);
+    a.total_blocks = a.ntx * a.nty * a.ntz;
+}
+
+template <class T, bool NT> __device__ __forceinline__ T ld_stream(const T *base, uint32_t byte_off)
+{
+    const T *p = reinterpret_cast<const T *>(reinterpret_cast<const char *>(base) + byte_off);
+    return NT ? __builtin_nontemporal_load(p) : *p;
+}
+template <class T, bool NT> __device__ __forceinline__ void st_stream(T *base, uint32_t byte_off, T v)
+{
+    T *p = reinterpret_cast<T *>(reinterpret_cast<char *>(base) + byte_off);
+    if (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+}  // namespace sadj

@@ -40,47 +40,17 @@
 // I cannot leak.  Along z the same rule is applied per plane with a wave-uniform
 // (scalar) test in both instantiations: planes outside I are skipped.  The regions
 // are disjoint and need no ordering, so they share one dispatch.
-#include "common.hpp"
 #include "launch.hpp"
+#include "tile3d.hpp"
 
 namespace sadj {
 
-struct AdjWave3dArgs {
-    const void *c, *r_bar;
-    void *u_bar, *u_prev_bar;
-    int nx, ny, nz;
-    int ntx, nty, ntz;      // tiles along x and y, chunks along z
-    int zchunk;             // output planes per chunk
-    int total_blocks;
-};
-
-template <class T, int R, int BX, int BY, int PY>
-struct AdjTile {
-    static constexpr int TX = BX, TY = BY * PY, NT = BX * BY;
-    static constexpr int LX = TX + 2 * R, LY = TY + 2 * R;
-    static constexpr int NH = 2 * R * TX + 2 * R * TY;     // halo cells without corners
-    static constexpr int HS = (NH + NT - 1) / NT;          // halo slots per thread
-    static constexpr int LDS_ELEMS = 2 * LY * LX;
-};
-
-template <class T, bool NT> __device__ __forceinline__ T ld_stream(const T *base, uint32_t byte_off)
-{
-    const T *p = reinterpret_cast<const T *>(reinterpret_cast<const char *>(base) + byte_off);
-    return NT ? __builtin_nontemporal_load(p) : *p;
-}
-template <class T, bool NT> __device__ __forceinline__ void st_stream(T *base, uint32_t byte_off, T v)
-{
-    T *p = reinterpret_cast<T *>(reinterpret_cast<char *>(base) + byte_off);
-    if (NT) __builtin_nontemporal_store(v, p);
-    else *p = v;
-}
-
 template <class T, int R, int BX, int BY, int PY, int D, bool NTU, bool GUARD, bool UPREV>
-__device__ __forceinline__ void adj3d_march(const AdjWave3dArgs &a, int tix, int tiy, int tiz,
+__device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int tiy, int tiz,
                                             T *__restrict__ sq)
 {
-    using G = AdjTile<T, R, BX, BY, PY>;
-    constexpr int TX = G::TX, TY = G::TY, NT = G::NT, LX = G::LX, LY = G::LY, NH = G::NH, HS = G::HS;
+    using G = Tile3d<T, R, BX, BY, PY>;
+    constexpr int TX = G::TX, TY = G::TY, LX = G::LX, LY = G::LY, HS = G::HS;
     constexpr int NACC = 2 * R + 1;
     const int tid = threadIdx.x;
     const int tx = tid % BX, ty = tid / BX;
@@ -90,10 +60,10 @@ __device__ __forceinline__ void adj3d_march(const AdjWave3dArgs &a, int tix, int
     const int zs = tiz * a.zchunk;
     const int ze = min(zs + a.zchunk, nz);
 
-    const T *__restrict__ cg = static_cast<const T *>(a.c);
-    const T *__restrict__ rg = static_cast<const T *>(a.r_bar);
-    T *__restrict__ ug = static_cast<T *>(a.u_bar);
-    T *__restrict__ upg = static_cast<T *>(a.u_prev_bar);
+    const T *__restrict__ cg = static_cast<const T *>(a.in0);
+    const T *__restrict__ rg = static_cast<const T *>(a.in1);
+    T *__restrict__ ug = static_cast<T *>(a.out0);
+    T *__restrict__ upg = static_cast<T *>(a.out1);
 
     // A cell that is always inside the grid: unused slots load it and discard it.
     const uint32_t dummy = (uint32_t)((size_t)y0 * nx + x0) * sizeof(T);
@@ -120,24 +90,14 @@ __device__ __forceinline__ void adj3d_march(const AdjWave3dArgs &a, int tix, int
     bool huse[HS];
 #pragma unroll
     for (int s = 0; s < HS; ++s) {
-        const int h = tid + s * NT;
         int lx, ly;
-        if (h < 2 * R * TX) {
-            const int row = h / TX;
-            lx = R + h % TX;
-            ly = row < R ? row : row + TY;
-        } else {
-            const int h2 = h - 2 * R * TX;
-            const int k = h2 % (2 * R);
-            lx = k < R ? k : k + TX;
-            ly = R + h2 / (2 * R);
-        }
+        const bool slot = G::halo_cell(tid, s, lx, ly);
         const int gx = x0 - R + lx, gy = y0 - R + ly;
-        bool use = h < NH;
+        bool use = slot;
         if (GUARD) use = use && gx >= R && gx < nx - R && gy >= R && gy < ny - R;
         huse[s] = use;
         hoff[s] = use ? (uint32_t)((size_t)gy * nx + gx) * sizeof(T) : dummy;
-        hlds[s] = h < NH ? ly * LX + lx : 0;      // cell (0,0) is a corner nobody reads
+        hlds[s] = slot ? ly * LX + lx : 0;      // cell (0,0) is a corner nobody reads
     }
 
     T acc[PY][NACC];
@@ -264,10 +224,10 @@ __device__ __forceinline__ void adj3d_march(const AdjWave3dArgs &a, int tix, int
 }
 
 template <class T, int R, int BX, int BY, int PY, int D, bool NTU, bool UPREV>
-__global__ __launch_bounds__(BX *BY) void adj_wave3d_kernel(AdjWave3dArgs a)
+__global__ __launch_bounds__(BX *BY) void adj_wave3d_kernel(March3dArgs a)
 {
-    using G = AdjTile<T, R, BX, BY, PY>;
-    __shared__ T sq[G::LDS_ELEMS];
+    using G = Tile3d<T, R, BX, BY, PY>;
+    __shared__ T sq[2 * G::PLANE];
     const int L = xcd_contiguous_id(blockIdx.x, a.total_blocks);
     const int tix = L % a.ntx;
     const int t = L / a.ntx;
@@ -280,41 +240,21 @@ __global__ __launch_bounds__(BX *BY) void adj_wave3d_kernel(AdjWave3dArgs a)
     else      adj3d_march<T, R, BX, BY, PY, D, NTU, true, UPREV>(a, tix, tiy, tiz, sq);
 }
 
-static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
-
 template <class T, int R, int BX, int BY, int PY, int D, bool NTU>
-static hipError_t launch_cfg(AdjWave3dArgs a, const LaunchOptions &opt, hipStream_t stream)
+static hipError_t launch_cfg(March3dArgs a, const LaunchOptions &opt, hipStream_t stream)
 {
-    using G = AdjTile<T, R, BX, BY, PY>;
-    a.ntx = cdiv(a.nx, G::TX);
-    a.nty = cdiv(a.ny, G::TY);
-    int zchunk = (int)opt.zchunk;
-    if (zchunk <= 0) {
-        // one resident wave of workgroups: as few z-chunks as still give every CU work
-        int dev = 0, ncu = 256;
-        if (hipGetDevice(&dev) == hipSuccess) {
-            int v = 0;
-            if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) ncu = v;
-        }
-        const int tiles = a.ntx * a.nty;
-        const int chunks = tiles >= ncu ? 1 : cdiv(ncu, tiles);
-        zchunk = cdiv(a.nz, chunks);
-        if (zchunk < 4 * R) zchunk = 4 * R;          // keep the re-read of 2R planes per chunk below 50 %
-    }
-    if (zchunk > a.nz) zchunk = a.nz;
-    a.zchunk = zchunk;
-    a.ntz = cdiv(a.nz, zchunk);
-    a.total_blocks = a.ntx * a.nty * a.ntz;
+    using G = Tile3d<T, R, BX, BY, PY>;
+    plan_march(a, G::TX, G::TY, R, opt.zchunk);
     dim3 grid(a.total_blocks), block(G::NT);
-    if (a.u_prev_bar) hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, D, NTU, true>), grid, block, 0, stream, a);
-    else              hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, D, NTU, false>), grid, block, 0, stream, a);
+    if (a.out1) hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, D, NTU, true>), grid, block, 0, stream, a);
+    else        hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, D, NTU, false>), grid, block, 0, stream, a);
     return hipGetLastError();
 }
 
 // Tile shapes.  Variant 0 picks the measured best per dtype: rows of 512 bytes per
 // tile (64 doubles / 128 floats), 32 x 16 rows, one workgroup per CU.
 template <class T, int R>
-static hipError_t launch_T(const AdjWave3dArgs &a, const LaunchOptions &opt, hipStream_t stream)
+static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipStream_t stream)
 {
     switch (opt.variant) {
     default:
@@ -336,8 +276,8 @@ hipError_t launch_adjoint_wave3d(int is_f64, int radius, int nx, int ny, int nz,
                                  const void *r_bar, void *u_bar, void *u_prev_bar,
                                  const LaunchOptions &opt, hipStream_t stream)
 {
-    AdjWave3dArgs a{};
-    a.c = c; a.r_bar = r_bar; a.u_bar = u_bar; a.u_prev_bar = u_prev_bar;
+    March3dArgs a{};
+    a.in0 = c; a.in1 = r_bar; a.out0 = u_bar; a.out1 = u_prev_bar;
     a.nx = nx; a.ny = ny; a.nz = nz;
     if (is_f64) {
         if (radius == 1) return launch_T<double, 1>(a, opt, stream);
