@@ -9,13 +9,14 @@
 
 namespace {
 
-std::atomic<long> g_zchunk{0}, g_variant{0};
+std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0};
 
 sadj::LaunchOptions current_options()
 {
     sadj::LaunchOptions o;
     o.zchunk = g_zchunk.load();
     o.variant = g_variant.load();
+    o.ychunk2d = g_ychunk2d.load();
     return o;
 }
 
@@ -103,6 +104,11 @@ sadj_status sadj_set_option(const char *name, long value)
         g_variant = value;
         return SADJ_OK;
     }
+    if (!std::strcmp(name, "wave2d.ychunk")) {
+        if (value < 0 || value > kMaxExtent) return SADJ_ERR_UNSUPPORTED;
+        g_ychunk2d = value;
+        return SADJ_OK;
+    }
 
     return SADJ_ERR_UNSUPPORTED;
 }
@@ -112,6 +118,7 @@ sadj_status sadj_get_option(const char *name, long *value)
     if (!name || !value) return SADJ_ERR_NULL;
     if (!std::strcmp(name, "wave3d.zchunk")) { *value = g_zchunk; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.variant")) { *value = g_variant; return SADJ_OK; }
+    if (!std::strcmp(name, "wave2d.ychunk")) { *value = g_ychunk2d; return SADJ_OK; }
     return SADJ_ERR_UNSUPPORTED;
 }
 
@@ -132,7 +139,7 @@ static sadj_status primal_wave(int ndim, sadj_dtype dtype, int radius, long nx, 
     clear_stale_hip_error();
     switch (ndim) {
     case 1: return from_hip(sadj::launch_primal_wave1d(f64, nx, u, u_prev, c, r, st));
-    case 2: return from_hip(sadj::launch_primal_wave2d(f64, (int)nx, (int)ny, u, u_prev, c, r, st));
+    case 2: return from_hip(sadj::launch_primal_wave2d(f64, (int)nx, (int)ny, u, u_prev, c, r, current_options(), st));
     default: return from_hip(sadj::launch_primal_wave3d(f64, radius, (int)nx, (int)ny, (int)nz, u, u_prev, c, r,
                                                         current_options(), st));
     }
@@ -155,7 +162,7 @@ static sadj_status adjoint_wave(int ndim, sadj_dtype dtype, int radius, long nx,
     clear_stale_hip_error();
     switch (ndim) {
     case 1: return from_hip(sadj::launch_adjoint_wave1d(f64, nx, c, r_bar, u_bar, u_prev_bar, st));
-    case 2: return from_hip(sadj::launch_adjoint_wave2d(f64, (int)nx, (int)ny, c, r_bar, u_bar, u_prev_bar, st));
+    case 2: return from_hip(sadj::launch_adjoint_wave2d(f64, (int)nx, (int)ny, c, r_bar, u_bar, u_prev_bar, current_options(), st));
     default: return from_hip(sadj::launch_adjoint_wave3d(f64, radius, (int)nx, (int)ny, (int)nz, c, r_bar, u_bar,
                                                          u_prev_bar, current_options(), st));
     }

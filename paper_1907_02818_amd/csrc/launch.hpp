@@ -7,6 +7,7 @@ namespace sadj {
 struct LaunchOptions {
     long zchunk = 0;     // wave3d: output planes per workgroup (0 = automatic)
     long variant = 0;    // wave3d: tile-shape variant
+    long ychunk2d = 0;   // wave2d: output rows per wave (0 = automatic)
 };
 
 hipError_t launch_adjoint_wave3d(int is_f64, int radius, int nx, int ny, int nz, const void *c,
@@ -17,9 +18,9 @@ hipError_t launch_primal_wave3d(int is_f64, int radius, int nx, int ny, int nz, 
                                 const LaunchOptions &opt, hipStream_t stream);
 
 hipError_t launch_adjoint_wave2d(int is_f64, int nx, int ny, const void *c, const void *r_bar,
-                                 void *u_bar, void *u_prev_bar, hipStream_t stream);
+                                 void *u_bar, void *u_prev_bar, const LaunchOptions &opt, hipStream_t stream);
 hipError_t launch_primal_wave2d(int is_f64, int nx, int ny, const void *u, const void *u_prev,
-                                const void *c, void *r, hipStream_t stream);
+                                const void *c, void *r, const LaunchOptions &opt, hipStream_t stream);
 
 hipError_t launch_adjoint_wave1d(int is_f64, long n, const void *c, const void *r_bar, void *u_bar,
                                  void *u_prev_bar, hipStream_t stream);

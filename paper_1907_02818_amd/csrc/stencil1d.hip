@@ -6,12 +6,14 @@
 // shuffles; the two cells beside the segment are loaded by lanes 0 and 63.  No LDS,
 // no barrier, no atomics: each output cell is written by exactly one lane.
 //
-// Regions (Sections 3.3.3, 3.3.4).  The core launch covers the segments whose reads
-// all lie in the primal iteration space I = [1, n-2]; it is compiled without any
-// guard.  The remainder launch covers the first and the last segment(s) with the
-// guarded instantiation: a term is kept iff its primal iteration exists, unused
-// values are replaced by zero with a select (never multiplied by zero), and loads
-// are element-wise and clamped into the array.
+// Regions (Sections 3.3.3, 3.3.4).  The core waves cover the segments whose reads
+// all lie in the primal iteration space I = [1, n-2]; they run an instantiation that
+// is compiled without any guard.  The remainder waves cover the first and the last
+// segment(s) with the guarded instantiation: a term is kept iff its primal iteration
+// exists, unused values are replaced by zero with a select (never multiplied by zero),
+// and loads are element-wise and clamped into the array.  Core and remainder are
+// disjoint and unordered, so they share one dispatch: the first workgroups are core,
+// the last one or two are remainder.
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -22,19 +24,13 @@ struct Args1d {
     void *o0, *o1;              // outputs
     long n;
     double C, D;
-    long seg_first;             // core launch: first segment
-    long seg_count;             // number of segments (= waves) of this launch
-    long seg_jump_after;        // remainder launch: local index 0 -> segment 0, k>0 -> seg_jump_after + k
-    int remainder;              // 0: core launch, 1: remainder launch
+    long core_segs;             // core waves handle segments 1 .. core_segs
+    long core_blocks;           // workgroups [0, core_blocks) are core, the rest remainder
+    long rem_segs;              // remainder waves: index 0 -> segment 0, k>0 -> segment core_segs + k
 };
 
 constexpr int kWaves1d = 4;
-
-__device__ __forceinline__ long segment_of(const Args1d &a, long local)
-{
-    if (!a.remainder) return a.seg_first + local;
-    return local == 0 ? 0 : a.seg_jump_after + local;
-}
+enum Op1d { OP_ADJ_WAVE, OP_ADJ_WAVE_UPREV, OP_PRI_WAVE, OP_PRI_BURGERS, OP_ADJ_BURGERS };
 
 // Load PX consecutive cells starting at x.  Unguarded: one vector load.  Guarded:
 // element-wise, indices clamped to [0, n-1].
@@ -53,10 +49,13 @@ __device__ __forceinline__ void load_cells(const T *p, long x, long n, T (&v)[PX
         }
     }
 }
-template <class T, bool GUARD> __device__ __forceinline__ T load_cell(const T *p, long i, long n)
+// The cell beside a wave's segment; only lanes 0 and 63 use it, so only they load it.
+template <class T, bool GUARD> __device__ __forceinline__ T load_cell(const T *p, long i, long n, int lane)
 {
     if (GUARD) i = i < 0 ? 0 : (i > n - 1 ? n - 1 : i);
-    return p[i];
+    T v = T(0);
+    if (lane == 0 || lane == 63) v = p[i];
+    return v;
 }
 template <class T, int PX, bool GUARD>
 __device__ __forceinline__ void store_cells(T *p, long x, long n, const T (&v)[PX], const bool (&ok)[PX])
@@ -91,7 +90,7 @@ __device__ __forceinline__ void adj_wave1d_segment(const Args1d &a, long xs, int
     load_cells<T, PX, GUARD>(rg, x, n, rv);
     load_cells<T, PX, GUARD>(ug, x, n, uv);
     if (UPREV) load_cells<T, PX, GUARD>(pg, x, n, pv);
-    const T hc = load_cell<T, GUARD>(cg, hx, n), hr = load_cell<T, GUARD>(rg, hx, n);
+    const T hc = load_cell<T, GUARD>(cg, hx, n, lane), hr = load_cell<T, GUARD>(rg, hx, n, lane);
     T q[PX], rr[PX];
     bool ok[PX];
 #pragma unroll
@@ -134,7 +133,7 @@ __device__ __forceinline__ void pri_wave1d_segment(const Args1d &a, long xs, int
     load_cells<T, PX, GUARD>(ug, x, n, uv);
     load_cells<T, PX, GUARD>(pg, x, n, pv);
     load_cells<T, PX, GUARD>(cg, x, n, cv);
-    const T uh = load_cell<T, GUARD>(ug, hx, n);
+    const T uh = load_cell<T, GUARD>(ug, hx, n, lane);
     T left, right;
     wave_neighbours<T, PX>(uv, uh, lane, left, right);
     T out[PX];
@@ -165,7 +164,7 @@ __device__ __forceinline__ void pri_burgers_segment(const Args1d &a, long xs, in
     const long hx = lane < 32 ? xs - 1 : xs + W;
     T uv[PX];
     load_cells<T, PX, GUARD>(ug, x, n, uv);
-    const T uh = load_cell<T, GUARD>(ug, hx, n);
+    const T uh = load_cell<T, GUARD>(ug, hx, n, lane);
     T left, right;
     wave_neighbours<T, PX>(uv, uh, lane, left, right);
     T out[PX];
@@ -202,8 +201,8 @@ __device__ __forceinline__ void adj_burgers_segment(const Args1d &a, long xs, in
     load_cells<T, PX, GUARD>(ug, x, n, uv);
     load_cells<T, PX, GUARD>(rg, x, n, rv);
     load_cells<T, PX, GUARD>(bg, x, n, bv);
-    const T uh = load_cell<T, GUARD>(ug, hx, n);
-    T rh = load_cell<T, GUARD>(rg, hx, n);
+    const T uh = load_cell<T, GUARD>(ug, hx, n, lane);
+    T rh = load_cell<T, GUARD>(rg, hx, n, lane);
     bool ok[PX], in[PX];
 #pragma unroll
     for (int e = 0; e < PX; ++e) {
@@ -234,16 +233,9 @@ __device__ __forceinline__ void adj_burgers_segment(const Args1d &a, long xs, in
 }
 
 // -------------------------------------------------------------------------- kernels
-enum Op1d { OP_ADJ_WAVE, OP_ADJ_WAVE_UPREV, OP_PRI_WAVE, OP_PRI_BURGERS, OP_ADJ_BURGERS };
-
 template <class T, int PX, bool GUARD, int OP>
-__global__ __launch_bounds__(64 * kWaves1d) void stencil1d_kernel(Args1d a)
+__device__ __forceinline__ void run_segment(const Args1d &a, long xs, int lane)
 {
-    constexpr int W = 64 * PX;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const long local = (long)blockIdx.x * kWaves1d + wave;
-    if (local >= a.seg_count) return;              // wave-uniform; no barrier in this kernel
-    const long xs = segment_of(a, local) * W;
     if (OP == OP_ADJ_WAVE) adj_wave1d_segment<T, PX, GUARD, false>(a, xs, lane);
     else if (OP == OP_ADJ_WAVE_UPREV) adj_wave1d_segment<T, PX, GUARD, true>(a, xs, lane);
     else if (OP == OP_PRI_WAVE) pri_wave1d_segment<T, PX, GUARD>(a, xs, lane);
@@ -251,8 +243,26 @@ __global__ __launch_bounds__(64 * kWaves1d) void stencil1d_kernel(Args1d a)
     else adj_burgers_segment<T, PX, GUARD>(a, xs, lane);
 }
 
-// Core launch: segments [1, s_hi] (all reads inside I, whole vectors inside the
-// array).  Remainder launch: segment 0 and segments s_hi+1 .. nseg-1.
+template <class T, int PX, int OP>
+__global__ __launch_bounds__(64 * kWaves1d) void stencil1d_kernel(Args1d a)
+{
+    constexpr int W = 64 * PX;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long b = blockIdx.x;
+    if (b < a.core_blocks) {                       // block-uniform; no barrier in this kernel
+        const long local = b * kWaves1d + wave;
+        if (local >= a.core_segs) return;
+        run_segment<T, PX, false, OP>(a, (1 + local) * W, lane);
+    } else {
+        const long local = (b - a.core_blocks) * kWaves1d + wave;
+        if (local >= a.rem_segs) return;
+        const long seg = local == 0 ? 0 : a.core_segs + local;
+        run_segment<T, PX, true, OP>(a, seg * W, lane);
+    }
+}
+
+// Core: segments 1 .. s_hi (all reads inside I, whole vectors inside the array).
+// Remainder: segment 0 and segments s_hi+1 .. nseg-1.
 template <class T, int PX, int OP>
 static hipError_t launch_1d(Args1d a, hipStream_t stream)
 {
@@ -261,21 +271,12 @@ static hipError_t launch_1d(Args1d a, hipStream_t stream)
     const long nseg = (n + W - 1) / W;
     long s_hi = (n - 2) / W - 1;                  // last segment with xs + W <= n-2
     if (s_hi < 1) s_hi = 0;                       // no core segment
-    if (s_hi >= 1) {
-        a.remainder = 0;
-        a.seg_first = 1;
-        a.seg_count = s_hi;                       // segments 1..s_hi
-        dim3 grid((unsigned)((a.seg_count + kWaves1d - 1) / kWaves1d));
-        hipLaunchKernelGGL((stencil1d_kernel<T, PX, false, OP>), grid, dim3(64 * kWaves1d), 0, stream, a);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
-    a.remainder = 1;
-    a.seg_first = 0;
-    a.seg_jump_after = s_hi;
-    a.seg_count = 1 + (nseg - 1 - s_hi);          // segment 0 and segments s_hi+1 .. nseg-1
-    dim3 grid((unsigned)((a.seg_count + kWaves1d - 1) / kWaves1d));
-    hipLaunchKernelGGL((stencil1d_kernel<T, PX, true, OP>), grid, dim3(64 * kWaves1d), 0, stream, a);
+    a.core_segs = s_hi;
+    a.core_blocks = (a.core_segs + kWaves1d - 1) / kWaves1d;
+    a.rem_segs = 1 + (nseg - 1 - s_hi);
+    const long rem_blocks = (a.rem_segs + kWaves1d - 1) / kWaves1d;
+    dim3 grid((unsigned)(a.core_blocks + rem_blocks));
+    hipLaunchKernelGGL((stencil1d_kernel<T, PX, OP>), grid, dim3(64 * kWaves1d), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -50,6 +50,7 @@ __device__ __forceinline__ void adj2d_strip(const Wave2dArgs &a, int xs, int ys,
     const int hx = lane < 32 ? xs - 1 : xs + W;
     const bool hin = GUARD ? (hx >= 1 && hx <= nx - 2) : true;
     const int hxc = hin ? hx : xs;
+    const bool edge_lane = lane == 0 || lane == 63;
 
     T acc[PX][3];
 #pragma unroll
@@ -63,8 +64,7 @@ __device__ __forceinline__ void adj2d_strip(const Wave2dArgs &a, int xs, int ys,
         const T *rp = rg + (size_t)y * nx;
         ncv = ld_vec<T, PX>(cp + xc);
         nrv = ld_vec<T, PX>(rp + xc);
-        nhc = cp[hxc];
-        nhr = rp[hxc];
+        if (edge_lane) { nhc = cp[hxc]; nhr = rp[hxc]; }     // only lanes 0 and 63 use the value
         if (UPREV) {
             if (y >= ys && y < ye) npv = ld_vec<T, PX>(pg + (size_t)y * nx + xc);
         }
@@ -170,7 +170,9 @@ __global__ __launch_bounds__(64 * kWavesPerBlock2d) void primal_wave2d_kernel(Wa
 #pragma unroll
     for (int e = 0; e < PX; ++e) { acc[e][0] = acc[e][1] = acc[e][2] = T(0); uq[e][0] = uq[e][1] = T(0); }
     V nuv = ld_vec<T, PX>(ug + (size_t)(ys - 1) * nx + xc);
-    T nh = ug[(size_t)(ys - 1) * nx + hxc];
+    const bool edge_lane = lane == 0 || lane == 63;
+    T nh = T(0);
+    if (edge_lane) nh = ug[(size_t)(ys - 1) * nx + hxc];
     V ncv{}, npv{};
     for (int yi = ys - 1; yi <= ye; ++yi) {
         const int yo = yi - 1;
@@ -181,7 +183,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock2d) void primal_wave2d_kernel(Wa
         const V cc = ncv, pp = npv;
         if (yi + 1 <= ye) {
             nuv = ld_vec<T, PX>(ug + (size_t)(yi + 1) * nx + xc);
-            nh = ug[(size_t)(yi + 1) * nx + hxc];
+            if (edge_lane) nh = ug[(size_t)(yi + 1) * nx + hxc];
             if (yo + 1 >= ys) {
                 ncv = ld_vec<T, PX>(cg + (size_t)(yo + 1) * nx + xc);
                 npv = ld_vec<T, PX>(pg + (size_t)(yo + 1) * nx + xc);
@@ -225,10 +227,10 @@ __global__ __launch_bounds__(64 * kWavesPerBlock2d) void primal_wave2d_kernel(Wa
 static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 template <class T, int PX>
-static hipError_t launch_adj2d(const Wave2dArgs &a0, hipStream_t stream)
+static hipError_t launch_adj2d(const Wave2dArgs &a0, const LaunchOptions &opt, hipStream_t stream)
 {
     Wave2dArgs a = a0;
-    a.ychunk = 64;
+    a.ychunk = opt.ychunk2d > 0 ? (int)opt.ychunk2d : 32;
     constexpr int W = 64 * PX;
     const int nstrips = (a.nx + W - 1) / W;
     dim3 grid((nstrips + kWavesPerBlock2d - 1) / kWavesPerBlock2d, (a.ny + a.ychunk - 1) / a.ychunk);
@@ -239,10 +241,10 @@ static hipError_t launch_adj2d(const Wave2dArgs &a0, hipStream_t stream)
 }
 
 template <class T, int PX>
-static hipError_t launch_pri2d(const Wave2dArgs &a0, hipStream_t stream)
+static hipError_t launch_pri2d(const Wave2dArgs &a0, const LaunchOptions &opt, hipStream_t stream)
 {
     Wave2dArgs a = a0;
-    a.ychunk = 64;
+    a.ychunk = opt.ychunk2d > 0 ? (int)opt.ychunk2d : 32;
     constexpr int W = 64 * PX;
     const int nstrips = (a.nx + W - 1) / W;
     const int rows = a.ny - 2;
@@ -253,33 +255,33 @@ static hipError_t launch_pri2d(const Wave2dArgs &a0, hipStream_t stream)
 }
 
 hipError_t launch_adjoint_wave2d(int is_f64, int nx, int ny, const void *c, const void *r_bar,
-                                 void *u_bar, void *u_prev_bar, hipStream_t stream)
+                                 void *u_bar, void *u_prev_bar, const LaunchOptions &opt, hipStream_t stream)
 {
     Wave2dArgs a{};
     a.c = c; a.r_bar = r_bar; a.u_bar = u_bar; a.u_prev_bar = u_prev_bar;
     a.nx = nx; a.ny = ny;
     const bool al = aligned16(c) && aligned16(r_bar) && aligned16(u_bar) && aligned16(u_prev_bar);
     if (is_f64) {
-        if (al && nx % 2 == 0) return launch_adj2d<double, 2>(a, stream);
-        return launch_adj2d<double, 1>(a, stream);
+        if (al && nx % 2 == 0) return launch_adj2d<double, 2>(a, opt, stream);
+        return launch_adj2d<double, 1>(a, opt, stream);
     }
-    if (al && nx % 4 == 0) return launch_adj2d<float, 4>(a, stream);
-    return launch_adj2d<float, 1>(a, stream);
+    if (al && nx % 4 == 0) return launch_adj2d<float, 4>(a, opt, stream);
+    return launch_adj2d<float, 1>(a, opt, stream);
 }
 
 hipError_t launch_primal_wave2d(int is_f64, int nx, int ny, const void *u, const void *u_prev,
-                                const void *c, void *r, hipStream_t stream)
+                                const void *c, void *r, const LaunchOptions &opt, hipStream_t stream)
 {
     Wave2dArgs a{};
     a.u = u; a.u_prev = u_prev; a.c = c; a.r = r;
     a.nx = nx; a.ny = ny;
     const bool al = aligned16(u) && aligned16(u_prev) && aligned16(c) && aligned16(r);
     if (is_f64) {
-        if (al && nx % 2 == 0) return launch_pri2d<double, 2>(a, stream);
-        return launch_pri2d<double, 1>(a, stream);
+        if (al && nx % 2 == 0) return launch_pri2d<double, 2>(a, opt, stream);
+        return launch_pri2d<double, 1>(a, opt, stream);
     }
-    if (al && nx % 4 == 0) return launch_pri2d<float, 4>(a, stream);
-    return launch_pri2d<float, 1>(a, stream);
+    if (al && nx % 4 == 0) return launch_pri2d<float, 4>(a, opt, stream);
+    return launch_pri2d<float, 1>(a, opt, stream);
 }
 
 }  // namespace sadj
