@@ -125,6 +125,7 @@ sadj_status sadj_adjoint_burgers1d(sadj_dtype dtype, long n, double C, double D,
  *   "wave3d.zchunk"  planes of output per workgroup along z (default 0 = automatic).
  *   "wave3d.variant" tile-shape variant index (default 0 = automatic).
  *   "wave2d.ychunk"  rows of output per wave along y (default 0 = automatic).
+ *   "wave2d.variant" load-pipeline depth / workgroup size variant (default 0 = automatic).
  * Unknown names or out-of-range values give SADJ_ERR_UNSUPPORTED and change nothing.
  * sadj_get_option returns SADJ_OK and stores the value, or SADJ_ERR_UNSUPPORTED.
  */

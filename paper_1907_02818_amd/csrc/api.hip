@@ -9,7 +9,7 @@
 
 namespace {
 
-std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0};
+std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0}, g_variant2d{0};
 
 sadj::LaunchOptions current_options()
 {
@@ -17,6 +17,7 @@ sadj::LaunchOptions current_options()
     o.zchunk = g_zchunk.load();
     o.variant = g_variant.load();
     o.ychunk2d = g_ychunk2d.load();
+    o.variant2d = g_variant2d.load();
     return o;
 }
 
@@ -109,6 +110,11 @@ sadj_status sadj_set_option(const char *name, long value)
         g_ychunk2d = value;
         return SADJ_OK;
     }
+    if (!std::strcmp(name, "wave2d.variant")) {
+        if (value < 0 || value > 15) return SADJ_ERR_UNSUPPORTED;
+        g_variant2d = value;
+        return SADJ_OK;
+    }
 
     return SADJ_ERR_UNSUPPORTED;
 }
@@ -119,6 +125,7 @@ sadj_status sadj_get_option(const char *name, long *value)
     if (!std::strcmp(name, "wave3d.zchunk")) { *value = g_zchunk; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.variant")) { *value = g_variant; return SADJ_OK; }
     if (!std::strcmp(name, "wave2d.ychunk")) { *value = g_ychunk2d; return SADJ_OK; }
+    if (!std::strcmp(name, "wave2d.variant")) { *value = g_variant2d; return SADJ_OK; }
     return SADJ_ERR_UNSUPPORTED;
 }
 

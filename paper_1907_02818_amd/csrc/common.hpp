@@ -67,6 +67,25 @@ template <class T, int N> __device__ __forceinline__ void st_vec(T *p, const Vec
     *reinterpret_cast<Vec<T, N> *>(p) = v;
 }
 
+// Streaming (non-temporal) variants for data that is touched exactly once.
+template <class T, int N> __device__ __forceinline__ Vec<T, N> ld_vec_stream(const T *p)
+{
+    typedef T VT __attribute__((ext_vector_type(N)));
+    const VT t = __builtin_nontemporal_load(reinterpret_cast<const VT *>(p));
+    Vec<T, N> r;
+#pragma unroll
+    for (int e = 0; e < N; ++e) r.v[e] = t[e];
+    return r;
+}
+template <class T, int N> __device__ __forceinline__ void st_vec_stream(T *p, const Vec<T, N> &v)
+{
+    typedef T VT __attribute__((ext_vector_type(N)));
+    VT t;
+#pragma unroll
+    for (int e = 0; e < N; ++e) t[e] = v.v[e];
+    __builtin_nontemporal_store(t, reinterpret_cast<VT *>(p));
+}
+
 // Neighbour exchange inside a 64-lane wave whose lanes own PX consecutive elements
 // each: left = element just before this lane's first, right = element just after
 // its last.  `halo` holds, in lane 0, the element before the wave's segment and, in

@@ -8,6 +8,7 @@ struct LaunchOptions {
     long zchunk = 0;     // wave3d: output planes per workgroup (0 = automatic)
     long variant = 0;    // wave3d: tile-shape variant
     long ychunk2d = 0;   // wave2d: output rows per wave (0 = automatic)
+    long variant2d = 0;  // wave2d: pipeline depth / workgroup size variant
 };
 
 hipError_t launch_adjoint_wave3d(int is_f64, int radius, int nx, int ny, int nz, const void *c,

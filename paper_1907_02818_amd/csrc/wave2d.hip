@@ -17,6 +17,8 @@
 #include "common.hpp"
 #include "launch.hpp"
 
+#include <type_traits>
+
 namespace sadj {
 
 struct Wave2dArgs {
@@ -30,7 +32,10 @@ struct Wave2dArgs {
 
 constexpr int kWavesPerBlock2d = 4;
 
-template <class T, int PX, bool GUARD, bool UPREV>
+// D rows of loads are kept in flight per wave.  In the steady part of the march every
+// row of a step is known to exist, so that part is compiled without branches and the
+// compiler can count exactly which loads may still be outstanding.
+template <class T, int PX, int D, bool GUARD, bool UPREV>
 __device__ __forceinline__ void adj2d_strip(const Wave2dArgs &a, int xs, int ys, int ye, int lane)
 {
     constexpr int W = 64 * PX;
@@ -55,48 +60,57 @@ __device__ __forceinline__ void adj2d_strip(const Wave2dArgs &a, int xs, int ys,
     T acc[PX][3];
 #pragma unroll
     for (int e = 0; e < PX; ++e) acc[e][0] = acc[e][1] = acc[e][2] = T(0);
-    V ncv{}, nrv{}, nuv{}, npv{};
-    T nhc = T(0), nhr = T(0);
+    V sc[D], sr[D], su[D], sp[D];
+    T shc[D], shr[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        sc[d] = V{}; sr[d] = V{}; su[d] = V{}; sp[d] = V{};
+        shc[d] = shr[d] = T(0);
+    }
 
-    auto row_in_I = [&](int y) { return GUARD ? (y >= 1 && y <= ny - 2) : true; };
-    auto load_row = [&](int y) {
-        const T *cp = cg + (size_t)y * nx;
-        const T *rp = rg + (size_t)y * nx;
-        ncv = ld_vec<T, PX>(cp + xc);
-        nrv = ld_vec<T, PX>(rp + xc);
-        if (edge_lane) { nhc = cp[hxc]; nhr = rp[hxc]; }     // only lanes 0 and 63 use the value
-        if (UPREV) {
-            if (y >= ys && y < ye) npv = ld_vec<T, PX>(pg + (size_t)y * nx + xc);
+    const int yi0 = ys - 1, yi1 = ye;            // input rows that reach output rows [ys, ye)
+    auto row_in_I = [&](int y) { return y >= 1 && y <= ny - 2; };
+
+    auto issue = [&](int y, auto dc, auto steady) {
+        constexpr int d = decltype(dc)::value;
+        constexpr bool STEADY = decltype(steady)::value;
+        if (!STEADY && y > yi1) return;
+        if (STEADY || row_in_I(y)) {
+            const T *cp = cg + (size_t)y * nx;
+            const T *rp = rg + (size_t)y * nx;
+            sc[d] = ld_vec<T, PX>(cp + xc);
+            sr[d] = ld_vec<T, PX>(rp + xc);
+            if (edge_lane) { shc[d] = cp[hxc]; shr[d] = rp[hxc]; }   // only lanes 0 and 63 use the value
+            if (UPREV) {
+                if (STEADY || (y >= ys && y < ye)) sp[d] = ld_vec_stream<T, PX>(pg + (size_t)y * nx + xc);
+            }
         }
+        const int yo = y - 1;
+        if (STEADY || yo >= ys) su[d] = ld_vec_stream<T, PX>(ug + (size_t)yo * nx + xc);
     };
-    const int yi0 = ys - 1, yi1 = ye;
-    if (row_in_I(yi0)) load_row(yi0);
-    for (int yi = yi0; yi <= yi1; ++yi) {
-        const bool rin = row_in_I(yi);
+
+    auto step = [&](int yi, auto dc, auto steady) {
+        constexpr int d = decltype(dc)::value;
+        constexpr bool STEADY = decltype(steady)::value;
+        const bool rin = STEADY || row_in_I(yi);
         const int yo = yi - 1;
-        T q[PX], rr[PX], qh = T(0);
+        const V cu = su[d];
         if (rin) {
+            T q[PX], rr[PX];
 #pragma unroll
             for (int e = 0; e < PX; ++e) {
-                rr[e] = GUARD ? (xin[e] ? nrv.v[e] : T(0)) : nrv.v[e];
-                q[e] = GUARD ? (xin[e] ? ncv.v[e] * nrv.v[e] : T(0)) : ncv.v[e] * nrv.v[e];
+                rr[e] = GUARD ? (xin[e] ? sr[d].v[e] : T(0)) : sr[d].v[e];
+                q[e] = GUARD ? (xin[e] ? sc[d].v[e] * sr[d].v[e] : T(0)) : sc[d].v[e] * sr[d].v[e];
             }
-            qh = GUARD ? (hin ? nhc * nhr : T(0)) : nhc * nhr;
+            const T qh = GUARD ? (hin ? shc[d] * shr[d] : T(0)) : shc[d] * shr[d];
             if (UPREV) {
-                if (yi >= ys && yi < ye && active) {
+                if ((STEADY || (yi >= ys && yi < ye)) && active) {
                     V o;
 #pragma unroll
-                    for (int e = 0; e < PX; ++e) o.v[e] = npv.v[e] - rr[e];
-                    st_vec<T, PX>(pg + (size_t)yi * nx + x, o);
+                    for (int e = 0; e < PX; ++e) o.v[e] = sp[d].v[e] - rr[e];
+                    st_vec_stream<T, PX>(pg + (size_t)yi * nx + x, o);
                 }
             }
-        }
-        const V cu = nuv;
-        if (yi + 1 <= yi1) {
-            if (row_in_I(yi + 1)) load_row(yi + 1);
-            if (yo + 1 >= ys) nuv = ld_vec<T, PX>(ug + (size_t)(yo + 1) * nx + xc);
-        }
-        if (rin) {
             T left, right;
             wave_neighbours<T, PX>(q, qh, lane, left, right);
 #pragma unroll
@@ -108,11 +122,12 @@ __device__ __forceinline__ void adj2d_strip(const Wave2dArgs &a, int xs, int ys,
                 acc[e][2] += q[e];
             }
         }
-        if (yo >= ys && active) {
+        issue(yi + D, dc, steady);
+        if ((STEADY || yo >= ys) && active) {
             V o;
 #pragma unroll
             for (int e = 0; e < PX; ++e) o.v[e] = cu.v[e] + acc[e][0];
-            st_vec<T, PX>(ug + (size_t)yo * nx + x, o);
+            st_vec_stream<T, PX>(ug + (size_t)yo * nx + x, o);
         }
 #pragma unroll
         for (int e = 0; e < PX; ++e) {
@@ -120,21 +135,56 @@ __device__ __forceinline__ void adj2d_strip(const Wave2dArgs &a, int xs, int ys,
             acc[e][1] = acc[e][2];
             acc[e][2] = T(0);
         }
+    };
+    using No = std::integral_constant<bool, false>;
+    using Yes = std::integral_constant<bool, true>;
+    auto step_any = [&](int yi, int d) {
+        if (D == 1 || d == 0) step(yi, std::integral_constant<int, 0>{}, No{});
+        else if (D == 2 || d == 1) step(yi, std::integral_constant<int, (D > 1 ? 1 : 0)>{}, No{});
+        else if (D == 3 || d == 2) step(yi, std::integral_constant<int, (D > 2 ? 2 : 0)>{}, No{});
+        else step(yi, std::integral_constant<int, (D > 3 ? 3 : 0)>{}, No{});
+    };
+    issue(yi0, std::integral_constant<int, 0>{}, No{});
+    if (D > 1) issue(yi0 + 1, std::integral_constant<int, (D > 1 ? 1 : 0)>{}, No{});
+    if (D > 2) issue(yi0 + 2, std::integral_constant<int, (D > 2 ? 2 : 0)>{}, No{});
+    if (D > 3) issue(yi0 + 3, std::integral_constant<int, (D > 3 ? 3 : 0)>{}, No{});
+
+    // steady steps yi in [lo, hi]: rows yi and yi+D lie in I and in this chunk's input
+    // range; output rows yi-1 and yi+D-1 (for u_prev_bar: yi and yi+D) belong to the chunk
+    const int lo = ys + 1;
+    const int hi = min(ny - 1, ye) - 1 - D;
+    int yi = yi0, d = 0;
+    while (yi <= yi1 && (yi < lo || d != 0)) {
+        step_any(yi, d);
+        ++yi;
+        d = d + 1 == D ? 0 : d + 1;
+    }
+    while (yi + D - 1 <= hi) {
+        step(yi, std::integral_constant<int, 0>{}, Yes{});
+        if (D > 1) step(yi + 1, std::integral_constant<int, (D > 1 ? 1 : 0)>{}, Yes{});
+        if (D > 2) step(yi + 2, std::integral_constant<int, (D > 2 ? 2 : 0)>{}, Yes{});
+        if (D > 3) step(yi + 3, std::integral_constant<int, (D > 3 ? 3 : 0)>{}, Yes{});
+        yi += D;
+    }
+    while (yi <= yi1) {
+        step_any(yi, d);
+        ++yi;
+        d = d + 1 == D ? 0 : d + 1;
     }
 }
 
-template <class T, int PX, bool UPREV>
-__global__ __launch_bounds__(64 * kWavesPerBlock2d) void adj_wave2d_kernel(Wave2dArgs a)
+template <class T, int PX, int D, int WAVES, bool UPREV>
+__global__ __launch_bounds__(64 * WAVES) void adj_wave2d_kernel(Wave2dArgs a)
 {
     constexpr int W = 64 * PX;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int xs = (blockIdx.x * kWavesPerBlock2d + wave) * W;
+    const int xs = (blockIdx.x * WAVES + wave) * W;
     if (xs >= a.nx) return;                     // wave-uniform; the kernel has no barrier
     const int ys = blockIdx.y * a.ychunk;
     const int ye = min(ys + a.ychunk, a.ny);
     const bool core = xs >= 2 && xs + W <= a.nx - 2 && ys >= 2 && ye <= a.ny - 2;
-    if (core) adj2d_strip<T, PX, false, UPREV>(a, xs, ys, ye, lane);
-    else      adj2d_strip<T, PX, true, UPREV>(a, xs, ys, ye, lane);
+    if (core) adj2d_strip<T, PX, D, false, UPREV>(a, xs, ys, ye, lane);
+    else      adj2d_strip<T, PX, D, true, UPREV>(a, xs, ys, ye, lane);
 }
 
 // ------------------------------------------------------------------------- primal
@@ -226,18 +276,42 @@ __global__ __launch_bounds__(64 * kWavesPerBlock2d) void primal_wave2d_kernel(Wa
 // ------------------------------------------------------------------------ launchers
 static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-template <class T, int PX>
-static hipError_t launch_adj2d(const Wave2dArgs &a0, const LaunchOptions &opt, hipStream_t stream)
+template <class T, int PX, int D, int WAVES>
+static hipError_t launch_adj2d_cfg(Wave2dArgs a, const LaunchOptions &opt, hipStream_t stream)
 {
-    Wave2dArgs a = a0;
-    a.ychunk = opt.ychunk2d > 0 ? (int)opt.ychunk2d : 32;
     constexpr int W = 64 * PX;
     const int nstrips = (a.nx + W - 1) / W;
-    dim3 grid((nstrips + kWavesPerBlock2d - 1) / kWavesPerBlock2d, (a.ny + a.ychunk - 1) / a.ychunk);
-    dim3 block(64 * kWavesPerBlock2d);
-    if (a.u_prev_bar) hipLaunchKernelGGL((adj_wave2d_kernel<T, PX, true>), grid, block, 0, stream, a);
-    else              hipLaunchKernelGGL((adj_wave2d_kernel<T, PX, false>), grid, block, 0, stream, a);
+    const int bx = (nstrips + WAVES - 1) / WAVES;
+    int ychunk = (int)opt.ychunk2d;
+    if (ychunk <= 0) {
+        // about one workgroup per CU: few waves, each with D rows in flight, marching long
+        // columns, so that the set of rows being streamed at any moment stays small
+        int dev = 0, ncu = 256, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            ncu = v;
+        const int chunks = bx >= ncu ? 1 : (ncu + bx - 1) / bx;
+        ychunk = (a.ny + chunks - 1) / chunks;
+        if (ychunk < 16) ychunk = 16;
+    }
+    if (ychunk > a.ny) ychunk = a.ny;
+    a.ychunk = ychunk;
+    dim3 grid(bx, (a.ny + ychunk - 1) / ychunk), block(64 * WAVES);
+    if (a.u_prev_bar) hipLaunchKernelGGL((adj_wave2d_kernel<T, PX, D, WAVES, true>), grid, block, 0, stream, a);
+    else              hipLaunchKernelGGL((adj_wave2d_kernel<T, PX, D, WAVES, false>), grid, block, 0, stream, a);
     return hipGetLastError();
+}
+
+template <class T, int PX>
+static hipError_t launch_adj2d(const Wave2dArgs &a, const LaunchOptions &opt, hipStream_t stream)
+{
+    switch (opt.variant2d) {
+    default:
+    case 0: return launch_adj2d_cfg<T, PX, 2, 8>(a, opt, stream);
+    case 1: return launch_adj2d_cfg<T, PX, 1, 4>(a, opt, stream);
+    case 2: return launch_adj2d_cfg<T, PX, 4, 8>(a, opt, stream);
+    case 3: return launch_adj2d_cfg<T, PX, 2, 16>(a, opt, stream);
+    }
 }
 
 template <class T, int PX>

@@ -265,13 +265,8 @@ static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipSt
     case 2: return launch_cfg<T, R, 128, 8, 2, 1, true>(a, opt, stream);
     case 3: return launch_cfg<T, R, 64, 8, 4, 2, true>(a, opt, stream);
     case 4: return launch_cfg<T, R, 64, 4, 4, 1, true>(a, opt, stream);
-    case 5: return launch_cfg<T, R, 64, 8, 2, 2, true>(a, opt, stream);
+    case 5: return launch_cfg<T, R, 128, 4, 4, 1, true>(a, opt, stream);
     case 6: return launch_cfg<T, R, 64, 8, 4, 1, false>(a, opt, stream);
-    case 7: return launch_cfg<T, R, 64, 16, 2, 1, true>(a, opt, stream);
-    case 8: return launch_cfg<T, R, 32, 16, 4, 1, true>(a, opt, stream);
-    case 9: return launch_cfg<T, R, 128, 4, 4, 1, true>(a, opt, stream);
-    case 10: return launch_cfg<T, R, 256, 2, 4, 1, true>(a, opt, stream);
-    case 11: return launch_cfg<T, R, 64, 8, 8, 1, true>(a, opt, stream);
     }
 }
 

@@ -165,6 +165,25 @@ def test_wave2d_adjoint_and_primal(sadj, shape, dtype):
     assert_close(got[m], want[m], np.abs(want[m]) + 3.0, dtype, "wave2d primal %s" % (shape,))
 
 
+@pytest.mark.parametrize("variant,ychunk", [(0, 0), (0, 5), (1, 16), (2, 7), (2, 0), (3, 33)])
+def test_wave2d_variants(sadj, variant, ychunk):
+    shape = (131, 523)
+    d = inputs.wave_inputs(shape, 0.01, 0.2, seed=variant + ychunk)
+    sadj.set_option("wave2d.variant", variant)
+    sadj.set_option("wave2d.ychunk", ychunk)
+    try:
+        ub, upb = to_gpu(d["u_bar"]), to_gpu(d["u_prev_bar"])
+        sadj.sadj_adjoint_wave2d(to_gpu(d["c"]), to_gpu(d["r_bar"]), ub, upb)
+        _sync()
+    finally:
+        sadj.set_option("wave2d.variant", 0)
+        sadj.set_option("wave2d.ychunk", 0)
+    want, wantp, scale = oracle.wave_adjoint(d["c"], d["r_bar"], d["u_bar"], 1, u_prev_bar=d["u_prev_bar"],
+                                             want_scale=True)
+    assert_close(to_host(ub), want, scale + np.abs(d["u_bar"]), np.float64, "wave2d variant %d" % variant)
+    assert_close(to_host(upb), wantp, np.abs(d["u_prev_bar"]) + np.abs(d["r_bar"]), np.float64, "u_prev_bar")
+
+
 def test_wave2d_nan_outside_interior_and_reproducible(sadj):
     shape = (150, 390)
     d = inputs.wave_inputs(shape, 0.01, 0.2, seed=4)
