@@ -1,14 +1,15 @@
 // Geometry shared by the 3-D marching kernels: an x-y tile of TX x TY cells owned by a
-// workgroup of BX x BY threads (PY consecutive rows per thread), staged in LDS with a
+// workgroup of BX x BY threads (PX consecutive cells in x times PY consecutive rows
+// per thread), staged in LDS with a
 // halo of width R on all four sides (corners omitted: a star never reads them).
 #pragma once
 #include "common.hpp"
 
 namespace sadj {
 
-template <class T, int R, int BX, int BY, int PY>
+template <class T, int R, int BX, int BY, int PY, int PX = 1>
 struct Tile3d {
-    static constexpr int TX = BX, TY = BY * PY, NT = BX * BY;
+    static constexpr int TX = BX * PX, TY = BY * PY, NT = BX * BY;
     static constexpr int LX = TX + 2 * R, LY = TY + 2 * R;      // LDS plane extents
     static constexpr int PLANE = LX * LY;
     static constexpr int NH = 2 * R * TX + 2 * R * TY;          // halo cells without corners
@@ -77,6 +78,19 @@ template <class T, bool NT> __device__ __forceinline__ void st_stream(T *base, u
     T *p = reinterpret_cast<T *>(reinterpret_cast<char *>(base) + byte_off);
     if (NT) __builtin_nontemporal_store(v, p);
     else *p = v;
+}
+
+// PX consecutive cells at a 32-bit byte offset from a uniform base pointer.
+template <class T, int N, bool NT> __device__ __forceinline__ Vec<T, N> ld_vec_off(const T *base, uint32_t byte_off)
+{
+    const T *p = reinterpret_cast<const T *>(reinterpret_cast<const char *>(base) + byte_off);
+    return NT ? ld_vec_stream<T, N>(p) : ld_vec<T, N>(p);
+}
+template <class T, int N, bool NT> __device__ __forceinline__ void st_vec_off(T *base, uint32_t byte_off, const Vec<T, N> &v)
+{
+    T *p = reinterpret_cast<T *>(reinterpret_cast<char *>(base) + byte_off);
+    if (NT) st_vec_stream<T, N>(p, v);
+    else st_vec<T, N>(p, v);
 }
 
 }  // namespace sadj

@@ -45,11 +45,12 @@
 
 namespace sadj {
 
-template <class T, int R, int BX, int BY, int PY, int D, bool NTU, bool GUARD, bool UPREV>
+template <class T, int R, int BX, int BY, int PY, int PX, int D, bool NTU, bool GUARD, bool UPREV>
 __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int tiy, int tiz,
                                             T *__restrict__ sq)
 {
-    using G = Tile3d<T, R, BX, BY, PY>;
+    using G = Tile3d<T, R, BX, BY, PY, PX>;
+    using V = Vec<T, PX>;
     constexpr int TX = G::TX, TY = G::TY, LX = G::LX, LY = G::LY, HS = G::HS;
     constexpr int NACC = 2 * R + 1;
     const int tid = threadIdx.x;
@@ -68,20 +69,18 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
     // A cell that is always inside the grid: unused slots load it and discard it.
     const uint32_t dummy = (uint32_t)((size_t)y0 * nx + x0) * sizeof(T);
 
-    // ---- owned points: x = x0+tx, y = y0 + ty*PY + p
+    // ---- owned cells: x = x0 + tx*PX + e, y = y0 + ty*PY + p  (nx is a multiple of PX,
+    //      so a vector of PX cells is entirely inside or entirely outside the grid)
     uint32_t ooff[PY];
-    bool ouse[PY], ostore[PY];
-    const int x = x0 + tx;
+    bool ouse[PY][PX], ostore[PY];
+    const int x = x0 + tx * PX;
 #pragma unroll
     for (int p = 0; p < PY; ++p) {
         const int y = y0 + ty * PY + p;
-        if (GUARD) {
-            ouse[p] = x >= R && x < nx - R && y >= R && y < ny - R;
-            ostore[p] = x < nx && y < ny;
-        } else {
-            ouse[p] = true;
-            ostore[p] = true;
-        }
+        ostore[p] = GUARD ? (x < nx && y < ny) : true;
+#pragma unroll
+        for (int e = 0; e < PX; ++e)
+            ouse[p][e] = GUARD ? (x + e >= R && x + e < nx - R && y >= R && y < ny - R) : true;
         ooff[p] = ostore[p] ? (uint32_t)((size_t)y * nx + x) * sizeof(T) : dummy;
     }
     // ---- halo slots
@@ -97,21 +96,24 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
         if (GUARD) use = use && gx >= R && gx < nx - R && gy >= R && gy < ny - R;
         huse[s] = use;
         hoff[s] = use ? (uint32_t)((size_t)gy * nx + gx) * sizeof(T) : dummy;
-        hlds[s] = slot ? ly * LX + lx : 0;      // cell (0,0) is a corner nobody reads
+        hlds[s] = slot ? ly * LX + lx : 0;        // cell (0,0) is a corner nobody reads
     }
 
-    T acc[PY][NACC];
+    T acc[PY][PX][NACC];
 #pragma unroll
     for (int p = 0; p < PY; ++p)
 #pragma unroll
-        for (int k = 0; k < NACC; ++k) acc[p][k] = T(0);
+        for (int e = 0; e < PX; ++e)
+#pragma unroll
+            for (int k = 0; k < NACC; ++k) acc[p][e][k] = T(0);
 
     // D stages of values in flight
-    T sc[D][PY], sr[D][PY], shc[D][HS], shr[D][HS], su[D][PY], sp[D][PY];
+    V sc[D][PY], sr[D][PY], su[D][PY], sp[D][PY];
+    T shc[D][HS], shr[D][HS];
 #pragma unroll
     for (int d = 0; d < D; ++d) {
 #pragma unroll
-        for (int p = 0; p < PY; ++p) { sc[d][p] = sr[d][p] = su[d][p] = sp[d][p] = T(0); }
+        for (int p = 0; p < PY; ++p) { sc[d][p] = V{}; sr[d][p] = V{}; su[d][p] = V{}; sp[d][p] = V{}; }
 #pragma unroll
         for (int s = 0; s < HS; ++s) { shc[d][s] = shr[d][s] = T(0); }
     }
@@ -126,14 +128,17 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
             const T *cp = cg + (size_t)z * plane;
             const T *rp = rg + (size_t)z * plane;
 #pragma unroll
-            for (int p = 0; p < PY; ++p) { sc[d][p] = ld_off(cp, ooff[p]); sr[d][p] = ld_off(rp, ooff[p]); }
+            for (int p = 0; p < PY; ++p) {
+                sc[d][p] = ld_vec_off<T, PX, false>(cp, ooff[p]);
+                sr[d][p] = ld_vec_off<T, PX, false>(rp, ooff[p]);
+            }
 #pragma unroll
             for (int s = 0; s < HS; ++s) { shc[d][s] = ld_off(cp, hoff[s]); shr[d][s] = ld_off(rp, hoff[s]); }
             if (UPREV) {
                 if (z >= zs && z < ze) {
                     const T *pp = upg + (size_t)z * plane;
 #pragma unroll
-                    for (int p = 0; p < PY; ++p) sp[d][p] = ld_stream<T, NTU>(pp, ooff[p]);
+                    for (int p = 0; p < PY; ++p) sp[d][p] = ld_vec_off<T, PX, NTU>(pp, ooff[p]);
                 }
             }
         }
@@ -141,7 +146,7 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
         if (zo >= zs) {                            // zo <= ze-1 because z <= zi1
             const T *up = ug + (size_t)zo * plane;
 #pragma unroll
-            for (int p = 0; p < PY; ++p) su[d][p] = ld_stream<T, NTU>(up, ooff[p]);
+            for (int p = 0; p < PY; ++p) su[d][p] = ld_vec_off<T, PX, NTU>(up, ooff[p]);
         }
     };
 
@@ -150,18 +155,20 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
         const bool zin = plane_in_I(zi);
         const int zo = zi - R;
         T *sb = sq + buf * (LY * LX);
-        T qo[PY], ro[PY], cu[PY];
+        T qo[PY][PX], ro[PY][PX];
+        V cu[PY];
 #pragma unroll
         for (int p = 0; p < PY; ++p) cu[p] = su[d][p];
         if (zin) {
 #pragma unroll
-            for (int p = 0; p < PY; ++p) {
-                const T rr = GUARD ? (ouse[p] ? sr[d][p] : T(0)) : sr[d][p];
-                const T qq = GUARD ? (ouse[p] ? sc[d][p] * sr[d][p] : T(0)) : sc[d][p] * sr[d][p];
-                ro[p] = rr;
-                qo[p] = qq;
-                sb[(R + ty * PY + p) * LX + R + tx] = qq;
-            }
+            for (int p = 0; p < PY; ++p)
+#pragma unroll
+                for (int e = 0; e < PX; ++e) {
+                    const T cc = sc[d][p].v[e], rv = sr[d][p].v[e];
+                    ro[p][e] = GUARD ? (ouse[p][e] ? rv : T(0)) : rv;
+                    qo[p][e] = GUARD ? (ouse[p][e] ? cc * rv : T(0)) : cc * rv;
+                    sb[(R + ty * PY + p) * LX + R + tx * PX + e] = qo[p][e];
+                }
 #pragma unroll
             for (int s = 0; s < HS; ++s) {
                 const T qq = GUARD ? (huse[s] ? shc[d][s] * shr[d][s] : T(0)) : shc[d][s] * shr[d][s];
@@ -171,8 +178,12 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
                 if (zi >= zs && zi < ze) {
                     T *pp = upg + (size_t)zi * plane;
 #pragma unroll
-                    for (int p = 0; p < PY; ++p)
-                        if (!GUARD || ouse[p]) st_stream<T, NTU>(pp, ooff[p], sp[d][p] - ro[p]);
+                    for (int p = 0; p < PY; ++p) {
+                        V o;
+#pragma unroll
+                        for (int e = 0; e < PX; ++e) o.v[e] = sp[d][p].v[e] - ro[p][e];
+                        if (!GUARD || ostore[p]) st_vec_off<T, PX, NTU>(pp, ooff[p], o);
+                    }
                 }
             }
         }
@@ -180,22 +191,25 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
         issue(zi + D, d);
         if (zin) {
             __syncthreads();
-            T col[PY + 2 * R];
 #pragma unroll
-            for (int i = 0; i < PY + 2 * R; ++i) col[i] = sb[(ty * PY + i) * LX + R + tx];
+            for (int e = 0; e < PX; ++e) {
+                T col[PY + 2 * R];
 #pragma unroll
-            for (int p = 0; p < PY; ++p) {
-                const T *row = sb + (R + ty * PY + p) * LX + R + tx;
-                T s = T(3.0 * star_w<R>(0)) * qo[p];
+                for (int i = 0; i < PY + 2 * R; ++i) col[i] = sb[(ty * PY + i) * LX + R + tx * PX + e];
 #pragma unroll
-                for (int k = 1; k <= R; ++k) s += T(star_w<R>(k)) * (row[-k] + row[k]);
+                for (int p = 0; p < PY; ++p) {
+                    const T *row = sb + (R + ty * PY + p) * LX + R + tx * PX + e;
+                    T s = T(3.0 * star_w<R>(0)) * qo[p][e];
 #pragma unroll
-                for (int k = 1; k <= R; ++k) s += T(star_w<R>(k)) * (col[R + p - k] + col[R + p + k]);
-                acc[p][R] += s + T(2) * ro[p];
+                    for (int k = 1; k <= R; ++k) s += T(star_w<R>(k)) * (row[-k] + row[k]);
 #pragma unroll
-                for (int k = 1; k <= R; ++k) {
-                    acc[p][R - k] += T(star_w<R>(k)) * qo[p];
-                    acc[p][R + k] += T(star_w<R>(k)) * qo[p];
+                    for (int k = 1; k <= R; ++k) s += T(star_w<R>(k)) * (col[R + p - k] + col[R + p + k]);
+                    acc[p][e][R] += s + T(2) * ro[p][e];
+#pragma unroll
+                    for (int k = 1; k <= R; ++k) {
+                        acc[p][e][R - k] += T(star_w<R>(k)) * qo[p][e];
+                        acc[p][e][R + k] += T(star_w<R>(k)) * qo[p][e];
+                    }
                 }
             }
             buf ^= 1;
@@ -203,15 +217,21 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
         if (zo >= zs) {
             T *up = ug + (size_t)zo * plane;
 #pragma unroll
-            for (int p = 0; p < PY; ++p)
-                if (!GUARD || ostore[p]) st_stream<T, NTU>(up, ooff[p], cu[p] + acc[p][0]);
+            for (int p = 0; p < PY; ++p) {
+                V o;
+#pragma unroll
+                for (int e = 0; e < PX; ++e) o.v[e] = cu[p].v[e] + acc[p][e][0];
+                if (!GUARD || ostore[p]) st_vec_off<T, PX, NTU>(up, ooff[p], o);
+            }
         }
 #pragma unroll
-        for (int p = 0; p < PY; ++p) {
+        for (int p = 0; p < PY; ++p)
 #pragma unroll
-            for (int k = 0; k < NACC - 1; ++k) acc[p][k] = acc[p][k + 1];
-            acc[p][NACC - 1] = T(0);
-        }
+            for (int e = 0; e < PX; ++e) {
+#pragma unroll
+                for (int k = 0; k < NACC - 1; ++k) acc[p][e][k] = acc[p][e][k + 1];
+                acc[p][e][NACC - 1] = T(0);
+            }
     };
 
 #pragma unroll
@@ -223,10 +243,10 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
     }
 }
 
-template <class T, int R, int BX, int BY, int PY, int D, bool NTU, bool UPREV>
+template <class T, int R, int BX, int BY, int PY, int PX, int D, bool NTU, bool UPREV>
 __global__ __launch_bounds__(BX *BY) void adj_wave3d_kernel(March3dArgs a)
 {
-    using G = Tile3d<T, R, BX, BY, PY>;
+    using G = Tile3d<T, R, BX, BY, PY, PX>;
     __shared__ T sq[2 * G::PLANE];
     const int L = xcd_contiguous_id(blockIdx.x, a.total_blocks);
     const int tix = L % a.ntx;
@@ -236,37 +256,49 @@ __global__ __launch_bounds__(BX *BY) void adj_wave3d_kernel(March3dArgs a)
     // core tile: own cells and halo cells all inside I in x and y
     const int x0 = tix * G::TX, y0 = tiy * G::TY;
     const bool core = x0 >= 2 * R && x0 + G::TX + 2 * R <= a.nx && y0 >= 2 * R && y0 + G::TY + 2 * R <= a.ny;
-    if (core) adj3d_march<T, R, BX, BY, PY, D, NTU, false, UPREV>(a, tix, tiy, tiz, sq);
-    else      adj3d_march<T, R, BX, BY, PY, D, NTU, true, UPREV>(a, tix, tiy, tiz, sq);
+    if (core) adj3d_march<T, R, BX, BY, PY, PX, D, NTU, false, UPREV>(a, tix, tiy, tiz, sq);
+    else      adj3d_march<T, R, BX, BY, PY, PX, D, NTU, true, UPREV>(a, tix, tiy, tiz, sq);
 }
 
-template <class T, int R, int BX, int BY, int PY, int D, bool NTU>
+static inline bool aligned_to(const void *p, size_t n) { return (reinterpret_cast<uintptr_t>(p) % n) == 0; }
+
+template <class T, int R, int BX, int BY, int PY, int PX, int D, bool NTU>
 static hipError_t launch_cfg(March3dArgs a, const LaunchOptions &opt, hipStream_t stream)
 {
-    using G = Tile3d<T, R, BX, BY, PY>;
+    using G = Tile3d<T, R, BX, BY, PY, PX>;
+    if (PX > 1) {
+        // PX cells per lane and memory instruction need whole vectors: nx a multiple of
+        // PX and every array aligned to the vector size; otherwise use a PX = 1 shape
+        const size_t al = PX * sizeof(T);
+        const bool ok = a.nx % PX == 0 && aligned_to(a.in0, al) && aligned_to(a.in1, al) &&
+                        aligned_to(a.out0, al) && aligned_to(a.out1, al);
+        if (!ok) return launch_cfg<T, R, 64, 8, 4, 1, 1, true>(a, opt, stream);
+    }
     plan_march(a, G::TX, G::TY, R, opt.zchunk);
     dim3 grid(a.total_blocks), block(G::NT);
-    if (a.out1) hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, D, NTU, true>), grid, block, 0, stream, a);
-    else        hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, D, NTU, false>), grid, block, 0, stream, a);
+    if (a.out1) hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, true>), grid, block, 0, stream, a);
+    else        hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, false>), grid, block, 0, stream, a);
     return hipGetLastError();
 }
 
-// Tile shapes.  Variant 0 picks the measured best per dtype: rows of 512 bytes per
-// tile (64 doubles / 128 floats), 32 x 16 rows, one workgroup per CU.
+// Tile shapes <BX, BY, PY, PX, D, NT>.  Variant 0 picks the measured best per dtype:
+// 16 bytes per lane and memory instruction (two doubles / four floats), tile rows of
+// 512 bytes, 32 rows, 32 x 16 threads (a wave covers two rows), one workgroup per CU.
 template <class T, int R>
 static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipStream_t stream)
 {
-    switch (opt.variant) {
+    long v = opt.variant;
+    if (v == 0) v = sizeof(T) == 8 ? 1 : 2;
+    switch (v) {
     default:
-    case 0:
-        if (sizeof(T) == 8) return launch_cfg<T, R, 64, 8, 4, 1, true>(a, opt, stream);
-        return launch_cfg<T, R, 128, 8, 2, 1, true>(a, opt, stream);
-    case 1: return launch_cfg<T, R, 64, 8, 4, 1, true>(a, opt, stream);
-    case 2: return launch_cfg<T, R, 128, 8, 2, 1, true>(a, opt, stream);
-    case 3: return launch_cfg<T, R, 64, 8, 4, 2, true>(a, opt, stream);
-    case 4: return launch_cfg<T, R, 64, 4, 4, 1, true>(a, opt, stream);
-    case 5: return launch_cfg<T, R, 128, 4, 4, 1, true>(a, opt, stream);
-    case 6: return launch_cfg<T, R, 64, 8, 4, 1, false>(a, opt, stream);
+    case 1: return launch_cfg<T, R, 32, 16, 2, 2, 1, true>(a, opt, stream);     // fp64 default
+    case 2: return launch_cfg<T, R, 32, 16, 2, 4, 1, true>(a, opt, stream);     // fp32 default
+    case 3: return launch_cfg<T, R, 64, 8, 4, 1, 1, true>(a, opt, stream);      // 8 bytes per lane (fallback shape)
+    case 4: return launch_cfg<T, R, 64, 8, 4, 1, 2, true>(a, opt, stream);      // two planes in flight
+    case 5: return launch_cfg<T, R, 64, 8, 2, 2, 1, true>(a, opt, stream);      // 128 x 16 tile
+    case 6: return launch_cfg<T, R, 32, 16, 2, 2, 1, false>(a, opt, stream);    // u_bar through L2 (no streaming hint)
+    case 7: return launch_cfg<T, R, 64, 4, 4, 1, 1, true>(a, opt, stream);      // 64 x 16 tile, 256 threads
+    case 8: return launch_cfg<T, R, 64, 8, 4, 2, 1, true>(a, opt, stream);      // 128 x 32 tile, PX = 2
     }
 }
 

@@ -65,14 +65,14 @@ def test_adjoint_small(sadj, radius, shape, dtype):
     _check_adjoint(sadj, d, radius, dtype, with_prev=True, what="R=%d %s with u_prev_bar" % (radius, shape))
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8])
 @pytest.mark.parametrize("radius", [1, 4])
 def test_adjoint_tile_variants(sadj, radius, variant):
-    shape = (30, 75, 140)
-    d = inputs.config_inputs("wave3d_r4", shape=shape, seed=variant)      # layered c, as benchmarked
     sadj.set_option("wave3d.variant", variant)
     try:
-        _check_adjoint(sadj, d, radius, np.float64, with_prev=True, what="variant %d" % variant)
+        for shape, dtype in (((30, 75, 140), np.float64), ((23, 41, 270), np.float32), ((12, 70, 133), np.float32)):
+            d = inputs.config_inputs("wave3d_r4", shape=shape, seed=variant, dtype=dtype)   # layered c, as benchmarked
+            _check_adjoint(sadj, d, radius, dtype, with_prev=True, what="variant %d %s" % (variant, shape))
     finally:
         sadj.set_option("wave3d.variant", 0)
 
