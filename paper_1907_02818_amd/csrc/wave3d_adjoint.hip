@@ -288,7 +288,7 @@ template <class T, int R>
 static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipStream_t stream)
 {
     long v = opt.variant;
-    if (v == 0) v = sizeof(T) == 8 ? 1 : 2;
+    if (v == 0) v = a.out1 ? (sizeof(T) == 8 ? 3 : 8) : (sizeof(T) == 8 ? 1 : 2);   // measured best
     switch (v) {
     default:
     case 1: return launch_cfg<T, R, 32, 16, 2, 2, 1, true>(a, opt, stream);     // fp64 default

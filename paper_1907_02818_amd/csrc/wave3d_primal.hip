@@ -23,10 +23,11 @@
 
 namespace sadj {
 
-template <class T, int R, int BX, int BY, int PY, bool NTS>
+template <class T, int R, int BX, int BY, int PY, int PX, bool NTS>
 __global__ __launch_bounds__(BX *BY) void primal_wave3d_kernel(March3dArgs a)
 {
-    using G = Tile3d<T, R, BX, BY, PY>;
+    using G = Tile3d<T, R, BX, BY, PY, PX>;
+    using V = Vec<T, PX>;
     constexpr int TX = G::TX, TY = G::TY, LX = G::LX, HS = G::HS;
     constexpr int NACC = 2 * R + 1;
     constexpr int NB = R + 2;                       // LDS ring of planes
@@ -50,13 +51,19 @@ __global__ __launch_bounds__(BX *BY) void primal_wave3d_kernel(March3dArgs a)
     T *__restrict__ rg = static_cast<T *>(a.out0);
     const uint32_t dummy = (uint32_t)((size_t)y0 * nx + x0) * sizeof(T);
 
+    // owned cells: x = x0 + tx*PX + e, y = y0 + ty*PY + p (nx is a multiple of PX)
     uint32_t ooff[PY];
-    bool ostore[PY];
-    const int x = x0 + tx;
+    bool ostore[PY][PX], oall[PY];
+    const int x = x0 + tx * PX;
 #pragma unroll
     for (int p = 0; p < PY; ++p) {
         const int y = y0 + ty * PY + p;
-        ostore[p] = x >= R && x < nx - R && y >= R && y < ny - R;
+        oall[p] = true;
+#pragma unroll
+        for (int e = 0; e < PX; ++e) {
+            ostore[p][e] = x + e >= R && x + e < nx - R && y >= R && y < ny - R;
+            oall[p] = oall[p] && ostore[p][e];
+        }
         ooff[p] = (x < nx && y < ny) ? (uint32_t)((size_t)y * nx + x) * sizeof(T) : dummy;
     }
     uint32_t hoff[HS];
@@ -71,15 +78,18 @@ __global__ __launch_bounds__(BX *BY) void primal_wave3d_kernel(March3dArgs a)
         hlds[s] = slot ? ly * LX + lx : 0;          // cell (0,0) is a corner nobody reads
     }
 
-    T acc[PY][NACC];
+    T acc[PY][PX][NACC];
 #pragma unroll
     for (int p = 0; p < PY; ++p)
 #pragma unroll
-        for (int k = 0; k < NACC; ++k) acc[p][k] = T(0);
-
-    T su[PY], sh[HS], scc[PY], spp[PY];
+        for (int e = 0; e < PX; ++e)
 #pragma unroll
-    for (int p = 0; p < PY; ++p) { su[p] = scc[p] = spp[p] = T(0); }
+            for (int k = 0; k < NACC; ++k) acc[p][e][k] = T(0);
+
+    V su[PY], scc[PY], spp[PY];
+    T sh[HS];
+#pragma unroll
+    for (int p = 0; p < PY; ++p) { su[p] = V{}; scc[p] = V{}; spp[p] = V{}; }
 #pragma unroll
     for (int s = 0; s < HS; ++s) sh[s] = T(0);
 
@@ -92,7 +102,7 @@ __global__ __launch_bounds__(BX *BY) void primal_wave3d_kernel(March3dArgs a)
         if (z > zi1) return;
         const T *up = ug + (size_t)z * plane;
 #pragma unroll
-        for (int p = 0; p < PY; ++p) su[p] = ld_off(up, ooff[p]);
+        for (int p = 0; p < PY; ++p) su[p] = ld_vec_off<T, PX, false>(up, ooff[p]);
 #pragma unroll
         for (int s = 0; s < HS; ++s) sh[s] = ld_off(up, hoff[s]);
         const int zo = z - R;
@@ -100,43 +110,53 @@ __global__ __launch_bounds__(BX *BY) void primal_wave3d_kernel(March3dArgs a)
             const T *cp = cg + (size_t)zo * plane;
             const T *pp = pg + (size_t)zo * plane;
 #pragma unroll
-            for (int p = 0; p < PY; ++p) { scc[p] = ld_stream<T, NTS>(cp, ooff[p]); spp[p] = ld_stream<T, NTS>(pp, ooff[p]); }
+            for (int p = 0; p < PY; ++p) {
+                scc[p] = ld_vec_off<T, PX, NTS>(cp, ooff[p]);
+                spp[p] = ld_vec_off<T, PX, NTS>(pp, ooff[p]);
+            }
         }
     };
 
     issue(zi0);
-    int buf = 0, bufo = R % NB;                      // ring slots of plane zi and of plane zi-R (first output plane is zi0+R)
+    int buf = 0, bufo = R % NB;                      // ring slots of plane zi and of plane zi-R
     for (int zi = zi0; zi <= zi1; ++zi) {
         const int zo = zi - R;
         T *sb = sq + buf * G::PLANE;
-        T uo[PY], cc[PY], pp[PY];
+        T uo[PY][PX];
+        V cc[PY], pp[PY];
 #pragma unroll
         for (int p = 0; p < PY; ++p) {
-            uo[p] = su[p];
             cc[p] = scc[p];
             pp[p] = spp[p];
-            sb[(R + ty * PY + p) * LX + R + tx] = uo[p];
+#pragma unroll
+            for (int e = 0; e < PX; ++e) {
+                uo[p][e] = su[p].v[e];
+                sb[(R + ty * PY + p) * LX + R + tx * PX + e] = uo[p][e];
+            }
         }
 #pragma unroll
         for (int s = 0; s < HS; ++s) sb[hlds[s]] = sh[s];
         issue(zi + 1);
         __syncthreads();
-        T col[PY + 2 * R];
 #pragma unroll
-        for (int i = 0; i < PY + 2 * R; ++i) col[i] = sb[(ty * PY + i) * LX + R + tx];
+        for (int e = 0; e < PX; ++e) {
+            T col[PY + 2 * R];
 #pragma unroll
-        for (int p = 0; p < PY; ++p) {
-            const T *row = sb + (R + ty * PY + p) * LX + R + tx;
-            T s = T(3.0 * star_w<R>(0)) * uo[p];
+            for (int i = 0; i < PY + 2 * R; ++i) col[i] = sb[(ty * PY + i) * LX + R + tx * PX + e];
 #pragma unroll
-            for (int k = 1; k <= R; ++k) s += T(star_w<R>(k)) * (row[-k] + row[k]);
+            for (int p = 0; p < PY; ++p) {
+                const T *row = sb + (R + ty * PY + p) * LX + R + tx * PX + e;
+                T s = T(3.0 * star_w<R>(0)) * uo[p][e];
 #pragma unroll
-            for (int k = 1; k <= R; ++k) s += T(star_w<R>(k)) * (col[R + p - k] + col[R + p + k]);
-            acc[p][R] += s;
+                for (int k = 1; k <= R; ++k) s += T(star_w<R>(k)) * (row[-k] + row[k]);
 #pragma unroll
-            for (int k = 1; k <= R; ++k) {
-                acc[p][R - k] += T(star_w<R>(k)) * uo[p];
-                acc[p][R + k] += T(star_w<R>(k)) * uo[p];
+                for (int k = 1; k <= R; ++k) s += T(star_w<R>(k)) * (col[R + p - k] + col[R + p + k]);
+                acc[p][e][R] += s;
+#pragma unroll
+                for (int k = 1; k <= R; ++k) {
+                    acc[p][e][R - k] += T(star_w<R>(k)) * uo[p][e];
+                    acc[p][e][R + k] += T(star_w<R>(k)) * uo[p][e];
+                }
             }
         }
         if (zo >= zo0) {
@@ -145,29 +165,70 @@ __global__ __launch_bounds__(BX *BY) void primal_wave3d_kernel(March3dArgs a)
             T *rp = rg + (size_t)zo * plane;
 #pragma unroll
             for (int p = 0; p < PY; ++p) {
-                const T uc = so[(R + ty * PY + p) * LX + R + tx];
-                if (ostore[p]) st_stream<T, NTS>(rp, ooff[p], T(2) * uc - pp[p] + cc[p] * acc[p][0]);
+                V o;
+#pragma unroll
+                for (int e = 0; e < PX; ++e) {
+                    const T uc = so[(R + ty * PY + p) * LX + R + tx * PX + e];
+                    o.v[e] = T(2) * uc - pp[p].v[e] + cc[p].v[e] * acc[p][e][0];
+                }
+                if (oall[p]) {
+                    st_vec_off<T, PX, NTS>(rp, ooff[p], o);
+                } else {                              // r outside I stays untouched
+#pragma unroll
+                    for (int e = 0; e < PX; ++e)
+                        if (ostore[p][e]) st_stream<T, NTS>(rp, ooff[p] + e * (uint32_t)sizeof(T), o.v[e]);
+                }
             }
             bufo = bufo + 1 == NB ? 0 : bufo + 1;
         }
         buf = buf + 1 == NB ? 0 : buf + 1;
 #pragma unroll
-        for (int p = 0; p < PY; ++p) {
+        for (int p = 0; p < PY; ++p)
 #pragma unroll
-            for (int k = 0; k < NACC - 1; ++k) acc[p][k] = acc[p][k + 1];
-            acc[p][NACC - 1] = T(0);
-        }
+            for (int e = 0; e < PX; ++e) {
+#pragma unroll
+                for (int k = 0; k < NACC - 1; ++k) acc[p][e][k] = acc[p][e][k + 1];
+                acc[p][e][NACC - 1] = T(0);
+            }
     }
 }
 
-template <class T, int R, int BX, int BY, int PY>
+static inline bool aligned_to_p(const void *p, size_t n) { return (reinterpret_cast<uintptr_t>(p) % n) == 0; }
+
+template <class T, int R, int BX, int BY, int PY, int PX>
 static hipError_t launch_primal_cfg(March3dArgs a, const LaunchOptions &opt, hipStream_t stream)
 {
-    using G = Tile3d<T, R, BX, BY, PY>;
+    using G = Tile3d<T, R, BX, BY, PY, PX>;
+    if constexpr ((R + 2) * G::PLANE * sizeof(T) > 160 * 1024) {
+        return launch_primal_cfg<T, R, 64, 8, 4, 1>(a, opt, stream);      // ring would not fit the 160 KB LDS
+    } else {
+    if (PX > 1) {
+        const size_t al = PX * sizeof(T);
+        const bool ok = a.nx % PX == 0 && aligned_to_p(a.in0, al) && aligned_to_p(a.in1, al) &&
+                        aligned_to_p(a.in2, al) && aligned_to_p(a.out0, al);
+        if (!ok) return launch_primal_cfg<T, R, 64, 8, 4, 1>(a, opt, stream);
+    }
     plan_march(a, G::TX, G::TY, R, opt.zchunk);
-    hipLaunchKernelGGL((primal_wave3d_kernel<T, R, BX, BY, PY, true>), dim3(a.total_blocks), dim3(G::NT), 0,
+    hipLaunchKernelGGL((primal_wave3d_kernel<T, R, BX, BY, PY, PX, true>), dim3(a.total_blocks), dim3(G::NT), 0,
                        stream, a);
     return hipGetLastError();
+    }
+}
+
+// Same shape numbering as the adjoint kernel (option "wave3d.variant").
+template <class T, int R>
+static hipError_t launch_primal_T(const March3dArgs &a, const LaunchOptions &opt, hipStream_t stream)
+{
+    long v = opt.variant;
+    if (v == 0) v = sizeof(T) == 8 ? 3 : 8;      // measured best per dtype
+    switch (v) {
+    default:
+    case 1: return launch_primal_cfg<T, R, 32, 16, 2, 2>(a, opt, stream);
+    case 2: return launch_primal_cfg<T, R, 32, 16, 2, 4>(a, opt, stream);
+    case 3: return launch_primal_cfg<T, R, 64, 8, 4, 1>(a, opt, stream);
+    case 5: return launch_primal_cfg<T, R, 64, 8, 2, 2>(a, opt, stream);
+    case 8: return launch_primal_cfg<T, R, 64, 8, 4, 2>(a, opt, stream);
+    }
 }
 
 hipError_t launch_primal_wave3d(int is_f64, int radius, int nx, int ny, int nz, const void *u,
@@ -177,12 +238,8 @@ hipError_t launch_primal_wave3d(int is_f64, int radius, int nx, int ny, int nz, 
     March3dArgs a{};
     a.in0 = u; a.in1 = u_prev; a.in2 = c; a.out0 = r;
     a.nx = nx; a.ny = ny; a.nz = nz;
-    if (is_f64) {
-        if (radius == 1) return launch_primal_cfg<double, 1, 64, 8, 4>(a, opt, stream);
-        return launch_primal_cfg<double, 4, 64, 8, 4>(a, opt, stream);
-    }
-    if (radius == 1) return launch_primal_cfg<float, 1, 128, 8, 2>(a, opt, stream);
-    return launch_primal_cfg<float, 4, 128, 8, 2>(a, opt, stream);
+    if (is_f64) return radius == 1 ? launch_primal_T<double, 1>(a, opt, stream) : launch_primal_T<double, 4>(a, opt, stream);
+    return radius == 1 ? launch_primal_T<float, 1>(a, opt, stream) : launch_primal_T<float, 4>(a, opt, stream);
 }
 
 }  // namespace sadj
