@@ -93,10 +93,10 @@ template <class T, int N> __device__ __forceinline__ void st_vec_stream(T *p, co
 template <class T, int PX>
 __device__ __forceinline__ void wave_neighbours(const T (&v)[PX], T halo, int lane, T &left, T &right)
 {
-    left = __shfl_up(v[PX - 1], 1);
-    right = __shfl_down(v[0], 1);
-    if (lane == 0) left = halo;
-    if (lane == 63) right = halo;
+    const T from_left = __shfl_up(v[PX - 1], 1);
+    const T from_right = __shfl_down(v[0], 1);
+    left = lane == 0 ? halo : from_left;        // selects, so that left/right stay in registers
+    right = lane == 63 ? halo : from_right;
 }
 
 }  // namespace sadj
