@@ -179,6 +179,10 @@ def main():
         c2, rb2, ub2 = (t.reshape(-1)[: s2[0] * s2[1]].reshape(s2) for t in (c, rb, ub))
         add("wave2d_f64_adjoint", lambda: sadj.sadj_adjoint_wave2d(c2, rb2, ub2), s2[0] * s2[1],
             wave_adjoint_bytes(s2, 1, 8), "f64")
+        r2 = torch.empty_like(ub2)
+        add("wave2d_f64_primal", lambda: sadj.sadj_primal_wave2d(ub2, rb2, c2, r2), s2[0] * s2[1],
+            8 * s2[0] * s2[1] + 24 * interior_points(s2, 1), "f64")
+        del r2
         # Burgers 2^24, rotating three buffer sets so the arrays do not stay in the 256 MB last-level cache
         nb = 1 << 24
         sets = [tuple(t.reshape(-1)[k * nb:(k + 1) * nb] for t in (rb, c, ub)) for k in range(3)]
@@ -189,6 +193,12 @@ def main():
             state["i"] += 1
             sadj.sadj_adjoint_burgers1d(0.1, 0.05, u_, r_, b_)
         add("burgers1d_f64_adjoint", burg, nb, 32 * nb, "f64")
+
+        def burg_primal():
+            u_, r_, b_ = sets[state["i"] % 3]
+            state["i"] += 1
+            sadj.sadj_primal_burgers1d(0.1, 0.05, u_, b_)
+        add("burgers1d_f64_primal", burg_primal, nb, 16 * nb, "f64")
         n1 = 4096
         c1, rb1, ub1 = (t.reshape(-1)[:n1] for t in (c, rb, ub))
         add("wave1d_f64_adjoint_n4096_latency", lambda: sadj.sadj_adjoint_wave1d(c1, rb1, ub1), n1, 32 * n1, "f64")

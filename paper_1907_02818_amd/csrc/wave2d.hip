@@ -30,7 +30,6 @@ struct Wave2dArgs {
     int ychunk;
 };
 
-constexpr int kWavesPerBlock2d = 4;
 
 // D rows of loads are kept in flight per wave.  In the steady part of the march every
 // row of a step is known to exist, so that part is compiled without branches and the
@@ -189,17 +188,18 @@ __global__ __launch_bounds__(64 * WAVES) void adj_wave2d_kernel(Wave2dArgs a)
 
 // ------------------------------------------------------------------------- primal
 // r = 2u - u_prev + c*(u[x-1]+u[x+1]+u[y-1]+u[y+1]-4u) on I (paper Section 4.1 in two
-// dimensions).  Same march applied to u; u of the completing row is kept in a
-// two-deep register queue.  Only cells of I are stored.
-template <class T, int PX>
-__global__ __launch_bounds__(64 * kWavesPerBlock2d) void primal_wave2d_kernel(Wave2dArgs a)
+// dimensions).  Same march applied to u, with the same D-row load pipeline; u of the
+// completing row is the previous step's row and is kept in registers.  c, u_prev and r
+// are streamed.  Only cells of I are stored; reads of u never leave the grid.
+template <class T, int PX, int D, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void primal_wave2d_kernel(Wave2dArgs a)
 {
     constexpr int W = 64 * PX;
     using V = Vec<T, PX>;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nx = a.nx, ny = a.ny;
-    const int xs = (blockIdx.x * kWavesPerBlock2d + wave) * W;
-    if (xs >= nx) return;
+    const int xs = (blockIdx.x * WAVES + wave) * W;
+    if (xs >= nx) return;                                 // wave-uniform; no barrier in this kernel
     const int ys = 1 + blockIdx.y * a.ychunk;             // output rows cover [1, ny-1)
     const int ye = min(ys + a.ychunk, ny - 1);
     const T *__restrict__ ug = static_cast<const T *>(a.u);
@@ -215,30 +215,40 @@ __global__ __launch_bounds__(64 * kWavesPerBlock2d) void primal_wave2d_kernel(Wa
     for (int e = 0; e < PX; ++e) { xin[e] = x + e >= 1 && x + e <= nx - 2; all_in = all_in && xin[e]; }
     const int hx = lane < 32 ? xs - 1 : xs + W;
     const int hxc = (hx >= 0 && hx < nx) ? hx : xs;
-
-    T acc[PX][3], uq[PX][2];
-#pragma unroll
-    for (int e = 0; e < PX; ++e) { acc[e][0] = acc[e][1] = acc[e][2] = T(0); uq[e][0] = uq[e][1] = T(0); }
-    V nuv = ld_vec<T, PX>(ug + (size_t)(ys - 1) * nx + xc);
     const bool edge_lane = lane == 0 || lane == 63;
-    T nh = T(0);
-    if (edge_lane) nh = ug[(size_t)(ys - 1) * nx + hxc];
-    V ncv{}, npv{};
-    for (int yi = ys - 1; yi <= ye; ++yi) {
+
+    T acc[PX][3], uq[PX];
+#pragma unroll
+    for (int e = 0; e < PX; ++e) { acc[e][0] = acc[e][1] = acc[e][2] = T(0); uq[e] = T(0); }
+    V su[D], scc[D], spp[D];
+    T sh[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) { su[d] = V{}; scc[d] = V{}; spp[d] = V{}; sh[d] = T(0); }
+
+    const int yi0 = ys - 1, yi1 = ye;                     // all inside the grid
+    auto issue = [&](int y, auto dc, auto steady) {
+        constexpr int d = decltype(dc)::value;
+        constexpr bool STEADY = decltype(steady)::value;
+        if (!STEADY && y > yi1) return;
+        const T *up = ug + (size_t)y * nx;
+        su[d] = ld_vec<T, PX>(up + xc);
+        if (edge_lane) sh[d] = up[hxc];
+        const int yo = y - 1;
+        if (STEADY || yo >= ys) {
+            scc[d] = ld_vec_stream<T, PX>(cg + (size_t)yo * nx + xc);
+            spp[d] = ld_vec_stream<T, PX>(pg + (size_t)yo * nx + xc);
+        }
+    };
+    auto step = [&](int yi, auto dc, auto steady) {
+        constexpr int d = decltype(dc)::value;
+        constexpr bool STEADY = decltype(steady)::value;
         const int yo = yi - 1;
         T u0[PX];
 #pragma unroll
-        for (int e = 0; e < PX; ++e) u0[e] = nuv.v[e];
-        const T uh = nh;
-        const V cc = ncv, pp = npv;
-        if (yi + 1 <= ye) {
-            nuv = ld_vec<T, PX>(ug + (size_t)(yi + 1) * nx + xc);
-            if (edge_lane) nh = ug[(size_t)(yi + 1) * nx + hxc];
-            if (yo + 1 >= ys) {
-                ncv = ld_vec<T, PX>(cg + (size_t)(yo + 1) * nx + xc);
-                npv = ld_vec<T, PX>(pg + (size_t)(yo + 1) * nx + xc);
-            }
-        }
+        for (int e = 0; e < PX; ++e) u0[e] = su[d].v[e];
+        const T uh = sh[d];
+        const V cc = scc[d], pp = spp[d];
+        issue(yi + D, dc, steady);
         T left, right;
         wave_neighbours<T, PX>(u0, uh, lane, left, right);
 #pragma unroll
@@ -248,16 +258,15 @@ __global__ __launch_bounds__(64 * kWavesPerBlock2d) void primal_wave2d_kernel(Wa
             acc[e][1] += T(-4) * u0[e] + (l + r);
             acc[e][0] += u0[e];
             acc[e][2] += u0[e];
-            uq[e][1] = u0[e];
         }
-        if (yo >= ys && active) {
+        if ((STEADY || yo >= ys) && active) {
             V o;
 #pragma unroll
-            for (int e = 0; e < PX; ++e) o.v[e] = T(2) * uq[e][0] - pp.v[e] + cc.v[e] * acc[e][0];
+            for (int e = 0; e < PX; ++e) o.v[e] = T(2) * uq[e] - pp.v[e] + cc.v[e] * acc[e][0];
             T *rp = rg + (size_t)yo * nx + x;
             if (all_in) {
-                st_vec<T, PX>(rp, o);
-            } else {
+                st_vec_stream<T, PX>(rp, o);
+            } else {                                       // r outside I stays untouched
 #pragma unroll
                 for (int e = 0; e < PX; ++e)
                     if (xin[e]) rp[e] = o.v[e];
@@ -268,21 +277,43 @@ __global__ __launch_bounds__(64 * kWavesPerBlock2d) void primal_wave2d_kernel(Wa
             acc[e][0] = acc[e][1];
             acc[e][1] = acc[e][2];
             acc[e][2] = T(0);
-            uq[e][0] = uq[e][1];
+            uq[e] = u0[e];
         }
+    };
+    using No = std::integral_constant<bool, false>;
+    using Yes = std::integral_constant<bool, true>;
+    auto step_any = [&](int yi, int d) {
+        if (D == 1 || d == 0) step(yi, std::integral_constant<int, 0>{}, No{});
+        else step(yi, std::integral_constant<int, (D > 1 ? 1 : 0)>{}, No{});
+    };
+    static_assert(D <= 2, "primal_wave2d_kernel: D is 1 or 2");
+    issue(yi0, std::integral_constant<int, 0>{}, No{});
+    if (D > 1) issue(yi0 + 1, std::integral_constant<int, (D > 1 ? 1 : 0)>{}, No{});
+    const int lo = ys + 1, hi = ye - D;                    // steady: rows yi-1 >= ys and yi+D <= ye
+    int yi = yi0, d = 0;
+    while (yi <= yi1 && (yi < lo || d != 0)) {
+        step_any(yi, d);
+        ++yi;
+        d = d + 1 == D ? 0 : d + 1;
+    }
+    while (yi + D - 1 <= hi) {
+        step(yi, std::integral_constant<int, 0>{}, Yes{});
+        if (D > 1) step(yi + 1, std::integral_constant<int, (D > 1 ? 1 : 0)>{}, Yes{});
+        yi += D;
+    }
+    while (yi <= yi1) {
+        step_any(yi, d);
+        ++yi;
+        d = d + 1 == D ? 0 : d + 1;
     }
 }
 
 // ------------------------------------------------------------------------ launchers
 static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-template <class T, int PX, int D, int WAVES>
-static hipError_t launch_adj2d_cfg(Wave2dArgs a, const LaunchOptions &opt, hipStream_t stream)
+static inline int auto_ychunk(int bx, int rows, long opt_ychunk)
 {
-    constexpr int W = 64 * PX;
-    const int nstrips = (a.nx + W - 1) / W;
-    const int bx = (nstrips + WAVES - 1) / WAVES;
-    int ychunk = (int)opt.ychunk2d;
+    int ychunk = (int)opt_ychunk;
     if (ychunk <= 0) {
         // about one workgroup per CU: few waves, each with D rows in flight, marching long
         // columns, so that the set of rows being streamed at any moment stays small
@@ -291,10 +322,20 @@ static hipError_t launch_adj2d_cfg(Wave2dArgs a, const LaunchOptions &opt, hipSt
             hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
             ncu = v;
         const int chunks = bx >= ncu ? 1 : (ncu + bx - 1) / bx;
-        ychunk = (a.ny + chunks - 1) / chunks;
+        ychunk = (rows + chunks - 1) / chunks;
         if (ychunk < 16) ychunk = 16;
     }
-    if (ychunk > a.ny) ychunk = a.ny;
+    if (ychunk > rows) ychunk = rows;
+    return ychunk;
+}
+
+template <class T, int PX, int D, int WAVES>
+static hipError_t launch_adj2d_cfg(Wave2dArgs a, const LaunchOptions &opt, hipStream_t stream)
+{
+    constexpr int W = 64 * PX;
+    const int nstrips = (a.nx + W - 1) / W;
+    const int bx = (nstrips + WAVES - 1) / WAVES;
+    const int ychunk = auto_ychunk(bx, a.ny, opt.ychunk2d);
     a.ychunk = ychunk;
     dim3 grid(bx, (a.ny + ychunk - 1) / ychunk), block(64 * WAVES);
     if (a.u_prev_bar) hipLaunchKernelGGL((adj_wave2d_kernel<T, PX, D, WAVES, true>), grid, block, 0, stream, a);
@@ -317,14 +358,15 @@ static hipError_t launch_adj2d(const Wave2dArgs &a, const LaunchOptions &opt, hi
 template <class T, int PX>
 static hipError_t launch_pri2d(const Wave2dArgs &a0, const LaunchOptions &opt, hipStream_t stream)
 {
+    constexpr int WAVES = 8, D = 2;
     Wave2dArgs a = a0;
-    a.ychunk = opt.ychunk2d > 0 ? (int)opt.ychunk2d : 32;
     constexpr int W = 64 * PX;
     const int nstrips = (a.nx + W - 1) / W;
+    const int bx = (nstrips + WAVES - 1) / WAVES;
     const int rows = a.ny - 2;
-    dim3 grid((nstrips + kWavesPerBlock2d - 1) / kWavesPerBlock2d, (rows + a.ychunk - 1) / a.ychunk);
-    dim3 block(64 * kWavesPerBlock2d);
-    hipLaunchKernelGGL((primal_wave2d_kernel<T, PX>), grid, block, 0, stream, a);
+    a.ychunk = auto_ychunk(bx, rows, opt.ychunk2d);
+    dim3 grid(bx, (rows + a.ychunk - 1) / a.ychunk), block(64 * WAVES);
+    hipLaunchKernelGGL((primal_wave2d_kernel<T, PX, D, WAVES>), grid, block, 0, stream, a);
     return hipGetLastError();
 }
 

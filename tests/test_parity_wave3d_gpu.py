@@ -92,6 +92,39 @@ def test_adjoint_is_bitwise_reproducible_and_ignores_values_outside_the_interior
     assert np.array_equal(p, a)
 
 
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_odd_extent_and_unaligned_arrays_take_the_scalar_shape(sadj, dtype):
+    """Shapes that move several cells per lane need nx to be a multiple of the vector
+    length and vector-aligned arrays; otherwise the library must fall back by itself."""
+    import torch
+    radius = 4
+    for shape, shift in (((19, 37, 131), 0), ((19, 37, 132), 1), ((12, 33, 130), 1)):
+        d = inputs.wave_inputs(shape, 0.01, 0.1, seed=shift + shape[2], dtype=dtype)
+        n = int(np.prod(shape))
+
+        def dev(a):
+            t = torch.empty(n + shift, dtype=torch.from_numpy(a).dtype, device="cuda")
+            v = t[shift:].view(shape)          # starts `shift` elements into the allocation
+            v.copy_(torch.from_numpy(a))
+            return v
+        c, rb, ub, upb = dev(d["c"]), dev(d["r_bar"]), dev(d["u_bar"]), dev(d["u_prev_bar"])
+        sadj.sadj_adjoint_wave3d(radius, c, rb, ub, upb)
+        r0 = inputs.uniform(3, "aux", shape, -1, 1).astype(dtype)
+        r = dev(r0)
+        sadj.sadj_primal_wave3d(radius, dev(d["u"]), dev(d["u_prev"]), c, r)
+        torch.cuda.synchronize()
+        want_u, want_p, scale = oracle.wave_adjoint(d["c"], d["r_bar"], d["u_bar"], radius,
+                                                    u_prev_bar=d["u_prev_bar"], want_scale=True)
+        assert_close(to_host(ub), want_u, scale + np.abs(d["u_bar"].astype(np.float64)), dtype, "fallback %s" % (shape,))
+        assert_close(to_host(upb), want_p, np.abs(d["u_prev_bar"].astype(np.float64)) + np.abs(d["r_bar"].astype(np.float64)),
+                     dtype, "fallback u_prev_bar")
+        want_r = oracle.wave_primal(d["u"], d["u_prev"], d["c"], radius, r_init=r0)
+        m = interior_mask(shape, radius)
+        got_r = to_host(r)
+        assert np.array_equal(got_r[~m], r0[~m])
+        assert_close(got_r[m], want_r[m], _primal_scale(d, radius)[m], dtype, "fallback primal")
+
+
 def test_adjoint_on_a_side_stream(sadj):
     import torch
     radius, shape = 4, (20, 40, 100)
