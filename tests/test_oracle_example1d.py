@@ -47,7 +47,7 @@ def test_scatter_oracle_equals_the_printed_remainder_and_core(n):
 
 
 def test_weights_swap_sides_between_primal_and_adjoint():
-    """'the constant factors 4.0 and 2.0 have swapped their position': with c = 1 the
+    """Section 3.2 ends by noting that the factors 4 and 2 trade places: with c = 1 the
     primal reads (2,-3,4) at (i-1,i,i+1), the core adjoint reads (4,-3,2)."""
     n = 12
     ones = np.ones(n + 1)
