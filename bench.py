@@ -100,7 +100,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the hot path is a single-GPU kernel "
-              "library; see DESIGN.md for how it would shard); run with --gpus 1", file=sys.stderr)
+              "library and no multi-GPU figure is produced); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
