@@ -46,7 +46,11 @@ struct March3dArgs {
 
 static inline int cdiv_i(int a, int b) { return (a + b - 1) / b; }
 
-// One resident wave of workgroups: as few z-chunks as still give every CU a workgroup.
+// Choose the number of z-chunks.  Each CU holds one workgroup of these kernels at a time,
+// so the dispatch runs in rounds of `ncu` workgroups, each marching zchunk + 2R planes
+// (the 2R planes beyond a chunk are read by two chunks).  Minimise rounds * planes per
+// workgroup; ties go to fewer chunks.  With tiles*chunks == ncu this is the single
+// resident wave in which neighbouring tiles move through z in lockstep.
 static inline void plan_march(March3dArgs &a, int TX, int TY, int R, long zchunk_opt)
 {
     a.ntx = cdiv_i(a.nx, TX);
@@ -57,12 +61,19 @@ static inline void plan_march(March3dArgs &a, int TX, int TY, int R, long zchunk
         if (hipGetDevice(&dev) == hipSuccess &&
             hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
             ncu = v;
-        const int tiles = a.ntx * a.nty;
-        const int chunks = tiles >= ncu ? 1 : cdiv_i(ncu, tiles);
-        zchunk = cdiv_i(a.nz, chunks);
-        if (zchunk < 4 * R) zchunk = 4 * R;      // keep the 2R re-read planes per chunk below 50 %
+        const long tiles = (long)a.ntx * a.nty;
+        long best_cost = -1;
+        int best_chunks = 1;
+        const int max_chunks = a.nz / (4 * R) > 0 ? a.nz / (4 * R) : 1;   // chunks of at least 4R planes
+        for (int c = 1; c <= max_chunks && c <= 64; ++c) {
+            const long rounds = (tiles * c + ncu - 1) / ncu;
+            const long cost = rounds * (cdiv_i(a.nz, c) + 2 * R);
+            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_chunks = c; }
+        }
+        zchunk = cdiv_i(a.nz, best_chunks);
     }
     if (zchunk > a.nz) zchunk = a.nz;
+    if (zchunk < 1) zchunk = 1;
     a.zchunk = zchunk;
     a.ntz = cdiv_i(a.nz, zchunk);
     a.total_blocks = a.ntx * a.nty * a.ntz;
