@@ -165,6 +165,13 @@ def main():
         upb = torch.from_numpy(inputs.config_inputs("wave3d_r4", shape=shape, fields=("u_prev_bar",))["u_prev_bar"]).to(dev)
         add("wave3d_r4_f64_adjoint_with_u_prev_bar", lambda: sadj.sadj_adjoint_wave3d(R, c, rb, ub, upb), N,
             wave_adjoint_bytes(shape, R, 8, True), "f64")
+        # reverse sweep of a time loop: per step read c and lam_a on I, read+write lam_b, write lam_p
+        ksteps = 6
+        I4 = interior_points(shape, R)
+        add("wave3d_r4_f64_adjoint_steps_per_step", lambda: sadj.sadj_adjoint_wave3d_steps(R, ksteps, c, rb, ub, upb),
+            N * ksteps, ksteps * (16 * I4 + 16 * N + 8 * N), "f64")
+        others["wave3d_r4_f64_adjoint_steps_per_step"]["ms"] /= ksteps
+        others["wave3d_r4_f64_adjoint_steps_per_step"]["kernel_ms_mean"] /= ksteps
         # primal: reads u, u_prev, c, writes r (u_bar/u_prev_bar buffers reused as u/u_prev)
         r = torch.empty_like(ub)
         I = interior_points(shape, R)

@@ -101,6 +101,27 @@ sadj_status sadj_adjoint_wave3d(sadj_dtype dtype, int radius, long nx, long ny, 
                                 const void *c, const void *r_bar,
                                 void *u_bar, void *u_prev_bar /* nullable */, void *stream);
 
+/* ---- reverse sweep of a time loop of 3-D wave steps -----------------------------------
+ * A solver runs many steps u^{k+1} = step(u^k, u^{k-1}) (the paper measures one step and
+ * notes that such solvers take many, Section 4); each step assigns u^{k+1} on I only, so
+ * cells of u^{k+1} outside I are inputs, not functions of earlier states.  With lam^k
+ * the adjoint of state u^k, the reverse sweep of one step is
+ *     lam^k     += (d step / d u^k)^T     lam^{k+1}        (the gather of sadj_adjoint_wave3d)
+ *     lam^{k-1} += (d step / d u^{k-1})^T lam^{k+1}  =  lam^{k-1} - lam^{k+1} on I .
+ * This call performs `nsteps` such reverse steps with three rotating buffers.  On entry
+ * lam0 = lam^{K+1}, lam1 = lam^K, lam2 = lam^{K-1} (whatever the objective contributes to
+ * them directly; often lam2 is zero).  Step s = 0, 1, ... reads a = lam[s%3] and updates
+ * b = lam[(s+1)%3] and p = lam[(s+2)%3]; from s = 1 on, p is the buffer whose content
+ * was consumed by the previous step, and it is ASSIGNED: p = -a on I, 0 elsewhere (the
+ * adjoint of a state that the objective does not touch directly starts from zero).
+ * After the call: lam[nsteps%3] = lam^{K+1-nsteps}, lam[(nsteps+1)%3] = lam^{K-nsteps},
+ * and lam[(nsteps+2)%3] holds consumed data.  nsteps = 0 does nothing.  One kernel per
+ * step is enqueued on `stream`; the four arrays must be mutually non-overlapping.
+ */
+sadj_status sadj_adjoint_wave3d_steps(sadj_dtype dtype, int radius, long nx, long ny, long nz,
+                                      long nsteps, const void *c,
+                                      void *lam0, void *lam1, void *lam2, void *stream);
+
 /* ---- 1-D upwinded Burgers step -----------------------------------------------------
  * Primal (paper Section 4.2, upwind formula and generating script), i in [1, n-2]:
  *     r[i] = u[i] - C*(max(u[i],0)*(u[i]-u[i-1]) + min(u[i],0)*(u[i+1]-u[i]))

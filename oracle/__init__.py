@@ -117,6 +117,18 @@ def wave_adjoint(c, r_bar, u_bar, radius: int, u_prev_bar=None, want_scale: bool
     return ub, upb, scale
 
 
+def wave_adjoint_steps(c, lam0, lam1, lam2, radius: int, nsteps: int):
+    """Reverse sweep of `nsteps` wave steps with three rotating buffers; returns the three
+    buffers (copies) after the sweep, in the caller's order."""
+    c = _f64(c)
+    ndim, nx, ny, nz = _dims(c.shape)
+    bufs = [_f64(x).copy() for x in (lam0, lam1, lam2)]
+    fn = _load().oracle_wave_adjoint_steps
+    _check(fn(_I(ndim), _I(radius), _L(nx), _L(ny), _L(nz), _L(nsteps), _ptr(c), _ptr(bufs[0]), _ptr(bufs[1]),
+              _ptr(bufs[2])), "wave_adjoint_steps")
+    return bufs
+
+
 def burgers_primal(u, C: float, D: float, r_init=None) -> np.ndarray:
     u = _f64(u)
     r = np.zeros_like(u) if r_init is None else _f64(r_init).copy()

@@ -166,6 +166,32 @@ int oracle_wave_adjoint(int ndim, int R, long nx, long ny, long nz,
     return ORACLE_OK;
 }
 
+/* Reverse sweep of a time loop of wave steps u^{k+1} = step(u^k, u^{k-1}), where a step
+ * assigns the new state on I only (cells outside I are inputs of their own).  Reverse
+ * mode visits the steps last to first; for the step that produced u^{k+1}:
+ *     lam^k += (d step/d u^k)^T lam^{k+1},   lam^{k-1} += (d step/d u^{k-1})^T lam^{k+1},
+ * which is the scatter adjoint above with r_bar = lam^{k+1}.  lam[0], lam[1], lam[2] are
+ * lam^{K+1}, lam^K, lam^{K-1} on entry; the adjoint of every older state starts from zero.
+ * Three buffers rotate: step s reads lam[s%3], updates lam[(s+1)%3] and lam[(s+2)%3];
+ * from s = 1 on the latter is the consumed buffer of the previous step and is zeroed
+ * first (it now stands for an older state).  (Paper Sections 3.1 and 4: chain rule over
+ * a solver that performs many such steps.) */
+int oracle_wave_adjoint_steps(int ndim, int R, long nx, long ny, long nz, long nsteps,
+                              const double *c, double *lam0, double *lam1, double *lam2)
+{
+    double *lam[3] = {lam0, lam1, lam2};
+    if (!c || !lam0 || !lam1 || !lam2 || nsteps < 0) return ORACLE_BAD_ARG;
+    const long n = nx * ny * nz;
+    for (long s = 0; s < nsteps; ++s) {
+        double *a = lam[s % 3], *b = lam[(s + 1) % 3], *p = lam[(s + 2) % 3];
+        if (s > 0)
+            for (long i = 0; i < n; ++i) p[i] = 0.0;
+        int rc = oracle_wave_adjoint(ndim, R, nx, ny, nz, c, a, b, p, NULL);
+        if (rc != ORACLE_OK) return rc;
+    }
+    return ORACLE_OK;
+}
+
 /* ------------------------------------------------------------------ Burgers 1-D */
 static double pos(double a) { return a > 0.0 ? a : 0.0; }   /* max(a,0) */
 static double neg(double a) { return a < 0.0 ? a : 0.0; }   /* min(a,0) */

@@ -17,6 +17,7 @@ __all__ = [
     "SadjError", "lib_path", "load", "set_option", "get_option", "version",
     "sadj_primal_wave1d", "sadj_adjoint_wave1d", "sadj_primal_wave2d", "sadj_adjoint_wave2d",
     "sadj_primal_wave3d", "sadj_adjoint_wave3d", "sadj_primal_burgers1d", "sadj_adjoint_burgers1d",
+    "sadj_adjoint_wave3d_steps",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -64,11 +65,12 @@ def load() -> ctypes.CDLL:
     lib.sadj_adjoint_wave2d.argtypes = [I, L, L, P, P, P, P, P]
     lib.sadj_primal_wave3d.argtypes = [I, I, L, L, L, P, P, P, P, P]
     lib.sadj_adjoint_wave3d.argtypes = [I, I, L, L, L, P, P, P, P, P]
+    lib.sadj_adjoint_wave3d_steps.argtypes = [I, I, L, L, L, L, P, P, P, P, P]
     lib.sadj_primal_burgers1d.argtypes = [I, L, D, D, P, P, P]
     lib.sadj_adjoint_burgers1d.argtypes = [I, L, D, D, P, P, P, P]
     for name in ("sadj_set_option", "sadj_get_option", "sadj_primal_wave1d", "sadj_adjoint_wave1d",
                  "sadj_primal_wave2d", "sadj_adjoint_wave2d", "sadj_primal_wave3d", "sadj_adjoint_wave3d",
-                 "sadj_primal_burgers1d", "sadj_adjoint_burgers1d"):
+                 "sadj_primal_burgers1d", "sadj_adjoint_burgers1d", "sadj_adjoint_wave3d_steps"):
         getattr(lib, name).restype = I
     _lib = lib
     return lib
@@ -156,6 +158,11 @@ def sadj_primal_wave3d(radius: int, u, u_prev, c, r) -> None:
 def sadj_adjoint_wave3d(radius: int, c, r_bar, u_bar, u_prev_bar=None) -> None:
     code, (nz, ny, nx), p, s = _marshal([c, r_bar, u_bar, u_prev_bar], 3, optional=(3,))
     _check(load().sadj_adjoint_wave3d(code, int(radius), nx, ny, nz, *p, s))
+
+
+def sadj_adjoint_wave3d_steps(radius: int, nsteps: int, c, lam0, lam1, lam2) -> None:
+    code, (nz, ny, nx), p, s = _marshal([c, lam0, lam1, lam2], 3)
+    _check(load().sadj_adjoint_wave3d_steps(code, int(radius), nx, ny, nz, int(nsteps), *p, s))
 
 
 def sadj_primal_burgers1d(C: float, D: float, u, r) -> None:

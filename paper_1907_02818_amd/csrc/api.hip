@@ -171,7 +171,7 @@ static sadj_status adjoint_wave(int ndim, sadj_dtype dtype, int radius, long nx,
     case 1: return from_hip(sadj::launch_adjoint_wave1d(f64, nx, c, r_bar, u_bar, u_prev_bar, st));
     case 2: return from_hip(sadj::launch_adjoint_wave2d(f64, (int)nx, (int)ny, c, r_bar, u_bar, u_prev_bar, current_options(), st));
     default: return from_hip(sadj::launch_adjoint_wave3d(f64, radius, (int)nx, (int)ny, (int)nz, c, r_bar, u_bar,
-                                                         u_prev_bar, current_options(), st));
+                                                         u_prev_bar, 0, current_options(), st));
     }
 }
 
@@ -206,6 +206,35 @@ sadj_status sadj_adjoint_wave3d(sadj_dtype dtype, int radius, long nx, long ny, 
 {
     if (radius != 1 && radius != 4) return SADJ_ERR_UNSUPPORTED;
     return adjoint_wave(3, dtype, radius, nx, ny, nz, c, r_bar, u_bar, u_prev_bar, stream);
+}
+
+// Reverse sweep of a time loop of wave steps.
+sadj_status sadj_adjoint_wave3d_steps(sadj_dtype dtype, int radius, long nx, long ny, long nz, long nsteps,
+                                      const void *c, void *lam0, void *lam1, void *lam2, void *stream)
+{
+    if (radius != 1 && radius != 4) return SADJ_ERR_UNSUPPORTED;
+    if (!dtype_ok(dtype)) return SADJ_ERR_UNSUPPORTED;
+    if (!c || !lam0 || !lam1 || !lam2) return SADJ_ERR_NULL;
+    if (nsteps < 0) return SADJ_ERR_SIZE;
+    sadj_status s = check_extents(radius, nx, ny, nz, 3);
+    if (s != SADJ_OK) return s;
+    const size_t bytes = (size_t)nx * ny * nz * elem(dtype);
+    const Span in[1] = {{c, bytes}};
+    const Span out[3] = {{lam0, bytes}, {lam1, bytes}, {lam2, bytes}};
+    if (any_alias(in, out)) return SADJ_ERR_ALIAS;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int f64 = dtype == SADJ_F64;
+    void *lam[3] = {lam0, lam1, lam2};
+    clear_stale_hip_error();
+    const sadj::LaunchOptions opt = current_options();
+    for (long k = 0; k < nsteps; ++k) {
+        void *a = lam[k % 3], *b = lam[(k + 1) % 3], *p = lam[(k + 2) % 3];
+        // the buffer that receives -a was the r_bar of the previous step: it is dead and is assigned
+        hipError_t e = sadj::launch_adjoint_wave3d(f64, radius, (int)nx, (int)ny, (int)nz, c, a, b, p, k > 0 ? 1 : 0,
+                                                   opt, st);
+        if (e != hipSuccess) return from_hip(e);
+    }
+    return SADJ_OK;
 }
 
 // ------------------------------------------------------------------------- Burgers

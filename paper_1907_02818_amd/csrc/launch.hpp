@@ -12,7 +12,7 @@ struct LaunchOptions {
 };
 
 hipError_t launch_adjoint_wave3d(int is_f64, int radius, int nx, int ny, int nz, const void *c,
-                                 const void *r_bar, void *u_bar, void *u_prev_bar,
+                                 const void *r_bar, void *u_bar, void *u_prev_bar, int u_prev_bar_assign,
                                  const LaunchOptions &opt, hipStream_t stream);
 hipError_t launch_primal_wave3d(int is_f64, int radius, int nx, int ny, int nz, const void *u,
                                 const void *u_prev, const void *c, void *r,

@@ -38,6 +38,7 @@ struct Tile3d {
 struct March3dArgs {
     const void *in0, *in1, *in2;   // adjoint: c, r_bar, -      primal: u, u_prev, c
     void *out0, *out1;             // adjoint: u_bar, u_prev_bar (nullable)   primal: r, -
+    int out1_assign;               // adjoint: 1 = u_prev_bar is assigned (-r_bar on I, 0 elsewhere), 0 = accumulated
     int nx, ny, nz;
     int ntx, nty, ntz;             // tiles along x and y, chunks along z
     int zchunk;                    // output planes per chunk

@@ -6,7 +6,8 @@
 //     u_bar[j] += 2 r_bar[j] [j in I] + sum_o w_o q[j-o]
 // i.e. the same star applied to q, because the weights are symmetric; the product
 // c*r_bar is formed once per staged element instead of once per term.  Optionally
-// u_prev_bar[j] -= r_bar[j] for j in I.
+// u_prev_bar[j] -= r_bar[j] for j in I (accumulate mode), or u_prev_bar[j] = -r_bar[j]
+// for j in I and 0 elsewhere (assign mode, used when a time loop recycles a buffer).
 //
 // Mapping to CDNA4.  The x-y plane is cut into tiles of TX x TY outputs; a workgroup
 // owns one tile and marches along z.  Each arriving plane of q is staged in LDS
@@ -45,7 +46,7 @@
 
 namespace sadj {
 
-template <class T, int R, int BX, int BY, int PY, int PX, int D, bool NTU, bool GUARD, bool UPREV>
+template <class T, int R, int BX, int BY, int PY, int PX, int D, bool NTU, bool GUARD, int UPREV>
 __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int tiy, int tiz,
                                             T *__restrict__ sq)
 {
@@ -134,7 +135,7 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
             }
 #pragma unroll
             for (int s = 0; s < HS; ++s) { shc[d][s] = ld_off(cp, hoff[s]); shr[d][s] = ld_off(rp, hoff[s]); }
-            if (UPREV) {
+            if (UPREV == 1) {                      // accumulate mode reads u_prev_bar; assign mode does not
                 if (z >= zs && z < ze) {
                     const T *pp = upg + (size_t)z * plane;
 #pragma unroll
@@ -181,10 +182,18 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
                     for (int p = 0; p < PY; ++p) {
                         V o;
 #pragma unroll
-                        for (int e = 0; e < PX; ++e) o.v[e] = sp[d][p].v[e] - ro[p][e];
+                        for (int e = 0; e < PX; ++e) o.v[e] = (UPREV == 1 ? sp[d][p].v[e] : T(0)) - ro[p][e];
                         if (!GUARD || ostore[p]) st_vec_off<T, PX, NTU>(pp, ooff[p], o);
                     }
                 }
+            }
+        } else if (UPREV == 2) {
+            // assign mode: planes of this chunk outside I receive zeros
+            if (zi >= zs && zi < ze) {
+                T *pp = upg + (size_t)zi * plane;
+#pragma unroll
+                for (int p = 0; p < PY; ++p)
+                    if (!GUARD || ostore[p]) st_vec_off<T, PX, NTU>(pp, ooff[p], V{});
             }
         }
         // the registers of stage d are free again: request plane zi+D
@@ -243,7 +252,7 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
     }
 }
 
-template <class T, int R, int BX, int BY, int PY, int PX, int D, bool NTU, bool UPREV>
+template <class T, int R, int BX, int BY, int PY, int PX, int D, bool NTU, int UPREV>
 __global__ __launch_bounds__(BX *BY) void adj_wave3d_kernel(March3dArgs a)
 {
     using G = Tile3d<T, R, BX, BY, PY, PX>;
@@ -276,8 +285,9 @@ static hipError_t launch_cfg(March3dArgs a, const LaunchOptions &opt, hipStream_
     }
     plan_march(a, G::TX, G::TY, R, opt.zchunk);
     dim3 grid(a.total_blocks), block(G::NT);
-    if (a.out1) hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, true>), grid, block, 0, stream, a);
-    else        hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, false>), grid, block, 0, stream, a);
+    if (!a.out1)                hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 0>), grid, block, 0, stream, a);
+    else if (a.out1_assign == 0) hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 1>), grid, block, 0, stream, a);
+    else                        hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 2>), grid, block, 0, stream, a);
     return hipGetLastError();
 }
 
@@ -303,11 +313,12 @@ static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipSt
 }
 
 hipError_t launch_adjoint_wave3d(int is_f64, int radius, int nx, int ny, int nz, const void *c,
-                                 const void *r_bar, void *u_bar, void *u_prev_bar,
+                                 const void *r_bar, void *u_bar, void *u_prev_bar, int u_prev_bar_assign,
                                  const LaunchOptions &opt, hipStream_t stream)
 {
     March3dArgs a{};
     a.in0 = c; a.in1 = r_bar; a.out0 = u_bar; a.out1 = u_prev_bar;
+    a.out1_assign = u_prev_bar_assign;
     a.nx = nx; a.ny = ny; a.nz = nz;
     if (is_f64) {
         if (radius == 1) return launch_T<double, 1>(a, opt, stream);

@@ -1,0 +1,76 @@
+"""GPU parity of sadj_adjoint_wave3d_steps (reverse sweep of a time loop of wave
+steps) against the CPU oracle."""
+import numpy as np
+import pytest
+
+import inputs
+import oracle
+from parity import TOL, to_gpu, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sadj():
+    import paper_1907_02818_amd as lib
+    lib.load()
+    return lib
+
+
+def _lams(shape, seed, dtype):
+    return [inputs.uniform(seed, name, shape, -1, 1).astype(dtype) for name in ("r_bar", "u_bar", "u_prev_bar")]
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("radius,shape,nsteps", [(4, (37, 45, 150), 1), (4, (37, 45, 150), 2), (4, (37, 45, 150), 6),
+                                                 (4, (12, 33, 131), 4), (1, (21, 37, 150), 5), (1, (3, 3, 3), 4),
+                                                 (4, (9, 9, 9), 3), (4, (40, 70, 64), 0)])
+def test_steps_match_the_oracle(sadj, radius, shape, nsteps, dtype):
+    import torch
+    c = inputs.uniform(1, "c", shape, 0.01, 0.1).astype(dtype)
+    lams = _lams(shape, 2 + nsteps, dtype)
+    g = [to_gpu(x) for x in lams]
+    sadj.sadj_adjoint_wave3d_steps(radius, nsteps, to_gpu(c), *g)
+    torch.cuda.synchronize()
+    want = oracle.wave_adjoint_steps(c, *lams, radius, nsteps)
+    live = [nsteps % 3, (nsteps + 1) % 3] if nsteps > 0 else [0, 1, 2]
+    tol = TOL[np.dtype(dtype)]
+    for k in live:
+        got = to_host(g[k]).astype(np.float64)
+        assert np.isfinite(got).all()
+        err = np.max(np.abs(got - want[k])) / max(np.max(np.abs(want[k])), 1e-300)
+        assert err <= tol, "buffer %d after %d steps: %.3e" % (k, nsteps, err)
+
+
+def test_steps_equal_repeated_single_calls_bitwise(sadj):
+    """The sweep is nothing but the single-step kernel with rotating buffers (the
+    recycled buffer zeroed by the assign mode instead of by the caller)."""
+    import torch
+    radius, shape, nsteps = 4, (30, 40, 140), 4
+    c = to_gpu(inputs.uniform(1, "c", shape, 0.01, 0.1))
+    lams = _lams(shape, 5, np.float64)
+    g = [to_gpu(x) for x in lams]
+    sadj.sadj_adjoint_wave3d_steps(radius, nsteps, c, *g)
+    h = [to_gpu(x) for x in lams]
+    for s in range(nsteps):
+        a, b, p = h[s % 3], h[(s + 1) % 3], h[(s + 2) % 3]
+        if s > 0:
+            p.zero_()
+        sadj.sadj_adjoint_wave3d(radius, c, a, b, p)
+    torch.cuda.synchronize()
+    for k in (nsteps % 3, (nsteps + 1) % 3):
+        assert np.array_equal(to_host(g[k]), to_host(h[k]))
+
+
+def test_steps_argument_errors(sadj):
+    import torch
+    t = [torch.zeros(16, 16, 16, dtype=torch.float64, device="cuda") for _ in range(4)]
+    with pytest.raises(sadj.SadjError) as e:
+        sadj.sadj_adjoint_wave3d_steps(1, 2, t[0], t[1], t[1], t[3])
+    assert e.value.status == 3
+    with pytest.raises(sadj.SadjError) as e:
+        sadj.sadj_adjoint_wave3d_steps(1, -1, *t)
+    assert e.value.status == 2
+    with pytest.raises(sadj.SadjError) as e:
+        sadj.sadj_adjoint_wave3d_steps(3, 1, *t)
+    assert e.value.status == 4
