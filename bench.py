@@ -180,6 +180,12 @@ def main():
             wave_adjoint_bytes(shape, 1, 8), "f64")
         add("wave3d_r1_f64_primal", lambda: sadj.sadj_primal_wave3d(1, ub, upb, c, r), N,
             8 * N + 24 * interior_points(shape, 1), "f64")
+        # dense 3x3x3 box stencil with asymmetric weights (27 terms), same grid
+        wbox = [[[0.1 * (i + 3 * j + 9 * k) - 1.0 for i in range(3)] for j in range(3)] for k in range(3)]
+        add("box3d_f64_adjoint", lambda: sadj.sadj_adjoint_box(wbox, c, rb, ub), N,
+            wave_adjoint_bytes(shape, 1, 8), "f64")
+        add("box3d_f64_primal", lambda: sadj.sadj_primal_box(wbox, ub, c, r), N,
+            8 * N + 16 * interior_points(shape, 1), "f64")
         del upb, r
         # 2-D 8192^2
         s2 = (8192, 8192)
@@ -189,6 +195,9 @@ def main():
         r2 = torch.empty_like(ub2)
         add("wave2d_f64_primal", lambda: sadj.sadj_primal_wave2d(ub2, rb2, c2, r2), s2[0] * s2[1],
             8 * s2[0] * s2[1] + 24 * interior_points(s2, 1), "f64")
+        wbox2 = [[0.1 * (i + 3 * j) - 0.4 for i in range(3)] for j in range(3)]
+        add("box2d_f64_adjoint", lambda: sadj.sadj_adjoint_box(wbox2, c2, rb2, ub2), s2[0] * s2[1],
+            wave_adjoint_bytes(s2, 1, 8), "f64")
         del r2
         # Burgers 2^24, rotating three buffer sets so the arrays do not stay in the 256 MB last-level cache
         nb = 1 << 24

@@ -122,6 +122,24 @@ sadj_status sadj_adjoint_wave3d_steps(sadj_dtype dtype, int radius, long nx, lon
                                       long nsteps, const void *c,
                                       void *lam0, void *lam1, void *lam2, void *stream);
 
+/* ---- dense 3^d box stencils with arbitrary weights --------------------------------------
+ * Primal:   r[i] = c[i] * sum_{o in {-1,0,1}^ndim} w[o] u[i+o]              for i in I = prod [1, n_d-2]
+ * Adjoint:  u_bar[j] += sum_o w[o] * c[j-o] r_bar[j-o] [j-o in I]           for all j
+ * These are the dense stencils of paper Section 3.3.4 (3 points in 1-D, 3x3, 3x3x3); the
+ * 1-D case with weights (2,-3,4) is the worked example of Section 3.2, whose outer
+ * weights change sides in the adjoint.  The weights may be asymmetric: the adjoint
+ * gathers with the point-mirrored table (index shifting, Section 3.3.2).
+ * `weights` is a HOST pointer to 3^ndim doubles, x fastest: entry (ox+1) + 3*(oy+1) +
+ * 9*(oz+1) (only the axes that exist); it is read during the call and converted to dtype.
+ * ndim = 1, 2 or 3; extents of unused axes are ignored.  Other conventions as above.
+ */
+sadj_status sadj_primal_box(sadj_dtype dtype, int ndim, long nx, long ny, long nz,
+                            const double *weights /* host */,
+                            const void *u, const void *c, void *r, void *stream);
+sadj_status sadj_adjoint_box(sadj_dtype dtype, int ndim, long nx, long ny, long nz,
+                             const double *weights /* host */,
+                             const void *c, const void *r_bar, void *u_bar, void *stream);
+
 /* ---- 1-D upwinded Burgers step -----------------------------------------------------
  * Primal (paper Section 4.2, upwind formula and generating script), i in [1, n-2]:
  *     r[i] = u[i] - C*(max(u[i],0)*(u[i]-u[i-1]) + min(u[i],0)*(u[i+1]-u[i]))

@@ -129,6 +129,42 @@ def wave_adjoint_steps(c, lam0, lam1, lam2, radius: int, nsteps: int):
     return bufs
 
 
+def _box_weights(w, ndim):
+    """Weights as an array of shape (3,)*ndim indexed [oz+1][oy+1][ox+1] -> flat table of 27
+    entries indexed (ox+1) + 3(oy+1) + 9(oz+1), zero where an axis is unused."""
+    w = np.asarray(w, dtype=np.float64)
+    assert w.shape == (3,) * ndim
+    full = np.zeros((3, 3, 3))
+    if ndim == 1:
+        full[1, 1, :] = w
+    elif ndim == 2:
+        full[1, :, :] = w
+    else:
+        full[:] = w
+    return np.ascontiguousarray(full.ravel())
+
+
+def box_primal(w, u, c, r_init=None) -> np.ndarray:
+    u, c = _f64(u), _f64(c)
+    ndim, nx, ny, nz = _dims(u.shape)
+    wt = _box_weights(w, ndim)
+    r = np.zeros_like(u) if r_init is None else _f64(r_init).copy()
+    _check(_load().oracle_box_primal(_I(ndim), _L(nx), _L(ny), _L(nz), _ptr(wt), _ptr(u), _ptr(c), _ptr(r)),
+           "box_primal")
+    return r
+
+
+def box_adjoint(w, c, r_bar, u_bar, want_scale: bool = False):
+    c, r_bar = _f64(c), _f64(r_bar)
+    ndim, nx, ny, nz = _dims(c.shape)
+    wt = _box_weights(w, ndim)
+    ub = _f64(u_bar).copy()
+    scale = np.zeros_like(ub) if want_scale else None
+    _check(_load().oracle_box_adjoint(_I(ndim), _L(nx), _L(ny), _L(nz), _ptr(wt), _ptr(c), _ptr(r_bar), _ptr(ub),
+                                      _ptr(scale)), "box_adjoint")
+    return ub, scale
+
+
 def burgers_primal(u, C: float, D: float, r_init=None) -> np.ndarray:
     u = _f64(u)
     r = np.zeros_like(u) if r_init is None else _f64(r_init).copy()

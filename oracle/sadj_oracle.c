@@ -253,6 +253,62 @@ int oracle_burgers_adjoint(long n, double C, double D, const double *u,
     return ORACLE_OK;
 }
 
+/* ------------------------- dense 3^d box stencil with arbitrary (asymmetric) weights */
+/* Primal  r[i] = c[i] * sum_{o in {-1,0,1}^d} w[o] * u[i+o]   for i in I = prod [1, n_d-2]
+ * (the dense stencils whose adjoint loop-nest counts Section 3.3.4 quotes: 3 points in
+ * 1-D -- the worked example of Section 3.2 --, 3x3 in 2-D, 3x3x3 in 3-D).  w is indexed
+ * (ox+1) + 3*(oy+1) + 9*(oz+1); unused axes have extent 1 and only offset 0.
+ * Scatter adjoint:  u_bar[i+o] += w[o] * c[i] * r_bar[i]. */
+static int box_check(int ndim, long nx, long ny, long nz)
+{
+    const long n[3] = {nx, ny, nz};
+    if (ndim < 1 || ndim > 3) return 1;
+    for (int d = 0; d < 3; ++d) {
+        if (d < ndim ? n[d] < 3 : n[d] != 1) return 1;
+    }
+    return 0;
+}
+
+int oracle_box_primal(int ndim, long nx, long ny, long nz, const double *w,
+                      const double *u, const double *c, double *r)
+{
+    if (!w || !u || !c || !r || box_check(ndim, nx, ny, nz)) return ORACLE_BAD_ARG;
+    const int ry = ndim >= 2, rz = ndim >= 3;
+    for (long z = rz; z <= nz - 1 - rz; ++z)
+    for (long y = ry; y <= ny - 1 - ry; ++y)
+    for (long x = 1; x <= nx - 2; ++x) {
+        double s = 0.0;
+        for (int oz = -rz; oz <= rz; ++oz)
+        for (int oy = -ry; oy <= ry; ++oy)
+        for (int ox = -1; ox <= 1; ++ox)
+            s += w[(ox + 1) + 3 * (oy + 1) + 9 * (oz + 1)] * u[(x + ox) + nx * ((y + oy) + ny * (z + oz))];
+        const long i = x + nx * (y + ny * z);
+        r[i] = c[i] * s;
+    }
+    return ORACLE_OK;
+}
+
+int oracle_box_adjoint(int ndim, long nx, long ny, long nz, const double *w,
+                       const double *c, const double *r_bar, double *u_bar, double *scale)
+{
+    if (!w || !c || !r_bar || !u_bar || box_check(ndim, nx, ny, nz)) return ORACLE_BAD_ARG;
+    const int ry = ndim >= 2, rz = ndim >= 3;
+    for (long z = rz; z <= nz - 1 - rz; ++z)
+    for (long y = ry; y <= ny - 1 - ry; ++y)
+    for (long x = 1; x <= nx - 2; ++x) {
+        const long i = x + nx * (y + ny * z);
+        for (int oz = -rz; oz <= rz; ++oz)
+        for (int oy = -ry; oy <= ry; ++oy)
+        for (int ox = -1; ox <= 1; ++ox) {
+            const double t = w[(ox + 1) + 3 * (oy + 1) + 9 * (oz + 1)] * c[i] * r_bar[i];
+            const long j = (x + ox) + nx * ((y + oy) + ny * (z + oz));
+            u_bar[j] += t;
+            if (scale) scale[j] += fabs(t);
+        }
+    }
+    return ORACLE_OK;
+}
+
 /* --------------------------------------- 1-D three-point example, general weights */
 /* Primal r[i] = c[i]*(wm*u[i-1] + w0*u[i] + wp*u[i+1]) for i in [lo,hi], arrays of
  * length len (Section 3.2: weights (2,-3,4), i in [1,n-1], arrays of length n+1). */

@@ -17,7 +17,7 @@ __all__ = [
     "SadjError", "lib_path", "load", "set_option", "get_option", "version",
     "sadj_primal_wave1d", "sadj_adjoint_wave1d", "sadj_primal_wave2d", "sadj_adjoint_wave2d",
     "sadj_primal_wave3d", "sadj_adjoint_wave3d", "sadj_primal_burgers1d", "sadj_adjoint_burgers1d",
-    "sadj_adjoint_wave3d_steps",
+    "sadj_adjoint_wave3d_steps", "sadj_primal_box", "sadj_adjoint_box",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -66,11 +66,14 @@ def load() -> ctypes.CDLL:
     lib.sadj_primal_wave3d.argtypes = [I, I, L, L, L, P, P, P, P, P]
     lib.sadj_adjoint_wave3d.argtypes = [I, I, L, L, L, P, P, P, P, P]
     lib.sadj_adjoint_wave3d_steps.argtypes = [I, I, L, L, L, L, P, P, P, P, P]
+    lib.sadj_primal_box.argtypes = [I, I, L, L, L, ctypes.POINTER(D), P, P, P, P]
+    lib.sadj_adjoint_box.argtypes = [I, I, L, L, L, ctypes.POINTER(D), P, P, P, P]
     lib.sadj_primal_burgers1d.argtypes = [I, L, D, D, P, P, P]
     lib.sadj_adjoint_burgers1d.argtypes = [I, L, D, D, P, P, P, P]
     for name in ("sadj_set_option", "sadj_get_option", "sadj_primal_wave1d", "sadj_adjoint_wave1d",
                  "sadj_primal_wave2d", "sadj_adjoint_wave2d", "sadj_primal_wave3d", "sadj_adjoint_wave3d",
-                 "sadj_primal_burgers1d", "sadj_adjoint_burgers1d", "sadj_adjoint_wave3d_steps"):
+                 "sadj_primal_burgers1d", "sadj_adjoint_burgers1d", "sadj_adjoint_wave3d_steps",
+                 "sadj_primal_box", "sadj_adjoint_box"):
         getattr(lib, name).restype = I
     _lib = lib
     return lib
@@ -163,6 +166,34 @@ def sadj_adjoint_wave3d(radius: int, c, r_bar, u_bar, u_prev_bar=None) -> None:
 def sadj_adjoint_wave3d_steps(radius: int, nsteps: int, c, lam0, lam1, lam2) -> None:
     code, (nz, ny, nx), p, s = _marshal([c, lam0, lam1, lam2], 3)
     _check(load().sadj_adjoint_wave3d_steps(code, int(radius), nx, ny, nz, int(nsteps), *p, s))
+
+
+def _box(fn_name, weights, tensors):
+    ndim = tensors[0].dim()
+    code, shape, p, s = _marshal(tensors, ndim)
+    dims = list(shape[::-1]) + [1] * (3 - ndim)            # nx, ny, nz
+    flat = [float(v) for v in _flatten(weights)]
+    if len(flat) != 3 ** ndim:
+        raise ValueError("weights must have 3**ndim entries, slowest axis first (shape (3,)*ndim)")
+    w = (ctypes.c_double * len(flat))(*flat)
+    _check(getattr(load(), fn_name)(code, ndim, dims[0], dims[1], dims[2], w, *p, s))
+
+
+def _flatten(w):
+    try:
+        for x in w:
+            yield from _flatten(x)
+    except TypeError:
+        yield w
+
+
+def sadj_primal_box(weights, u, c, r) -> None:
+    """weights: nested sequence / array of shape (3,)*ndim indexed [oz+1][oy+1][ox+1]."""
+    _box("sadj_primal_box", weights, [u, c, r])
+
+
+def sadj_adjoint_box(weights, c, r_bar, u_bar) -> None:
+    _box("sadj_adjoint_box", weights, [c, r_bar, u_bar])
 
 
 def sadj_primal_burgers1d(C: float, D: float, u, r) -> None:

@@ -237,6 +237,49 @@ sadj_status sadj_adjoint_wave3d_steps(sadj_dtype dtype, int radius, long nx, lon
     return SADJ_OK;
 }
 
+// ------------------------------------------------------------ dense 3^d box stencils
+static sadj_status box_call(int adjoint, sadj_dtype dtype, int ndim, long nx, long ny, long nz,
+                            const double *weights, const void *in0, const void *in1, void *out, void *stream)
+{
+    if (!dtype_ok(dtype) || ndim < 1 || ndim > 3) return SADJ_ERR_UNSUPPORTED;
+    if (!weights || !in0 || !in1 || !out) return SADJ_ERR_NULL;
+    if (ndim < 3) nz = 1;
+    if (ndim < 2) ny = 1;
+    sadj_status s = check_extents(1, nx, ny, nz, ndim);
+    if (s != SADJ_OK) return s;
+    const size_t bytes = (size_t)nx * ny * nz * elem(dtype);
+    const Span in[2] = {{in0, bytes}, {in1, bytes}};
+    const Span outs[1] = {{out, bytes}};
+    if (any_alias(in, outs)) return SADJ_ERR_ALIAS;
+    // expand the caller's 3^ndim table to 27 entries (x fastest); the adjoint gathers with
+    // the point-mirrored table W[o] = w[-o] (index shifting)
+    double full[27] = {0};
+    const int ey = ndim >= 2 ? 1 : 0, ez = ndim >= 3 ? 1 : 0;
+    int k = 0;
+    for (int oz = -ez; oz <= ez; ++oz)
+        for (int oy = -ey; oy <= ey; ++oy)
+            for (int ox = -1; ox <= 1; ++ox) full[(ox + 1) + 3 * (oy + 1) + 9 * (oz + 1)] = weights[k++];
+    double gather[27];
+    for (int i = 0; i < 27; ++i) gather[i] = adjoint ? full[26 - i] : full[i];
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    clear_stale_hip_error();
+    if (ndim == 1) return from_hip(sadj::launch_box1d(adjoint, dtype == SADJ_F64, nx, gather + 12, in0, in1, out, st));
+    return from_hip(sadj::launch_box(adjoint, dtype == SADJ_F64, ndim, (int)nx, (int)ny, (int)nz, gather, in0, in1, out,
+                                     current_options(), st));
+}
+
+sadj_status sadj_primal_box(sadj_dtype dtype, int ndim, long nx, long ny, long nz, const double *weights,
+                            const void *u, const void *c, void *r, void *stream)
+{
+    return box_call(0, dtype, ndim, nx, ny, nz, weights, u, c, r, stream);
+}
+
+sadj_status sadj_adjoint_box(sadj_dtype dtype, int ndim, long nx, long ny, long nz, const double *weights,
+                             const void *c, const void *r_bar, void *u_bar, void *stream)
+{
+    return box_call(1, dtype, ndim, nx, ny, nz, weights, c, r_bar, u_bar, stream);
+}
+
 // ------------------------------------------------------------------------- Burgers
 sadj_status sadj_primal_burgers1d(sadj_dtype dtype, long n, double C, double D, const void *u, void *r,
                                   void *stream)

@@ -1,0 +1,420 @@
+// Dense 3^d box stencils with arbitrary (asymmetric) weights: primal and gather-form
+// adjoint in 2-D and 3-D (the 1-D case lives with the other wave-per-segment kernels).
+//
+//   primal   r[i]      = c[i] * sum_{o in {-1,0,1}^d} w[o] u[i+o]                 for i in I
+//   adjoint  u_bar[j] += sum_o w[o] * c[j-o] r_bar[j-o]  [j-o in I]               for all j
+//
+// These are the dense stencils for which paper Section 3.3.4 counts 5 / 25 / 125 adjoint
+// loop nests; the 1-D instance with weights (2,-3,4) is the worked example of Section
+// 3.2.  Index shifting (Section 3.3.2) turns the scatter into a gather over the
+// point-mirrored weight table: u_bar[j] += sum_o' w[-o'] q[j+o'] with q = c*r_bar masked
+// to I.  The launcher mirrors the table on the host, so primal and adjoint are the same
+// gather  out[j] <- sum_o W[o] S[j+o]  over a staged field S (u, or q), and share one
+// kernel body per dimension:
+//   2-D: a wave owns a strip of columns and marches down y; an arriving row of S feeds
+//        three running sums (output rows y-1, y, y+1); x-neighbours by wave shuffles.
+//   3-D: a workgroup owns an x-y tile and marches along z; an arriving plane of S is
+//        staged in LDS with a full halo ring (a box reads the corners) and feeds three
+//        running sums per owned cell.
+// Cells whose reads all lie in I take the unguarded instantiation; the others the
+// guarded one (selects, never multiplications by zero).
+#include "launch.hpp"
+#include "tile3d.hpp"
+
+#include <type_traits>
+
+namespace sadj {
+
+struct BoxArgs {
+    const void *in0, *in1;      // adjoint: c, r_bar          primal: u, c
+    void *out;                  // adjoint: u_bar (accumulated)   primal: r (assigned on I)
+    int nx, ny, nz;
+    int chunk;                  // output rows (2-D) / planes (3-D) per march
+    int ntx, nty, ntz, total_blocks;
+    double w[27];               // gather weights W[(ox+1) + 3(oy+1) + 9(oz+1)]
+};
+
+// ------------------------------------------------------------------------------ 2-D
+// D rows of loads in flight per wave; the steady part of the march has no branches so
+// that the wait counters know which loads may still be outstanding.
+template <class T, int PX, int D, bool ADJ, bool GUARD>
+__device__ __forceinline__ void box2d_strip(const BoxArgs &a, int xs, int ys, int ye, int lane)
+{
+    constexpr int W = 64 * PX;
+    using V = Vec<T, PX>;
+    const int nx = a.nx, ny = a.ny;
+    const T *__restrict__ g0 = static_cast<const T *>(a.in0);
+    const T *__restrict__ g1 = static_cast<const T *>(a.in1);
+    T *__restrict__ og = static_cast<T *>(a.out);
+    T wt[3][3];                                     // wt[oy+1][ox+1]
+#pragma unroll
+    for (int j = 0; j < 3; ++j)
+#pragma unroll
+        for (int i = 0; i < 3; ++i) wt[j][i] = (T)a.w[i + 3 * j + 9];
+
+    const int x = xs + lane * PX;
+    const bool active = x < nx;
+    const int xc = active ? x : xs;
+    bool xin[PX], all_in = true;
+#pragma unroll
+    for (int e = 0; e < PX; ++e) { xin[e] = x + e >= 1 && x + e <= nx - 2; all_in = all_in && xin[e]; }
+    const int hx = lane < 32 ? xs - 1 : xs + W;
+    const bool hgrid = hx >= 0 && hx < nx;
+    const bool hin = hx >= 1 && hx <= nx - 2;
+    const int hxc = hgrid ? hx : xs;
+    const bool edge_lane = lane == 0 || lane == 63;
+
+    T acc[PX][3];
+#pragma unroll
+    for (int e = 0; e < PX; ++e) acc[e][0] = acc[e][1] = acc[e][2] = T(0);
+    V s0[D], s1[D], so[D];
+    T sh0[D], sh1[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) { s0[d] = V{}; s1[d] = V{}; so[d] = V{}; sh0[d] = sh1[d] = T(0); }
+
+    // rows of S that exist: adjoint: rows of I (q is zero elsewhere); primal: all grid rows
+    auto row_used = [&](int y) { return ADJ ? (y >= 1 && y <= ny - 2) : (y >= 0 && y < ny); };
+    const int yi0 = ys - 1, yi1 = ye;
+
+    // everything step y consumes: row y of the staged field, and for output row y-1 the
+    // array it is combined with (adjoint: u_bar, primal: c)
+    auto issue = [&](int y, auto dc, auto steady) {
+        constexpr int d = decltype(dc)::value;
+        constexpr bool STEADY = decltype(steady)::value;
+        if (!STEADY && y > yi1) return;
+        if (STEADY || row_used(y)) {
+            s0[d] = ld_vec<T, PX>(g0 + (size_t)y * nx + xc);
+            if (edge_lane) sh0[d] = g0[(size_t)y * nx + hxc];
+            if (ADJ) {
+                s1[d] = ld_vec<T, PX>(g1 + (size_t)y * nx + xc);
+                if (edge_lane) sh1[d] = g1[(size_t)y * nx + hxc];
+            }
+        }
+        const int yo = y - 1;
+        if (STEADY || yo >= ys)
+            so[d] = ADJ ? ld_vec_stream<T, PX>(og + (size_t)yo * nx + xc) : ld_vec_stream<T, PX>(g1 + (size_t)yo * nx + xc);
+    };
+    auto step = [&](int yi, auto dc, auto steady) {
+        constexpr int d = decltype(dc)::value;
+        constexpr bool STEADY = decltype(steady)::value;
+        const bool rin = STEADY || row_used(yi);
+        const int yo = yi - 1;
+        const V cur_out = so[d];
+        if (rin) {
+            T s[PX], sh;
+#pragma unroll
+            for (int e = 0; e < PX; ++e) {
+                if (ADJ) s[e] = (!GUARD || xin[e]) ? s0[d].v[e] * s1[d].v[e] : T(0);
+                else     s[e] = s0[d].v[e];
+            }
+            if (ADJ) sh = (!GUARD || hin) ? sh0[d] * sh1[d] : T(0);
+            else     sh = sh0[d];
+            T left, right;
+            wave_neighbours<T, PX>(s, sh, lane, left, right);
+#pragma unroll
+            for (int e = 0; e < PX; ++e) {
+                const T l = e == 0 ? left : s[e - 1];
+                const T r = e == PX - 1 ? right : s[e + 1];
+                // S row yi sits at offset oy = yi - yo of output row yo: k = 0: yo = yi-1 (oy=+1),
+                // k = 1: yo = yi, k = 2: yo = yi+1 (oy=-1)
+#pragma unroll
+                for (int k = 0; k < 3; ++k)
+                    acc[e][k] += (wt[2 - k][0] * l + wt[2 - k][1] * s[e]) + wt[2 - k][2] * r;
+            }
+        }
+        issue(yi + D, dc, steady);
+        if ((STEADY || yo >= ys) && active) {
+            V o;
+            if (ADJ) {
+#pragma unroll
+                for (int e = 0; e < PX; ++e) o.v[e] = cur_out.v[e] + acc[e][0];
+                st_vec_stream<T, PX>(og + (size_t)yo * nx + x, o);
+            } else if (STEADY || (yo >= 1 && yo <= ny - 2)) {
+#pragma unroll
+                for (int e = 0; e < PX; ++e) o.v[e] = cur_out.v[e] * acc[e][0];
+                T *rp = og + (size_t)yo * nx + x;
+                if (all_in) {
+                    st_vec_stream<T, PX>(rp, o);
+                } else {                              // r outside I stays untouched
+#pragma unroll
+                    for (int e = 0; e < PX; ++e)
+                        if (xin[e]) rp[e] = o.v[e];
+                }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < PX; ++e) {
+            acc[e][0] = acc[e][1];
+            acc[e][1] = acc[e][2];
+            acc[e][2] = T(0);
+        }
+    };
+    using No = std::integral_constant<bool, false>;
+    using Yes = std::integral_constant<bool, true>;
+    static_assert(D <= 2, "box2d_strip: D is 1 or 2");
+    auto step_any = [&](int yi, int d) {
+        if (D == 1 || d == 0) step(yi, std::integral_constant<int, 0>{}, No{});
+        else step(yi, std::integral_constant<int, (D > 1 ? 1 : 0)>{}, No{});
+    };
+    issue(yi0, std::integral_constant<int, 0>{}, No{});
+    if (D > 1) issue(yi0 + 1, std::integral_constant<int, (D > 1 ? 1 : 0)>{}, No{});
+    // steady steps yi in [lo, hi]: rows yi and yi+D exist and lie in I; output rows yi-1 and
+    // yi+D-1 belong to this chunk and (primal) to I
+    const int lo = max(ys + 1, 2);
+    const int hi = min(ny - 1, ye) - 1 - D;
+    int yi = yi0, d = 0;
+    while (yi <= yi1 && (yi < lo || d != 0)) {
+        step_any(yi, d);
+        ++yi;
+        d = d + 1 == D ? 0 : d + 1;
+    }
+    while (yi + D - 1 <= hi) {
+        step(yi, std::integral_constant<int, 0>{}, Yes{});
+        if (D > 1) step(yi + 1, std::integral_constant<int, (D > 1 ? 1 : 0)>{}, Yes{});
+        yi += D;
+    }
+    while (yi <= yi1) {
+        step_any(yi, d);
+        ++yi;
+        d = d + 1 == D ? 0 : d + 1;
+    }
+}
+
+template <class T, int PX, bool ADJ, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void box2d_kernel(BoxArgs a)
+{
+    constexpr int W = 64 * PX;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int xs = (blockIdx.x * WAVES + wave) * W;
+    if (xs >= a.nx) return;                         // wave-uniform; no barrier in this kernel
+    const int ys = blockIdx.y * a.chunk;
+    const int ye = min(ys + a.chunk, a.ny);
+    const bool core = xs >= 2 && xs + W <= a.nx - 2 && ys >= 2 && ye <= a.ny - 2;
+    if (core) box2d_strip<T, PX, 2, ADJ, false>(a, xs, ys, ye, lane);
+    else      box2d_strip<T, PX, 2, ADJ, true>(a, xs, ys, ye, lane);
+}
+
+// ------------------------------------------------------------------------------ 3-D
+template <class T, int BX, int BY, int PY>
+struct BoxTile {
+    static constexpr int TX = BX, TY = BY * PY, NT = BX * BY;
+    static constexpr int LX = TX + 2, LY = TY + 2, PLANE = LX * LY;
+    static constexpr int NH = PLANE - TX * TY;          // full ring, corners included
+    static constexpr int HS = (NH + NT - 1) / NT;
+    // ring cell h -> LDS coordinates: row 0, row LY-1, then the two side columns
+    __device__ static __forceinline__ bool halo_cell(int h, int &lx, int &ly)
+    {
+        if (h < LX) { lx = h; ly = 0; }
+        else if (h < 2 * LX) { lx = h - LX; ly = LY - 1; }
+        else { const int h2 = h - 2 * LX; lx = (h2 & 1) ? LX - 1 : 0; ly = 1 + (h2 >> 1); }
+        return h < NH;
+    }
+};
+
+template <class T, int BX, int BY, int PY, bool ADJ, bool GUARD>
+__device__ __forceinline__ void box3d_march(const BoxArgs &a, int tix, int tiy, int tiz, T *__restrict__ sq)
+{
+    using G = BoxTile<T, BX, BY, PY>;
+    constexpr int TX = G::TX, TY = G::TY, LX = G::LX, HS = G::HS;
+    const int tid = threadIdx.x;
+    const int tx = tid % BX, ty = tid / BX;
+    const int nx = a.nx, ny = a.ny, nz = a.nz;
+    const size_t plane = (size_t)nx * ny;
+    const int x0 = tix * TX, y0 = tiy * TY;
+    const int zs = tiz * a.chunk;
+    const int ze = min(zs + a.chunk, nz);
+    const T *__restrict__ g0 = static_cast<const T *>(a.in0);
+    const T *__restrict__ g1 = static_cast<const T *>(a.in1);
+    T *__restrict__ og = static_cast<T *>(a.out);
+    T wt[27];
+#pragma unroll
+    for (int i = 0; i < 27; ++i) wt[i] = (T)a.w[i];
+    const uint32_t dummy = (uint32_t)((size_t)y0 * nx + x0) * sizeof(T);
+
+    uint32_t ooff[PY];
+    bool ouse[PY], ostore[PY];                      // ouse: cell in I (x,y); ostore: cell receives output
+    const int x = x0 + tx;
+#pragma unroll
+    for (int p = 0; p < PY; ++p) {
+        const int y = y0 + ty * PY + p;
+        const bool ingrid = x < nx && y < ny;
+        ouse[p] = x >= 1 && x <= nx - 2 && y >= 1 && y <= ny - 2;
+        ostore[p] = ADJ ? ingrid : ouse[p];
+        ooff[p] = ingrid ? (uint32_t)((size_t)y * nx + x) * sizeof(T) : dummy;
+    }
+    uint32_t hoff[HS];
+    int hlds[HS];
+    bool huse[HS];
+#pragma unroll
+    for (int s = 0; s < HS; ++s) {
+        int lx, ly;
+        const bool slot = G::halo_cell(tid + s * G::NT, lx, ly);
+        const int gx = x0 - 1 + lx, gy = y0 - 1 + ly;
+        const bool ingrid = slot && gx >= 0 && gx < nx && gy >= 0 && gy < ny;
+        huse[s] = ADJ ? (slot && gx >= 1 && gx <= nx - 2 && gy >= 1 && gy <= ny - 2) : ingrid;
+        hoff[s] = ingrid ? (uint32_t)((size_t)gy * nx + gx) * sizeof(T) : dummy;
+        hlds[s] = slot ? ly * LX + lx : -1;
+    }
+
+    T acc[PY][3];
+#pragma unroll
+    for (int p = 0; p < PY; ++p) acc[p][0] = acc[p][1] = acc[p][2] = T(0);
+    T n0[PY], n1[PY], nh0[HS], nh1[HS], nout[PY];
+#pragma unroll
+    for (int p = 0; p < PY; ++p) n0[p] = n1[p] = nout[p] = T(0);
+#pragma unroll
+    for (int s = 0; s < HS; ++s) nh0[s] = nh1[s] = T(0);
+
+    auto plane_used = [&](int z) { return ADJ ? (z >= 1 && z <= nz - 2) : (z >= 0 && z < nz); };
+    auto load_plane = [&](int z) {
+        const T *p0 = g0 + (size_t)z * plane;
+        const T *p1 = g1 + (size_t)z * plane;
+#pragma unroll
+        for (int p = 0; p < PY; ++p) { n0[p] = ld_off(p0, ooff[p]); if (ADJ) n1[p] = ld_off(p1, ooff[p]); }
+#pragma unroll
+        for (int s = 0; s < HS; ++s) { nh0[s] = ld_off(p0, hoff[s]); if (ADJ) nh1[s] = ld_off(p1, hoff[s]); }
+    };
+    auto load_out = [&](int zo) {
+        const T *po = (ADJ ? static_cast<const T *>(og) : g1) + (size_t)zo * plane;
+#pragma unroll
+        for (int p = 0; p < PY; ++p) nout[p] = ld_stream<T, true>(po, ooff[p]);
+    };
+    const int zi0 = zs - 1, zi1 = ze;
+    if (plane_used(zi0)) load_plane(zi0);
+    int buf = 0;
+    for (int zi = zi0; zi <= zi1; ++zi) {
+        const bool zin = plane_used(zi);
+        const int zo = zi - 1;
+        T *sb = sq + buf * G::PLANE;
+        if (zin) {
+#pragma unroll
+            for (int p = 0; p < PY; ++p) {
+                T s;
+                if (ADJ) s = (!GUARD || ouse[p]) ? n0[p] * n1[p] : T(0);
+                else     s = n0[p];
+                sb[(1 + ty * PY + p) * LX + 1 + tx] = s;
+            }
+#pragma unroll
+            for (int s = 0; s < HS; ++s) {
+                T v;
+                if (ADJ) v = huse[s] ? nh0[s] * nh1[s] : T(0);
+                else     v = nh0[s];
+                if (hlds[s] >= 0) sb[hlds[s]] = v;
+            }
+        }
+        T cur_out[PY];
+#pragma unroll
+        for (int p = 0; p < PY; ++p) cur_out[p] = nout[p];
+        if (zi + 1 <= zi1) {
+            if (plane_used(zi + 1)) load_plane(zi + 1);
+            if (zo + 1 >= zs) load_out(zo + 1);
+        }
+        if (zin) {
+            __syncthreads();
+            // rows ty*PY .. ty*PY+PY+1 of the LDS plane, three columns each
+            T win[PY + 2][3];
+#pragma unroll
+            for (int i = 0; i < PY + 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 3; ++j) win[i][j] = sb[(ty * PY + i) * LX + tx + j];
+#pragma unroll
+            for (int p = 0; p < PY; ++p)
+#pragma unroll
+                for (int k = 0; k < 3; ++k) {       // k = 0: zo = zi-1 (oz=+1), 1: zo = zi, 2: zo = zi+1 (oz=-1)
+                    const T *w9 = wt + 9 * (2 - k);
+                    T s = T(0);
+#pragma unroll
+                    for (int oy = 0; oy < 3; ++oy)
+#pragma unroll
+                        for (int ox = 0; ox < 3; ++ox) s += w9[ox + 3 * oy] * win[p + oy][ox];
+                    acc[p][k] += s;
+                }
+            buf ^= 1;
+        }
+        if (zo >= zs && (ADJ || (zo >= 1 && zo <= nz - 2))) {
+            T *po = og + (size_t)zo * plane;
+#pragma unroll
+            for (int p = 0; p < PY; ++p)
+                if (ostore[p]) st_stream<T, true>(po, ooff[p], ADJ ? cur_out[p] + acc[p][0] : cur_out[p] * acc[p][0]);
+        }
+#pragma unroll
+        for (int p = 0; p < PY; ++p) {
+            acc[p][0] = acc[p][1];
+            acc[p][1] = acc[p][2];
+            acc[p][2] = T(0);
+        }
+    }
+}
+
+template <class T, int BX, int BY, int PY, bool ADJ>
+__global__ __launch_bounds__(BX *BY) void box3d_kernel(BoxArgs a)
+{
+    using G = BoxTile<T, BX, BY, PY>;
+    __shared__ T sq[2 * G::PLANE];
+    const int L = xcd_contiguous_id(blockIdx.x, a.total_blocks);
+    const int tix = L % a.ntx;
+    const int t = L / a.ntx;
+    const int tiy = t % a.nty, tiz = t / a.nty;
+    const int x0 = tix * G::TX, y0 = tiy * G::TY;
+    const bool core = x0 >= 2 && x0 + G::TX + 2 <= a.nx && y0 >= 2 && y0 + G::TY + 2 <= a.ny;
+    if (core) box3d_march<T, BX, BY, PY, ADJ, false>(a, tix, tiy, tiz, sq);
+    else      box3d_march<T, BX, BY, PY, ADJ, true>(a, tix, tiy, tiz, sq);
+}
+
+// ------------------------------------------------------------------------- launchers
+static inline bool box_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+template <class T, int PX, bool ADJ>
+static hipError_t launch_box2d(BoxArgs a, hipStream_t stream)
+{
+    constexpr int WAVES = 8, W = 64 * PX;
+    const int nstrips = cdiv_i(a.nx, W);
+    const int bx = cdiv_i(nstrips, WAVES);
+    int dev = 0, ncu = 256, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+        ncu = v;
+    // about one workgroup of 8 waves per CU, each wave with two rows in flight
+    const int chunks = bx >= ncu ? 1 : cdiv_i(ncu, bx);
+    int chunk = cdiv_i(a.ny, chunks);
+    if (chunk < 16) chunk = 16;
+    if (chunk > a.ny) chunk = a.ny;
+    a.chunk = chunk;
+    dim3 grid(bx, cdiv_i(a.ny, chunk)), block(64 * WAVES);
+    hipLaunchKernelGGL((box2d_kernel<T, PX, ADJ, WAVES>), grid, block, 0, stream, a);
+    return hipGetLastError();
+}
+
+template <class T, bool ADJ>
+static hipError_t launch_box3d(BoxArgs a, const LaunchOptions &opt, hipStream_t stream)
+{
+    using G = BoxTile<T, 64, 8, 4>;
+    March3dArgs m{};
+    m.nx = a.nx; m.ny = a.ny; m.nz = a.nz;
+    plan_march(m, G::TX, G::TY, 1, opt.zchunk);
+    a.ntx = m.ntx; a.nty = m.nty; a.ntz = m.ntz; a.chunk = m.zchunk; a.total_blocks = m.total_blocks;
+    hipLaunchKernelGGL((box3d_kernel<T, 64, 8, 4, ADJ>), dim3(a.total_blocks), dim3(G::NT), 0, stream, a);
+    return hipGetLastError();
+}
+
+template <bool ADJ>
+static hipError_t launch_box_nd(int is_f64, int ndim, const BoxArgs &a, const LaunchOptions &opt, hipStream_t stream)
+{
+    if (ndim == 3) return is_f64 ? launch_box3d<double, ADJ>(a, opt, stream) : launch_box3d<float, ADJ>(a, opt, stream);
+    const bool al = box_aligned16(a.in0) && box_aligned16(a.in1) && box_aligned16(a.out);
+    if (is_f64) return (al && a.nx % 2 == 0) ? launch_box2d<double, 2, ADJ>(a, stream) : launch_box2d<double, 1, ADJ>(a, stream);
+    return (al && a.nx % 4 == 0) ? launch_box2d<float, 4, ADJ>(a, stream) : launch_box2d<float, 1, ADJ>(a, stream);
+}
+
+// w: 27 gather weights indexed (ox+1) + 3(oy+1) + 9(oz+1) (already mirrored for the adjoint)
+hipError_t launch_box(int adjoint, int is_f64, int ndim, int nx, int ny, int nz, const double *w,
+                      const void *in0, const void *in1, void *out, const LaunchOptions &opt, hipStream_t stream)
+{
+    BoxArgs a{};
+    a.in0 = in0; a.in1 = in1; a.out = out;
+    a.nx = nx; a.ny = ny; a.nz = nz;
+    for (int i = 0; i < 27; ++i) a.w[i] = w[i];
+    return adjoint ? launch_box_nd<true>(is_f64, ndim, a, opt, stream) : launch_box_nd<false>(is_f64, ndim, a, opt, stream);
+}
+
+}  // namespace sadj

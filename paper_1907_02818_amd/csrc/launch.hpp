@@ -33,4 +33,10 @@ hipError_t launch_adjoint_burgers1d(int is_f64, long n, double C, double D, cons
 hipError_t launch_primal_burgers1d(int is_f64, long n, double C, double D, const void *u, void *r,
                                    hipStream_t stream);
 
+// Dense 3^d box stencils; w = gather weights (mirrored by the caller for the adjoint).
+hipError_t launch_box1d(int adjoint, int is_f64, long n, const double *w, const void *in0, const void *in1,
+                        void *out, hipStream_t stream);
+hipError_t launch_box(int adjoint, int is_f64, int ndim, int nx, int ny, int nz, const double *w,
+                      const void *in0, const void *in1, void *out, const LaunchOptions &opt, hipStream_t stream);
+
 }  // namespace sadj

@@ -24,13 +24,14 @@ struct Args1d {
     void *o0, *o1;              // outputs
     long n;
     double C, D;
+    double w[3];                // box stencil: gather weights at offsets -1, 0, +1
     long core_segs;             // core waves handle segments 1 .. core_segs
     long core_blocks;           // workgroups [0, core_blocks) are core, the rest remainder
     long rem_segs;              // remainder waves: index 0 -> segment 0, k>0 -> segment core_segs + k
 };
 
 constexpr int kWaves1d = 4;
-enum Op1d { OP_ADJ_WAVE, OP_ADJ_WAVE_UPREV, OP_PRI_WAVE, OP_PRI_BURGERS, OP_ADJ_BURGERS };
+enum Op1d { OP_ADJ_WAVE, OP_ADJ_WAVE_UPREV, OP_PRI_WAVE, OP_PRI_BURGERS, OP_ADJ_BURGERS, OP_ADJ_BOX, OP_PRI_BOX };
 
 // Load PX consecutive cells starting at x.  Unguarded: one vector load.  Guarded:
 // element-wise, indices clamped to [0, n-1].
@@ -148,6 +149,54 @@ __device__ __forceinline__ void pri_wave1d_segment(const Args1d &a, long xs, int
     store_cells<T, PX, GUARD>(rg, x, n, out, ok);
 }
 
+// ------------------------------------------------ three-point stencil, general weights
+// primal   r[i] = c[i]*(w[-1] u[i-1] + w[0] u[i] + w[+1] u[i+1])            for i in I
+// adjoint  u_bar[j] += W[-1] q[j-1] + W[0] q[j] + W[+1] q[j+1], q = c*r_bar on I, else 0,
+// with W the mirrored table W[o] = w[-o] (paper Section 3.2: the worked example with
+// weights (2,-3,4), whose outer weights trade places in the adjoint).  a.w holds the
+// gather weights, i.e. w for the primal and W for the adjoint.
+template <class T, int PX, bool GUARD, bool ADJ>
+__device__ __forceinline__ void box1d_segment(const Args1d &a, long xs, int lane)
+{
+    constexpr int W = 64 * PX;
+    const long n = a.n;
+    const T wm = (T)a.w[0], w0 = (T)a.w[1], wp = (T)a.w[2];
+    const T *g0 = static_cast<const T *>(a.a0);      // adjoint: c      primal: u
+    const T *g1 = static_cast<const T *>(a.a1);      // adjoint: r_bar  primal: c
+    T *og = static_cast<T *>(a.o0);
+    const long x = xs + (long)lane * PX;
+    const long hx = lane < 32 ? xs - 1 : xs + W;
+    T v0[PX], v1[PX], vo[PX];
+    load_cells<T, PX, GUARD>(g0, x, n, v0);
+    load_cells<T, PX, GUARD>(g1, x, n, v1);
+    if (ADJ) load_cells<T, PX, GUARD>(og, x, n, vo);
+    T sh = load_cell<T, GUARD>(g0, hx, n, lane);
+    if (ADJ) {
+        const T h1 = load_cell<T, GUARD>(g1, hx, n, lane);
+        const bool hin = GUARD ? (hx >= 1 && hx <= n - 2) : true;
+        sh = hin ? sh * h1 : T(0);
+    }
+    T s[PX];
+    bool ok[PX];
+#pragma unroll
+    for (int e = 0; e < PX; ++e) {
+        const bool in = GUARD ? (x + e >= 1 && x + e <= n - 2) : true;
+        if (ADJ) { s[e] = in ? v0[e] * v1[e] : T(0); ok[e] = GUARD ? (x + e < n) : true; }
+        else     { s[e] = v0[e]; ok[e] = in; }
+    }
+    T left, right;
+    wave_neighbours<T, PX>(s, sh, lane, left, right);
+    T out[PX];
+#pragma unroll
+    for (int e = 0; e < PX; ++e) {
+        const T l = e == 0 ? left : s[e - 1];
+        const T r = e == PX - 1 ? right : s[e + 1];
+        const T sum = (wm * l + w0 * s[e]) + wp * r;
+        out[e] = ADJ ? vo[e] + sum : v1[e] * sum;
+    }
+    store_cells<T, PX, GUARD>(og, x, n, out, ok);
+}
+
 // ----------------------------------------------------------------- Burgers, primal
 template <class T> __device__ __forceinline__ T pos_part(T v) { return v > T(0) ? v : T(0); }
 template <class T> __device__ __forceinline__ T neg_part(T v) { return v < T(0) ? v : T(0); }
@@ -240,6 +289,8 @@ __device__ __forceinline__ void run_segment(const Args1d &a, long xs, int lane)
     else if (OP == OP_ADJ_WAVE_UPREV) adj_wave1d_segment<T, PX, GUARD, true>(a, xs, lane);
     else if (OP == OP_PRI_WAVE) pri_wave1d_segment<T, PX, GUARD>(a, xs, lane);
     else if (OP == OP_PRI_BURGERS) pri_burgers_segment<T, PX, GUARD>(a, xs, lane);
+    else if (OP == OP_ADJ_BOX) box1d_segment<T, PX, GUARD, true>(a, xs, lane);
+    else if (OP == OP_PRI_BOX) box1d_segment<T, PX, GUARD, false>(a, xs, lane);
     else adj_burgers_segment<T, PX, GUARD>(a, xs, lane);
 }
 
@@ -318,6 +369,15 @@ hipError_t launch_primal_burgers1d(int is_f64, long n, double C, double D, const
     Args1d a{};
     a.a0 = u; a.o0 = r; a.n = n; a.C = C; a.D = D;
     return dispatch_1d<OP_PRI_BURGERS>(is_f64, a, stream);
+}
+
+hipError_t launch_box1d(int adjoint, int is_f64, long n, const double *w, const void *in0, const void *in1,
+                        void *out, hipStream_t stream)
+{
+    Args1d a{};
+    a.a0 = in0; a.a1 = in1; a.o0 = out; a.n = n;
+    a.w[0] = w[0]; a.w[1] = w[1]; a.w[2] = w[2];
+    return adjoint ? dispatch_1d<OP_ADJ_BOX>(is_f64, a, stream) : dispatch_1d<OP_PRI_BOX>(is_f64, a, stream);
 }
 
 }  // namespace sadj

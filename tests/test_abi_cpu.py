@@ -25,7 +25,7 @@ def test_header_declares_the_expected_entry_points():
     names = _declared_functions()
     for n in ("sadj_primal_wave1d", "sadj_adjoint_wave1d", "sadj_primal_wave2d", "sadj_adjoint_wave2d",
               "sadj_primal_wave3d", "sadj_adjoint_wave3d", "sadj_primal_burgers1d",
-              "sadj_adjoint_burgers1d", "sadj_adjoint_wave3d_steps", "sadj_status_string", "sadj_version", "sadj_set_option",
+              "sadj_adjoint_burgers1d", "sadj_adjoint_wave3d_steps", "sadj_primal_box", "sadj_adjoint_box", "sadj_status_string", "sadj_version", "sadj_set_option",
               "sadj_get_option", "sadj_last_device_error"):
         assert n in names
 
@@ -96,6 +96,12 @@ def test_argument_errors_are_reported_before_any_launch():
     assert lib.sadj_adjoint_wave3d_steps(F64, 4, 32, 32, 32, 3, A, B, C_, B, None) == 3
     assert lib.sadj_adjoint_wave3d_steps(F64, 4, 32, 32, 32, 3, A, A, C_, D_, None) == 3
     assert lib.sadj_adjoint_wave3d_steps(F64, 2, 32, 32, 32, 3, A, B, C_, D_, None) == 4
+    # box stencils: host weight table required, ndim in 1..3
+    W9 = (ctypes.c_double * 27)(*([1.0] * 27))
+    assert lib.sadj_adjoint_box(F64, 2, 32, 32, 1, None, A, B, C_, None) == 1
+    assert lib.sadj_adjoint_box(F64, 4, 32, 32, 32, W9, A, B, C_, None) == 4
+    assert lib.sadj_adjoint_box(F64, 3, 32, 2, 32, W9, A, B, C_, None) == 2
+    assert lib.sadj_primal_box(F64, 1, 64, 1, 1, W9, A, B, A, None) == 3
     # unsupported radius / dtype
     assert lib.sadj_adjoint_wave3d(F64, 2, 32, 32, 32, A, B, C_, None, None) == 4
     assert lib.sadj_adjoint_wave3d(7, 4, 32, 32, 32, A, B, C_, None, None) == 4
