@@ -92,6 +92,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--all", action="store_true", help="also time the other workloads")
+    ap.add_argument("--remainder-study", action="store_true",
+                    help="also time the three remainder strategies of the 3-D adjoint")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--size", type=int, default=512, help="grid edge of the headline workload")
     ap.add_argument("--copy-probe", action="store_true",
@@ -160,6 +162,22 @@ def main():
     add("wave3d_r4_f32_adjoint", lambda: sadj.sadj_adjoint_wave3d(R, c32, rb32, ub32), N,
         wave_adjoint_bytes(shape, R, 4), "f32")
     del c32, rb32, ub32
+
+    if args.remainder_study:
+        # Section 3.3.4's alternatives on the GPU: 0 guarded only where needed (default),
+        # 1 guarded everywhere ("zero padding"), 2 core and remainder as separate dispatches
+        for rad in (4, 1):
+            for strat in (0, 1, 2):
+                sadj.set_option("wave3d.remainder", strat)
+                add("remainder_strategy%d_r%d_f64_adjoint" % (strat, rad),
+                    lambda: sadj.sadj_adjoint_wave3d(rad, c, rb, ub), N, wave_adjoint_bytes(shape, rad, 8), "f64")
+        sadj.set_option("wave3d.remainder", 0)
+        # Section 3.5: terms added in the order and rounding of the sequential scatter
+        sadj.set_option("wave3d.order", 1)
+        for rad in (4, 1):
+            add("scatter_order_r%d_f64_adjoint" % rad, lambda: sadj.sadj_adjoint_wave3d(rad, c, rb, ub), N,
+                wave_adjoint_bytes(shape, rad, 8), "f64")
+        sadj.set_option("wave3d.order", 0)
 
     if args.all:
         upb = torch.from_numpy(inputs.config_inputs("wave3d_r4", shape=shape, fields=("u_prev_bar",))["u_prev_bar"]).to(dev)

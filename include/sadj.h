@@ -165,6 +165,25 @@ sadj_status sadj_adjoint_burgers1d(sadj_dtype dtype, long n, double C, double D,
  *   "wave3d.variant" tile-shape variant index (default 0 = automatic).
  *   "wave2d.ychunk"  rows of output per wave along y (default 0 = automatic).
  *   "wave2d.variant" load-pipeline depth / workgroup size variant (default 0 = automatic).
+ *   "wave3d.remainder" treatment of the boundary / remainder regions (Section 3.3.4) by
+ *                    sadj_adjoint_wave3d:  0 (default) one dispatch, tiles that touch the
+ *                    remainder run guarded statements, core tiles unguarded ones;
+ *                    1 every tile runs the guarded statements (as if the inputs were
+ *                    zero-padded); 2 core tiles and remainder tiles in two disjoint
+ *                    dispatches.  1 and 2 serve to measure the strategies; they need
+ *                    u_prev_bar == NULL, variant 0-2, nx a multiple of 16 bytes' worth of
+ *                    elements and 16-byte aligned arrays, else SADJ_ERR_UNSUPPORTED.
+ *   "wave3d.order"   order in which sadj_adjoint_wave3d adds the terms of one u_bar[j]
+ *                    (Section 3.5: a gather can respect an order the user chooses and
+ *                    stay parallel).  0 (default): the kernel's own fixed order, fastest.
+ *                    1: the order and rounding of the sequential scatter adjoint that
+ *                    conventional reverse mode produces (Section 3.2) -- starting from the
+ *                    incoming u_bar[j], terms by ascending memory index of their primal
+ *                    iteration i, each term (c[i]*w)*r_bar[i] and each addition rounded
+ *                    separately; in fp64 the result equals that sequential loop bit for
+ *                    bit.  Both orders are deterministic.  "wave3d.variant" and
+ *                    "wave3d.remainder" do not apply to order 1; other entry points
+ *                    ignore this option.
  * Unknown names or out-of-range values give SADJ_ERR_UNSUPPORTED and change nothing.
  * sadj_get_option returns SADJ_OK and stores the value, or SADJ_ERR_UNSUPPORTED.
  */

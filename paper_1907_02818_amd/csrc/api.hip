@@ -9,7 +9,7 @@
 
 namespace {
 
-std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0}, g_variant2d{0};
+std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0}, g_variant2d{0}, g_remainder{0}, g_order{0};
 
 sadj::LaunchOptions current_options()
 {
@@ -18,6 +18,7 @@ sadj::LaunchOptions current_options()
     o.variant = g_variant.load();
     o.ychunk2d = g_ychunk2d.load();
     o.variant2d = g_variant2d.load();
+    o.remainder = g_remainder.load();
     return o;
 }
 
@@ -63,6 +64,7 @@ thread_local hipError_t g_last_hip_error = hipSuccess;
 sadj_status from_hip(hipError_t e)
 {
     if (e == hipSuccess) return SADJ_OK;
+    if (e == hipErrorNotSupported) return SADJ_ERR_UNSUPPORTED;   // a launcher declined before enqueueing
     g_last_hip_error = e;
     return SADJ_ERR_DEVICE;
 }
@@ -115,6 +117,16 @@ sadj_status sadj_set_option(const char *name, long value)
         g_variant2d = value;
         return SADJ_OK;
     }
+    if (!std::strcmp(name, "wave3d.remainder")) {
+        if (value < 0 || value > 2) return SADJ_ERR_UNSUPPORTED;
+        g_remainder = value;
+        return SADJ_OK;
+    }
+    if (!std::strcmp(name, "wave3d.order")) {
+        if (value < 0 || value > 1) return SADJ_ERR_UNSUPPORTED;
+        g_order = value;
+        return SADJ_OK;
+    }
 
     return SADJ_ERR_UNSUPPORTED;
 }
@@ -126,6 +138,8 @@ sadj_status sadj_get_option(const char *name, long *value)
     if (!std::strcmp(name, "wave3d.variant")) { *value = g_variant; return SADJ_OK; }
     if (!std::strcmp(name, "wave2d.ychunk")) { *value = g_ychunk2d; return SADJ_OK; }
     if (!std::strcmp(name, "wave2d.variant")) { *value = g_variant2d; return SADJ_OK; }
+    if (!std::strcmp(name, "wave3d.remainder")) { *value = g_remainder; return SADJ_OK; }
+    if (!std::strcmp(name, "wave3d.order")) { *value = g_order; return SADJ_OK; }
     return SADJ_ERR_UNSUPPORTED;
 }
 
@@ -170,8 +184,12 @@ static sadj_status adjoint_wave(int ndim, sadj_dtype dtype, int radius, long nx,
     switch (ndim) {
     case 1: return from_hip(sadj::launch_adjoint_wave1d(f64, nx, c, r_bar, u_bar, u_prev_bar, st));
     case 2: return from_hip(sadj::launch_adjoint_wave2d(f64, (int)nx, (int)ny, c, r_bar, u_bar, u_prev_bar, current_options(), st));
-    default: return from_hip(sadj::launch_adjoint_wave3d(f64, radius, (int)nx, (int)ny, (int)nz, c, r_bar, u_bar,
-                                                         u_prev_bar, 0, current_options(), st));
+    default:
+        if (g_order.load() == 1)
+            return from_hip(sadj::launch_adjoint_wave3d_ordered(f64, radius, (int)nx, (int)ny, (int)nz, c, r_bar, u_bar,
+                                                                u_prev_bar, current_options(), st));
+        return from_hip(sadj::launch_adjoint_wave3d(f64, radius, (int)nx, (int)ny, (int)nz, c, r_bar, u_bar,
+                                                    u_prev_bar, 0, current_options(), st));
     }
 }
 
@@ -226,7 +244,8 @@ sadj_status sadj_adjoint_wave3d_steps(sadj_dtype dtype, int radius, long nx, lon
     const int f64 = dtype == SADJ_F64;
     void *lam[3] = {lam0, lam1, lam2};
     clear_stale_hip_error();
-    const sadj::LaunchOptions opt = current_options();
+    sadj::LaunchOptions opt = current_options();
+    opt.remainder = 0;   // the strategy variants exist for the single-step call only
     for (long k = 0; k < nsteps; ++k) {
         void *a = lam[k % 3], *b = lam[(k + 1) % 3], *p = lam[(k + 2) % 3];
         // the buffer that receives -a was the r_bar of the previous step: it is dead and is assigned

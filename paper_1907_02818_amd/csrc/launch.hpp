@@ -9,11 +9,16 @@ struct LaunchOptions {
     long variant = 0;    // wave3d: tile-shape variant
     long ychunk2d = 0;   // wave2d: output rows per wave (0 = automatic)
     long variant2d = 0;  // wave2d: pipeline depth / workgroup size variant
+    long remainder = 0;  // wave3d adjoint: remainder strategy (0 guarded where needed, 1 guarded everywhere, 2 split dispatches)
 };
 
 hipError_t launch_adjoint_wave3d(int is_f64, int radius, int nx, int ny, int nz, const void *c,
                                  const void *r_bar, void *u_bar, void *u_prev_bar, int u_prev_bar_assign,
                                  const LaunchOptions &opt, hipStream_t stream);
+// Same result up to rounding; terms added in the order and rounding of the sequential scatter.
+hipError_t launch_adjoint_wave3d_ordered(int is_f64, int radius, int nx, int ny, int nz, const void *c,
+                                         const void *r_bar, void *u_bar, void *u_prev_bar,
+                                         const LaunchOptions &opt, hipStream_t stream);
 hipError_t launch_primal_wave3d(int is_f64, int radius, int nx, int ny, int nz, const void *u,
                                 const void *u_prev, const void *c, void *r,
                                 const LaunchOptions &opt, hipStream_t stream);

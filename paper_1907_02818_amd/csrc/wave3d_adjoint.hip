@@ -252,7 +252,13 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
     }
 }
 
-template <class T, int R, int BX, int BY, int PY, int PX, int D, bool NTU, int UPREV>
+// REM selects how the remainder (Section 3.3.4) is treated:
+//   0  one dispatch; a block-uniform test picks the unguarded (core) or the guarded body
+//   1  every tile runs the guarded body: all shifted statements everywhere, reads outside
+//      I yield zero -- the zero-padding strategy without owning the caller's memory
+//   2  core tiles only   } two disjoint dispatches, each with a single body and no
+//   3  remainder tiles only } choice between bodies (the split-nests strategy at tile level)
+template <class T, int R, int BX, int BY, int PY, int PX, int D, bool NTU, int UPREV, int REM>
 __global__ __launch_bounds__(BX *BY) void adj_wave3d_kernel(March3dArgs a)
 {
     using G = Tile3d<T, R, BX, BY, PY, PX>;
@@ -265,8 +271,16 @@ __global__ __launch_bounds__(BX *BY) void adj_wave3d_kernel(March3dArgs a)
     // core tile: own cells and halo cells all inside I in x and y
     const int x0 = tix * G::TX, y0 = tiy * G::TY;
     const bool core = x0 >= 2 * R && x0 + G::TX + 2 * R <= a.nx && y0 >= 2 * R && y0 + G::TY + 2 * R <= a.ny;
-    if (core) adj3d_march<T, R, BX, BY, PY, PX, D, NTU, false, UPREV>(a, tix, tiy, tiz, sq);
-    else      adj3d_march<T, R, BX, BY, PY, PX, D, NTU, true, UPREV>(a, tix, tiy, tiz, sq);
+    if (REM == 0) {
+        if (core) adj3d_march<T, R, BX, BY, PY, PX, D, NTU, false, UPREV>(a, tix, tiy, tiz, sq);
+        else      adj3d_march<T, R, BX, BY, PY, PX, D, NTU, true, UPREV>(a, tix, tiy, tiz, sq);
+    } else if (REM == 1) {
+        adj3d_march<T, R, BX, BY, PY, PX, D, NTU, true, UPREV>(a, tix, tiy, tiz, sq);
+    } else if (REM == 2) {
+        if (core) adj3d_march<T, R, BX, BY, PY, PX, D, NTU, false, UPREV>(a, tix, tiy, tiz, sq);
+    } else {
+        if (!core) adj3d_march<T, R, BX, BY, PY, PX, D, NTU, true, UPREV>(a, tix, tiy, tiz, sq);
+    }
 }
 
 static inline bool aligned_to(const void *p, size_t n) { return (reinterpret_cast<uintptr_t>(p) % n) == 0; }
@@ -285,9 +299,24 @@ static hipError_t launch_cfg(March3dArgs a, const LaunchOptions &opt, hipStream_
     }
     plan_march(a, G::TX, G::TY, R, opt.zchunk);
     dim3 grid(a.total_blocks), block(G::NT);
-    if (!a.out1)                hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 0>), grid, block, 0, stream, a);
-    else if (a.out1_assign == 0) hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 1>), grid, block, 0, stream, a);
-    else                        hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 2>), grid, block, 0, stream, a);
+    if (opt.remainder != 0) {
+        // the strategy study is built for the two default shapes and u_bar only
+        if constexpr (BX == 32 && BY == 16 && D == 1 && NTU) {
+            if (a.out1) return hipErrorNotSupported;
+            if (opt.remainder == 1) {
+                hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 0, 1>), grid, block, 0, stream, a);
+            } else {
+                hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 0, 2>), grid, block, 0, stream, a);
+                hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 0, 3>), grid, block, 0, stream, a);
+            }
+            return hipGetLastError();
+        } else {
+            return hipErrorNotSupported;
+        }
+    }
+    if (!a.out1)                hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 0, 0>), grid, block, 0, stream, a);
+    else if (a.out1_assign == 0) hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 1, 0>), grid, block, 0, stream, a);
+    else                        hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 2, 0>), grid, block, 0, stream, a);
     return hipGetLastError();
 }
 

@@ -1,0 +1,267 @@
+// 3-D linear wave stencil of radius R: gather-form adjoint that adds the terms of every
+// u_bar[j] in the order, and with the rounding, of the sequential scatter adjoint.
+//
+// Paper Section 3.5: the method assumes that the contributions to an output index may be
+// reordered, notes that floating point does not honour this, and observes that a gather
+// can respect any order the user chooses and still run in parallel, because all updates
+// of an index sit in one iteration.  The order offered here is the one a conventional
+// reverse-mode tool produces when its scatter loop runs sequentially (Section 3.2):
+// primal iterations i in ascending memory order (z slowest, x fastest), iteration i adding
+//     (2 + c[i]*3*w_0) * r_bar[i]     to u_bar[i]
+//     (c[i]*w_|k|) * r_bar[i]         to u_bar[i + k e_d],  k != 0, d = x, y, z
+// one rounded product and one rounded addition each, no fused multiply-add.  Output j
+// receives at most one term per iteration, so its terms arrive in the order of their
+// source cell:
+//     (x,y,z-R) .. (x,y,z-1),  (x,y-R,z) .. (x,y-1,z),  (x-R,y,z) .. (x-1,y,z),  (x,y,z),
+//     (x+1,y,z) .. (x+R,y,z),  (x,y+1,z) .. (x,y+R,z),  (x,y,z+1) .. (x,y,z+R),
+// starting from the incoming u_bar[j]; sources outside I contribute nothing (they are
+// skipped, not added as zeros, so that even the sign of a zero result is the scatter's).
+// In fp64 the result equals the sequential scatter adjoint bit for bit.
+//
+// Mapping.  Same z-march as the default kernel (a workgroup owns an x-y tile, 2R+1 running
+// sums per owned cell in registers, ascending source planes), with three differences:
+// c and r_bar are staged in LDS separately (a term is (c*w)*r_bar, not w*(c*r_bar)); a
+// running sum is initialised with u_bar when it is created, R planes before its own plane
+// arrives, instead of adding u_bar at the end; and contraction of multiply-add is off.
+#include "launch.hpp"
+#include "tile3d.hpp"
+
+#pragma clang fp contract(off)
+
+namespace sadj {
+
+template <class T, int R, int BX, int BY, int PY, bool GUARD, bool UPREV>
+__device__ __forceinline__ void adj3d_march_ordered(const March3dArgs &a, int tix, int tiy, int tiz,
+                                                    T *__restrict__ lds)
+{
+    using G = Tile3d<T, R, BX, BY, PY, 1>;
+    constexpr int TX = G::TX, TY = G::TY, LX = G::LX, LY = G::LY, HS = G::HS;
+    constexpr int NACC = 2 * R + 1;
+    const int tid = threadIdx.x;
+    const int tx = tid % BX, ty = tid / BX;
+    const int nx = a.nx, ny = a.ny, nz = a.nz;
+    const size_t plane = (size_t)nx * ny;
+    const int x0 = tix * TX, y0 = tiy * TY;
+    const int zs = tiz * a.zchunk;
+    const int ze = min(zs + a.zchunk, nz);
+
+    const T *__restrict__ cg = static_cast<const T *>(a.in0);
+    const T *__restrict__ rg = static_cast<const T *>(a.in1);
+    T *__restrict__ ug = static_cast<T *>(a.out0);
+    T *__restrict__ upg = static_cast<T *>(a.out1);
+
+    const uint32_t dummy = (uint32_t)((size_t)y0 * nx + x0) * sizeof(T);   // always inside the grid
+
+    // owned cells (x, y0 + ty*PY + p) and, per cell, which of its sources lie in I:
+    // bit R+d of xbits: x+d in I_x;  bit R+d of ybits[p]: y_p+d in I_y
+    const int x = x0 + tx;
+    uint32_t ooff[PY], ybits[PY], xbits = 0;
+    bool ostore[PY];
+#pragma unroll
+    for (int d = -R; d <= R; ++d)
+        if (!GUARD || (x + d >= R && x + d < nx - R)) xbits |= 1u << (R + d);
+#pragma unroll
+    for (int p = 0; p < PY; ++p) {
+        const int y = y0 + ty * PY + p;
+        ostore[p] = GUARD ? (x < nx && y < ny) : true;
+        ooff[p] = ostore[p] ? (uint32_t)((size_t)y * nx + x) * sizeof(T) : dummy;
+        ybits[p] = 0;
+#pragma unroll
+        for (int d = -R; d <= R; ++d)
+            if (!GUARD || (y + d >= R && y + d < ny - R)) ybits[p] |= 1u << (R + d);
+    }
+    auto xin = [&](int d) { return !GUARD || ((xbits >> (R + d)) & 1u); };
+    auto yin = [&](int p, int d) { return !GUARD || ((ybits[p] >> (R + d)) & 1u); };
+
+    // halo slots: loaded only where the cell lies in the grid (its use is decided per term)
+    uint32_t hoff[HS];
+    int hlds[HS];
+#pragma unroll
+    for (int s = 0; s < HS; ++s) {
+        int lx, ly;
+        const bool slot = G::halo_cell(tid, s, lx, ly);
+        const int gx = x0 - R + lx, gy = y0 - R + ly;
+        const bool ingrid = slot && (!GUARD || (gx >= 0 && gx < nx && gy >= 0 && gy < ny));
+        hoff[s] = ingrid ? (uint32_t)((size_t)gy * nx + gx) * sizeof(T) : dummy;
+        hlds[s] = slot ? ly * LX + lx : 0;          // cell (0,0) is a corner nobody reads
+    }
+
+    T acc[PY][NACC];
+#pragma unroll
+    for (int p = 0; p < PY; ++p)
+#pragma unroll
+        for (int k = 0; k < NACC; ++k) acc[p][k] = T(0);
+
+    T sc[PY], sr[PY], su[PY], sp[PY], shc[HS], shr[HS];
+#pragma unroll
+    for (int p = 0; p < PY; ++p) sc[p] = sr[p] = su[p] = sp[p] = T(0);
+#pragma unroll
+    for (int s = 0; s < HS; ++s) shc[s] = shr[s] = T(0);
+
+    const int zi0 = zs - R, zi1 = ze - 1 + R;       // source planes that reach outputs [zs, ze)
+    auto plane_in_I = [&](int z) { return z >= R && z < nz - R; };
+
+    // everything step z consumes: plane z of c and r_bar (if in I), u_bar of plane z+R
+    // (the running sum created in step z), u_prev_bar of plane z
+    auto issue = [&](int z) {
+        if (z > zi1) return;
+        if (plane_in_I(z)) {
+            const T *cp = cg + (size_t)z * plane;
+            const T *rp = rg + (size_t)z * plane;
+#pragma unroll
+            for (int p = 0; p < PY; ++p) { sc[p] = ld_off(cp, ooff[p]); sr[p] = ld_off(rp, ooff[p]); }
+#pragma unroll
+            for (int s = 0; s < HS; ++s) { shc[s] = ld_off(cp, hoff[s]); shr[s] = ld_off(rp, hoff[s]); }
+            if (UPREV && z >= zs && z < ze) {
+                const T *pp = upg + (size_t)z * plane;
+#pragma unroll
+                for (int p = 0; p < PY; ++p) sp[p] = ld_stream<T, true>(pp, ooff[p]);
+            }
+        }
+        const int zn = z + R;
+        if (zn >= zs && zn < ze) {
+            const T *up = ug + (size_t)zn * plane;
+#pragma unroll
+            for (int p = 0; p < PY; ++p) su[p] = ld_stream<T, true>(up, ooff[p]);
+        }
+    };
+
+    int buf = 0;
+    issue(zi0);
+    for (int zi = zi0; zi <= zi1; ++zi) {
+        const bool zin = plane_in_I(zi);
+        const int zo = zi - R, zn = zi + R;
+        T *lc = lds + buf * (2 * G::PLANE);
+        T *lr = lc + G::PLANE;
+        // the running sum of output plane zi+R starts from the incoming u_bar
+        if (zn >= zs && zn < ze) {
+#pragma unroll
+            for (int p = 0; p < PY; ++p) acc[p][NACC - 1] = su[p];
+        }
+        T cc[PY], rv[PY];
+#pragma unroll
+        for (int p = 0; p < PY; ++p) { cc[p] = sc[p]; rv[p] = sr[p]; }
+        if (zin) {
+#pragma unroll
+            for (int p = 0; p < PY; ++p) {
+                lc[(R + ty * PY + p) * LX + R + tx] = cc[p];
+                lr[(R + ty * PY + p) * LX + R + tx] = rv[p];
+            }
+#pragma unroll
+            for (int s = 0; s < HS; ++s) { lc[hlds[s]] = shc[s]; lr[hlds[s]] = shr[s]; }
+            if (UPREV && zi >= zs && zi < ze) {
+                T *pp = upg + (size_t)zi * plane;
+#pragma unroll
+                for (int p = 0; p < PY; ++p)
+                    if (ostore[p] && xin(0) && yin(p, 0)) st_stream<T, true>(pp, ooff[p], sp[p] - rv[p]);
+            }
+        }
+        issue(zi + 1);
+        if (zin) {
+            __syncthreads();
+#pragma unroll
+            for (int p = 0; p < PY; ++p) {
+                const int lrow = R + ty * PY + p, lcol = R + tx;
+                const bool own = xin(0) && yin(p, 0);
+                // this plane lies above the output planes zi-R .. zi-1: for them it is a
+                // source "z+k"; and below zi+1 .. zi+R: a source "z-k".  One term each.
+                T tz[R + 1];
+#pragma unroll
+                for (int k = 1; k <= R; ++k) tz[k] = (cc[p] * T(star_w<R>(k))) * rv[p];
+#pragma unroll
+                for (int k = 1; k <= R; ++k) {
+                    acc[p][R - k] = own ? acc[p][R - k] + tz[k] : acc[p][R - k];
+                    acc[p][R + k] = own ? acc[p][R + k] + tz[k] : acc[p][R + k];
+                }
+                // in-plane terms of output plane zi, in ascending order of the source cell
+                T s = acc[p][R];
+#pragma unroll
+                for (int k = R; k >= 1; --k) {      // (x, y-k)
+                    const T t = (lc[(lrow - k) * LX + lcol] * T(star_w<R>(k))) * lr[(lrow - k) * LX + lcol];
+                    s = (xin(0) && yin(p, -k)) ? s + t : s;
+                }
+#pragma unroll
+                for (int k = R; k >= 1; --k) {      // (x-k, y)
+                    const T t = (lc[lrow * LX + lcol - k] * T(star_w<R>(k))) * lr[lrow * LX + lcol - k];
+                    s = (xin(-k) && yin(p, 0)) ? s + t : s;
+                }
+                {
+                    const T t = (T(2) + cc[p] * T(3) * T(star_w<R>(0))) * rv[p];
+                    s = own ? s + t : s;
+                }
+#pragma unroll
+                for (int k = 1; k <= R; ++k) {      // (x+k, y)
+                    const T t = (lc[lrow * LX + lcol + k] * T(star_w<R>(k))) * lr[lrow * LX + lcol + k];
+                    s = (xin(k) && yin(p, 0)) ? s + t : s;
+                }
+#pragma unroll
+                for (int k = 1; k <= R; ++k) {      // (x, y+k)
+                    const T t = (lc[(lrow + k) * LX + lcol] * T(star_w<R>(k))) * lr[(lrow + k) * LX + lcol];
+                    s = (xin(0) && yin(p, k)) ? s + t : s;
+                }
+                acc[p][R] = s;
+            }
+            buf ^= 1;
+        }
+        if (zo >= zs) {                             // zo <= ze-1 because zi <= zi1
+            T *up = ug + (size_t)zo * plane;
+#pragma unroll
+            for (int p = 0; p < PY; ++p)
+                if (ostore[p]) st_stream<T, true>(up, ooff[p], acc[p][0]);
+        }
+#pragma unroll
+        for (int p = 0; p < PY; ++p) {
+#pragma unroll
+            for (int k = 0; k < NACC - 1; ++k) acc[p][k] = acc[p][k + 1];
+            acc[p][NACC - 1] = T(0);
+        }
+    }
+}
+
+template <class T, int R, int BX, int BY, int PY, bool UPREV>
+__global__ __launch_bounds__(BX *BY) void adj_wave3d_ordered_kernel(March3dArgs a)
+{
+    using G = Tile3d<T, R, BX, BY, PY, 1>;
+    __shared__ T lds[4 * G::PLANE];                 // two buffers of (c plane, r_bar plane)
+    const int L = xcd_contiguous_id(blockIdx.x, a.total_blocks);
+    const int tix = L % a.ntx;
+    const int t = L / a.ntx;
+    const int tiy = t % a.nty;
+    const int tiz = t / a.nty;
+    const int x0 = tix * G::TX, y0 = tiy * G::TY;
+    const bool core = x0 >= 2 * R && x0 + G::TX + 2 * R <= a.nx && y0 >= 2 * R && y0 + G::TY + 2 * R <= a.ny;
+    if (core) adj3d_march_ordered<T, R, BX, BY, PY, false, UPREV>(a, tix, tiy, tiz, lds);
+    else      adj3d_march_ordered<T, R, BX, BY, PY, true, UPREV>(a, tix, tiy, tiz, lds);
+}
+
+template <class T, int R, int PY>
+static hipError_t launch_ordered_P(March3dArgs a, const LaunchOptions &opt, hipStream_t stream)
+{
+    constexpr int BX = 64, BY = 8;
+    using G = Tile3d<T, R, BX, BY, PY, 1>;
+    plan_march(a, G::TX, G::TY, R, opt.zchunk);
+    dim3 grid(a.total_blocks), block(G::NT);
+    if (a.out1) hipLaunchKernelGGL((adj_wave3d_ordered_kernel<T, R, BX, BY, PY, true>), grid, block, 0, stream, a);
+    else        hipLaunchKernelGGL((adj_wave3d_ordered_kernel<T, R, BX, BY, PY, false>), grid, block, 0, stream, a);
+    return hipGetLastError();
+}
+
+template <class T, int R>
+static hipError_t launch_ordered_T(const March3dArgs &a, const LaunchOptions &opt, hipStream_t stream)
+{
+    // 64 x 32 tile, 512 threads; a 64 x 16 tile (two workgroups per CU) measured 9-15 % slower
+    return launch_ordered_P<T, R, 4>(a, opt, stream);
+}
+
+hipError_t launch_adjoint_wave3d_ordered(int is_f64, int radius, int nx, int ny, int nz, const void *c,
+                                         const void *r_bar, void *u_bar, void *u_prev_bar,
+                                         const LaunchOptions &opt, hipStream_t stream)
+{
+    March3dArgs a{};
+    a.in0 = c; a.in1 = r_bar; a.out0 = u_bar; a.out1 = u_prev_bar;
+    a.nx = nx; a.ny = ny; a.nz = nz;
+    if (is_f64) return radius == 1 ? launch_ordered_T<double, 1>(a, opt, stream) : launch_ordered_T<double, 4>(a, opt, stream);
+    return radius == 1 ? launch_ordered_T<float, 1>(a, opt, stream) : launch_ordered_T<float, 4>(a, opt, stream);
+}
+
+}  // namespace sadj

@@ -58,6 +58,16 @@ def test_options_roundtrip_and_reject_unknown():
     sadj.set_option("wave3d.zchunk", 32)
     assert sadj.get_option("wave3d.zchunk") == 32
     sadj.set_option("wave3d.zchunk", old)
+    for v in (1, 2, 0):
+        sadj.set_option("wave3d.remainder", v)
+        assert sadj.get_option("wave3d.remainder") == v
+    with pytest.raises(sadj.SadjError):
+        sadj.set_option("wave3d.remainder", 3)
+    for v in (1, 0):
+        sadj.set_option("wave3d.order", v)
+        assert sadj.get_option("wave3d.order") == v
+    with pytest.raises(sadj.SadjError):
+        sadj.set_option("wave3d.order", 2)
     with pytest.raises(sadj.SadjError) as e:
         sadj.set_option("no.such.option", 1)
     assert e.value.status == 4

@@ -320,3 +320,16 @@ def test_bad_arguments_are_rejected():
         oracle.wave_adjoint(z, z, z, 4)          # nz = 8 < 2R+1
     with pytest.raises(ValueError):
         oracle.wave_adjoint(np.zeros((9, 9, 9)), np.zeros((9, 9, 9)), np.zeros((9, 9, 9)), 5)
+
+
+@pytest.mark.parametrize("radius,shape", [(4, (13, 17, 21)), (4, (9, 9, 9)), (4, (20, 11, 30)), (1, (3, 3, 3)), (1, (5, 6, 7))])
+def test_scatter_order_emulation_equals_the_sequential_scatter_bit_for_bit(radius, shape):
+    """The whole-array formulation of the scatter's summation order (tests/scatter_order.py)
+    must reproduce the oracle's sequential loop exactly, signs of zeros included; it then
+    serves as the fp32 reference of the library's scatter-order mode (Section 3.5)."""
+    from scatter_order import wave3d_adjoint_scatter_order
+    d = inputs.wave_inputs(shape, 0.01, 0.1, seed=radius + shape[0], c_mode="iid")
+    d["u_bar"][1, 1, :] = -0.0
+    want = oracle.wave_adjoint(d["c"], d["r_bar"], d["u_bar"], radius)[0]
+    got = wave3d_adjoint_scatter_order(d["c"], d["r_bar"], d["u_bar"], radius)
+    assert np.array_equal(got.view(np.int64), want.view(np.int64))

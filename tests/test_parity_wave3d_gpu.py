@@ -51,6 +51,8 @@ def sadj():
     yield lib
     lib.set_option("wave3d.zchunk", 0)
     lib.set_option("wave3d.variant", 0)
+    lib.set_option("wave3d.remainder", 0)
+    lib.set_option("wave3d.order", 0)
 
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
@@ -75,6 +77,78 @@ def test_adjoint_tile_variants(sadj, radius, variant):
             _check_adjoint(sadj, d, radius, dtype, with_prev=True, what="variant %d %s" % (variant, shape))
     finally:
         sadj.set_option("wave3d.variant", 0)
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("radius", [1, 4])
+def test_remainder_strategies_agree(sadj, radius, dtype):
+    """Section 3.3.4 names several treatments of the remainder (disjoint nests, guarded
+    statements, zero padding).  The library's three strategies must match the oracle and,
+    since every cell sums the same terms in the same order, each other bit for bit."""
+    for shape in ((30, 75, 140), (23, 41, 272), (12, 20, 64), (9, 9, 12)):
+        d = inputs.wave_inputs(shape, 0.01, 0.1, seed=shape[1], dtype=dtype, c_mode="iid")
+        ref, _ = _run_adjoint(sadj, d, radius, False)
+        try:
+            for strategy in (1, 2):
+                sadj.set_option("wave3d.remainder", strategy)
+                _check_adjoint(sadj, d, radius, dtype, with_prev=False,
+                               what="remainder strategy %d R=%d %s" % (strategy, radius, shape))
+                got, _ = _run_adjoint(sadj, d, radius, False)
+                assert np.array_equal(got, ref), (strategy, shape)
+        finally:
+            sadj.set_option("wave3d.remainder", 0)
+
+
+def _bits(a):
+    return a.view(np.int64 if a.dtype == np.float64 else np.int32)
+
+
+@pytest.mark.parametrize("radius,shape", SMALL + [(4, (30, 75, 140)), (1, (23, 41, 272))])
+def test_scatter_order_mode_equals_the_sequential_scatter_bit_for_bit(sadj, radius, shape):
+    """Section 3.5: a gather can respect a summation order the user chooses.  With
+    "wave3d.order" = 1 the library adds the terms of each u_bar[j] in the order and with
+    the rounding of the sequential scatter loop; in fp64 that loop is the oracle itself,
+    in fp32 its whole-array formulation (pinned to the oracle in test_oracle_wave.py)."""
+    d = inputs.wave_inputs(shape, 0.01, 0.1, seed=7 + sum(shape), c_mode="iid")
+    d["u_bar"][0, 0, :] = -0.0                      # a cell without terms keeps even the sign of zero
+    m = interior_mask(shape, radius)
+    poisoned = dict(d, c=np.where(m, d["c"], np.nan), r_bar=np.where(m, d["r_bar"], np.nan))
+    want_u, want_p, _ = oracle.wave_adjoint(d["c"], d["r_bar"], d["u_bar"], radius, u_prev_bar=d["u_prev_bar"])
+    sadj.set_option("wave3d.order", 1)
+    try:
+        for zchunk in (0, 11):
+            sadj.set_option("wave3d.zchunk", zchunk)
+            for data in (d, poisoned):
+                got_u, got_p = _run_adjoint(sadj, data, radius, True)
+                assert np.array_equal(_bits(got_u), _bits(want_u)), (zchunk, "u_bar")
+                assert np.array_equal(_bits(got_p), _bits(want_p)), (zchunk, "u_prev_bar")
+            got_u, _ = _run_adjoint(sadj, d, radius, False)
+            assert np.array_equal(_bits(got_u), _bits(want_u))
+        sadj.set_option("wave3d.zchunk", 0)
+        from scatter_order import wave3d_adjoint_scatter_order
+        d32 = {k: v.astype(np.float32) for k, v in d.items()}
+        got32, _ = _run_adjoint(sadj, d32, radius, False)
+        want32 = wave3d_adjoint_scatter_order(d32["c"], d32["r_bar"], d32["u_bar"], radius)
+        assert np.array_equal(_bits(got32), _bits(want32))
+    finally:
+        sadj.set_option("wave3d.order", 0)
+        sadj.set_option("wave3d.zchunk", 0)
+
+
+def test_remainder_strategy_declines_what_it_does_not_cover(sadj):
+    import paper_1907_02818_amd as lib
+    d = inputs.wave_inputs((12, 20, 64), 0.01, 0.1, seed=1)
+    c, rb, ub, upb = (to_gpu(d[k]) for k in ("c", "r_bar", "u_bar", "u_prev_bar"))
+    sadj.set_option("wave3d.remainder", 2)
+    try:
+        with pytest.raises(lib.SadjError) as e:
+            sadj.sadj_adjoint_wave3d(4, c, rb, ub, upb)
+        assert e.value.status == 4
+        import torch
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host(ub), d["u_bar"]) and np.array_equal(to_host(upb), d["u_prev_bar"])
+    finally:
+        sadj.set_option("wave3d.remainder", 0)
 
 
 def test_adjoint_is_bitwise_reproducible_and_ignores_values_outside_the_interior(sadj):
