@@ -227,6 +227,9 @@ def main():
             state["i"] += 1
             sadj.sadj_adjoint_burgers1d(0.1, 0.05, u_, r_, b_)
         add("burgers1d_f64_adjoint", burg, nb, 32 * nb, "f64")
+        sadj.set_option("stencil1d.functor", 1)      # same stencil through the generic functor kernel
+        add("burgers1d_f64_adjoint_functor", burg, nb, 32 * nb, "f64")
+        sadj.set_option("stencil1d.functor", 0)
 
         def burg_primal():
             u_, r_, b_ = sets[state["i"] % 3]

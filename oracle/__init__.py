@@ -205,3 +205,36 @@ def lin3_adjoint(c, r_bar, u_bar, lo: int, hi: int, wm: float, w0: float, wp: fl
                                        _ptr(r_bar), _ptr(ub)), "lin3_adjoint")
     return ub
 
+
+_BODY = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_double)
+_PARTIALS = ctypes.CFUNCTYPE(None, ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_double,
+                             ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                             ctypes.POINTER(ctypes.c_double))
+
+
+def stencil1d_primal(f, u, p=None, r_init=None) -> np.ndarray:
+    """r[i] = f(u[i-1], u[i], u[i+1], p[i]) on [1, n-2]; f is a Python callable of four floats.
+    Slow (one callback per cell): for small n."""
+    u = _f64(u)
+    p = _f64(p) if p is not None else None
+    r = _f64(r_init).copy() if r_init is not None else np.zeros_like(u)
+    cb = _BODY(lambda um, u0, up, pp: float(f(um, u0, up, pp)))
+    _check(_load().oracle_stencil1d_primal(_L(u.size), cb, _ptr(u), _ptr(p), _ptr(r)), "stencil1d_primal")
+    return r
+
+
+def stencil1d_adjoint(df, u, p, r_bar, u_bar, want_scale: bool = False):
+    """Scatter adjoint of the loop above; df(um, u0, up, p) returns the three partials."""
+    u, r_bar = _f64(u), _f64(r_bar)
+    p = _f64(p) if p is not None else None
+    ub = _f64(u_bar).copy()
+    scale = np.zeros_like(ub) if want_scale else None
+
+    def partials(um, u0, up, pp, dm, d0, dp):
+        a, b, c = df(um, u0, up, pp)
+        dm[0], d0[0], dp[0] = float(a), float(b), float(c)
+
+    cb = _PARTIALS(partials)
+    _check(_load().oracle_stencil1d_adjoint(_L(u.size), cb, _ptr(u), _ptr(p), _ptr(r_bar), _ptr(ub), _ptr(scale)),
+           "stencil1d_adjoint")
+    return (ub, scale) if want_scale else ub

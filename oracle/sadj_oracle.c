@@ -332,3 +332,42 @@ int oracle_lin3_adjoint(long len, long lo, long hi, double wm, double w0, double
     }
     return ORACLE_OK;
 }
+
+/* ------------------ 1-D three-point stencil with a caller-supplied loop body (callbacks) */
+/* Section 3.3.1: the loop body may be an uninterpreted function f of the three reads
+ * (and of a passive value p[i]); its adjoint then refers to the partial derivatives of f
+ * as functions too.  Primal r[i] = f(u[i-1], u[i], u[i+1], p[i]) for i in [1, n-2];
+ * conventional scatter adjoint, iteration by iteration:
+ *     u_bar[i-1] += df/d(um) * r_bar[i];  u_bar[i] += df/d(u0) * r_bar[i];  u_bar[i+1] += df/d(up) * r_bar[i]
+ * with the partials evaluated at (u[i-1], u[i], u[i+1], p[i]).  p may be NULL (then 0 is passed). */
+typedef double (*oracle_body_fn)(double um, double u0, double up, double p);
+typedef void (*oracle_body_partials_fn)(double um, double u0, double up, double p,
+                                        double *dm, double *d0, double *dp);
+
+int oracle_stencil1d_primal(long n, oracle_body_fn f, const double *u, const double *p, double *r)
+{
+    if (!f || !u || !r || n < 3) return ORACLE_BAD_ARG;
+    for (long i = 1; i <= n - 2; ++i)
+        r[i] = f(u[i - 1], u[i], u[i + 1], p ? p[i] : 0.0);
+    return ORACLE_OK;
+}
+
+int oracle_stencil1d_adjoint(long n, oracle_body_partials_fn df, const double *u, const double *p,
+                             const double *r_bar, double *u_bar, double *scale)
+{
+    if (!df || !u || !r_bar || !u_bar || n < 3) return ORACLE_BAD_ARG;
+    for (long i = 1; i <= n - 2; ++i) {
+        double dm, d0, dp;
+        df(u[i - 1], u[i], u[i + 1], p ? p[i] : 0.0, &dm, &d0, &dp);
+        double rb = r_bar[i];
+        u_bar[i - 1] += dm * rb;
+        u_bar[i]     += d0 * rb;
+        u_bar[i + 1] += dp * rb;
+        if (scale) {
+            scale[i - 1] += fabs(dm * rb);
+            scale[i]     += fabs(d0 * rb);
+            scale[i + 1] += fabs(dp * rb);
+        }
+    }
+    return ORACLE_OK;
+}

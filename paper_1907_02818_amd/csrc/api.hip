@@ -9,7 +9,7 @@
 
 namespace {
 
-std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0}, g_variant2d{0}, g_remainder{0}, g_order{0};
+std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0}, g_variant2d{0}, g_remainder{0}, g_order{0}, g_functor1d{0};
 
 sadj::LaunchOptions current_options()
 {
@@ -127,6 +127,11 @@ sadj_status sadj_set_option(const char *name, long value)
         g_order = value;
         return SADJ_OK;
     }
+    if (!std::strcmp(name, "stencil1d.functor")) {
+        if (value < 0 || value > 1) return SADJ_ERR_UNSUPPORTED;
+        g_functor1d = value;
+        return SADJ_OK;
+    }
 
     return SADJ_ERR_UNSUPPORTED;
 }
@@ -140,6 +145,7 @@ sadj_status sadj_get_option(const char *name, long *value)
     if (!std::strcmp(name, "wave2d.variant")) { *value = g_variant2d; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.remainder")) { *value = g_remainder; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.order")) { *value = g_order; return SADJ_OK; }
+    if (!std::strcmp(name, "stencil1d.functor")) { *value = g_functor1d; return SADJ_OK; }
     return SADJ_ERR_UNSUPPORTED;
 }
 
@@ -282,6 +288,9 @@ static sadj_status box_call(int adjoint, sadj_dtype dtype, int ndim, long nx, lo
     for (int i = 0; i < 27; ++i) gather[i] = adjoint ? full[26 - i] : full[i];
     hipStream_t st = static_cast<hipStream_t>(stream);
     clear_stale_hip_error();
+    if (ndim == 1 && g_functor1d.load() == 1)      // primal: (u, c) -> r;  adjoint: (c, r_bar) -> u_bar, u not needed
+        return from_hip(adjoint ? sadj::launch_weighted3_functor(1, dtype == SADJ_F64, nx, full + 12, nullptr, in0, in1, out, st)
+                                : sadj::launch_weighted3_functor(0, dtype == SADJ_F64, nx, full + 12, in0, in1, nullptr, out, st));
     if (ndim == 1) return from_hip(sadj::launch_box1d(adjoint, dtype == SADJ_F64, nx, gather + 12, in0, in1, out, st));
     return from_hip(sadj::launch_box(adjoint, dtype == SADJ_F64, ndim, (int)nx, (int)ny, (int)nz, gather, in0, in1, out,
                                      current_options(), st));
@@ -311,6 +320,8 @@ sadj_status sadj_primal_burgers1d(sadj_dtype dtype, long n, double C, double D, 
     const Span out[1] = {{r, bytes}};
     if (any_alias(in, out)) return SADJ_ERR_ALIAS;
     clear_stale_hip_error();
+    if (g_functor1d.load() == 1)
+        return from_hip(sadj::launch_burgers1d_functor(0, dtype == SADJ_F64, n, C, D, u, nullptr, r, static_cast<hipStream_t>(stream)));
     return from_hip(sadj::launch_primal_burgers1d(dtype == SADJ_F64, n, C, D, u, r, static_cast<hipStream_t>(stream)));
 }
 
@@ -325,6 +336,9 @@ sadj_status sadj_adjoint_burgers1d(sadj_dtype dtype, long n, double C, double D,
     const Span out[1] = {{u_bar, bytes}};
     if (any_alias(in, out)) return SADJ_ERR_ALIAS;
     clear_stale_hip_error();
+    if (g_functor1d.load() == 1)
+        return from_hip(sadj::launch_burgers1d_functor(1, dtype == SADJ_F64, n, C, D, u, r_bar, u_bar,
+                                                       static_cast<hipStream_t>(stream)));
     return from_hip(sadj::launch_adjoint_burgers1d(dtype == SADJ_F64, n, C, D, u, r_bar, u_bar,
                                                    static_cast<hipStream_t>(stream)));
 }

@@ -38,6 +38,13 @@ hipError_t launch_adjoint_burgers1d(int is_f64, long n, double C, double D, cons
 hipError_t launch_primal_burgers1d(int is_f64, long n, double C, double D, const void *u, void *r,
                                    hipStream_t stream);
 
+// The same 1-D stencils as instantiations of the generic functor kernel
+// (include/sadj_stencil1d.hpp); w = PRIMAL weights at offsets -1, 0, +1.
+hipError_t launch_burgers1d_functor(int adjoint, int is_f64, long n, double C, double D, const void *u,
+                                    const void *r_bar, void *out, hipStream_t stream);
+hipError_t launch_weighted3_functor(int adjoint, int is_f64, long n, const double *w, const void *u,
+                                    const void *c, const void *r_bar, void *out, hipStream_t stream);
+
 // Dense 3^d box stencils; w = gather weights (mirrored by the caller for the adjoint).
 hipError_t launch_box1d(int adjoint, int is_f64, long n, const double *w, const void *in0, const void *in1,
                         void *out, hipStream_t stream);

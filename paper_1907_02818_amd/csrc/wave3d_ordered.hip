@@ -35,7 +35,7 @@ __device__ __forceinline__ void adj3d_march_ordered(const March3dArgs &a, int ti
                                                     T *__restrict__ lds)
 {
     using G = Tile3d<T, R, BX, BY, PY, 1>;
-    constexpr int TX = G::TX, TY = G::TY, LX = G::LX, LY = G::LY, HS = G::HS;
+    constexpr int TX = G::TX, TY = G::TY, LX = G::LX, HS = G::HS;
     constexpr int NACC = 2 * R + 1;
     const int tid = threadIdx.x;
     const int tx = tid % BX, ty = tid / BX;

@@ -68,6 +68,9 @@ def test_options_roundtrip_and_reject_unknown():
         assert sadj.get_option("wave3d.order") == v
     with pytest.raises(sadj.SadjError):
         sadj.set_option("wave3d.order", 2)
+    for v in (1, 0):
+        sadj.set_option("stencil1d.functor", v)
+        assert sadj.get_option("stencil1d.functor") == v
     with pytest.raises(sadj.SadjError) as e:
         sadj.set_option("no.such.option", 1)
     assert e.value.status == 4
@@ -123,3 +126,14 @@ def test_binding_refuses_cpu_tensors():
     t = torch.zeros(16, dtype=torch.float64)
     with pytest.raises(ValueError):
         sadj.sadj_adjoint_wave1d(t, t.clone(), t.clone())
+
+
+def test_functor_header_example_is_built_and_exports_its_entry_points():
+    """include/sadj_stencil1d.hpp is a header-only template API; the user-side example
+    compiled against it alone (tests/functor_example) must load and export its two calls."""
+    path = os.path.join(ROOT, "tests", "functor_example", "libsine_flux.so")
+    if not os.path.exists(path):
+        pytest.skip("tests/functor_example/libsine_flux.so not built (__graft_entry__.build())")
+    sadj.load()                                    # torch's HIP runtime first
+    lib = ctypes.CDLL(path)
+    assert hasattr(lib, "sine_flux_primal") and hasattr(lib, "sine_flux_adjoint")

@@ -23,15 +23,26 @@ def sadj():
     return lib
 
 
+@pytest.fixture(params=[0, 1], ids=["handwritten", "functor"])
+def path1d(sadj, request):
+    """The 1-D case runs through its own kernel and through the generic three-point functor
+    kernel (include/sadj_stencil1d.hpp, a linear functor with a passive coefficient)."""
+    sadj.set_option("stencil1d.functor", request.param)
+    yield request.param
+    sadj.set_option("stencil1d.functor", 0)
+
+
 def _weights(ndim, seed):
     return inputs.uniform(seed, "aux", (3,) * ndim, -2.0, 2.0)
 
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 @pytest.mark.parametrize("shape", SHAPES)
-def test_box_adjoint_and_primal(sadj, shape, dtype):
+def test_box_adjoint_and_primal(sadj, path1d, shape, dtype):
     import torch
     ndim = len(shape)
+    if path1d == 1 and ndim > 1:
+        pytest.skip("the functor path exists in 1-D only")
     w = _weights(ndim, sum(shape))
     wq = w.astype(dtype).astype(np.float64)            # the library converts the weights to dtype
     u = inputs.uniform(1, "u", shape, -1, 1).astype(dtype)
@@ -59,7 +70,7 @@ def test_box_adjoint_and_primal(sadj, shape, dtype):
     assert_close(got[m], wantr[m], sc[m], dtype, "box primal %s" % (shape,))
 
 
-def test_the_papers_one_dimensional_example(sadj):
+def test_the_papers_one_dimensional_example(sadj, path1d):
     """Weights (2,-3,4) on [1, n-1] of arrays of length n+1 (Section 3.2)."""
     import torch
     n = 4096

@@ -20,6 +20,15 @@ def sadj():
     return lib
 
 
+@pytest.fixture(params=[0, 1], ids=["handwritten", "functor"])
+def path1d(sadj, request):
+    """Burgers runs through its hand-written kernel and through the generic three-point
+    functor kernel (include/sadj_stencil1d.hpp); both must meet the same bar."""
+    sadj.set_option("stencil1d.functor", request.param)
+    yield request.param
+    sadj.set_option("stencil1d.functor", 0)
+
+
 def _sync():
     import torch
     torch.cuda.synchronize()
@@ -82,7 +91,7 @@ def test_wave1d_unaligned_pointers_and_nan_outside_interior(sadj):
 # ----------------------------------------------------------------------- Burgers
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 @pytest.mark.parametrize("n", N1D + [1 << 20])
-def test_burgers_adjoint_and_primal(sadj, n, dtype):
+def test_burgers_adjoint_and_primal(sadj, path1d, n, dtype):
     d = inputs.burgers_inputs(n, seed=n, dtype=dtype)
     u = d["u"].copy()
     if n > 300:
@@ -105,7 +114,7 @@ def test_burgers_adjoint_and_primal(sadj, n, dtype):
     assert_close(got, want, np.abs(want) + 1.0, dtype, "burgers primal n=%d" % n)
 
 
-def test_burgers_nan_in_r_bar_outside_interior_and_reproducible(sadj):
+def test_burgers_nan_in_r_bar_outside_interior_and_reproducible(sadj, path1d):
     n = 5000
     d = inputs.burgers_inputs(n, seed=3)
     rb = d["r_bar"].copy()
@@ -120,7 +129,7 @@ def test_burgers_nan_in_r_bar_outside_interior_and_reproducible(sadj):
     assert np.array_equal(outs[0], outs[1])
 
 
-def test_burgers_full_size(sadj):
+def test_burgers_full_size(sadj, path1d):
     n = 1 << 24
     d = inputs.config_inputs("burgers1d")
     ub = to_gpu(d["u_bar"])
