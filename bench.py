@@ -178,6 +178,10 @@ def main():
             add("scatter_order_r%d_f64_adjoint" % rad, lambda: sadj.sadj_adjoint_wave3d(rad, c, rb, ub), N,
                 wave_adjoint_bytes(shape, rad, 8), "f64")
         sadj.set_option("wave3d.order", 0)
+        # contrast: the conventional scatter with atomic updates (not the method)
+        for rad in (4, 1):
+            add("atomic_scatter_r%d_f64_adjoint" % rad, lambda: sadj.sadj_adjoint_wave3d_atomic_scatter(rad, c, rb, ub),
+                N, wave_adjoint_bytes(shape, rad, 8), "f64")
 
     if args.all:
         upb = torch.from_numpy(inputs.config_inputs("wave3d_r4", shape=shape, fields=("u_prev_bar",))["u_prev_bar"]).to(dev)

@@ -101,6 +101,20 @@ sadj_status sadj_adjoint_wave3d(sadj_dtype dtype, int radius, long nx, long ny, 
                                 const void *c, const void *r_bar,
                                 void *u_bar, void *u_prev_bar /* nullable */, void *stream);
 
+/* ---- contrast baseline (NOT the method): conventional scatter with atomic updates ----------
+ * Computes the same u_bar += J^T r_bar as sadj_adjoint_wave3d (u_prev_bar not offered),
+ * but the way conventional reverse mode parallelised with atomics does (paper Sections 1
+ * and 3.2; the OpenMP-atomics baseline of Section 4.1): one GPU thread per primal
+ * iteration i in I scatters its 6R+1 terms with hardware atomic adds.  It exists so that
+ * the gather kernels can be compared with it on the same hardware.  The order of the
+ * additions into one element is not fixed: results vary in the last bits from run to run.
+ * Arrays must be ordinary (coarse-grained) device allocations.  Same argument rules and
+ * errors as sadj_adjoint_wave3d; additionally nz - 2R and (ny - 2R)/4 must not exceed
+ * 65535 (SADJ_ERR_UNSUPPORTED).
+ */
+sadj_status sadj_adjoint_wave3d_atomic_scatter(sadj_dtype dtype, int radius, long nx, long ny, long nz,
+                                               const void *c, const void *r_bar, void *u_bar, void *stream);
+
 /* ---- reverse sweep of a time loop of 3-D wave steps -----------------------------------
  * A solver runs many steps u^{k+1} = step(u^k, u^{k-1}) (the paper measures one step and
  * notes that such solvers take many, Section 4); each step assigns u^{k+1} on I only, so

@@ -65,6 +65,7 @@ def load() -> ctypes.CDLL:
     lib.sadj_adjoint_wave2d.argtypes = [I, L, L, P, P, P, P, P]
     lib.sadj_primal_wave3d.argtypes = [I, I, L, L, L, P, P, P, P, P]
     lib.sadj_adjoint_wave3d.argtypes = [I, I, L, L, L, P, P, P, P, P]
+    lib.sadj_adjoint_wave3d_atomic_scatter.argtypes = [I, I, L, L, L, P, P, P, P]
     lib.sadj_adjoint_wave3d_steps.argtypes = [I, I, L, L, L, L, P, P, P, P, P]
     lib.sadj_primal_box.argtypes = [I, I, L, L, L, ctypes.POINTER(D), P, P, P, P]
     lib.sadj_adjoint_box.argtypes = [I, I, L, L, L, ctypes.POINTER(D), P, P, P, P]
@@ -73,7 +74,7 @@ def load() -> ctypes.CDLL:
     for name in ("sadj_set_option", "sadj_get_option", "sadj_primal_wave1d", "sadj_adjoint_wave1d",
                  "sadj_primal_wave2d", "sadj_adjoint_wave2d", "sadj_primal_wave3d", "sadj_adjoint_wave3d",
                  "sadj_primal_burgers1d", "sadj_adjoint_burgers1d", "sadj_adjoint_wave3d_steps",
-                 "sadj_primal_box", "sadj_adjoint_box"):
+                 "sadj_primal_box", "sadj_adjoint_box", "sadj_adjoint_wave3d_atomic_scatter"):
         getattr(lib, name).restype = I
     _lib = lib
     return lib
@@ -161,6 +162,11 @@ def sadj_primal_wave3d(radius: int, u, u_prev, c, r) -> None:
 def sadj_adjoint_wave3d(radius: int, c, r_bar, u_bar, u_prev_bar=None) -> None:
     code, (nz, ny, nx), p, s = _marshal([c, r_bar, u_bar, u_prev_bar], 3, optional=(3,))
     _check(load().sadj_adjoint_wave3d(code, int(radius), nx, ny, nz, *p, s))
+
+
+def sadj_adjoint_wave3d_atomic_scatter(radius: int, c, r_bar, u_bar) -> None:
+    code, (nz, ny, nx), p, s = _marshal([c, r_bar, u_bar], 3)
+    _check(load().sadj_adjoint_wave3d_atomic_scatter(code, int(radius), nx, ny, nz, *p, s))
 
 
 def sadj_adjoint_wave3d_steps(radius: int, nsteps: int, c, lam0, lam1, lam2) -> None:

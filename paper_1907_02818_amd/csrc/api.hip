@@ -232,6 +232,24 @@ sadj_status sadj_adjoint_wave3d(sadj_dtype dtype, int radius, long nx, long ny, 
     return adjoint_wave(3, dtype, radius, nx, ny, nz, c, r_bar, u_bar, u_prev_bar, stream);
 }
 
+// Contrast baseline, not the method: scatter with atomic updates.
+sadj_status sadj_adjoint_wave3d_atomic_scatter(sadj_dtype dtype, int radius, long nx, long ny, long nz,
+                                               const void *c, const void *r_bar, void *u_bar, void *stream)
+{
+    if (radius != 1 && radius != 4) return SADJ_ERR_UNSUPPORTED;
+    if (!dtype_ok(dtype)) return SADJ_ERR_UNSUPPORTED;
+    if (!c || !r_bar || !u_bar) return SADJ_ERR_NULL;
+    sadj_status s = check_extents(radius, nx, ny, nz, 3);
+    if (s != SADJ_OK) return s;
+    const size_t bytes = (size_t)nx * ny * nz * elem(dtype);
+    const Span in[2] = {{c, bytes}, {r_bar, bytes}};
+    const Span out[1] = {{u_bar, bytes}};
+    if (any_alias(in, out)) return SADJ_ERR_ALIAS;
+    clear_stale_hip_error();
+    return from_hip(sadj::launch_adjoint_wave3d_scatter_atomic(dtype == SADJ_F64, radius, (int)nx, (int)ny, (int)nz, c,
+                                                               r_bar, u_bar, static_cast<hipStream_t>(stream)));
+}
+
 // Reverse sweep of a time loop of wave steps.
 sadj_status sadj_adjoint_wave3d_steps(sadj_dtype dtype, int radius, long nx, long ny, long nz, long nsteps,
                                       const void *c, void *lam0, void *lam1, void *lam2, void *stream)

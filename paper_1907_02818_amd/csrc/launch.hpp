@@ -19,6 +19,9 @@ hipError_t launch_adjoint_wave3d(int is_f64, int radius, int nx, int ny, int nz,
 hipError_t launch_adjoint_wave3d_ordered(int is_f64, int radius, int nx, int ny, int nz, const void *c,
                                          const void *r_bar, void *u_bar, void *u_prev_bar,
                                          const LaunchOptions &opt, hipStream_t stream);
+// Contrast baseline: conventional scatter with atomic updates (not the method).
+hipError_t launch_adjoint_wave3d_scatter_atomic(int is_f64, int radius, int nx, int ny, int nz, const void *c,
+                                                const void *r_bar, void *u_bar, hipStream_t stream);
 hipError_t launch_primal_wave3d(int is_f64, int radius, int nx, int ny, int nz, const void *u,
                                 const void *u_prev, const void *c, void *r,
                                 const LaunchOptions &opt, hipStream_t stream);

@@ -99,6 +99,25 @@ def test_remainder_strategies_agree(sadj, radius, dtype):
             sadj.set_option("wave3d.remainder", 0)
 
 
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("radius,shape", [(4, (37, 45, 150)), (4, (9, 9, 9)), (4, (17, 40, 70)), (1, (3, 3, 3)),
+                                          (1, (21, 37, 150)), (1, (70, 18, 65))])
+def test_atomic_scatter_contrast_kernel_matches_the_oracle(sadj, radius, shape, dtype):
+    """The conventional scatter with atomic updates (Sections 1, 3.2, 4.1), kept as a
+    baseline to compare the gather with; same result up to summation order."""
+    import torch
+    d = inputs.wave_inputs(shape, 0.01, 0.1, seed=11 + sum(shape), dtype=dtype, c_mode="iid")
+    m = interior_mask(shape, radius)
+    c = to_gpu(np.where(m, d["c"], np.nan).astype(dtype))
+    rb = to_gpu(np.where(m, d["r_bar"], np.nan).astype(dtype))
+    ub = to_gpu(d["u_bar"])
+    sadj.sadj_adjoint_wave3d_atomic_scatter(radius, c, rb, ub)
+    torch.cuda.synchronize()
+    want, _, scale = oracle.wave_adjoint(d["c"], d["r_bar"], d["u_bar"], radius, want_scale=True)
+    assert_close(to_host(ub), want, scale + np.abs(d["u_bar"].astype(np.float64)), dtype,
+                 "atomic scatter R=%d %s" % (radius, shape))
+
+
 def _bits(a):
     return a.view(np.int64 if a.dtype == np.float64 else np.int32)
 
