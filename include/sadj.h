@@ -179,6 +179,12 @@ sadj_status sadj_adjoint_burgers1d(sadj_dtype dtype, long n, double C, double D,
  *   "wave3d.variant" tile-shape variant index (default 0 = automatic).
  *   "wave2d.ychunk"  rows of output per wave along y (default 0 = automatic).
  *   "wave2d.variant" load-pipeline depth / workgroup size variant (default 0 = automatic).
+ *   "wave3d.xcdmap"  how workgroups of the 3-D marching kernels are assigned to x-y tiles:
+ *                    0/1 (default) per round of resident workgroups every XCD (chiplet with
+ *                    its own L2) owns a contiguous range of tiles, 2 one contiguous range
+ *                    per XCD over the whole dispatch, 3 tiles dealt round-robin to XCDs.
+ *   "wave3d.band"    numbering of the tiles of a plane: 0 (default) rows of tiles, k > 0
+ *                    bands of k tile rows with y fastest inside a band.
  *   "wave3d.remainder" treatment of the boundary / remainder regions (Section 3.3.4) by
  *                    sadj_adjoint_wave3d:  0 (default) one dispatch, tiles that touch the
  *                    remainder run guarded statements, core tiles unguarded ones;

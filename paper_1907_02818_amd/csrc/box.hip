@@ -31,6 +31,7 @@ struct BoxArgs {
     int nx, ny, nz;
     int chunk;                  // output rows (2-D) / planes (3-D) per march
     int ntx, nty, ntz, total_blocks;
+    int xcd_map, band, round_blocks;   // workgroup id -> tile mapping of the 3-D march
     double w[27];               // gather weights W[(ox+1) + 3(oy+1) + 9(oz+1)]
 };
 
@@ -351,10 +352,8 @@ __global__ __launch_bounds__(BX *BY) void box3d_kernel(BoxArgs a)
 {
     using G = BoxTile<T, BX, BY, PY>;
     __shared__ T sq[2 * G::PLANE];
-    const int L = xcd_contiguous_id(blockIdx.x, a.total_blocks);
-    const int tix = L % a.ntx;
-    const int t = L / a.ntx;
-    const int tiy = t % a.nty, tiz = t / a.nty;
+    int tix, tiy, tiz;
+    block_to_tile(a, blockIdx.x, tix, tiy, tiz);
     const int x0 = tix * G::TX, y0 = tiy * G::TY;
     const bool core = x0 >= 2 && x0 + G::TX + 2 <= a.nx && y0 >= 2 && y0 + G::TY + 2 <= a.ny;
     if (core) box3d_march<T, BX, BY, PY, ADJ, false>(a, tix, tiy, tiz, sq);
@@ -391,8 +390,9 @@ static hipError_t launch_box3d(BoxArgs a, const LaunchOptions &opt, hipStream_t 
     using G = BoxTile<T, 64, 8, 4>;
     March3dArgs m{};
     m.nx = a.nx; m.ny = a.ny; m.nz = a.nz;
-    plan_march(m, G::TX, G::TY, 1, opt.zchunk);
+    plan_march(m, G::TX, G::TY, 1, opt);
     a.ntx = m.ntx; a.nty = m.nty; a.ntz = m.ntz; a.chunk = m.zchunk; a.total_blocks = m.total_blocks;
+    a.xcd_map = m.xcd_map; a.band = m.band; a.round_blocks = m.round_blocks;
     hipLaunchKernelGGL((box3d_kernel<T, 64, 8, 4, ADJ>), dim3(a.total_blocks), dim3(G::NT), 0, stream, a);
     return hipGetLastError();
 }

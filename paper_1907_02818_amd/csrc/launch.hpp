@@ -9,6 +9,8 @@ struct LaunchOptions {
     long variant = 0;    // wave3d: tile-shape variant
     long ychunk2d = 0;   // wave2d: output rows per wave (0 = automatic)
     long variant2d = 0;  // wave2d: pipeline depth / workgroup size variant
+    long xcd_map = 0;    // wave3d: workgroup id -> logical id (0 = automatic, see block_to_tile)
+    long band = 0;       // wave3d: tile rows per band of the tile numbering (0 = rows of tiles)
     long remainder = 0;  // wave3d adjoint: remainder strategy (0 guarded where needed, 1 guarded everywhere, 2 split dispatches)
 };
 

@@ -4,6 +4,7 @@
 // halo of width R on all four sides (corners omitted: a star never reads them).
 #pragma once
 #include "common.hpp"
+#include "launch.hpp"
 
 namespace sadj {
 
@@ -43,7 +44,49 @@ struct March3dArgs {
     int ntx, nty, ntz;             // tiles along x and y, chunks along z
     int zchunk;                    // output planes per chunk
     int total_blocks;
+    int xcd_map, band;             // workgroup id -> tile mapping, see block_to_tile
+    int round_blocks;              // workgroups resident at a time
 };
+
+// Workgroup id -> (tile x, tile y, z-chunk).
+// Logical ids.  Workgroups are dealt to the 8 XCDs round-robin by hardware id and run in
+// rounds of round_blocks (what the chip holds at a time).  xcd_map 1: within each round
+// every XCD owns a contiguous range of logical ids, so all XCDs work on neighbouring tiles
+// of the same chunk at a time and tiles that share halo cells meet in one L2 (default).
+// xcd_map 2: one contiguous range per XCD over the whole dispatch (the same thing when
+// there is a single round; with several rounds the XCDs drift to different z-chunks,
+// measured 3-5 % slower).  xcd_map 3: logical id = hardware id (neighbouring tiles on
+// different XCDs).
+// Tiles of a chunk are numbered x fastest (band = 0) or in bands of `band` tile rows with
+// y fastest inside a band, which makes the 32 tiles an XCD holds a compact patch.
+template <class Args>
+__device__ __forceinline__ void block_to_tile(const Args &a, int hw_id, int &tix, int &tiy, int &tiz)
+{
+    int L;
+    if (a.xcd_map == 3) {
+        L = hw_id;
+    } else if (a.xcd_map == 2) {
+        L = xcd_contiguous_id(hw_id, a.total_blocks);
+    } else {
+        const int round = hw_id / a.round_blocks;
+        const int first = round * a.round_blocks;
+        const int m = min(a.round_blocks, a.total_blocks - first);
+        L = first + xcd_contiguous_id(hw_id - first, m);
+    }
+    const int tiles = a.ntx * a.nty;
+    tiz = L / tiles;
+    const int t = L - tiz * tiles;
+    if (a.band > 0) {
+        const int b = t / (a.ntx * a.band);
+        const int r = t - b * a.ntx * a.band;
+        const int h = min(a.band, a.nty - b * a.band);
+        tix = r / h;
+        tiy = b * a.band + (r - tix * h);
+    } else {
+        tiy = t / a.ntx;
+        tix = t - tiy * a.ntx;
+    }
+}
 
 static inline int cdiv_i(int a, int b) { return (a + b - 1) / b; }
 
@@ -52,16 +95,19 @@ static inline int cdiv_i(int a, int b) { return (a + b - 1) / b; }
 // (the 2R planes beyond a chunk are read by two chunks).  Minimise rounds * planes per
 // workgroup; ties go to fewer chunks.  With tiles*chunks == ncu this is the single
 // resident wave in which neighbouring tiles move through z in lockstep.
-static inline void plan_march(March3dArgs &a, int TX, int TY, int R, long zchunk_opt)
+static inline void plan_march(March3dArgs &a, int TX, int TY, int R, const LaunchOptions &opt)
 {
     a.ntx = cdiv_i(a.nx, TX);
     a.nty = cdiv_i(a.ny, TY);
-    int zchunk = (int)zchunk_opt;
+    int dev = 0, ncu = 256, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+        ncu = v;
+    a.xcd_map = opt.xcd_map > 0 ? (int)opt.xcd_map : 1;
+    a.band = (int)opt.band;
+    a.round_blocks = ncu >= 8 ? ncu - ncu % 8 : 8;
+    int zchunk = (int)opt.zchunk;
     if (zchunk <= 0) {
-        int dev = 0, ncu = 256, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            ncu = v;
         const long tiles = (long)a.ntx * a.nty;
         long best_cost = -1;
         int best_chunks = 1;

@@ -263,11 +263,8 @@ __global__ __launch_bounds__(BX *BY) void adj_wave3d_kernel(March3dArgs a)
 {
     using G = Tile3d<T, R, BX, BY, PY, PX>;
     __shared__ T sq[2 * G::PLANE];
-    const int L = xcd_contiguous_id(blockIdx.x, a.total_blocks);
-    const int tix = L % a.ntx;
-    const int t = L / a.ntx;
-    const int tiy = t % a.nty;
-    const int tiz = t / a.nty;
+    int tix, tiy, tiz;
+    block_to_tile(a, blockIdx.x, tix, tiy, tiz);
     // core tile: own cells and halo cells all inside I in x and y
     const int x0 = tix * G::TX, y0 = tiy * G::TY;
     const bool core = x0 >= 2 * R && x0 + G::TX + 2 * R <= a.nx && y0 >= 2 * R && y0 + G::TY + 2 * R <= a.ny;
@@ -297,7 +294,7 @@ static hipError_t launch_cfg(March3dArgs a, const LaunchOptions &opt, hipStream_
                         aligned_to(a.out0, al) && aligned_to(a.out1, al);
         if (!ok) return launch_cfg<T, R, 64, 8, 4, 1, 1, true>(a, opt, stream);
     }
-    plan_march(a, G::TX, G::TY, R, opt.zchunk);
+    plan_march(a, G::TX, G::TY, R, opt);
     dim3 grid(a.total_blocks), block(G::NT);
     if (opt.remainder != 0) {
         // the strategy study is built for the two default shapes and u_bar only

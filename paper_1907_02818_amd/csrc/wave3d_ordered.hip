@@ -223,11 +223,8 @@ __global__ __launch_bounds__(BX *BY) void adj_wave3d_ordered_kernel(March3dArgs 
 {
     using G = Tile3d<T, R, BX, BY, PY, 1>;
     __shared__ T lds[4 * G::PLANE];                 // two buffers of (c plane, r_bar plane)
-    const int L = xcd_contiguous_id(blockIdx.x, a.total_blocks);
-    const int tix = L % a.ntx;
-    const int t = L / a.ntx;
-    const int tiy = t % a.nty;
-    const int tiz = t / a.nty;
+    int tix, tiy, tiz;
+    block_to_tile(a, blockIdx.x, tix, tiy, tiz);
     const int x0 = tix * G::TX, y0 = tiy * G::TY;
     const bool core = x0 >= 2 * R && x0 + G::TX + 2 * R <= a.nx && y0 >= 2 * R && y0 + G::TY + 2 * R <= a.ny;
     if (core) adj3d_march_ordered<T, R, BX, BY, PY, false, UPREV>(a, tix, tiy, tiz, lds);
@@ -239,7 +236,7 @@ static hipError_t launch_ordered_P(March3dArgs a, const LaunchOptions &opt, hipS
 {
     constexpr int BX = 64, BY = 8;
     using G = Tile3d<T, R, BX, BY, PY, 1>;
-    plan_march(a, G::TX, G::TY, R, opt.zchunk);
+    plan_march(a, G::TX, G::TY, R, opt);
     dim3 grid(a.total_blocks), block(G::NT);
     if (a.out1) hipLaunchKernelGGL((adj_wave3d_ordered_kernel<T, R, BX, BY, PY, true>), grid, block, 0, stream, a);
     else        hipLaunchKernelGGL((adj_wave3d_ordered_kernel<T, R, BX, BY, PY, false>), grid, block, 0, stream, a);

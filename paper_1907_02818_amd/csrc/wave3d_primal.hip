@@ -33,10 +33,8 @@ __global__ __launch_bounds__(BX *BY) void primal_wave3d_kernel(March3dArgs a)
     constexpr int NB = R + 2;                       // LDS ring of planes
     __shared__ T sq[NB * G::PLANE];
 
-    const int L = xcd_contiguous_id(blockIdx.x, a.total_blocks);
-    const int tix = L % a.ntx;
-    const int tt = L / a.ntx;
-    const int tiy = tt % a.nty, tiz = tt / a.nty;
+    int tix, tiy, tiz;
+    block_to_tile(a, blockIdx.x, tix, tiy, tiz);
 
     const int tid = threadIdx.x;
     const int tx = tid % BX, ty = tid / BX;
@@ -208,7 +206,7 @@ static hipError_t launch_primal_cfg(March3dArgs a, const LaunchOptions &opt, hip
                         aligned_to_p(a.in2, al) && aligned_to_p(a.out0, al);
         if (!ok) return launch_primal_cfg<T, R, 64, 8, 4, 1>(a, opt, stream);
     }
-    plan_march(a, G::TX, G::TY, R, opt.zchunk);
+    plan_march(a, G::TX, G::TY, R, opt);
     hipLaunchKernelGGL((primal_wave3d_kernel<T, R, BX, BY, PY, PX, true>), dim3(a.total_blocks), dim3(G::NT), 0,
                        stream, a);
     return hipGetLastError();

@@ -68,6 +68,10 @@ def test_options_roundtrip_and_reject_unknown():
         assert sadj.get_option("wave3d.order") == v
     with pytest.raises(sadj.SadjError):
         sadj.set_option("wave3d.order", 2)
+    for name, vals in (("wave3d.xcdmap", (3, 2, 1, 0)), ("wave3d.band", (8, 0))):
+        for v in vals:
+            sadj.set_option(name, v)
+            assert sadj.get_option(name) == v
     for v in (1, 0):
         sadj.set_option("stencil1d.functor", v)
         assert sadj.get_option("stencil1d.functor") == v

@@ -154,6 +154,29 @@ def test_scatter_order_mode_equals_the_sequential_scatter_bit_for_bit(sadj, radi
         sadj.set_option("wave3d.zchunk", 0)
 
 
+@pytest.mark.parametrize("xcdmap,band", [(1, 0), (2, 0), (3, 0), (1, 2), (2, 3), (1, 8)])
+def test_tile_mappings_give_identical_results(sadj, xcdmap, band):
+    """Which workgroup marches which tile is a scheduling choice; every mapping must be a
+    bijection onto the tiles (each u_bar element written exactly once) for ragged tile
+    grids and several z-chunks, hence bit-identical results and parity with the oracle."""
+    try:
+        for radius, shape, zchunk in ((4, (40, 150, 330), 9), (1, (33, 70, 200), 0), (4, (700, 40, 70), 0)):
+            d = inputs.wave_inputs(shape, 0.01, 0.1, seed=shape[2], c_mode="iid")
+            sadj.set_option("wave3d.zchunk", zchunk)
+            sadj.set_option("wave3d.xcdmap", 0)
+            sadj.set_option("wave3d.band", 0)
+            ref, _ = _run_adjoint(sadj, d, radius, False)
+            sadj.set_option("wave3d.xcdmap", xcdmap)
+            sadj.set_option("wave3d.band", band)
+            _check_adjoint(sadj, d, radius, np.float64, with_prev=True, what="xcdmap %d band %d %s" % (xcdmap, band, shape))
+            got, _ = _run_adjoint(sadj, d, radius, False)
+            assert np.array_equal(got, ref)
+    finally:
+        sadj.set_option("wave3d.xcdmap", 0)
+        sadj.set_option("wave3d.band", 0)
+        sadj.set_option("wave3d.zchunk", 0)
+
+
 def test_remainder_strategy_declines_what_it_does_not_cover(sadj):
     import paper_1907_02818_amd as lib
     d = inputs.wave_inputs((12, 20, 64), 0.01, 0.1, seed=1)
