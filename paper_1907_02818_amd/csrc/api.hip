@@ -9,7 +9,7 @@
 
 namespace {
 
-std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0}, g_variant2d{0}, g_remainder{0}, g_order{0}, g_functor1d{0}, g_xcdmap{0}, g_band{0};
+std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0}, g_variant2d{0}, g_remainder{0}, g_order{0}, g_functor1d{0}, g_xcdmap{0}, g_band{0}, g_ldspad{0};
 
 sadj::LaunchOptions current_options()
 {
@@ -21,6 +21,7 @@ sadj::LaunchOptions current_options()
     o.remainder = g_remainder.load();
     o.xcd_map = g_xcdmap.load();
     o.band = g_band.load();
+    o.lds_pad = g_ldspad.load();
     return o;
 }
 
@@ -129,6 +130,11 @@ sadj_status sadj_set_option(const char *name, long value)
         g_xcdmap = value;
         return SADJ_OK;
     }
+    if (!std::strcmp(name, "wave3d.ldspad")) {
+        if (value < -1 || value > 65536) return SADJ_ERR_UNSUPPORTED;
+        g_ldspad = value;
+        return SADJ_OK;
+    }
     if (!std::strcmp(name, "wave3d.band")) {
         if (value < 0 || value > 4096) return SADJ_ERR_UNSUPPORTED;
         g_band = value;
@@ -159,6 +165,7 @@ sadj_status sadj_get_option(const char *name, long *value)
     if (!std::strcmp(name, "wave3d.order")) { *value = g_order; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.xcdmap")) { *value = g_xcdmap; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.band")) { *value = g_band; return SADJ_OK; }
+    if (!std::strcmp(name, "wave3d.ldspad")) { *value = g_ldspad; return SADJ_OK; }
     if (!std::strcmp(name, "stencil1d.functor")) { *value = g_functor1d; return SADJ_OK; }
     return SADJ_ERR_UNSUPPORTED;
 }

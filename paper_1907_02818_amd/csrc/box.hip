@@ -393,7 +393,8 @@ static hipError_t launch_box3d(BoxArgs a, const LaunchOptions &opt, hipStream_t 
     plan_march(m, G::TX, G::TY, 1, opt);
     a.ntx = m.ntx; a.nty = m.nty; a.ntz = m.ntz; a.chunk = m.zchunk; a.total_blocks = m.total_blocks;
     a.xcd_map = m.xcd_map; a.band = m.band; a.round_blocks = m.round_blocks;
-    hipLaunchKernelGGL((box3d_kernel<T, 64, 8, 4, ADJ>), dim3(a.total_blocks), dim3(G::NT), 0, stream, a);
+    const unsigned pad = one_workgroup_per_cu_pad(sizeof(T) * 2 * G::PLANE, opt.lds_pad);
+    hipLaunchKernelGGL((box3d_kernel<T, 64, 8, 4, ADJ>), dim3(a.total_blocks), dim3(G::NT), pad, stream, a);
     return hipGetLastError();
 }
 

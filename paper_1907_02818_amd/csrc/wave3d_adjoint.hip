@@ -296,24 +296,25 @@ static hipError_t launch_cfg(March3dArgs a, const LaunchOptions &opt, hipStream_
     }
     plan_march(a, G::TX, G::TY, R, opt);
     dim3 grid(a.total_blocks), block(G::NT);
+    const unsigned pad = one_workgroup_per_cu_pad(sizeof(T) * 2 * G::PLANE, opt.lds_pad);
     if (opt.remainder != 0) {
         // the strategy study is built for the two default shapes and u_bar only
         if constexpr (BX == 32 && BY == 16 && D == 1 && NTU) {
             if (a.out1) return hipErrorNotSupported;
             if (opt.remainder == 1) {
-                hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 0, 1>), grid, block, 0, stream, a);
+                hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 0, 1>), grid, block, pad, stream, a);
             } else {
-                hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 0, 2>), grid, block, 0, stream, a);
-                hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 0, 3>), grid, block, 0, stream, a);
+                hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 0, 2>), grid, block, pad, stream, a);
+                hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 0, 3>), grid, block, pad, stream, a);
             }
             return hipGetLastError();
         } else {
             return hipErrorNotSupported;
         }
     }
-    if (!a.out1)                hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 0, 0>), grid, block, 0, stream, a);
-    else if (a.out1_assign == 0) hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 1, 0>), grid, block, 0, stream, a);
-    else                        hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 2, 0>), grid, block, 0, stream, a);
+    if (!a.out1)                hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 0, 0>), grid, block, pad, stream, a);
+    else if (a.out1_assign == 0) hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 1, 0>), grid, block, pad, stream, a);
+    else                        hipLaunchKernelGGL((adj_wave3d_kernel<T, R, BX, BY, PY, PX, D, NTU, 2, 0>), grid, block, pad, stream, a);
     return hipGetLastError();
 }
 

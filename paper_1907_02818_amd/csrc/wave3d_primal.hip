@@ -207,7 +207,8 @@ static hipError_t launch_primal_cfg(March3dArgs a, const LaunchOptions &opt, hip
         if (!ok) return launch_primal_cfg<T, R, 64, 8, 4, 1>(a, opt, stream);
     }
     plan_march(a, G::TX, G::TY, R, opt);
-    hipLaunchKernelGGL((primal_wave3d_kernel<T, R, BX, BY, PY, PX, true>), dim3(a.total_blocks), dim3(G::NT), 0,
+    const unsigned pad = one_workgroup_per_cu_pad(sizeof(T) * (R + 2) * G::PLANE, opt.lds_pad);
+    hipLaunchKernelGGL((primal_wave3d_kernel<T, R, BX, BY, PY, PX, true>), dim3(a.total_blocks), dim3(G::NT), pad,
                        stream, a);
     return hipGetLastError();
     }
