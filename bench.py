@@ -231,6 +231,15 @@ def main():
             state["i"] += 1
             sadj.sadj_adjoint_burgers1d(0.1, 0.05, u_, r_, b_)
         add("burgers1d_f64_adjoint", burg, nb, 32 * nb, "f64")
+        # reverse sweep over stored Burgers states: per step read u^t and lam, write lam (24 B/pt)
+        ks = 12
+        states = torch.rand(ks + 1, nb, device=dev, dtype=torch.float64)
+        la, lb = torch.rand(nb, device=dev, dtype=torch.float64), torch.zeros(nb, device=dev, dtype=torch.float64)
+        add("burgers1d_f64_adjoint_steps_per_step", lambda: sadj.sadj_adjoint_burgers1d_steps(0.1, 0.05, ks, ks, states, la, lb),
+            nb * ks, 32 * nb + (ks - 1) * 24 * nb, "f64")
+        others["burgers1d_f64_adjoint_steps_per_step"]["ms"] /= ks
+        others["burgers1d_f64_adjoint_steps_per_step"]["kernel_ms_mean"] /= ks
+        del states, la, lb
         sadj.set_option("stencil1d.functor", 1)      # same stencil through the generic functor kernel
         add("burgers1d_f64_adjoint_functor", burg, nb, 32 * nb, "f64")
         sadj.set_option("stencil1d.functor", 0)

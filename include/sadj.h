@@ -172,6 +172,31 @@ sadj_status sadj_adjoint_burgers1d(sadj_dtype dtype, long n, double C, double D,
                                    const void *u, const void *r_bar, void *u_bar,
                                    void *stream);
 
+/* ---- time loop of Burgers steps: store every state, then sweep backwards -------------------
+ * The Burgers stencil is nonlinear, so the reverse sweep of step u^t -> u^{t+1} needs the
+ * primal state u^t (paper Section 3.1: a nonlinear statement's adjoint reads primal values;
+ * Section 4.2).  With 288 GB of HBM the states of a 1-D solver are simply all kept:
+ *
+ * sadj_primal_burgers1d_steps: `states` holds nsteps+1 rows of n elements, row t = u^t.
+ *   Row 0 is the initial state; for t = 0 .. nsteps-1 the call assigns row t+1 on I = [1, n-2]
+ *   from row t.  Elements 0 and n-1 of every row are inputs (boundary data), never written.
+ *
+ * sadj_adjoint_burgers1d_steps: reverse sweep over the steps last-1, last-2, ..., last-nsteps
+ *   (step t maps row t to row t+1; rows last-nsteps .. last-1 of `states` are read).  On entry
+ *   lam0 = adjoint of u^{last}, lam1 = whatever the objective contributes directly to the
+ *   adjoint of u^{last-1} (often zero).  Reverse step s = 0, 1, ... reads lam[s%2] and
+ *   updates lam[(s+1)%2] with (d step_t / d u^t)^T lam[s%2], t = last-1-s: accumulated for
+ *   s = 0, ASSIGNED for s >= 1 (the buffer's old content, the adjoint of a later state, is
+ *   consumed; adjoints of earlier states start from zero).  As in every adjoint call, values
+ *   of lam[s%2] outside I are never used.  After the call lam[nsteps%2] holds the adjoint of
+ *   u^{last-nsteps}.  nsteps = 0 does nothing; nsteps > last -> SADJ_ERR_SIZE.  lam0, lam1 and
+ *   the rows read must not overlap.  One kernel per step is enqueued.
+ */
+sadj_status sadj_primal_burgers1d_steps(sadj_dtype dtype, long n, long nsteps, double C, double D,
+                                        void *states, void *stream);
+sadj_status sadj_adjoint_burgers1d_steps(sadj_dtype dtype, long n, long last, long nsteps, double C, double D,
+                                         const void *states, void *lam0, void *lam1, void *stream);
+
 /* ---- launch options -------------------------------------------------------------------
  * Process-wide integer options that select among equivalent launch strategies; they
  * never change what is computed, only how the regions are mapped to kernels.

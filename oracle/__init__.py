@@ -190,6 +190,26 @@ def burgers_adjoint(u, r_bar, u_bar, C: float, D: float, want_scale: bool = Fals
     return ub, scale
 
 
+def burgers_primal_steps(states, nsteps: int, C: float, D: float) -> np.ndarray:
+    """states: (rows >= nsteps+1, n); row 0 = initial state, boundary elements of all rows are
+    inputs.  Returns a copy with rows 1..nsteps assigned on the interior."""
+    st = _f64(states).copy()
+    assert st.ndim == 2 and st.shape[0] >= nsteps + 1
+    _check(_load().oracle_burgers_primal_steps(_L(st.shape[1]), _L(nsteps), _D(C), _D(D), _ptr(st)),
+           "burgers_primal_steps")
+    return st
+
+
+def burgers_adjoint_steps(states, last: int, nsteps: int, lam0, lam1, C: float, D: float):
+    """Reverse sweep over steps last-1 .. last-nsteps; returns the two buffers after the sweep."""
+    st = _f64(states)
+    assert st.ndim == 2 and st.shape[0] >= last
+    a, b = _f64(lam0).copy(), _f64(lam1).copy()
+    _check(_load().oracle_burgers_adjoint_steps(_L(st.shape[1]), _L(last), _L(nsteps), _D(C), _D(D), _ptr(st),
+                                                _ptr(a), _ptr(b)), "burgers_adjoint_steps")
+    return a, b
+
+
 def lin3_primal(c, u, lo: int, hi: int, wm: float, w0: float, wp: float) -> np.ndarray:
     c, u = _f64(c), _f64(u)
     r = np.zeros_like(u)

@@ -253,6 +253,39 @@ int oracle_burgers_adjoint(long n, double C, double D, const double *u,
     return ORACLE_OK;
 }
 
+/* Time loop of Burgers steps u^{t+1} = step(u^t) on I (elements 0 and n-1 of every state
+ * are inputs of their own).  states: rows u^0 .. u^{nsteps}, row length n. */
+int oracle_burgers_primal_steps(long n, long nsteps, double C, double D, double *states)
+{
+    if (!states || nsteps < 0) return ORACLE_BAD_ARG;
+    for (long t = 0; t < nsteps; ++t) {
+        int rc = oracle_burgers_primal(n, C, D, states + t * n, states + (t + 1) * n);
+        if (rc != ORACLE_OK) return rc;
+    }
+    return ORACLE_OK;
+}
+
+/* Reverse sweep over the steps last-1, ..., last-nsteps (chain rule, Section 3.1; the
+ * nonlinear step needs the stored primal state u^t, Section 4.2).  lam[0] is the adjoint
+ * of u^{last}, lam[1] holds what the objective adds directly to the adjoint of u^{last-1};
+ * adjoints of older states start from zero.  Two buffers alternate: reverse step s reads
+ * lam[s%2] as r_bar and accumulates into lam[(s+1)%2], which from s = 1 on is zeroed first. */
+int oracle_burgers_adjoint_steps(long n, long last, long nsteps, double C, double D,
+                                 const double *states, double *lam0, double *lam1)
+{
+    double *lam[2] = {lam0, lam1};
+    if (!states || !lam0 || !lam1 || nsteps < 0 || nsteps > last) return ORACLE_BAD_ARG;
+    for (long s = 0; s < nsteps; ++s) {
+        long t = last - 1 - s;
+        double *a = lam[s % 2], *b = lam[(s + 1) % 2];
+        if (s > 0)
+            for (long i = 0; i < n; ++i) b[i] = 0.0;
+        int rc = oracle_burgers_adjoint(n, C, D, states + t * n, a, b, NULL);
+        if (rc != ORACLE_OK) return rc;
+    }
+    return ORACLE_OK;
+}
+
 /* ------------------------- dense 3^d box stencil with arbitrary (asymmetric) weights */
 /* Primal  r[i] = c[i] * sum_{o in {-1,0,1}^d} w[o] * u[i+o]   for i in I = prod [1, n_d-2]
  * (the dense stencils whose adjoint loop-nest counts Section 3.3.4 quotes: 3 points in

@@ -71,10 +71,13 @@ def load() -> ctypes.CDLL:
     lib.sadj_adjoint_box.argtypes = [I, I, L, L, L, ctypes.POINTER(D), P, P, P, P]
     lib.sadj_primal_burgers1d.argtypes = [I, L, D, D, P, P, P]
     lib.sadj_adjoint_burgers1d.argtypes = [I, L, D, D, P, P, P, P]
+    lib.sadj_primal_burgers1d_steps.argtypes = [I, L, L, D, D, P, P]
+    lib.sadj_adjoint_burgers1d_steps.argtypes = [I, L, L, L, D, D, P, P, P, P]
     for name in ("sadj_set_option", "sadj_get_option", "sadj_primal_wave1d", "sadj_adjoint_wave1d",
                  "sadj_primal_wave2d", "sadj_adjoint_wave2d", "sadj_primal_wave3d", "sadj_adjoint_wave3d",
                  "sadj_primal_burgers1d", "sadj_adjoint_burgers1d", "sadj_adjoint_wave3d_steps",
-                 "sadj_primal_box", "sadj_adjoint_box", "sadj_adjoint_wave3d_atomic_scatter"):
+                 "sadj_primal_box", "sadj_adjoint_box", "sadj_adjoint_wave3d_atomic_scatter",
+                 "sadj_primal_burgers1d_steps", "sadj_adjoint_burgers1d_steps"):
         getattr(lib, name).restype = I
     _lib = lib
     return lib
@@ -210,3 +213,22 @@ def sadj_primal_burgers1d(C: float, D: float, u, r) -> None:
 def sadj_adjoint_burgers1d(C: float, D: float, u, r_bar, u_bar) -> None:
     code, (n,), p, s = _marshal([u, r_bar, u_bar], 1)
     _check(load().sadj_adjoint_burgers1d(code, n, float(C), float(D), *p, s))
+
+
+def sadj_primal_burgers1d_steps(C: float, D: float, nsteps: int, states) -> None:
+    """states: (rows, n) tensor with rows >= nsteps + 1; row 0 is the initial state."""
+    code, (rows, n), p, s = _marshal([states], 2)
+    if rows < int(nsteps) + 1:
+        raise ValueError("states needs nsteps + 1 rows")
+    _check(load().sadj_primal_burgers1d_steps(code, n, int(nsteps), float(C), float(D), *p, s))
+
+
+def sadj_adjoint_burgers1d_steps(C: float, D: float, last: int, nsteps: int, states, lam0, lam1) -> None:
+    """states: (rows, n) tensor with rows >= last; lam0, lam1: (n,) tensors."""
+    code, (rows, n), ps, s = _marshal([states], 2)
+    code2, (n2,), pl, _ = _marshal([lam0, lam1], 1)
+    if code2 != code or n2 != n or lam0.device != states.device:
+        raise ValueError("states and lam buffers share dtype, row length and device")
+    if rows < int(last):
+        raise ValueError("states needs at least `last` rows")
+    _check(load().sadj_adjoint_burgers1d_steps(code, n, int(last), int(nsteps), float(C), float(D), *ps, *pl, s))

@@ -378,8 +378,50 @@ sadj_status sadj_adjoint_burgers1d(sadj_dtype dtype, long n, double C, double D,
     if (g_functor1d.load() == 1)
         return from_hip(sadj::launch_burgers1d_functor(1, dtype == SADJ_F64, n, C, D, u, r_bar, u_bar,
                                                        static_cast<hipStream_t>(stream)));
-    return from_hip(sadj::launch_adjoint_burgers1d(dtype == SADJ_F64, n, C, D, u, r_bar, u_bar,
+    return from_hip(sadj::launch_adjoint_burgers1d(dtype == SADJ_F64, n, C, D, u, r_bar, u_bar, 0,
                                                    static_cast<hipStream_t>(stream)));
+}
+
+// Time loop of Burgers steps: forward sweep that stores every state, reverse sweep over them.
+sadj_status sadj_primal_burgers1d_steps(sadj_dtype dtype, long n, long nsteps, double C, double D, void *states,
+                                        void *stream)
+{
+    if (!dtype_ok(dtype)) return SADJ_ERR_UNSUPPORTED;
+    if (!states) return SADJ_ERR_NULL;
+    if (n < 3 || n > kMaxExtent || nsteps < 0 || nsteps > kMaxExtent) return SADJ_ERR_SIZE;
+    const size_t row = (size_t)n * elem(dtype);
+    clear_stale_hip_error();
+    char *base = static_cast<char *>(states);
+    for (long t = 0; t < nsteps; ++t) {
+        hipError_t e = sadj::launch_primal_burgers1d(dtype == SADJ_F64, n, C, D, base + (size_t)t * row,
+                                                     base + (size_t)(t + 1) * row, static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return from_hip(e);
+    }
+    return SADJ_OK;
+}
+
+sadj_status sadj_adjoint_burgers1d_steps(sadj_dtype dtype, long n, long last, long nsteps, double C, double D,
+                                         const void *states, void *lam0, void *lam1, void *stream)
+{
+    if (!dtype_ok(dtype)) return SADJ_ERR_UNSUPPORTED;
+    if (!states || !lam0 || !lam1) return SADJ_ERR_NULL;
+    if (n < 3 || n > kMaxExtent || nsteps < 0 || last < 0 || nsteps > last || last > kMaxExtent) return SADJ_ERR_SIZE;
+    const size_t row = (size_t)n * elem(dtype);
+    // states u^{last-nsteps} .. u^{last-1} are read; lam0, lam1 are written
+    const Span in[1] = {{static_cast<const char *>(states) + (size_t)(last - nsteps) * row, (size_t)nsteps * row}};
+    const Span out[2] = {{lam0, row}, {lam1, row}};
+    if (any_alias(in, out)) return SADJ_ERR_ALIAS;
+    clear_stale_hip_error();
+    void *lam[2] = {lam0, lam1};
+    const char *base = static_cast<const char *>(states);
+    for (long s = 0; s < nsteps; ++s) {
+        const long t = last - 1 - s;                 // the primal step u^t -> u^{t+1}
+        // lam[(s+1)%2] receives lam^t; from s = 1 on it is the consumed buffer and is assigned
+        hipError_t e = sadj::launch_adjoint_burgers1d(dtype == SADJ_F64, n, C, D, base + (size_t)t * row, lam[s % 2],
+                                                      lam[(s + 1) % 2], s > 0 ? 1 : 0, static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return from_hip(e);
+    }
+    return SADJ_OK;
 }
 
 }  // extern "C"

@@ -39,8 +39,9 @@ hipError_t launch_adjoint_wave1d(int is_f64, long n, const void *c, const void *
 hipError_t launch_primal_wave1d(int is_f64, long n, const void *u, const void *u_prev, const void *c,
                                 void *r, hipStream_t stream);
 
+// assign != 0: u_bar = J^T r_bar (u_bar is not read) instead of u_bar += J^T r_bar
 hipError_t launch_adjoint_burgers1d(int is_f64, long n, double C, double D, const void *u,
-                                    const void *r_bar, void *u_bar, hipStream_t stream);
+                                    const void *r_bar, void *u_bar, int assign, hipStream_t stream);
 hipError_t launch_primal_burgers1d(int is_f64, long n, double C, double D, const void *u, void *r,
                                    hipStream_t stream);
 

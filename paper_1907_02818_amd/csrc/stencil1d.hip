@@ -31,7 +31,8 @@ struct Args1d {
 };
 
 constexpr int kWaves1d = 4;
-enum Op1d { OP_ADJ_WAVE, OP_ADJ_WAVE_UPREV, OP_PRI_WAVE, OP_PRI_BURGERS, OP_ADJ_BURGERS, OP_ADJ_BOX, OP_PRI_BOX };
+enum Op1d { OP_ADJ_WAVE, OP_ADJ_WAVE_UPREV, OP_PRI_WAVE, OP_PRI_BURGERS, OP_ADJ_BURGERS, OP_ADJ_BOX, OP_PRI_BOX,
+            OP_ADJ_BURGERS_ASSIGN };
 
 // Load PX consecutive cells starting at x.  Unguarded: one vector load.  Guarded:
 // element-wise, indices clamped to [0, n-1].
@@ -235,7 +236,9 @@ __device__ __forceinline__ void pri_burgers_segment(const Args1d &a, long xs, in
 //   g_-(i) = C max(u_i,0) + D,  g_+(i) = -C min(u_i,0) + D,
 //   g_0(i) = 1 - 2D - C( [u_i>=0](u_i-u_{i-1}) + max(u_i,0) + [-u_i>=0](u_{i+1}-u_i) - min(u_i,0) )
 // The primal u is read at j-1, j, j+1 (shifted reads, Section 3.3.2).
-template <class T, int PX, bool GUARD>
+// ASSIGN: u_bar[j] = (the three terms) instead of +=, for a time loop that recycles a
+// buffer whose accumulated value is known to be zero (u_bar is then not read).
+template <class T, int PX, bool GUARD, bool ASSIGN>
 __device__ __forceinline__ void adj_burgers_segment(const Args1d &a, long xs, int lane)
 {
     constexpr int W = 64 * PX;
@@ -249,7 +252,7 @@ __device__ __forceinline__ void adj_burgers_segment(const Args1d &a, long xs, in
     T uv[PX], rv[PX], bv[PX];
     load_cells<T, PX, GUARD>(ug, x, n, uv);
     load_cells<T, PX, GUARD>(rg, x, n, rv);
-    load_cells<T, PX, GUARD>(bg, x, n, bv);
+    if (!ASSIGN) load_cells<T, PX, GUARD>(bg, x, n, bv);
     const T uh = load_cell<T, GUARD>(ug, hx, n, lane);
     T rh = load_cell<T, GUARD>(rg, hx, n, lane);
     bool ok[PX], in[PX];
@@ -276,7 +279,8 @@ __device__ __forceinline__ void adj_burgers_segment(const Args1d &a, long xs, in
         const T g0 = T(1) - C * (dpos * (u0 - um) + pos_part(u0) + dneg * (up - u0) - neg_part(u0)) - T(2) * D;
         const T from_right = (C * pos_part(up) + D) * rp;      // iteration j+1 read u[j] as its left cell
         const T from_left = (-C * neg_part(um) + D) * rm;      // iteration j-1 read u[j] as its right cell
-        out[e] = bv[e] + (from_right + (in[e] ? g0 * rv[e] : T(0)) + from_left);
+        const T terms = from_right + (in[e] ? g0 * rv[e] : T(0)) + from_left;
+        out[e] = ASSIGN ? terms : bv[e] + terms;
     }
     store_cells<T, PX, GUARD>(bg, x, n, out, ok);
 }
@@ -291,7 +295,8 @@ __device__ __forceinline__ void run_segment(const Args1d &a, long xs, int lane)
     else if (OP == OP_PRI_BURGERS) pri_burgers_segment<T, PX, GUARD>(a, xs, lane);
     else if (OP == OP_ADJ_BOX) box1d_segment<T, PX, GUARD, true>(a, xs, lane);
     else if (OP == OP_PRI_BOX) box1d_segment<T, PX, GUARD, false>(a, xs, lane);
-    else adj_burgers_segment<T, PX, GUARD>(a, xs, lane);
+    else if (OP == OP_ADJ_BURGERS_ASSIGN) adj_burgers_segment<T, PX, GUARD, true>(a, xs, lane);
+    else adj_burgers_segment<T, PX, GUARD, false>(a, xs, lane);
 }
 
 template <class T, int PX, int OP>
@@ -357,11 +362,11 @@ hipError_t launch_primal_wave1d(int is_f64, long n, const void *u, const void *u
     return dispatch_1d<OP_PRI_WAVE>(is_f64, a, stream);
 }
 hipError_t launch_adjoint_burgers1d(int is_f64, long n, double C, double D, const void *u,
-                                    const void *r_bar, void *u_bar, hipStream_t stream)
+                                    const void *r_bar, void *u_bar, int assign, hipStream_t stream)
 {
     Args1d a{};
     a.a0 = u; a.a1 = r_bar; a.o0 = u_bar; a.n = n; a.C = C; a.D = D;
-    return dispatch_1d<OP_ADJ_BURGERS>(is_f64, a, stream);
+    return assign ? dispatch_1d<OP_ADJ_BURGERS_ASSIGN>(is_f64, a, stream) : dispatch_1d<OP_ADJ_BURGERS>(is_f64, a, stream);
 }
 hipError_t launch_primal_burgers1d(int is_f64, long n, double C, double D, const void *u, void *r,
                                    hipStream_t stream)

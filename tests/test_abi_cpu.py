@@ -25,7 +25,7 @@ def test_header_declares_the_expected_entry_points():
     names = _declared_functions()
     for n in ("sadj_primal_wave1d", "sadj_adjoint_wave1d", "sadj_primal_wave2d", "sadj_adjoint_wave2d",
               "sadj_primal_wave3d", "sadj_adjoint_wave3d", "sadj_primal_burgers1d",
-              "sadj_adjoint_burgers1d", "sadj_adjoint_wave3d_steps", "sadj_adjoint_wave3d_atomic_scatter", "sadj_primal_box", "sadj_adjoint_box", "sadj_status_string", "sadj_version", "sadj_set_option",
+              "sadj_adjoint_burgers1d", "sadj_adjoint_wave3d_steps", "sadj_adjoint_wave3d_atomic_scatter", "sadj_primal_burgers1d_steps", "sadj_adjoint_burgers1d_steps", "sadj_primal_box", "sadj_adjoint_box", "sadj_status_string", "sadj_version", "sadj_set_option",
               "sadj_get_option", "sadj_last_device_error"):
         assert n in names
 

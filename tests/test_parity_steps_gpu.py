@@ -5,7 +5,7 @@ import pytest
 
 import inputs
 import oracle
-from parity import TOL, to_gpu, to_host
+from parity import TOL, assert_close, to_gpu, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -74,3 +74,58 @@ def test_steps_argument_errors(sadj):
     with pytest.raises(sadj.SadjError) as e:
         sadj.sadj_adjoint_wave3d_steps(3, 1, *t)
     assert e.value.status == 4
+
+
+# ----------------------------------------------------------- Burgers time loop (stored states)
+BC, BD = 0.1, 0.05
+
+
+def _burgers_states(n, nsteps, seed, dtype):
+    st = np.empty((nsteps + 1, n), dtype=dtype)
+    st[0] = inputs.burgers_inputs(n, seed=seed, dtype=dtype)["u"]
+    for t in range(1, nsteps + 1):
+        st[t] = inputs.uniform(seed + t, "u_prev", (n,), -0.5, 0.5).astype(dtype)
+    return st
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("n,nsteps", [(3, 2), (64, 1), (257, 5), (1000, 4), (100003, 6)])
+def test_burgers_forward_and_reverse_sweeps(sadj, n, nsteps, dtype):
+    import torch
+    Cd, Dd = (float(np.float32(BC)), float(np.float32(BD))) if dtype == np.float32 else (BC, BD)
+    st0 = _burgers_states(n, nsteps, n, dtype)
+    stg = to_gpu(st0)
+    sadj.sadj_primal_burgers1d_steps(BC, BD, nsteps, stg)
+    torch.cuda.synchronize()
+    got_st = to_host(stg)
+    want_st = oracle.burgers_primal_steps(st0, nsteps, Cd, Dd)
+    assert np.array_equal(got_st[:, 0], st0[:, 0]) and np.array_equal(got_st[:, -1], st0[:, -1])
+    assert_close(got_st, want_st, np.abs(want_st) + 1.0, dtype, "burgers forward sweep n=%d steps=%d" % (n, nsteps))
+    # reverse sweep over the GPU's own stored states (what a solver would do); the oracle
+    # sweeps over the same states, so differences are those of the adjoint steps alone
+    lam0 = inputs.uniform(n, "r_bar", (n,), -1, 1).astype(dtype)
+    lam1 = inputs.uniform(n, "u_bar", (n,), -1, 1).astype(dtype)
+    lam0_p = lam0.copy(); lam0_p[0] = lam0_p[-1] = np.nan            # outside I: never used
+    g0, g1 = to_gpu(lam0_p), to_gpu(lam1)
+    sadj.sadj_adjoint_burgers1d_steps(BC, BD, nsteps, nsteps, stg, g0, g1)
+    torch.cuda.synchronize()
+    w0, w1 = oracle.burgers_adjoint_steps(got_st, nsteps, nsteps, lam0, lam1, Cd, Dd)
+    got = to_host((g0, g1)[nsteps % 2])
+    want = (w0, w1)[nsteps % 2]
+    scale = np.abs(want) + np.abs(lam0.astype(np.float64)).max() * (1.5 ** nsteps)
+    assert_close(got, want, scale, dtype, "burgers reverse sweep n=%d steps=%d" % (n, nsteps))
+
+
+def test_burgers_sweep_argument_checks(sadj):
+    import paper_1907_02818_amd as lib
+    st = to_gpu(np.zeros((4, 100)))
+    a, b = to_gpu(np.zeros(100)), to_gpu(np.zeros(100))
+    with pytest.raises(lib.SadjError) as e:
+        sadj.sadj_adjoint_burgers1d_steps(BC, BD, 3, 4, st, a, b)      # more steps than states
+    assert e.value.status == 2
+    with pytest.raises(lib.SadjError) as e:
+        sadj.sadj_adjoint_burgers1d_steps(BC, BD, 3, 2, st, a, a)      # lam0 and lam1 overlap
+    assert e.value.status == 3
+    with pytest.raises(lib.SadjError) as e:
+        sadj.sadj_adjoint_burgers1d_steps(BC, BD, 3, 2, st, st[1], b)  # lam0 inside the rows read
+    assert e.value.status == 3
