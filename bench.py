@@ -36,6 +36,17 @@ HBM_PEAK_GBS = 8000.0
 METRIC = "adjoint stencil Gpoints/s + % of peak HBM GB/s, 3D wave r=4 512^3 fp64"
 
 
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for ln in fh:
+                if ln.startswith("model name"):
+                    return ln.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def interior_points(shape, radius):
     n = 1
     for s in shape:
@@ -274,7 +285,7 @@ def main():
         out["cpu_baseline"] = {"value": nzs * n * n / dt / 1e9, "unit": "Gpoints/s", "cores": 1, "kind": "oracle",
                                "sample": "first %d z-planes of the same %d^3 arrays (%d x %d x %d grid), one run, "
                                          "%.1f s" % (nzs, n, n, n, nzs, dt),
-                               "host_cpus": os.cpu_count()}
+                               "host_cpus": os.cpu_count(), "host_cpu_model": cpu_model()}
     print(json.dumps(out))
 
 

@@ -34,8 +34,19 @@ def rel_err(got, want, scale):
     return out
 
 
+def norm_err(got, want):
+    """The plain measure max|got - want| / max|want| over the whole array."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    den = float(np.max(np.abs(want))) if want.size else 0.0
+    num = float(np.max(np.abs(got - want))) if want.size else 0.0
+    return num / den if den > 0 else (0.0 if num == 0 else np.inf)
+
+
 def assert_close(got, want, scale, dtype, what=""):
     err = rel_err(got, want, scale)
     tol = TOL[np.dtype(dtype)]
     assert err <= tol, "%s: max relative error %.3e > %.1e" % (what, err, tol)
+    plain = norm_err(got, want)
+    assert plain <= tol, "%s: max|g-o|/max|o| = %.3e > %.1e" % (what, plain, tol)
     return err

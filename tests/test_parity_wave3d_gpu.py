@@ -291,6 +291,14 @@ def test_adjoint_full_size_headline(sadj, dtype):
     d = inputs.config_inputs("wave3d_r4", dtype=dtype)
     e = _check_adjoint(sadj, d, 4, dtype, with_prev=False, what="512^3 R=4 %s" % np.dtype(dtype).name)
     print("512^3 R=4 %s max rel err %.3e" % (np.dtype(dtype).name, e))
+    # closed form that holds at any size: the star weights sum to zero, so the increments of
+    # u_bar add up to 2 * sum of r_bar over the primal interior (u_dot = 1 in the dot-product test)
+    got, _ = _run_adjoint(sadj, d, 4, False)
+    delta = got.astype(np.float64) - d["u_bar"].astype(np.float64)
+    m = interior_mask(d["c"].shape, 4)
+    want_sum = 2.0 * d["r_bar"].astype(np.float64)[m].sum()
+    bound = (1e-12 if dtype == np.float64 else 1e-5) * np.abs(delta).sum()
+    assert abs(delta.sum() - want_sum) <= bound, (delta.sum(), want_sum, bound)
 
 
 def test_adjoint_full_size_r1(sadj):
