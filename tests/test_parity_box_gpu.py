@@ -36,13 +36,23 @@ def _weights(ndim, seed):
     return inputs.uniform(seed, "aux", (3,) * ndim, -2.0, 2.0)
 
 
+# the functor path exists in 1-D only
+CASES = [(s, 0) for s in SHAPES] + [(s, 1) for s in SHAPES if len(s) == 1]
+
+
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
-@pytest.mark.parametrize("shape", SHAPES)
-def test_box_adjoint_and_primal(sadj, path1d, shape, dtype):
+@pytest.mark.parametrize("shape,functor", CASES)
+def test_box_adjoint_and_primal(sadj, shape, functor, dtype):
     import torch
     ndim = len(shape)
-    if path1d == 1 and ndim > 1:
-        pytest.skip("the functor path exists in 1-D only")
+    sadj.set_option("stencil1d.functor", functor)
+    try:
+        _box_case(sadj, shape, dtype, ndim, torch)
+    finally:
+        sadj.set_option("stencil1d.functor", 0)
+
+
+def _box_case(sadj, shape, dtype, ndim, torch):
     w = _weights(ndim, sum(shape))
     wq = w.astype(dtype).astype(np.float64)            # the library converts the weights to dtype
     u = inputs.uniform(1, "u", shape, -1, 1).astype(dtype)
