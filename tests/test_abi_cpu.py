@@ -119,6 +119,20 @@ def test_argument_errors_are_reported_before_any_launch():
     assert lib.sadj_adjoint_box(F64, 4, 32, 32, 32, W9, A, B, C_, None) == 4
     assert lib.sadj_adjoint_box(F64, 3, 32, 2, 32, W9, A, B, C_, None) == 2
     assert lib.sadj_primal_box(F64, 1, 64, 1, 1, W9, A, B, A, None) == 3
+    # Burgers time loop: null, more steps than stored states, overlap of the two buffers /
+    # of a buffer with the rows that are read (row = 100 doubles = 800 bytes)
+    assert lib.sadj_primal_burgers1d_steps(F64, 100, 3, 0.1, 0.05, None, None) == 1
+    assert lib.sadj_primal_burgers1d_steps(F64, 2, 3, 0.1, 0.05, A, None) == 2
+    assert lib.sadj_primal_burgers1d_steps(F64, 100, -1, 0.1, 0.05, A, None) == 2
+    assert lib.sadj_adjoint_burgers1d_steps(F64, 100, 5, 3, 0.1, 0.05, A, B, None, None) == 1
+    assert lib.sadj_adjoint_burgers1d_steps(F64, 100, 2, 3, 0.1, 0.05, A, B, C_, None) == 2
+    assert lib.sadj_adjoint_burgers1d_steps(F64, 100, 5, 3, 0.1, 0.05, A, B, B, None) == 3
+    assert lib.sadj_adjoint_burgers1d_steps(F64, 100, 5, 3, 0.1, 0.05, A, P(0x10000000 + 3 * 800), C_, None) == 3
+    # the atomic-scatter contrast call validates like the gather call
+    assert lib.sadj_adjoint_wave3d_atomic_scatter(F64, 4, 32, 32, 32, A, None, C_, None) == 1
+    assert lib.sadj_adjoint_wave3d_atomic_scatter(F64, 4, 32, 8, 32, A, B, C_, None) == 2
+    assert lib.sadj_adjoint_wave3d_atomic_scatter(F64, 1, 16, 16, 16, A, B, B, None) == 3
+    assert lib.sadj_adjoint_wave3d_atomic_scatter(F64, 3, 32, 32, 32, A, B, C_, None) == 4
     # unsupported radius / dtype
     assert lib.sadj_adjoint_wave3d(F64, 2, 32, 32, 32, A, B, C_, None, None) == 4
     assert lib.sadj_adjoint_wave3d(7, 4, 32, 32, 32, A, B, C_, None, None) == 4
