@@ -336,9 +336,6 @@ static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipSt
     case 6: return launch_cfg<T, R, 32, 16, 2, 2, 1, false>(a, opt, stream);    // u_bar through L2 (no streaming hint)
     case 7: return launch_cfg<T, R, 64, 4, 4, 1, 1, true>(a, opt, stream);      // 64 x 16 tile, 256 threads
     case 8: return launch_cfg<T, R, 64, 8, 4, 2, 1, true>(a, opt, stream);      // 128 x 32 tile, PX = 2
-    case 9: return launch_cfg<T, R, 32, 16, 2, 4, 2, true>(a, opt, stream);     // fp32 shape, two planes in flight
-    case 10: return launch_cfg<T, R, 32, 16, 1, 4, 1, true>(a, opt, stream);    // 128 x 16 tile, 512 threads
-    case 11: return launch_cfg<T, R, 32, 8, 2, 4, 1, true>(a, opt, stream);     // 128 x 16 tile, 256 threads
     }
 }
 
