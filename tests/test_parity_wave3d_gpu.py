@@ -304,3 +304,34 @@ def test_adjoint_full_size_headline(sadj, dtype):
 def test_adjoint_full_size_r1(sadj):
     d = inputs.config_inputs("wave3d_r1")
     _check_adjoint(sadj, d, 1, np.float64, with_prev=True, what="512^3 R=1")
+
+
+def test_arrays_beyond_4_gib_are_addressed_with_64_bits(sadj):
+    """1024 x 1024 x 640 in fp64: every array holds 5.4 GB, so element offsets pass 2^32
+    bytes and the dispatch takes two rounds of workgroups.  The oracle runs on three slabs
+    of planes (bottom with the global boundary, one across the 4 GiB mark, top); a slab is
+    a grid of its own, so its planes from 2R to S-2R-1 (all their sources lie in the slab's
+    interior) -- and, at the bottom / top of the grid, also its first / last planes --
+    equal those of the full problem."""
+    import torch
+    radius, shape = 4, (640, 1024, 1024)
+    nz = shape[0]
+    d = inputs.wave_inputs(shape, 0.01, 0.1, seed=21, c_mode="iid", fields=("c", "r_bar", "u_bar"))
+    c, rb, ub = to_gpu(d["c"]), to_gpu(d["r_bar"]), to_gpu(d["u_bar"])
+    sadj.sadj_adjoint_wave3d(radius, c, rb, ub)
+    torch.cuda.synchronize()
+    got = to_host(ub)
+    del c, rb, ub
+    plane_bytes = shape[1] * shape[2] * 8
+    zmark = (1 << 32) // plane_bytes                       # the plane that contains byte offset 2^32
+    S = 24
+    for z0, lo, hi in ((0, 0, S - 2 * radius), (zmark - S // 2, 2 * radius, S - 2 * radius), (nz - S, 2 * radius, S)):
+        sl = slice(z0, z0 + S)
+        want, _, scale = oracle.wave_adjoint(d["c"][sl], d["r_bar"][sl], d["u_bar"][sl], radius, want_scale=True)
+        scale = scale + np.abs(d["u_bar"][sl])
+        assert_close(got[sl][lo:hi], want[lo:hi], scale[lo:hi], np.float64, "planes %d..%d" % (z0 + lo, z0 + hi - 1))
+    # and nothing else was left untouched or written twice: the closed-form sum over the grid
+    delta = got - d["u_bar"]
+    m = interior_mask(shape, radius)
+    want_sum = 2.0 * d["r_bar"][m].sum()
+    assert abs(delta.sum() - want_sum) <= 1e-12 * np.abs(delta).sum()
