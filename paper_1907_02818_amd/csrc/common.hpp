@@ -34,24 +34,9 @@ __device__ __forceinline__ int xcd_contiguous_id(int hw_id, int total)
     return start + idx;
 }
 
-struct Box { int x0, x1, y0, y1, z0, z1; };   // half-open index ranges
-
-// One rectangular region of output indices with its own tiling.
-struct Region {
-    Box box;
-    int ntx, nty, ntz;     // tiles along x, y and z-chunks
-    int first_block;       // logical id of the region's first workgroup
-};
-
-constexpr int kMaxRegions = 8;
-
 template <class T> __device__ __forceinline__ T ld_off(const T *base, uint32_t byte_off)
 {
     return *reinterpret_cast<const T *>(reinterpret_cast<const char *>(base) + byte_off);
-}
-template <class T> __device__ __forceinline__ void st_off(T *base, uint32_t byte_off, T v)
-{
-    *reinterpret_cast<T *>(reinterpret_cast<char *>(base) + byte_off) = v;
 }
 
 

@@ -26,12 +26,14 @@
 // constant, hence no register copies.
 //
 // HBM traffic.  The chip is bound by traffic that misses the 4 MB L2 of an XCD, so
-// halo cells must be found in L2.  Workgroup ids are mapped such that each XCD owns
-// a compact patch of neighbouring tiles, and the grid is sized to one resident wave
-// of workgroups; all of them start together, do identical work per plane and hence
-// move through z in near lockstep: a halo cell is fetched from memory by whichever
-// tile asks first and is an L2 hit for its neighbour.  u_bar is streamed with
-// non-temporal loads and stores so that it does not displace c and r_bar from L2.
+// halo cells must be found in L2.  Workgroup ids are mapped such that, within each
+// round of resident workgroups, every XCD owns a compact patch of neighbouring tiles
+// (block_to_tile), and the number of z-chunks is chosen so that the dispatch is one
+// round (one workgroup per CU) or as few full rounds as possible; the workgroups of a
+// round start together, do identical work per plane and hence move through z in near
+// lockstep: a halo cell is fetched from memory by whichever tile asks first and is an
+// L2 hit for its neighbour.  u_bar is streamed with non-temporal loads and stores so
+// that it does not displace c and r_bar from L2.
 //
 // Regions (Section 3.3.4).  Tiles whose reads in x and y all lie in I run the
 // unguarded instantiation (core): every staged element is loaded and used
