@@ -213,6 +213,9 @@ def main():
             wave_adjoint_bytes(shape, 1, 8), "f64")
         add("wave3d_r1_f64_primal", lambda: sadj.sadj_primal_wave3d(1, ub, upb, c, r), N,
             8 * N + 24 * interior_points(shape, 1), "f64")
+        for rad in (2, 3):
+            add("wave3d_r%d_f64_adjoint" % rad, lambda: sadj.sadj_adjoint_wave3d(rad, c, rb, ub), N,
+                wave_adjoint_bytes(shape, rad, 8), "f64")
         # dense 3x3x3 box stencil with asymmetric weights (27 terms), same grid
         wbox = [[[0.1 * (i + 3 * j + 9 * k) - 1.0 for i in range(3)] for j in range(3)] for k in range(3)]
         add("box3d_f64_adjoint", lambda: sadj.sadj_adjoint_box(wbox, c, rb, ub), N,

@@ -38,8 +38,9 @@
  *    a failed call has no effect.  No function throws or aborts.
  *  - Calls are thread-safe; one GPU (the current HIP device of the calling thread).
  *
- * Star Laplacian weights: R=1: (-2, 1); R=4: the 8th-order central weights
- * (-205/72, 8/5, -1/5, 8/315, -1/560) per axis; the centre weight is multiplied by
+ * Star Laplacian weights (standard central second-derivative weights, centre first):
+ * R=1: (-2, 1); R=2: (-5/2, 4/3, -1/12); R=3: (-49/18, 3/2, -3/20, 1/90);
+ * R=4: (-205/72, 8/5, -1/5, 8/315, -1/560) per axis; the centre weight is multiplied by
  * the number of dimensions.  Grid spacing and time step are folded into c.
  */
 #ifndef SADJ_H
@@ -78,7 +79,9 @@ const char *sadj_last_device_error(void);
  *     u_bar[j]      += 2 r_bar[j] [j in I] + sum_o w_o * c[j-o] r_bar[j-o] [j-o in I]
  *     u_prev_bar[j] -= r_bar[j] [j in I]            (skipped when u_prev_bar is NULL)
  * The linear stencil's adjoint does not need the primal u (Section 3.1).
- * 1-D and 2-D: radius 1 (3- and 5-point).  3-D: radius 1 (7-point) or 4 (25-point).
+ * 1-D and 2-D: radius 1 (3- and 5-point).  3-D: radius 1 .. 4 (7-, 13-, 19- and 25-point
+ * stars; radius 1 is the paper's test case, radius 4 the benchmark's; the launch-shape
+ * variants of "wave3d.variant" exist for radius 1 and 4, other radii use the default shape).
  */
 sadj_status sadj_primal_wave1d(sadj_dtype dtype, long n,
                                const void *u, const void *u_prev, const void *c, void *r,

@@ -243,13 +243,13 @@ sadj_status sadj_adjoint_wave2d(sadj_dtype dtype, long nx, long ny, const void *
 sadj_status sadj_primal_wave3d(sadj_dtype dtype, int radius, long nx, long ny, long nz, const void *u,
                                const void *u_prev, const void *c, void *r, void *stream)
 {
-    if (radius != 1 && radius != 4) return SADJ_ERR_UNSUPPORTED;
+    if (radius < 1 || radius > 4) return SADJ_ERR_UNSUPPORTED;
     return primal_wave(3, dtype, radius, nx, ny, nz, u, u_prev, c, r, stream);
 }
 sadj_status sadj_adjoint_wave3d(sadj_dtype dtype, int radius, long nx, long ny, long nz, const void *c,
                                 const void *r_bar, void *u_bar, void *u_prev_bar, void *stream)
 {
-    if (radius != 1 && radius != 4) return SADJ_ERR_UNSUPPORTED;
+    if (radius < 1 || radius > 4) return SADJ_ERR_UNSUPPORTED;
     return adjoint_wave(3, dtype, radius, nx, ny, nz, c, r_bar, u_bar, u_prev_bar, stream);
 }
 
@@ -257,7 +257,7 @@ sadj_status sadj_adjoint_wave3d(sadj_dtype dtype, int radius, long nx, long ny, 
 sadj_status sadj_adjoint_wave3d_atomic_scatter(sadj_dtype dtype, int radius, long nx, long ny, long nz,
                                                const void *c, const void *r_bar, void *u_bar, void *stream)
 {
-    if (radius != 1 && radius != 4) return SADJ_ERR_UNSUPPORTED;
+    if (radius < 1 || radius > 4) return SADJ_ERR_UNSUPPORTED;
     if (!dtype_ok(dtype)) return SADJ_ERR_UNSUPPORTED;
     if (!c || !r_bar || !u_bar) return SADJ_ERR_NULL;
     sadj_status s = check_extents(radius, nx, ny, nz, 3);
@@ -275,7 +275,7 @@ sadj_status sadj_adjoint_wave3d_atomic_scatter(sadj_dtype dtype, int radius, lon
 sadj_status sadj_adjoint_wave3d_steps(sadj_dtype dtype, int radius, long nx, long ny, long nz, long nsteps,
                                       const void *c, void *lam0, void *lam1, void *lam2, void *stream)
 {
-    if (radius != 1 && radius != 4) return SADJ_ERR_UNSUPPORTED;
+    if (radius < 1 || radius > 4) return SADJ_ERR_UNSUPPORTED;
     if (!dtype_ok(dtype)) return SADJ_ERR_UNSUPPORTED;
     if (!c || !lam0 || !lam1 || !lam2) return SADJ_ERR_NULL;
     if (nsteps < 0) return SADJ_ERR_SIZE;

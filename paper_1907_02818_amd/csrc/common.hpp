@@ -6,10 +6,18 @@
 namespace sadj {
 
 // Central finite-difference weights of the second derivative on a unit grid
-// (orders 2 and 8), the nearest double of each rational; w(0) is the per-axis
+// (orders 2, 4, 6 and 8 for radius 1 .. 4), the nearest double of each rational; w(0) is the per-axis
 // centre weight.
 template <int R> __host__ __device__ constexpr double star_w(int k);
 template <> __host__ __device__ constexpr double star_w<1>(int k) { return k == 0 ? -2.0 : 1.0; }
+template <> __host__ __device__ constexpr double star_w<2>(int k)
+{
+    return k == 0 ? -5.0 / 2.0 : k == 1 ? 4.0 / 3.0 : -1.0 / 12.0;
+}
+template <> __host__ __device__ constexpr double star_w<3>(int k)
+{
+    return k == 0 ? -49.0 / 18.0 : k == 1 ? 3.0 / 2.0 : k == 2 ? -3.0 / 20.0 : 1.0 / 90.0;
+}
 template <> __host__ __device__ constexpr double star_w<4>(int k)
 {
     return k == 0 ? -205.0 / 72.0

@@ -328,16 +328,27 @@ static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipSt
 {
     long v = opt.variant;
     if (v == 0) v = a.out1 ? (sizeof(T) == 8 ? 3 : 8) : (sizeof(T) == 8 ? 1 : 2);   // measured best
-    switch (v) {
-    default:
-    case 1: return launch_cfg<T, R, 32, 16, 2, 2, 1, true>(a, opt, stream);     // fp64 default
-    case 2: return launch_cfg<T, R, 32, 16, 2, 4, 1, true>(a, opt, stream);     // fp32 default
-    case 3: return launch_cfg<T, R, 64, 8, 4, 1, 1, true>(a, opt, stream);      // 8 bytes per lane (fallback shape)
-    case 4: return launch_cfg<T, R, 64, 8, 4, 1, 2, true>(a, opt, stream);      // two planes in flight
-    case 5: return launch_cfg<T, R, 64, 8, 2, 2, 1, true>(a, opt, stream);      // 128 x 16 tile
-    case 6: return launch_cfg<T, R, 32, 16, 2, 2, 1, false>(a, opt, stream);    // u_bar through L2 (no streaming hint)
-    case 7: return launch_cfg<T, R, 64, 4, 4, 1, 1, true>(a, opt, stream);      // 64 x 16 tile, 256 threads
-    case 8: return launch_cfg<T, R, 64, 8, 4, 2, 1, true>(a, opt, stream);      // 128 x 32 tile, PX = 2
+    if constexpr (R == 2 || R == 3) {            // the default shapes of the dtype only
+        if constexpr (sizeof(T) == 8) {
+            return v == 3 ? launch_cfg<T, R, 64, 8, 4, 1, 1, true>(a, opt, stream)
+                          : launch_cfg<T, R, 32, 16, 2, 2, 1, true>(a, opt, stream);
+        } else {
+            return v == 3 ? launch_cfg<T, R, 64, 8, 4, 1, 1, true>(a, opt, stream)
+                 : v == 8 ? launch_cfg<T, R, 64, 8, 4, 2, 1, true>(a, opt, stream)
+                          : launch_cfg<T, R, 32, 16, 2, 4, 1, true>(a, opt, stream);
+        }
+    } else {
+        switch (v) {
+        default:
+        case 1: return launch_cfg<T, R, 32, 16, 2, 2, 1, true>(a, opt, stream);     // fp64 default
+        case 2: return launch_cfg<T, R, 32, 16, 2, 4, 1, true>(a, opt, stream);     // fp32 default
+        case 3: return launch_cfg<T, R, 64, 8, 4, 1, 1, true>(a, opt, stream);      // 8 bytes per lane (fallback shape)
+        case 4: return launch_cfg<T, R, 64, 8, 4, 1, 2, true>(a, opt, stream);      // two planes in flight
+        case 5: return launch_cfg<T, R, 64, 8, 2, 2, 1, true>(a, opt, stream);      // 128 x 16 tile
+        case 6: return launch_cfg<T, R, 32, 16, 2, 2, 1, false>(a, opt, stream);    // u_bar through L2 (no streaming hint)
+        case 7: return launch_cfg<T, R, 64, 4, 4, 1, 1, true>(a, opt, stream);      // 64 x 16 tile, 256 threads
+        case 8: return launch_cfg<T, R, 64, 8, 4, 2, 1, true>(a, opt, stream);      // 128 x 32 tile, PX = 2
+        }
     }
 }
 
@@ -350,11 +361,19 @@ hipError_t launch_adjoint_wave3d(int is_f64, int radius, int nx, int ny, int nz,
     a.out1_assign = u_prev_bar_assign;
     a.nx = nx; a.ny = ny; a.nz = nz;
     if (is_f64) {
-        if (radius == 1) return launch_T<double, 1>(a, opt, stream);
-        return launch_T<double, 4>(a, opt, stream);
+        switch (radius) {
+        case 1: return launch_T<double, 1>(a, opt, stream);
+        case 2: return launch_T<double, 2>(a, opt, stream);
+        case 3: return launch_T<double, 3>(a, opt, stream);
+        default: return launch_T<double, 4>(a, opt, stream);
+        }
     }
-    if (radius == 1) return launch_T<float, 1>(a, opt, stream);
-    return launch_T<float, 4>(a, opt, stream);
+    switch (radius) {
+    case 1: return launch_T<float, 1>(a, opt, stream);
+    case 2: return launch_T<float, 2>(a, opt, stream);
+    case 3: return launch_T<float, 3>(a, opt, stream);
+    default: return launch_T<float, 4>(a, opt, stream);
+    }
 }
 
 }  // namespace sadj

@@ -257,8 +257,20 @@ hipError_t launch_adjoint_wave3d_ordered(int is_f64, int radius, int nx, int ny,
     March3dArgs a{};
     a.in0 = c; a.in1 = r_bar; a.out0 = u_bar; a.out1 = u_prev_bar;
     a.nx = nx; a.ny = ny; a.nz = nz;
-    if (is_f64) return radius == 1 ? launch_ordered_T<double, 1>(a, opt, stream) : launch_ordered_T<double, 4>(a, opt, stream);
-    return radius == 1 ? launch_ordered_T<float, 1>(a, opt, stream) : launch_ordered_T<float, 4>(a, opt, stream);
+    if (is_f64) {
+        switch (radius) {
+        case 1: return launch_ordered_T<double, 1>(a, opt, stream);
+        case 2: return launch_ordered_T<double, 2>(a, opt, stream);
+        case 3: return launch_ordered_T<double, 3>(a, opt, stream);
+        default: return launch_ordered_T<double, 4>(a, opt, stream);
+        }
+    }
+    switch (radius) {
+    case 1: return launch_ordered_T<float, 1>(a, opt, stream);
+    case 2: return launch_ordered_T<float, 2>(a, opt, stream);
+    case 3: return launch_ordered_T<float, 3>(a, opt, stream);
+    default: return launch_ordered_T<float, 4>(a, opt, stream);
+    }
 }
 
 }  // namespace sadj

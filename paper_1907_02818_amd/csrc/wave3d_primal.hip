@@ -220,13 +220,18 @@ static hipError_t launch_primal_T(const March3dArgs &a, const LaunchOptions &opt
 {
     long v = opt.variant;
     if (v == 0) v = sizeof(T) == 8 ? 3 : 8;      // measured best per dtype
-    switch (v) {
-    default:
-    case 1: return launch_primal_cfg<T, R, 32, 16, 2, 2>(a, opt, stream);
-    case 2: return launch_primal_cfg<T, R, 32, 16, 2, 4>(a, opt, stream);
-    case 3: return launch_primal_cfg<T, R, 64, 8, 4, 1>(a, opt, stream);
-    case 5: return launch_primal_cfg<T, R, 64, 8, 2, 2>(a, opt, stream);
-    case 8: return launch_primal_cfg<T, R, 64, 8, 4, 2>(a, opt, stream);
+    if constexpr (R == 2 || R == 3) {            // the default shapes only
+        if constexpr (sizeof(T) == 8) return launch_primal_cfg<T, R, 64, 8, 4, 1>(a, opt, stream);
+        else return v == 3 ? launch_primal_cfg<T, R, 64, 8, 4, 1>(a, opt, stream) : launch_primal_cfg<T, R, 64, 8, 4, 2>(a, opt, stream);
+    } else {
+        switch (v) {
+        default:
+        case 1: return launch_primal_cfg<T, R, 32, 16, 2, 2>(a, opt, stream);
+        case 2: return launch_primal_cfg<T, R, 32, 16, 2, 4>(a, opt, stream);
+        case 3: return launch_primal_cfg<T, R, 64, 8, 4, 1>(a, opt, stream);
+        case 5: return launch_primal_cfg<T, R, 64, 8, 2, 2>(a, opt, stream);
+        case 8: return launch_primal_cfg<T, R, 64, 8, 4, 2>(a, opt, stream);
+        }
     }
 }
 
@@ -237,8 +242,20 @@ hipError_t launch_primal_wave3d(int is_f64, int radius, int nx, int ny, int nz, 
     March3dArgs a{};
     a.in0 = u; a.in1 = u_prev; a.in2 = c; a.out0 = r;
     a.nx = nx; a.ny = ny; a.nz = nz;
-    if (is_f64) return radius == 1 ? launch_primal_T<double, 1>(a, opt, stream) : launch_primal_T<double, 4>(a, opt, stream);
-    return radius == 1 ? launch_primal_T<float, 1>(a, opt, stream) : launch_primal_T<float, 4>(a, opt, stream);
+    if (is_f64) {
+        switch (radius) {
+        case 1: return launch_primal_T<double, 1>(a, opt, stream);
+        case 2: return launch_primal_T<double, 2>(a, opt, stream);
+        case 3: return launch_primal_T<double, 3>(a, opt, stream);
+        default: return launch_primal_T<double, 4>(a, opt, stream);
+        }
+    }
+    switch (radius) {
+    case 1: return launch_primal_T<float, 1>(a, opt, stream);
+    case 2: return launch_primal_T<float, 2>(a, opt, stream);
+    case 3: return launch_primal_T<float, 3>(a, opt, stream);
+    default: return launch_primal_T<float, 4>(a, opt, stream);
+    }
 }
 
 }  // namespace sadj

@@ -54,10 +54,20 @@ static hipError_t launch_scatter_T(int nx, int ny, int nz, const void *c, const 
 hipError_t launch_adjoint_wave3d_scatter_atomic(int is_f64, int radius, int nx, int ny, int nz, const void *c,
                                                 const void *r_bar, void *u_bar, hipStream_t stream)
 {
-    if (is_f64) return radius == 1 ? launch_scatter_T<double, 1>(nx, ny, nz, c, r_bar, u_bar, stream)
-                                   : launch_scatter_T<double, 4>(nx, ny, nz, c, r_bar, u_bar, stream);
-    return radius == 1 ? launch_scatter_T<float, 1>(nx, ny, nz, c, r_bar, u_bar, stream)
-                       : launch_scatter_T<float, 4>(nx, ny, nz, c, r_bar, u_bar, stream);
+    if (is_f64) {
+        switch (radius) {
+        case 1: return launch_scatter_T<double, 1>(nx, ny, nz, c, r_bar, u_bar, stream);
+        case 2: return launch_scatter_T<double, 2>(nx, ny, nz, c, r_bar, u_bar, stream);
+        case 3: return launch_scatter_T<double, 3>(nx, ny, nz, c, r_bar, u_bar, stream);
+        default: return launch_scatter_T<double, 4>(nx, ny, nz, c, r_bar, u_bar, stream);
+        }
+    }
+    switch (radius) {
+    case 1: return launch_scatter_T<float, 1>(nx, ny, nz, c, r_bar, u_bar, stream);
+    case 2: return launch_scatter_T<float, 2>(nx, ny, nz, c, r_bar, u_bar, stream);
+    case 3: return launch_scatter_T<float, 3>(nx, ny, nz, c, r_bar, u_bar, stream);
+    default: return launch_scatter_T<float, 4>(nx, ny, nz, c, r_bar, u_bar, stream);
+    }
 }
 
 }  // namespace sadj

@@ -112,7 +112,7 @@ def test_argument_errors_are_reported_before_any_launch():
     assert lib.sadj_adjoint_wave3d_steps(F64, 4, 32, 32, 32, -1, A, B, C_, D_, None) == 2
     assert lib.sadj_adjoint_wave3d_steps(F64, 4, 32, 32, 32, 3, A, B, C_, B, None) == 3
     assert lib.sadj_adjoint_wave3d_steps(F64, 4, 32, 32, 32, 3, A, A, C_, D_, None) == 3
-    assert lib.sadj_adjoint_wave3d_steps(F64, 2, 32, 32, 32, 3, A, B, C_, D_, None) == 4
+    assert lib.sadj_adjoint_wave3d_steps(F64, 5, 32, 32, 32, 3, A, B, C_, D_, None) == 4
     # box stencils: host weight table required, ndim in 1..3
     W9 = (ctypes.c_double * 27)(*([1.0] * 27))
     assert lib.sadj_adjoint_box(F64, 2, 32, 32, 1, None, A, B, C_, None) == 1
@@ -132,9 +132,10 @@ def test_argument_errors_are_reported_before_any_launch():
     assert lib.sadj_adjoint_wave3d_atomic_scatter(F64, 4, 32, 32, 32, A, None, C_, None) == 1
     assert lib.sadj_adjoint_wave3d_atomic_scatter(F64, 4, 32, 8, 32, A, B, C_, None) == 2
     assert lib.sadj_adjoint_wave3d_atomic_scatter(F64, 1, 16, 16, 16, A, B, B, None) == 3
-    assert lib.sadj_adjoint_wave3d_atomic_scatter(F64, 3, 32, 32, 32, A, B, C_, None) == 4
+    assert lib.sadj_adjoint_wave3d_atomic_scatter(F64, 0, 32, 32, 32, A, B, C_, None) == 4
     # unsupported radius / dtype
-    assert lib.sadj_adjoint_wave3d(F64, 2, 32, 32, 32, A, B, C_, None, None) == 4
+    assert lib.sadj_adjoint_wave3d(F64, 5, 32, 32, 32, A, B, C_, None, None) == 4
+    assert lib.sadj_primal_wave3d(F64, 0, 32, 32, 32, A, B, C_, D_, None) == 4
     assert lib.sadj_adjoint_wave3d(7, 4, 32, 32, 32, A, B, C_, None, None) == 4
     assert lib.sadj_primal_wave2d(-1, 32, 32, A, B, C_, D_, None) == 4
 

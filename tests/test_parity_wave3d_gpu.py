@@ -16,6 +16,7 @@ SMALL = [
     (4, (37, 45, 150)), (4, (9, 9, 9)), (4, (16, 17, 19)), (4, (17, 40, 70)), (4, (40, 16, 200)),
     (4, (21, 33, 64)), (4, (70, 20, 129)),
     (1, (3, 3, 3)), (1, (4, 5, 7)), (1, (21, 37, 150)), (1, (70, 18, 65)), (1, (5, 64, 128)),
+    (2, (5, 5, 5)), (2, (9, 11, 70)), (2, (33, 45, 150)), (3, (7, 7, 7)), (3, (13, 15, 17)), (3, (30, 41, 136)),
 ]
 
 
@@ -101,7 +102,8 @@ def test_remainder_strategies_agree(sadj, radius, dtype):
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 @pytest.mark.parametrize("radius,shape", [(4, (37, 45, 150)), (4, (9, 9, 9)), (4, (17, 40, 70)), (1, (3, 3, 3)),
-                                          (1, (21, 37, 150)), (1, (70, 18, 65))])
+                                          (1, (21, 37, 150)), (1, (70, 18, 65)), (2, (20, 30, 70)), (3, (7, 7, 7)),
+                                          (3, (21, 30, 66))])
 def test_atomic_scatter_contrast_kernel_matches_the_oracle(sadj, radius, shape, dtype):
     """The conventional scatter with atomic updates (Sections 1, 3.2, 4.1), kept as a
     baseline to compare the gather with; same result up to summation order."""
