@@ -266,6 +266,21 @@ def main():
         n1 = 4096
         c1, rb1, ub1 = (t.reshape(-1)[:n1] for t in (c, rb, ub))
         add("wave1d_f64_adjoint_n4096_latency", lambda: sadj.sadj_adjoint_wave1d(c1, rb1, ub1), n1, 32 * n1, "f64")
+        # the same call recorded 100 times into a HIP graph: the launch-bound size without host launch cost
+        per_graph = 100
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            sadj.sadj_adjoint_wave1d(c1, rb1, ub1)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(per_graph):
+                sadj.sadj_adjoint_wave1d(c1, rb1, ub1)
+        add("wave1d_f64_adjoint_n4096_in_hip_graph_per_call", graph.replay, n1 * per_graph, 32 * n1 * per_graph, "f64")
+        for key in ("ms", "kernel_ms_mean"):
+            others["wave1d_f64_adjoint_n4096_in_hip_graph_per_call"][key] /= per_graph
     out["others"] = others
     if args.copy_probe:
         ub.copy_(c)

@@ -217,3 +217,57 @@ def test_wave2d_full_size(sadj):
     _sync()
     want, _, scale = oracle.wave_adjoint(d["c"], d["r_bar"], d["u_bar"], 1, want_scale=True)
     assert_close(to_host(ub), want, scale + np.abs(d["u_bar"]), np.float64, "wave2d 8192^2")
+
+
+# ------------------------------------------------------------------ graph capture
+def test_calls_can_be_captured_in_a_hip_graph_and_replayed(sadj):
+    """The entry points only enqueue kernels on the given stream (no allocation, no
+    synchronisation, no memset), so a caller may record them into a HIP graph -- the way
+    to run the launch-bound small sizes.  Every replay must reproduce the eager result."""
+    import torch
+    n, reps = 4096, 6
+    d = inputs.config_inputs("wave1d")
+    b = inputs.burgers_inputs(n, seed=2)
+    c, rb = to_gpu(d["c"]), to_gpu(d["r_bar"])
+    u, brb = to_gpu(b["u"]), to_gpu(b["r_bar"])
+    shape3 = (20, 33, 64)
+    w = inputs.wave_inputs(shape3, 0.01, 0.1, seed=4)
+    c3, rb3 = to_gpu(w["c"]), to_gpu(w["r_bar"])
+
+    def work(ub, bub, ub3):
+        for _ in range(reps):
+            sadj.sadj_adjoint_wave1d(c, rb, ub)
+            sadj.sadj_adjoint_burgers1d(C, D, u, brb, bub)
+        sadj.sadj_adjoint_wave3d(4, c3, rb3, ub3)
+
+    def fresh():
+        return to_gpu(d["u_bar"]), to_gpu(b["u_bar"]), to_gpu(w["u_bar"])
+
+    eager = fresh()
+    work(*eager)
+    _sync()
+    want = [to_host(t) for t in eager]
+
+    static = fresh()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up on the capture stream
+        work(*static)
+    torch.cuda.current_stream().wait_stream(side)
+    _sync()
+    graph = torch.cuda.CUDAGraph()
+    for t, src in zip(static, fresh()):
+        t.copy_(src)
+    _sync()
+    with torch.cuda.graph(graph):
+        work(*static)
+    for replay in range(3):
+        for t, src in zip(static, fresh()):
+            t.copy_(src)
+        other = torch.ones(1000, device="cuda").sum()  # unrelated eager work between replays
+        _sync()
+        graph.replay()
+        _sync()
+        for got, ref in zip(static, want):
+            assert np.array_equal(to_host(got), ref), "replay %d" % replay
+        assert float(other) == 1000.0
