@@ -85,10 +85,10 @@ __device__ __forceinline__ void box2d_strip(const BoxArgs &a, int xs, int ys, in
         if (!STEADY && y > yi1) return;
         if (STEADY || row_used(y)) {
             s0[d] = ld_vec<T, PX>(g0 + (size_t)y * nx + xc);
-            if (edge_lane) sh0[d] = g0[(size_t)y * nx + hxc];
-            if (ADJ) {
-                s1[d] = ld_vec<T, PX>(g1 + (size_t)y * nx + xc);
-                if (edge_lane) sh1[d] = g1[(size_t)y * nx + hxc];
+            if (ADJ) s1[d] = ld_vec<T, PX>(g1 + (size_t)y * nx + xc);
+            if (edge_lane) {                        // only lanes 0 and 63 use the values
+                sh0[d] = g0[(size_t)y * nx + hxc];
+                if (ADJ) sh1[d] = g1[(size_t)y * nx + hxc];
             }
         }
         const int yo = y - 1;
@@ -124,7 +124,7 @@ __device__ __forceinline__ void box2d_strip(const BoxArgs &a, int xs, int ys, in
             }
         }
         issue(yi + D, dc, steady);
-        if ((STEADY || yo >= ys) && active) {
+        if ((STEADY || yo >= ys) && (!GUARD || active)) {
             V o;
             if (ADJ) {
 #pragma unroll

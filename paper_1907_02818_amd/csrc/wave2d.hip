@@ -191,30 +191,30 @@ __global__ __launch_bounds__(64 * WAVES) void adj_wave2d_kernel(Wave2dArgs a)
 // dimensions).  Same march applied to u, with the same D-row load pipeline; u of the
 // completing row is the previous step's row and is kept in registers.  c, u_prev and r
 // are streamed.  Only cells of I are stored; reads of u never leave the grid.
-template <class T, int PX, int D, int WAVES>
-__global__ __launch_bounds__(64 * WAVES) void primal_wave2d_kernel(Wave2dArgs a)
+// GUARD = false: strips whose columns all lie in I (and hence in the grid): no lane is
+// masked anywhere in the march.  GUARD = true: the first and the last strip of a row.
+template <class T, int PX, int D, bool GUARD>
+__device__ __forceinline__ void primal2d_strip(const Wave2dArgs &a, int xs, int ys, int ye, int lane)
 {
     constexpr int W = 64 * PX;
     using V = Vec<T, PX>;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int nx = a.nx, ny = a.ny;
-    const int xs = (blockIdx.x * WAVES + wave) * W;
-    if (xs >= nx) return;                                 // wave-uniform; no barrier in this kernel
-    const int ys = 1 + blockIdx.y * a.ychunk;             // output rows cover [1, ny-1)
-    const int ye = min(ys + a.ychunk, ny - 1);
+    const int nx = a.nx;
     const T *__restrict__ ug = static_cast<const T *>(a.u);
     const T *__restrict__ pg = static_cast<const T *>(a.u_prev);
     const T *__restrict__ cg = static_cast<const T *>(a.c);
     T *__restrict__ rg = static_cast<T *>(a.r);
 
     const int x = xs + lane * PX;
-    const bool active = x < nx;
+    const bool active = GUARD ? (x < nx) : true;
     const int xc = active ? x : xs;
     bool xin[PX], all_in = true;
 #pragma unroll
-    for (int e = 0; e < PX; ++e) { xin[e] = x + e >= 1 && x + e <= nx - 2; all_in = all_in && xin[e]; }
+    for (int e = 0; e < PX; ++e) {
+        xin[e] = GUARD ? (x + e >= 1 && x + e <= nx - 2) : true;
+        all_in = all_in && xin[e];
+    }
     const int hx = lane < 32 ? xs - 1 : xs + W;
-    const int hxc = (hx >= 0 && hx < nx) ? hx : xs;
+    const int hxc = (!GUARD || (hx >= 0 && hx < nx)) ? hx : xs;
     const bool edge_lane = lane == 0 || lane == 63;
 
     T acc[PX][3], uq[PX];
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(64 * WAVES) void primal_wave2d_kernel(Wave2dArgs a)
         if (!STEADY && y > yi1) return;
         const T *up = ug + (size_t)y * nx;
         su[d] = ld_vec<T, PX>(up + xc);
-        if (edge_lane) sh[d] = up[hxc];
+        if (edge_lane) sh[d] = up[hxc];                    // only lanes 0 and 63 use the value
         const int yo = y - 1;
         if (STEADY || yo >= ys) {
             scc[d] = ld_vec_stream<T, PX>(cg + (size_t)yo * nx + xc);
@@ -264,7 +264,7 @@ __global__ __launch_bounds__(64 * WAVES) void primal_wave2d_kernel(Wave2dArgs a)
 #pragma unroll
             for (int e = 0; e < PX; ++e) o.v[e] = T(2) * uq[e] - pp.v[e] + cc.v[e] * acc[e][0];
             T *rp = rg + (size_t)yo * nx + x;
-            if (all_in) {
+            if (!GUARD || all_in) {
                 st_vec_stream<T, PX>(rp, o);
             } else {                                       // r outside I stays untouched
 #pragma unroll
@@ -306,6 +306,19 @@ __global__ __launch_bounds__(64 * WAVES) void primal_wave2d_kernel(Wave2dArgs a)
         ++yi;
         d = d + 1 == D ? 0 : d + 1;
     }
+}
+
+template <class T, int PX, int D, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void primal_wave2d_kernel(Wave2dArgs a)
+{
+    constexpr int W = 64 * PX;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int xs = (blockIdx.x * WAVES + wave) * W;
+    if (xs >= a.nx) return;                               // wave-uniform; no barrier in this kernel
+    const int ys = 1 + blockIdx.y * a.ychunk;             // output rows cover [1, ny-1)
+    const int ye = min(ys + a.ychunk, a.ny - 1);
+    if (xs >= 1 && xs + W <= a.nx - 1) primal2d_strip<T, PX, D, false>(a, xs, ys, ye, lane);
+    else                               primal2d_strip<T, PX, D, true>(a, xs, ys, ye, lane);
 }
 
 // ------------------------------------------------------------------------ launchers
