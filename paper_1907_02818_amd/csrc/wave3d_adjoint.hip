@@ -327,7 +327,9 @@ template <class T, int R>
 static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipStream_t stream)
 {
     long v = opt.variant;
-    if (v == 0) v = a.out1 ? (sizeof(T) == 8 ? 3 : 8) : (sizeof(T) == 8 ? 1 : 2);   // measured best
+    // measured best: 16 bytes per lane (1 for fp64, 2 for fp32) unless u_prev_bar is read and
+    // written as well, where the wider tiles with fewer registers per cell win
+    if (v == 0) v = (a.out1 && !a.out1_assign) ? (sizeof(T) == 8 ? 3 : 8) : (sizeof(T) == 8 ? 1 : 2);
     if constexpr (R == 2 || R == 3) {            // the default shapes of the dtype only
         if constexpr (sizeof(T) == 8) {
             return v == 3 ? launch_cfg<T, R, 64, 8, 4, 1, 1, true>(a, opt, stream)
