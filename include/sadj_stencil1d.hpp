@@ -70,17 +70,18 @@ template <class T, class F> struct Args {
     long rem_segs;            // remainder waves: index 0 -> segment 0, k > 0 -> segment core_segs + k
 };
 
-template <class T, int N> struct alignas(sizeof(T) * N) Pack { T v[N]; };
-
-// PX consecutive cells from x.  Unguarded: one memory instruction.  Guarded: element-wise,
-// indices clamped into the array (the values of clamped reads are discarded later).
+// PX consecutive cells from x.  Unguarded: one memory instruction, with the streaming
+// (non-temporal) hint: every array of a call is touched exactly once, and keeping these
+// lines out of the way in L2 measured 5-9 points faster.  Guarded: element-wise, indices
+// clamped into the array (the values of clamped reads are discarded later).
 template <class T, int PX, bool GUARD>
 __device__ __forceinline__ void load_cells(const T *g, long x, long n, T (&v)[PX])
 {
     if (!GUARD) {
-        const Pack<T, PX> t = *reinterpret_cast<const Pack<T, PX> *>(g + x);
+        typedef T VT __attribute__((ext_vector_type(PX)));
+        const VT t = __builtin_nontemporal_load(reinterpret_cast<const VT *>(g + x));
 #pragma unroll
-        for (int e = 0; e < PX; ++e) v[e] = t.v[e];
+        for (int e = 0; e < PX; ++e) v[e] = t[e];
     } else {
 #pragma unroll
         for (int e = 0; e < PX; ++e) v[e] = g[x + e < n ? x + e : n - 1];
@@ -90,10 +91,11 @@ template <class T, int PX, bool GUARD>
 __device__ __forceinline__ void store_cells(T *g, long x, const T (&v)[PX], const bool (&ok)[PX])
 {
     if (!GUARD) {
-        Pack<T, PX> t;
+        typedef T VT __attribute__((ext_vector_type(PX)));
+        VT t;
 #pragma unroll
-        for (int e = 0; e < PX; ++e) t.v[e] = v[e];
-        *reinterpret_cast<Pack<T, PX> *>(g + x) = t;
+        for (int e = 0; e < PX; ++e) t[e] = v[e];
+        __builtin_nontemporal_store(t, reinterpret_cast<VT *>(g + x));
     } else {
 #pragma unroll
         for (int e = 0; e < PX; ++e)

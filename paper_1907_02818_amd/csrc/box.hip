@@ -84,7 +84,9 @@ __device__ __forceinline__ void box2d_strip(const BoxArgs &a, int xs, int ys, in
         constexpr bool STEADY = decltype(steady)::value;
         if (!STEADY && y > yi1) return;
         if (STEADY || row_used(y)) {
-            s0[d] = ld_vec<T, PX>(g0 + (size_t)y * nx + xc);
+            // adjoint: c and r_bar through L2 (streaming either measured 2 points slower);
+            // primal: u streamed (3 points faster)
+            s0[d] = ADJ ? ld_vec<T, PX>(g0 + (size_t)y * nx + xc) : ld_vec_stream<T, PX>(g0 + (size_t)y * nx + xc);
             if (ADJ) s1[d] = ld_vec<T, PX>(g1 + (size_t)y * nx + xc);
             if (edge_lane) {                        // only lanes 0 and 63 use the values
                 sh0[d] = g0[(size_t)y * nx + hxc];

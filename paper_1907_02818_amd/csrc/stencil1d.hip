@@ -31,16 +31,17 @@ struct Args1d {
 };
 
 constexpr int kWaves1d = 4;
+constexpr bool kStreamStores = true;
 enum Op1d { OP_ADJ_WAVE, OP_ADJ_WAVE_UPREV, OP_PRI_WAVE, OP_PRI_BURGERS, OP_ADJ_BURGERS, OP_ADJ_BOX, OP_PRI_BOX,
             OP_ADJ_BURGERS_ASSIGN };
 
 // Load PX consecutive cells starting at x.  Unguarded: one vector load.  Guarded:
 // element-wise, indices clamped to [0, n-1].
-template <class T, int PX, bool GUARD>
+template <class T, int PX, bool GUARD, bool STREAM = false>
 __device__ __forceinline__ void load_cells(const T *p, long x, long n, T (&v)[PX])
 {
     if (!GUARD) {
-        const Vec<T, PX> t = ld_vec<T, PX>(p + x);
+        const Vec<T, PX> t = STREAM ? ld_vec_stream<T, PX>(p + x) : ld_vec<T, PX>(p + x);
 #pragma unroll
         for (int e = 0; e < PX; ++e) v[e] = t.v[e];
     } else {
@@ -66,7 +67,8 @@ __device__ __forceinline__ void store_cells(T *p, long x, long n, const T (&v)[P
         Vec<T, PX> t;
 #pragma unroll
         for (int e = 0; e < PX; ++e) t.v[e] = v[e];
-        st_vec<T, PX>(p + x, t);
+        if (kStreamStores) st_vec_stream<T, PX>(p + x, t);
+        else st_vec<T, PX>(p + x, t);
     } else {
 #pragma unroll
         for (int e = 0; e < PX; ++e)
@@ -88,10 +90,10 @@ __device__ __forceinline__ void adj_wave1d_segment(const Args1d &a, long xs, int
     const long x = xs + (long)lane * PX;
     const long hx = lane < 32 ? xs - 1 : xs + W;
     T cv[PX], rv[PX], uv[PX], pv[PX];
-    load_cells<T, PX, GUARD>(cg, x, n, cv);
-    load_cells<T, PX, GUARD>(rg, x, n, rv);
-    load_cells<T, PX, GUARD>(ug, x, n, uv);
-    if (UPREV) load_cells<T, PX, GUARD>(pg, x, n, pv);
+    load_cells<T, PX, GUARD, true>(cg, x, n, cv);
+    load_cells<T, PX, GUARD, true>(rg, x, n, rv);
+    load_cells<T, PX, GUARD, true>(ug, x, n, uv);
+    if (UPREV) load_cells<T, PX, GUARD, true>(pg, x, n, pv);
     const T hc = load_cell<T, GUARD>(cg, hx, n, lane), hr = load_cell<T, GUARD>(rg, hx, n, lane);
     T q[PX], rr[PX];
     bool ok[PX];
@@ -132,9 +134,9 @@ __device__ __forceinline__ void pri_wave1d_segment(const Args1d &a, long xs, int
     const long x = xs + (long)lane * PX;
     const long hx = lane < 32 ? xs - 1 : xs + W;
     T uv[PX], pv[PX], cv[PX];
-    load_cells<T, PX, GUARD>(ug, x, n, uv);
-    load_cells<T, PX, GUARD>(pg, x, n, pv);
-    load_cells<T, PX, GUARD>(cg, x, n, cv);
+    load_cells<T, PX, GUARD, true>(ug, x, n, uv);
+    load_cells<T, PX, GUARD, true>(pg, x, n, pv);
+    load_cells<T, PX, GUARD, true>(cg, x, n, cv);
     const T uh = load_cell<T, GUARD>(ug, hx, n, lane);
     T left, right;
     wave_neighbours<T, PX>(uv, uh, lane, left, right);
@@ -168,9 +170,9 @@ __device__ __forceinline__ void box1d_segment(const Args1d &a, long xs, int lane
     const long x = xs + (long)lane * PX;
     const long hx = lane < 32 ? xs - 1 : xs + W;
     T v0[PX], v1[PX], vo[PX];
-    load_cells<T, PX, GUARD>(g0, x, n, v0);
-    load_cells<T, PX, GUARD>(g1, x, n, v1);
-    if (ADJ) load_cells<T, PX, GUARD>(og, x, n, vo);
+    load_cells<T, PX, GUARD, true>(g0, x, n, v0);
+    load_cells<T, PX, GUARD, true>(g1, x, n, v1);
+    if (ADJ) load_cells<T, PX, GUARD, true>(og, x, n, vo);
     T sh = load_cell<T, GUARD>(g0, hx, n, lane);
     if (ADJ) {
         const T h1 = load_cell<T, GUARD>(g1, hx, n, lane);
@@ -213,7 +215,7 @@ __device__ __forceinline__ void pri_burgers_segment(const Args1d &a, long xs, in
     const long x = xs + (long)lane * PX;
     const long hx = lane < 32 ? xs - 1 : xs + W;
     T uv[PX];
-    load_cells<T, PX, GUARD>(ug, x, n, uv);
+    load_cells<T, PX, GUARD, true>(ug, x, n, uv);
     const T uh = load_cell<T, GUARD>(ug, hx, n, lane);
     T left, right;
     wave_neighbours<T, PX>(uv, uh, lane, left, right);
@@ -250,9 +252,9 @@ __device__ __forceinline__ void adj_burgers_segment(const Args1d &a, long xs, in
     const long x = xs + (long)lane * PX;
     const long hx = lane < 32 ? xs - 1 : xs + W;
     T uv[PX], rv[PX], bv[PX];
-    load_cells<T, PX, GUARD>(ug, x, n, uv);
-    load_cells<T, PX, GUARD>(rg, x, n, rv);
-    if (!ASSIGN) load_cells<T, PX, GUARD>(bg, x, n, bv);
+    load_cells<T, PX, GUARD, true>(ug, x, n, uv);
+    load_cells<T, PX, GUARD, true>(rg, x, n, rv);
+    if (!ASSIGN) load_cells<T, PX, GUARD, true>(bg, x, n, bv);
     const T uh = load_cell<T, GUARD>(ug, hx, n, lane);
     T rh = load_cell<T, GUARD>(rg, hx, n, lane);
     bool ok[PX], in[PX];

@@ -77,7 +77,7 @@ __device__ __forceinline__ void adj2d_strip(const Wave2dArgs &a, int xs, int ys,
         if (STEADY || row_in_I(y)) {
             const T *cp = cg + (size_t)y * nx;
             const T *rp = rg + (size_t)y * nx;
-            sc[d] = ld_vec<T, PX>(cp + xc);
+            sc[d] = ld_vec<T, PX>(cp + xc);           // plain: streaming c or r_bar measured 2-3 points slower
             sr[d] = ld_vec<T, PX>(rp + xc);
             if (edge_lane) { shc[d] = cp[hxc]; shr[d] = rp[hxc]; }   // only lanes 0 and 63 use the value
             if (UPREV) {
@@ -231,7 +231,7 @@ __device__ __forceinline__ void primal2d_strip(const Wave2dArgs &a, int xs, int 
         constexpr bool STEADY = decltype(steady)::value;
         if (!STEADY && y > yi1) return;
         const T *up = ug + (size_t)y * nx;
-        su[d] = ld_vec<T, PX>(up + xc);
+        su[d] = ld_vec_stream<T, PX>(up + xc);
         if (edge_lane) sh[d] = up[hxc];                    // only lanes 0 and 63 use the value
         const int yo = y - 1;
         if (STEADY || yo >= ys) {
