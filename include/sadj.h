@@ -213,6 +213,9 @@ sadj_status sadj_adjoint_burgers1d_steps(sadj_dtype dtype, long n, long last, lo
  *                    per XCD over the whole dispatch, 3 tiles dealt round-robin to XCDs.
  *   "wave3d.band"    numbering of the tiles of a plane: 0 (default) rows of tiles, k > 0
  *                    bands of k tile rows with y fastest inside a band.
+ *   "wave3d.ldspad"  dynamic LDS bytes requested per workgroup of the 3-D marching kernels,
+ *                    which limits how many workgroups share a CU: 0 (default) as much as
+ *                    keeps it at one workgroup per CU, -1 none, n > 0 exactly n (<= 65536).
  *   "wave3d.remainder" treatment of the boundary / remainder regions (Section 3.3.4) by
  *                    sadj_adjoint_wave3d:  0 (default) one dispatch, tiles that touch the
  *                    remainder run guarded statements, core tiles unguarded ones;
@@ -221,6 +224,8 @@ sadj_status sadj_adjoint_burgers1d_steps(sadj_dtype dtype, long n, long last, lo
  *                    dispatches.  1 and 2 serve to measure the strategies; they need
  *                    u_prev_bar == NULL, variant 0-2, nx a multiple of 16 bytes' worth of
  *                    elements and 16-byte aligned arrays, else SADJ_ERR_UNSUPPORTED.
+ *   "stencil1d.functor" 1: sadj_*_burgers1d and the 1-D sadj_*_box run through the generic
+ *                    functor kernel of sadj_stencil1d.hpp instead of their own (default 0).
  *   "wave3d.order"   order in which sadj_adjoint_wave3d adds the terms of one u_bar[j]
  *                    (Section 3.5: a gather can respect an order the user chooses and
  *                    stay parallel).  0 (default): the kernel's own fixed order, fastest.

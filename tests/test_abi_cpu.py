@@ -156,3 +156,14 @@ def test_functor_header_example_is_built_and_exports_its_entry_points():
     sadj.load()                                    # torch's HIP runtime first
     lib = ctypes.CDLL(path)
     assert hasattr(lib, "sine_flux_primal") and hasattr(lib, "sine_flux_adjoint")
+
+
+def test_every_option_the_library_knows_is_documented_in_the_header():
+    """Option names are plain strings; the header's list and the library's must agree."""
+    header = open(HEADER).read()
+    documented = set(re.findall(r'"((?:wave[23]d|stencil1d)\.[a-z0-9]+)"', header))
+    src = open(os.path.join(ROOT, "paper_1907_02818_amd", "csrc", "api.hip")).read()
+    known = set(re.findall(r'"((?:wave[23]d|stencil1d)\.[a-z0-9]+)"', src))
+    assert documented == known
+    for name in sorted(known):
+        assert isinstance(sadj.get_option(name), int)
