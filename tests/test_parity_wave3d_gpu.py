@@ -303,6 +303,19 @@ def test_adjoint_full_size_headline(sadj, dtype):
     assert abs(delta.sum() - want_sum) <= bound, (delta.sum(), want_sum, bound)
 
 
+def test_scatter_order_mode_full_size_is_bit_identical_to_the_sequential_scatter(sadj):
+    """512^3, radius 4, fp64 with "wave3d.order" = 1: all 134 million elements equal the
+    oracle's sequential scatter loop bit for bit (Section 3.5)."""
+    d = inputs.config_inputs("wave3d_r4")
+    want, _, _ = oracle.wave_adjoint(d["c"], d["r_bar"], d["u_bar"], 4)
+    sadj.set_option("wave3d.order", 1)
+    try:
+        got, _ = _run_adjoint(sadj, d, 4, False)
+    finally:
+        sadj.set_option("wave3d.order", 0)
+    assert np.array_equal(got.view(np.int64), want.view(np.int64))
+
+
 def test_adjoint_full_size_r1(sadj):
     d = inputs.config_inputs("wave3d_r1")
     _check_adjoint(sadj, d, 1, np.float64, with_prev=True, what="512^3 R=1")
