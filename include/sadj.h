@@ -200,6 +200,19 @@ sadj_status sadj_primal_burgers1d_steps(sadj_dtype dtype, long n, long nsteps, d
 sadj_status sadj_adjoint_burgers1d_steps(sadj_dtype dtype, long n, long last, long nsteps, double C, double D,
                                          const void *states, void *lam0, void *lam1, void *stream);
 
+/* ---- diagnostic: how a 3-D adjoint call is cut into workgroups ----------------------------
+ * Section 3.3.4 requires the loop nests (here: workgroups) to be disjoint and to cover every
+ * output index exactly once.  This host-only call reports the decomposition the default tile
+ * shape of sadj_adjoint_wave3d would use under the current options, so that a test can check
+ * that property without a GPU: plan[0..5] = tiles along x, tiles along y, z-chunks, planes
+ * per chunk, tile width, tile height (cells); if `tiles` is not NULL it receives, for each of
+ * the first max_blocks workgroup ids, the triple (tile x, tile y, chunk).  `plan` and
+ * `tiles` are HOST pointers.  Nothing is launched.
+ */
+sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, long ny, long nz,
+                                      long *plan /* host, 6 */, int *tiles /* host, 3*max_blocks, nullable */,
+                                      long max_blocks);
+
 /* ---- launch options -------------------------------------------------------------------
  * Process-wide integer options that select among equivalent launch strategies; they
  * never change what is computed, only how the regions are mapped to kernels.

@@ -65,6 +65,7 @@ def load() -> ctypes.CDLL:
     lib.sadj_adjoint_wave2d.argtypes = [I, L, L, P, P, P, P, P]
     lib.sadj_primal_wave3d.argtypes = [I, I, L, L, L, P, P, P, P, P]
     lib.sadj_adjoint_wave3d.argtypes = [I, I, L, L, L, P, P, P, P, P]
+    lib.sadj_describe_wave3d_plan.argtypes = [I, I, L, L, L, ctypes.POINTER(L), ctypes.POINTER(ctypes.c_int), L]
     lib.sadj_adjoint_wave3d_atomic_scatter.argtypes = [I, I, L, L, L, P, P, P, P]
     lib.sadj_adjoint_wave3d_steps.argtypes = [I, I, L, L, L, L, P, P, P, P, P]
     lib.sadj_primal_box.argtypes = [I, I, L, L, L, ctypes.POINTER(D), P, P, P, P]
@@ -76,7 +77,7 @@ def load() -> ctypes.CDLL:
     for name in ("sadj_set_option", "sadj_get_option", "sadj_primal_wave1d", "sadj_adjoint_wave1d",
                  "sadj_primal_wave2d", "sadj_adjoint_wave2d", "sadj_primal_wave3d", "sadj_adjoint_wave3d",
                  "sadj_primal_burgers1d", "sadj_adjoint_burgers1d", "sadj_adjoint_wave3d_steps",
-                 "sadj_primal_box", "sadj_adjoint_box", "sadj_adjoint_wave3d_atomic_scatter",
+                 "sadj_primal_box", "sadj_adjoint_box", "sadj_adjoint_wave3d_atomic_scatter", "sadj_describe_wave3d_plan",
                  "sadj_primal_burgers1d_steps", "sadj_adjoint_burgers1d_steps"):
         getattr(lib, name).restype = I
     _lib = lib
@@ -165,6 +166,20 @@ def sadj_primal_wave3d(radius: int, u, u_prev, c, r) -> None:
 def sadj_adjoint_wave3d(radius: int, c, r_bar, u_bar, u_prev_bar=None) -> None:
     code, (nz, ny, nx), p, s = _marshal([c, r_bar, u_bar, u_prev_bar], 3, optional=(3,))
     _check(load().sadj_adjoint_wave3d(code, int(radius), nx, ny, nz, *p, s))
+
+
+def sadj_describe_wave3d_plan(dtype_code: int, radius: int, nx: int, ny: int, nz: int, with_tiles: bool = True):
+    """Host-only: (plan dict, list of (tile x, tile y, chunk) per workgroup id)."""
+    plan = (ctypes.c_long * 6)()
+    _check(load().sadj_describe_wave3d_plan(dtype_code, int(radius), nx, ny, nz, plan, None, 0))
+    ntx, nty, ntz, zchunk, tw, th = (int(v) for v in plan)
+    info = dict(ntx=ntx, nty=nty, ntz=ntz, zchunk=zchunk, tile_w=tw, tile_h=th)
+    if not with_tiles:
+        return info, None
+    total = ntx * nty * ntz
+    buf = (ctypes.c_int * (3 * total))()
+    _check(load().sadj_describe_wave3d_plan(dtype_code, int(radius), nx, ny, nz, plan, buf, total))
+    return info, [(buf[3 * b], buf[3 * b + 1], buf[3 * b + 2]) for b in range(total)]
 
 
 def sadj_adjoint_wave3d_atomic_scatter(radius: int, c, r_bar, u_bar) -> None:

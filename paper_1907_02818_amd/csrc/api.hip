@@ -253,6 +253,21 @@ sadj_status sadj_adjoint_wave3d(sadj_dtype dtype, int radius, long nx, long ny, 
     return adjoint_wave(3, dtype, radius, nx, ny, nz, c, r_bar, u_bar, u_prev_bar, stream);
 }
 
+// Diagnostic: the decomposition sadj_adjoint_wave3d would use (no launch, no device access
+// beyond reading the CU count).
+sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, long ny, long nz, long *plan,
+                                      int *tiles, long max_blocks)
+{
+    if (radius < 1 || radius > 4 || !dtype_ok(dtype)) return SADJ_ERR_UNSUPPORTED;
+    if (!plan) return SADJ_ERR_NULL;
+    sadj_status s = check_extents(radius, nx, ny, nz, 3);
+    if (s != SADJ_OK) return s;
+    sadj::describe_march_plan(dtype == SADJ_F64, radius, (int)nx, (int)ny, (int)nz, current_options(), plan, tiles,
+                              max_blocks);
+    (void)hipGetLastError();       // a machine without a GPU leaves an error code behind; it is not ours to keep
+    return SADJ_OK;
+}
+
 // Contrast baseline, not the method: scatter with atomic updates.
 sadj_status sadj_adjoint_wave3d_atomic_scatter(sadj_dtype dtype, int radius, long nx, long ny, long nz,
                                                const void *c, const void *r_bar, void *u_bar, void *stream)

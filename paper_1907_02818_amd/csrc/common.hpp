@@ -31,7 +31,7 @@ template <> __host__ __device__ constexpr double star_w<4>(int k)
 // has its own L2.  Map the hardware id to a logical id such that every XCD works
 // on one contiguous range of logical ids (so that neighbouring tiles, which share
 // halo cells, meet in the same L2).  Bijective for any total.
-__device__ __forceinline__ int xcd_contiguous_id(int hw_id, int total)
+__host__ __device__ __forceinline__ int xcd_contiguous_id(int hw_id, int total)
 {
     constexpr int NXCD = 8;
     const int xcd = hw_id % NXCD;

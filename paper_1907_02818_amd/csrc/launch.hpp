@@ -52,6 +52,12 @@ hipError_t launch_burgers1d_functor(int adjoint, int is_f64, long n, double C, d
 hipError_t launch_weighted3_functor(int adjoint, int is_f64, long n, const double *w, const void *u,
                                     const void *c, const void *r_bar, void *out, hipStream_t stream);
 
+// Host-side view of how the default 3-D adjoint shape decomposes a grid (for tests): fills
+// plan[0..5] = tiles in x, tiles in y, z-chunks, planes per chunk, tile width, tile height,
+// and, if `tiles` is not null, for every workgroup id its (tile x, tile y, chunk) triple.
+void describe_march_plan(int is_f64, int radius, int nx, int ny, int nz, const LaunchOptions &opt,
+                         long *plan, int *tiles, long max_blocks);
+
 // Dense 3^d box stencils; w = gather weights (mirrored by the caller for the adjoint).
 hipError_t launch_box1d(int adjoint, int is_f64, long n, const double *w, const void *in0, const void *in1,
                         void *out, hipStream_t stream);

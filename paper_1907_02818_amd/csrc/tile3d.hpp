@@ -60,7 +60,7 @@ struct March3dArgs {
 // Tiles of a chunk are numbered x fastest (band = 0) or in bands of `band` tile rows with
 // y fastest inside a band, which makes the 32 tiles an XCD holds a compact patch.
 template <class Args>
-__device__ __forceinline__ void block_to_tile(const Args &a, int hw_id, int &tix, int &tiy, int &tiz)
+__host__ __device__ __forceinline__ void block_to_tile(const Args &a, int hw_id, int &tix, int &tiy, int &tiz)
 {
     int L;
     if (a.xcd_map == 3) {
@@ -70,7 +70,8 @@ __device__ __forceinline__ void block_to_tile(const Args &a, int hw_id, int &tix
     } else {
         const int round = hw_id / a.round_blocks;
         const int first = round * a.round_blocks;
-        const int m = min(a.round_blocks, a.total_blocks - first);
+        const int left = a.total_blocks - first;
+        const int m = a.round_blocks < left ? a.round_blocks : left;
         L = first + xcd_contiguous_id(hw_id - first, m);
     }
     const int tiles = a.ntx * a.nty;
@@ -79,7 +80,8 @@ __device__ __forceinline__ void block_to_tile(const Args &a, int hw_id, int &tix
     if (a.band > 0) {
         const int b = t / (a.ntx * a.band);
         const int r = t - b * a.ntx * a.band;
-        const int h = min(a.band, a.nty - b * a.band);
+        const int rows_left = a.nty - b * a.band;
+        const int h = a.band < rows_left ? a.band : rows_left;
         tix = r / h;
         tiy = b * a.band + (r - tix * h);
     } else {

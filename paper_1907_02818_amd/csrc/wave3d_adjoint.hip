@@ -354,6 +354,23 @@ static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipSt
     }
 }
 
+void describe_march_plan(int is_f64, int radius, int nx, int ny, int nz, const LaunchOptions &opt,
+                         long *plan, int *tiles, long max_blocks)
+{
+    // the default shapes: 32 x 16 threads, two rows per thread, 16 bytes per lane
+    const int TX = is_f64 ? 64 : 128, TY = 32;
+    March3dArgs a{};
+    a.nx = nx; a.ny = ny; a.nz = nz;
+    plan_march(a, TX, TY, radius, opt);
+    plan[0] = a.ntx; plan[1] = a.nty; plan[2] = a.ntz; plan[3] = a.zchunk; plan[4] = TX; plan[5] = TY;
+    if (!tiles) return;
+    for (int b = 0; b < a.total_blocks && b < max_blocks; ++b) {
+        int tix, tiy, tiz;
+        block_to_tile(a, b, tix, tiy, tiz);
+        tiles[3 * b] = tix; tiles[3 * b + 1] = tiy; tiles[3 * b + 2] = tiz;
+    }
+}
+
 hipError_t launch_adjoint_wave3d(int is_f64, int radius, int nx, int ny, int nz, const void *c,
                                  const void *r_bar, void *u_bar, void *u_prev_bar, int u_prev_bar_assign,
                                  const LaunchOptions &opt, hipStream_t stream)

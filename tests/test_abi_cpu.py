@@ -167,3 +167,43 @@ def test_every_option_the_library_knows_is_documented_in_the_header():
     assert documented == known
     for name in sorted(known):
         assert isinstance(sadj.get_option(name), int)
+
+
+@pytest.mark.parametrize("xcdmap,band,zchunk", [(0, 0, 0), (1, 0, 7), (2, 0, 0), (3, 0, 16), (1, 3, 0), (2, 8, 5), (1, 2, 33)])
+@pytest.mark.parametrize("dtype_code,radius,shape", [(1, 4, (512, 512, 512)), (1, 4, (300, 500, 700)), (0, 4, (512, 512, 512)),
+                                                     (1, 1, (1000, 1000, 1000)), (1, 2, (9, 9, 9)), (0, 3, (100, 33, 65)),
+                                                     (1, 4, (768, 768, 768)), (1, 1, (3, 3, 3))])
+def test_workgroups_tile_the_grid_exactly_once(dtype_code, radius, shape, xcdmap, band, zchunk):
+    """Disjoint cover (Section 3.3.4): under every mapping option the workgroup ids map
+    one-to-one onto (tile, z-chunk) pairs, and the tiles and chunks cover the grid."""
+    nz, ny, nx = shape
+    try:
+        sadj.set_option("wave3d.xcdmap", xcdmap)
+        sadj.set_option("wave3d.band", band)
+        sadj.set_option("wave3d.zchunk", zchunk)
+        info, tiles = sadj.sadj_describe_wave3d_plan(dtype_code, radius, nx, ny, nz)
+    finally:
+        sadj.set_option("wave3d.xcdmap", 0)
+        sadj.set_option("wave3d.band", 0)
+        sadj.set_option("wave3d.zchunk", 0)
+    assert info["ntx"] * info["tile_w"] >= nx > (info["ntx"] - 1) * info["tile_w"]
+    assert info["nty"] * info["tile_h"] >= ny > (info["nty"] - 1) * info["tile_h"]
+    assert info["ntz"] * info["zchunk"] >= nz > (info["ntz"] - 1) * info["zchunk"]
+    want = {(x, y, z) for z in range(info["ntz"]) for y in range(info["nty"]) for x in range(info["ntx"])}
+    assert len(tiles) == len(want)
+    assert set(tiles) == want
+
+
+def test_gather_kernels_use_no_atomics():
+    """The method's point (Sections 1, 3.2): every u_bar element has exactly one writer, so
+    no kernel of the method may contain an atomic; only the contrast kernel does."""
+    import glob
+    offenders = []
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_1907_02818_amd", "csrc", "*.h*")) +
+                       [os.path.join(ROOT, "include", "sadj_stencil1d.hpp")]):
+        code = re.sub(r"//.*|/\*.*?\*/", "", open(path).read(), flags=re.S)
+        if re.search(r"atomic(?!<long>)", code, flags=re.I) and not path.endswith("wave3d_scatter_atomic.hip"):
+            if os.path.basename(path) == "api.hip" and not re.search(r"atomicAdd|unsafeAtomic|__atomic|atomic_fetch", code):
+                continue                               # std::atomic<long> option variables on the host
+            offenders.append(os.path.basename(path))
+    assert offenders == []
