@@ -92,12 +92,13 @@ __host__ __device__ __forceinline__ void block_to_tile(const Args &a, int hw_id,
 
 static inline int cdiv_i(int a, int b) { return (a + b - 1) / b; }
 
-// Choose the number of z-chunks.  Each CU holds one workgroup of these kernels at a time,
-// so the dispatch runs in rounds of `ncu` workgroups, each marching zchunk + 2R planes
+// Choose the number of z-chunks.  Each CU holds wg_per_cu workgroups of these kernels at a
+// time (one, except where a kernel is built to overlap two), so the dispatch runs in rounds
+// of `ncu` = CUs x wg_per_cu workgroups, each marching zchunk + 2R planes
 // (the 2R planes beyond a chunk are read by two chunks).  Minimise rounds * planes per
 // workgroup; ties go to fewer chunks.  With tiles*chunks == ncu this is the single
 // resident wave in which neighbouring tiles move through z in lockstep.
-static inline void plan_march(March3dArgs &a, int TX, int TY, int R, const LaunchOptions &opt)
+static inline void plan_march(March3dArgs &a, int TX, int TY, int R, const LaunchOptions &opt, int wg_per_cu = 1)
 {
     a.ntx = cdiv_i(a.nx, TX);
     a.nty = cdiv_i(a.ny, TY);
@@ -107,7 +108,10 @@ static inline void plan_march(March3dArgs &a, int TX, int TY, int R, const Launc
         ncu = v;
     a.xcd_map = opt.xcd_map > 0 ? (int)opt.xcd_map : 1;
     a.band = (int)opt.band;
+    // ids are made XCD-contiguous per group of one workgroup per CU, also where two groups
+    // are resident together (measured better than one contiguous range per XCD over both)
     a.round_blocks = ncu >= 8 ? ncu - ncu % 8 : 8;
+    ncu *= wg_per_cu;                                  // workgroups resident at a time
     int zchunk = (int)opt.zchunk;
     if (zchunk <= 0) {
         const long tiles = (long)a.ntx * a.nty;

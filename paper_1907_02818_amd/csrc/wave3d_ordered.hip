@@ -20,9 +20,11 @@
 //
 // Mapping.  Same z-march as the default kernel (a workgroup owns an x-y tile, 2R+1 running
 // sums per owned cell in registers, ascending source planes), with three differences:
-// c and r_bar are staged in LDS separately (a term is (c*w)*r_bar, not w*(c*r_bar)); a
-// running sum is initialised with u_bar when it is created, R planes before its own plane
-// arrives, instead of adding u_bar at the end; and contraction of multiply-add is off.
+// LDS holds the finished terms (c*w_k)*r_bar of every staged cell, one plane per |k| (a term
+// is (c*w)*r_bar, not w*(c*r_bar), so the product c*r_bar cannot be shared between the k);
+// a running sum is initialised with u_bar when it is created, R planes before its own
+// plane arrives, instead of adding u_bar at the end; and contraction of multiply-add is
+// off.
 #include "launch.hpp"
 #include "tile3d.hpp"
 
@@ -126,13 +128,17 @@ __device__ __forceinline__ void adj3d_march_ordered(const March3dArgs &a, int ti
         }
     };
 
+    // LDS holds, per |k| = 1..R, the plane of finished terms P_k = (c w_k) r_bar of the
+    // staged cells: a term is formed once per source cell and read by the (up to) four
+    // in-plane neighbours at distance k.  One buffer, two barriers per plane (NBUF = 2 would
+    // save a barrier but the LDS is better spent on a second workgroup per CU).
+    constexpr int NBUF = 1;
     int buf = 0;
     issue(zi0);
     for (int zi = zi0; zi <= zi1; ++zi) {
         const bool zin = plane_in_I(zi);
         const int zo = zi - R, zn = zi + R;
-        T *lc = lds + buf * (2 * G::PLANE);
-        T *lr = lc + G::PLANE;
+        T *lp = lds + (NBUF == 2 ? buf : 0) * (R * G::PLANE);
         // the running sum of output plane zi+R starts from the incoming u_bar
         if (zn >= zs && zn < ze) {
 #pragma unroll
@@ -142,13 +148,26 @@ __device__ __forceinline__ void adj3d_march_ordered(const March3dArgs &a, int ti
 #pragma unroll
         for (int p = 0; p < PY; ++p) { cc[p] = sc[p]; rv[p] = sr[p]; }
         if (zin) {
+            if (NBUF == 1) __syncthreads();         // all reads of the previous plane are done
 #pragma unroll
             for (int p = 0; p < PY; ++p) {
-                lc[(R + ty * PY + p) * LX + R + tx] = cc[p];
-                lr[(R + ty * PY + p) * LX + R + tx] = rv[p];
+                const bool own = xin(0) && yin(p, 0);
+                const int cell = (R + ty * PY + p) * LX + R + tx;
+#pragma unroll
+                for (int k = 1; k <= R; ++k) {
+                    const T t = (cc[p] * T(star_w<R>(k))) * rv[p];
+                    lp[(k - 1) * G::PLANE + cell] = t;
+                    // this plane lies above the output planes zi-R .. zi-1 (for them it is the
+                    // source "z+k") and below zi+1 .. zi+R (source "z-k"): one term each
+                    acc[p][R - k] = own ? acc[p][R - k] + t : acc[p][R - k];
+                    acc[p][R + k] = own ? acc[p][R + k] + t : acc[p][R + k];
+                }
             }
 #pragma unroll
-            for (int s = 0; s < HS; ++s) { lc[hlds[s]] = shc[s]; lr[hlds[s]] = shr[s]; }
+            for (int s = 0; s < HS; ++s) {
+#pragma unroll
+                for (int k = 1; k <= R; ++k) lp[(k - 1) * G::PLANE + hlds[s]] = (shc[s] * T(star_w<R>(k))) * shr[s];
+            }
             if (UPREV && zi >= zs && zi < ze) {
                 T *pp = upg + (size_t)zi * plane;
 #pragma unroll
@@ -162,41 +181,30 @@ __device__ __forceinline__ void adj3d_march_ordered(const March3dArgs &a, int ti
 #pragma unroll
             for (int p = 0; p < PY; ++p) {
                 const int lrow = R + ty * PY + p, lcol = R + tx;
-                const bool own = xin(0) && yin(p, 0);
-                // this plane lies above the output planes zi-R .. zi-1: for them it is a
-                // source "z+k"; and below zi+1 .. zi+R: a source "z-k".  One term each.
-                T tz[R + 1];
-#pragma unroll
-                for (int k = 1; k <= R; ++k) tz[k] = (cc[p] * T(star_w<R>(k))) * rv[p];
-#pragma unroll
-                for (int k = 1; k <= R; ++k) {
-                    acc[p][R - k] = own ? acc[p][R - k] + tz[k] : acc[p][R - k];
-                    acc[p][R + k] = own ? acc[p][R + k] + tz[k] : acc[p][R + k];
-                }
                 // in-plane terms of output plane zi, in ascending order of the source cell
                 T s = acc[p][R];
 #pragma unroll
                 for (int k = R; k >= 1; --k) {      // (x, y-k)
-                    const T t = (lc[(lrow - k) * LX + lcol] * T(star_w<R>(k))) * lr[(lrow - k) * LX + lcol];
+                    const T t = lp[(k - 1) * G::PLANE + (lrow - k) * LX + lcol];
                     s = (xin(0) && yin(p, -k)) ? s + t : s;
                 }
 #pragma unroll
                 for (int k = R; k >= 1; --k) {      // (x-k, y)
-                    const T t = (lc[lrow * LX + lcol - k] * T(star_w<R>(k))) * lr[lrow * LX + lcol - k];
+                    const T t = lp[(k - 1) * G::PLANE + lrow * LX + lcol - k];
                     s = (xin(-k) && yin(p, 0)) ? s + t : s;
                 }
                 {
                     const T t = (T(2) + cc[p] * T(3) * T(star_w<R>(0))) * rv[p];
-                    s = own ? s + t : s;
+                    s = (xin(0) && yin(p, 0)) ? s + t : s;
                 }
 #pragma unroll
                 for (int k = 1; k <= R; ++k) {      // (x+k, y)
-                    const T t = (lc[lrow * LX + lcol + k] * T(star_w<R>(k))) * lr[lrow * LX + lcol + k];
+                    const T t = lp[(k - 1) * G::PLANE + lrow * LX + lcol + k];
                     s = (xin(k) && yin(p, 0)) ? s + t : s;
                 }
 #pragma unroll
                 for (int k = 1; k <= R; ++k) {      // (x, y+k)
-                    const T t = (lc[(lrow + k) * LX + lcol] * T(star_w<R>(k))) * lr[(lrow + k) * LX + lcol];
+                    const T t = lp[(k - 1) * G::PLANE + (lrow + k) * LX + lcol];
                     s = (xin(0) && yin(p, k)) ? s + t : s;
                 }
                 acc[p][R] = s;
@@ -222,7 +230,8 @@ template <class T, int R, int BX, int BY, int PY, bool UPREV>
 __global__ __launch_bounds__(BX *BY) void adj_wave3d_ordered_kernel(March3dArgs a)
 {
     using G = Tile3d<T, R, BX, BY, PY, 1>;
-    __shared__ T lds[4 * G::PLANE];                 // two buffers of (c plane, r_bar plane)
+    constexpr int NBUF = 1;
+    __shared__ T lds[NBUF * R * G::PLANE];          // per |k| a plane of finished terms, see the march
     int tix, tiy, tiz;
     block_to_tile(a, blockIdx.x, tix, tiy, tiz);
     const int x0 = tix * G::TX, y0 = tiy * G::TY;
@@ -231,23 +240,25 @@ __global__ __launch_bounds__(BX *BY) void adj_wave3d_ordered_kernel(March3dArgs 
     else      adj3d_march_ordered<T, R, BX, BY, PY, true, UPREV>(a, tix, tiy, tiz, lds);
 }
 
-template <class T, int R, int PY>
-static hipError_t launch_ordered_P(March3dArgs a, const LaunchOptions &opt, hipStream_t stream)
-{
-    constexpr int BX = 64, BY = 8;
-    using G = Tile3d<T, R, BX, BY, PY, 1>;
-    plan_march(a, G::TX, G::TY, R, opt);
-    dim3 grid(a.total_blocks), block(G::NT);
-    if (a.out1) hipLaunchKernelGGL((adj_wave3d_ordered_kernel<T, R, BX, BY, PY, true>), grid, block, 0, stream, a);
-    else        hipLaunchKernelGGL((adj_wave3d_ordered_kernel<T, R, BX, BY, PY, false>), grid, block, 0, stream, a);
-    return hipGetLastError();
-}
-
+// 64 x 16 tile, 256 threads, one LDS buffer: two workgroups share a CU, so that one computes
+// while the other waits for memory.  Measured at 512^3 fp64 against one workgroup of 512
+// threads on a 64 x 32 tile with two buffers: radius 4 1.22 vs 1.41 ms, radius 1 0.74 vs 0.82 ms.
 template <class T, int R>
-static hipError_t launch_ordered_T(const March3dArgs &a, const LaunchOptions &opt, hipStream_t stream)
+static hipError_t launch_ordered_T(March3dArgs a, const LaunchOptions &opt, hipStream_t stream)
 {
-    // 64 x 32 tile, 512 threads; a 64 x 16 tile (two workgroups per CU) measured 9-15 % slower
-    return launch_ordered_P<T, R, 4>(a, opt, stream);
+    constexpr int BX = 64, BY = 4, PY = 4;
+    using G = Tile3d<T, R, BX, BY, PY, 1>;
+    static_assert(sizeof(T) * R * G::PLANE <= 80 * 1024, "two workgroups must fit into the LDS of a CU");
+    plan_march(a, G::TX, G::TY, R, opt, 2);
+    dim3 grid(a.total_blocks), block(G::NT);
+    // exactly two per CU: request LDS up to just over a third of a CU's 160 KB
+    constexpr size_t static_lds = sizeof(T) * R * G::PLANE, third = 54 * 1024;
+    unsigned pad = static_lds < third ? (unsigned)(third - static_lds) : 0;
+    if (opt.lds_pad > 0) pad = (unsigned)opt.lds_pad;
+    if (opt.lds_pad < 0) pad = 0;
+    if (a.out1) hipLaunchKernelGGL((adj_wave3d_ordered_kernel<T, R, BX, BY, PY, true>), grid, block, pad, stream, a);
+    else        hipLaunchKernelGGL((adj_wave3d_ordered_kernel<T, R, BX, BY, PY, false>), grid, block, pad, stream, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_adjoint_wave3d_ordered(int is_f64, int radius, int nx, int ny, int nz, const void *c,
