@@ -179,6 +179,38 @@ def test_tile_mappings_give_identical_results(sadj, xcdmap, band):
         sadj.set_option("wave3d.zchunk", 0)
 
 
+@pytest.mark.parametrize("case", range(24))
+def test_adjoint_and_primal_on_drawn_shapes_and_options(sadj, case):
+    """Shapes, radius, dtype and scheduling options drawn from a seeded generator: ragged
+    tiles in both directions, z-chunks that do not divide nz, every id mapping."""
+    rng = np.random.default_rng(1000 + case)
+    radius = int(rng.integers(1, 5))
+    dtype = [np.float64, np.float32][int(rng.integers(0, 2))]
+    lo = 2 * radius + 1
+    shape = (int(rng.integers(lo, 90)), int(rng.integers(lo, 120)), int(rng.integers(lo, 300)))
+    opts = {"wave3d.zchunk": int(rng.choice([0, 0, 5, 13, 40])), "wave3d.xcdmap": int(rng.integers(0, 4)),
+            "wave3d.band": int(rng.choice([0, 0, 2, 5])), "wave3d.ldspad": int(rng.choice([0, -1]))}
+    d = inputs.wave_inputs(shape, 0.01, 0.1, seed=case, dtype=dtype, c_mode="iid")
+    try:
+        for k, v in opts.items():
+            sadj.set_option(k, v)
+        what = "case %d R=%d %s %s %s" % (case, radius, shape, np.dtype(dtype).name, opts)
+        _check_adjoint(sadj, d, radius, dtype, with_prev=bool(rng.integers(0, 2)), what=what)
+        import torch
+        r0 = inputs.uniform(case, "aux", shape, -1, 1).astype(dtype)
+        r = to_gpu(r0)
+        sadj.sadj_primal_wave3d(radius, to_gpu(d["u"]), to_gpu(d["u_prev"]), to_gpu(d["c"]), r)
+        torch.cuda.synchronize()
+        got = to_host(r)
+        want = oracle.wave_primal(d["u"], d["u_prev"], d["c"], radius, r_init=r0)
+        m = interior_mask(shape, radius)
+        assert np.array_equal(got[~m], r0[~m])
+        assert_close(got[m], want[m], _primal_scale(d, radius)[m], dtype, what + " primal")
+    finally:
+        for k in opts:
+            sadj.set_option(k, 0)
+
+
 def test_remainder_strategy_declines_what_it_does_not_cover(sadj):
     import paper_1907_02818_amd as lib
     d = inputs.wave_inputs((12, 20, 64), 0.01, 0.1, seed=1)
