@@ -114,3 +114,19 @@ def test_box_full_size_3d(sadj):
     torch.cuda.synchronize()
     want, scale = oracle.box_adjoint(w, c, rb, ub, want_scale=True)
     assert_close(to_host(ug), want, scale + np.abs(ub), np.float64, "box 3-D 256x256x512")
+
+
+@pytest.mark.parametrize("case", range(16))
+def test_box_on_drawn_shapes(sadj, case):
+    """Dimension, shape, dtype and z-chunk drawn from a seeded generator."""
+    import torch
+    rng = np.random.default_rng(500 + case)
+    ndim = int(rng.integers(2, 4))
+    dtype = [np.float64, np.float32][int(rng.integers(0, 2))]
+    shape = tuple(int(rng.integers(3, hi)) for hi in ((60, 400) if ndim == 2 else (40, 90, 260)))
+    zchunk = int(rng.choice([0, 0, 6, 17]))
+    sadj.set_option("wave3d.zchunk", zchunk)
+    try:
+        _box_case(sadj, shape, dtype, ndim, torch)
+    finally:
+        sadj.set_option("wave3d.zchunk", 0)

@@ -271,3 +271,37 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed(sadj):
         for got, ref in zip(static, want):
             assert np.array_equal(to_host(got), ref), "replay %d" % replay
         assert float(other) == 1000.0
+
+
+@pytest.mark.parametrize("case", range(16))
+def test_wave2d_on_drawn_shapes_and_options(sadj, case):
+    rng = np.random.default_rng(700 + case)
+    dtype = [np.float64, np.float32][int(rng.integers(0, 2))]
+    shape = (int(rng.integers(3, 300)), int(rng.integers(3, 1200)))
+    opts = {"wave2d.variant": int(rng.integers(0, 4)), "wave2d.ychunk": int(rng.choice([0, 0, 4, 9, 50]))}
+    d = inputs.wave_inputs(shape, 0.01, 0.2, seed=case, dtype=dtype, c_mode="iid")
+    m = interior_mask(shape, 1)
+    try:
+        for k, v in opts.items():
+            sadj.set_option(k, v)
+        ub, upb = to_gpu(d["u_bar"]), to_gpu(d["u_prev_bar"])
+        sadj.sadj_adjoint_wave2d(to_gpu(np.where(m, d["c"], np.nan).astype(dtype)),
+                                 to_gpu(np.where(m, d["r_bar"], np.nan).astype(dtype)), ub, upb)
+        _sync()
+        want_u, want_p, scale = oracle.wave_adjoint(d["c"], d["r_bar"], d["u_bar"], 1, u_prev_bar=d["u_prev_bar"],
+                                                    want_scale=True)
+        what = "case %d %s %s %s" % (case, shape, np.dtype(dtype).name, opts)
+        assert_close(to_host(ub), want_u, scale + np.abs(d["u_bar"].astype(np.float64)), dtype, what)
+        assert_close(to_host(upb), want_p, np.abs(d["u_prev_bar"].astype(np.float64)) + np.abs(d["r_bar"].astype(np.float64)),
+                     dtype, what + " u_prev_bar")
+        r0 = inputs.uniform(case, "aux", shape, -1, 1).astype(dtype)
+        r = to_gpu(r0)
+        sadj.sadj_primal_wave2d(to_gpu(d["u"]), to_gpu(d["u_prev"]), to_gpu(d["c"]), r)
+        _sync()
+        got = to_host(r)
+        want = oracle.wave_primal(d["u"], d["u_prev"], d["c"], 1, r_init=r0)
+        assert np.array_equal(got[~m], r0[~m])
+        assert_close(got[m], want[m], (np.abs(want) + 8.0)[m], dtype, what + " primal")
+    finally:
+        for k in opts:
+            sadj.set_option(k, 0)
