@@ -222,6 +222,12 @@ def main():
             wave_adjoint_bytes(shape, 1, 8), "f64")
         add("box3d_f64_primal", lambda: sadj.sadj_primal_box(wbox, ub, c, r), N,
             8 * N + 16 * interior_points(shape, 1), "f64")
+        # general star of radius 4 with an asymmetric weight table (25 free weights)
+        wstar = [0.3] + [0.05 * (i % 7) - 0.12 for i in range(24)]
+        add("star3d_r4_f64_adjoint", lambda: sadj.sadj_adjoint_star3d(4, wstar, c, rb, ub), N,
+            wave_adjoint_bytes(shape, 4, 8), "f64")
+        add("star3d_r4_f64_primal", lambda: sadj.sadj_primal_star3d(4, wstar, ub, c, r), N,
+            8 * N + 16 * interior_points(shape, 4), "f64")
         del upb, r
         # 2-D 8192^2
         s2 = (8192, 8192)

@@ -175,6 +175,25 @@ sadj_status sadj_adjoint_burgers1d(sadj_dtype dtype, long n, double C, double D,
                                    const void *u, const void *r_bar, void *u_bar,
                                    void *stream);
 
+/* ---- 3-D star stencils of radius 1..4 with arbitrary weights --------------------------------
+ * The general linear star: one free weight per read offset, e.g. upwind-biased differences.
+ *   primal   r[i]      = c[i] * ( w_0 u[i] + sum_{d=x,y,z} sum_{o=-R..R, o!=0} w_{d,o} u[i + o e_d] )  for i in I
+ *   adjoint  u_bar[j] += w_0 q[j] + sum_d sum_o w_{d,o} q[j - o e_d],  q = c*r_bar on I, 0 elsewhere, for all j
+ * (Sections 3.2-3.3: the term of read offset o is shifted by -o, so an asymmetric table
+ * appears mirrored in the adjoint, as in the worked 1-D example.)  `weights` is a HOST array
+ * of 1 + 6R doubles read during the call: the centre weight, then for the axes x, y, z in
+ * turn the 2R weights of the offsets -R, .., -1, +1, .., +R; they are converted to dtype.
+ * Same conventions and errors as the wave calls (primal assigns r on I, adjoint accumulates
+ * into u_bar, c and r_bar outside I never used).  With the symmetric Laplacian weights the
+ * adjoint equals sadj_adjoint_wave3d without its 2 r_bar term.
+ */
+sadj_status sadj_primal_star3d(sadj_dtype dtype, int radius, long nx, long ny, long nz,
+                               const double *weights /* host, 1 + 6*radius */,
+                               const void *u, const void *c, void *r, void *stream);
+sadj_status sadj_adjoint_star3d(sadj_dtype dtype, int radius, long nx, long ny, long nz,
+                                const double *weights /* host, 1 + 6*radius */,
+                                const void *c, const void *r_bar, void *u_bar, void *stream);
+
 /* ---- time loop of Burgers steps: store every state, then sweep backwards -------------------
  * The Burgers stencil is nonlinear, so the reverse sweep of step u^t -> u^{t+1} needs the
  * primal state u^t (paper Section 3.1: a nonlinear statement's adjoint reads primal values;

@@ -165,6 +165,31 @@ def box_adjoint(w, c, r_bar, u_bar, want_scale: bool = False):
     return ub, scale
 
 
+def star3d_primal(w, u, c, radius: int, r_init=None) -> np.ndarray:
+    """w: 1 + 6*radius values: centre, then per axis x, y, z the offsets -R..-1, +1..+R."""
+    u, c = _f64(u), _f64(c)
+    w = _f64(np.asarray(w, dtype=np.float64).ravel())
+    assert u.ndim == 3 and w.size == 1 + 6 * radius
+    nz, ny, nx = u.shape
+    r = np.zeros_like(u) if r_init is None else _f64(r_init).copy()
+    _check(_load().oracle_star3d_primal(_I(radius), _L(nx), _L(ny), _L(nz), _ptr(w), _ptr(u), _ptr(c), _ptr(r)),
+           "star3d_primal")
+    return r
+
+
+def star3d_adjoint(w, c, r_bar, u_bar, radius: int, want_scale: bool = False):
+    """Returns (u_bar_out, scale or None)."""
+    c, r_bar = _f64(c), _f64(r_bar)
+    w = _f64(np.asarray(w, dtype=np.float64).ravel())
+    assert c.ndim == 3 and w.size == 1 + 6 * radius
+    nz, ny, nx = c.shape
+    ub = _f64(u_bar).copy()
+    scale = np.zeros_like(ub) if want_scale else None
+    _check(_load().oracle_star3d_adjoint(_I(radius), _L(nx), _L(ny), _L(nz), _ptr(w), _ptr(c), _ptr(r_bar), _ptr(ub),
+                                         _ptr(scale)), "star3d_adjoint")
+    return ub, scale
+
+
 def burgers_primal(u, C: float, D: float, r_init=None) -> np.ndarray:
     u = _f64(u)
     r = np.zeros_like(u) if r_init is None else _f64(r_init).copy()

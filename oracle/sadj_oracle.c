@@ -342,6 +342,59 @@ int oracle_box_adjoint(int ndim, long nx, long ny, long nz, const double *w,
     return ORACLE_OK;
 }
 
+/* ---------------------------- 3-D star stencil of radius R with arbitrary weights */
+/* Primal r[i] = c[i]*(w_0 u[i] + sum_{d} sum_{o=-R..R, o!=0} w_{d,o} u[i + o e_d]) for i in I
+ * (the general linear star; Sections 3.2-3.3 treat exactly this: one derivative expression
+ * per read offset).  w: 1 + 6R values: centre, then per axis x, y, z the offsets
+ * -R..-1, +1..+R.  Scatter adjoint: u_bar[i + o e_d] += w_{d,o} c[i] r_bar[i]. */
+static double star_w_at(const double *w, int R, int d, int o)
+{
+    return w[1 + d * 2 * R + (o < 0 ? o + R : o + R - 1)];
+}
+
+int oracle_star3d_primal(int R, long nx, long ny, long nz, const double *w,
+                         const double *u, const double *c, double *r)
+{
+    grid_t g;
+    if (!w || !u || !c || !r || grid_init(&g, 3, R, nx, ny, nz)) return ORACLE_BAD_ARG;
+    for (long z = g.lo[2]; z <= g.hi[2]; ++z)
+    for (long y = g.lo[1]; y <= g.hi[1]; ++y)
+    for (long x = g.lo[0]; x <= g.hi[0]; ++x) {
+        long i = x + nx * (y + ny * z);
+        double s = w[0] * u[i];
+        for (int d = 0; d < 3; ++d)
+            for (int o = -R; o <= R; ++o)
+                if (o != 0) s += star_w_at(w, R, d, o) * u[i + o * g.stride[d]];
+        r[i] = c[i] * s;
+    }
+    return ORACLE_OK;
+}
+
+int oracle_star3d_adjoint(int R, long nx, long ny, long nz, const double *w,
+                          const double *c, const double *r_bar, double *u_bar, double *scale)
+{
+    grid_t g;
+    if (!w || !c || !r_bar || !u_bar || grid_init(&g, 3, R, nx, ny, nz)) return ORACLE_BAD_ARG;
+    for (long z = g.lo[2]; z <= g.hi[2]; ++z)
+    for (long y = g.lo[1]; y <= g.hi[1]; ++y)
+    for (long x = g.lo[0]; x <= g.hi[0]; ++x) {
+        long i = x + nx * (y + ny * z);
+        double rb = r_bar[i];
+        double t = (c[i] * w[0]) * rb;
+        u_bar[i] += t;
+        if (scale) scale[i] += fabs(t);
+        for (int d = 0; d < 3; ++d)
+            for (int o = -R; o <= R; ++o) {
+                if (o == 0) continue;
+                long j = i + o * g.stride[d];
+                t = (c[i] * star_w_at(w, R, d, o)) * rb;
+                u_bar[j] += t;
+                if (scale) scale[j] += fabs(t);
+            }
+    }
+    return ORACLE_OK;
+}
+
 /* --------------------------------------- 1-D three-point example, general weights */
 /* Primal r[i] = c[i]*(wm*u[i-1] + w0*u[i] + wp*u[i+1]) for i in [lo,hi], arrays of
  * length len (Section 3.2: weights (2,-3,4), i in [1,n-1], arrays of length n+1). */

@@ -68,6 +68,8 @@ def load() -> ctypes.CDLL:
     lib.sadj_describe_wave3d_plan.argtypes = [I, I, L, L, L, ctypes.POINTER(L), ctypes.POINTER(ctypes.c_int), L]
     lib.sadj_adjoint_wave3d_atomic_scatter.argtypes = [I, I, L, L, L, P, P, P, P]
     lib.sadj_adjoint_wave3d_steps.argtypes = [I, I, L, L, L, L, P, P, P, P, P]
+    lib.sadj_primal_star3d.argtypes = [I, I, L, L, L, ctypes.POINTER(D), P, P, P, P]
+    lib.sadj_adjoint_star3d.argtypes = [I, I, L, L, L, ctypes.POINTER(D), P, P, P, P]
     lib.sadj_primal_box.argtypes = [I, I, L, L, L, ctypes.POINTER(D), P, P, P, P]
     lib.sadj_adjoint_box.argtypes = [I, I, L, L, L, ctypes.POINTER(D), P, P, P, P]
     lib.sadj_primal_burgers1d.argtypes = [I, L, D, D, P, P, P]
@@ -78,6 +80,7 @@ def load() -> ctypes.CDLL:
                  "sadj_primal_wave2d", "sadj_adjoint_wave2d", "sadj_primal_wave3d", "sadj_adjoint_wave3d",
                  "sadj_primal_burgers1d", "sadj_adjoint_burgers1d", "sadj_adjoint_wave3d_steps",
                  "sadj_primal_box", "sadj_adjoint_box", "sadj_adjoint_wave3d_atomic_scatter", "sadj_describe_wave3d_plan",
+                 "sadj_primal_star3d", "sadj_adjoint_star3d",
                  "sadj_primal_burgers1d_steps", "sadj_adjoint_burgers1d_steps"):
         getattr(lib, name).restype = I
     _lib = lib
@@ -201,6 +204,23 @@ def _box(fn_name, weights, tensors):
         raise ValueError("weights must have 3**ndim entries, slowest axis first (shape (3,)*ndim)")
     w = (ctypes.c_double * len(flat))(*flat)
     _check(getattr(load(), fn_name)(code, ndim, dims[0], dims[1], dims[2], w, *p, s))
+
+
+def _star(fn_name, radius, weights, tensors):
+    code, (nz, ny, nx), p, s = _marshal(tensors, 3)
+    flat = [float(v) for v in _flatten(weights)]
+    if len(flat) != 1 + 6 * int(radius):
+        raise ValueError("weights: centre, then 2*radius values per axis x, y, z (offsets -R..-1, +1..+R)")
+    w = (ctypes.c_double * len(flat))(*flat)
+    _check(getattr(load(), fn_name)(code, int(radius), nx, ny, nz, w, *p, s))
+
+
+def sadj_primal_star3d(radius: int, weights, u, c, r) -> None:
+    _star("sadj_primal_star3d", radius, weights, [u, c, r])
+
+
+def sadj_adjoint_star3d(radius: int, weights, c, r_bar, u_bar) -> None:
+    _star("sadj_adjoint_star3d", radius, weights, [c, r_bar, u_bar])
 
 
 def _flatten(w):

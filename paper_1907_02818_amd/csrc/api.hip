@@ -362,6 +362,41 @@ sadj_status sadj_adjoint_box(sadj_dtype dtype, int ndim, long nx, long ny, long 
     return box_call(1, dtype, ndim, nx, ny, nz, weights, c, r_bar, u_bar, stream);
 }
 
+// --------------------------------------------- 3-D star stencils with free weights
+static sadj_status star_call(int adjoint, sadj_dtype dtype, int radius, long nx, long ny, long nz,
+                             const double *weights, const void *in0, const void *in1, void *out, void *stream)
+{
+    if (!dtype_ok(dtype) || radius < 1 || radius > 4) return SADJ_ERR_UNSUPPORTED;
+    if (!weights || !in0 || !in1 || !out) return SADJ_ERR_NULL;
+    sadj_status s = check_extents(radius, nx, ny, nz, 3);
+    if (s != SADJ_OK) return s;
+    const size_t bytes = (size_t)nx * ny * nz * elem(dtype);
+    const Span in[2] = {{in0, bytes}, {in1, bytes}};
+    const Span outs[1] = {{out, bytes}};
+    if (any_alias(in, outs)) return SADJ_ERR_ALIAS;
+    // caller's table: centre, then per axis the offsets -R..-1, +1..+R; the adjoint gathers
+    // with the mirrored table W[d][o] = w[d][-o] (index shifting)
+    double w[3][8] = {};
+    const int n = 2 * radius;
+    for (int d = 0; d < 3; ++d)
+        for (int i = 0; i < n; ++i) w[d][i] = weights[1 + d * n + (adjoint ? n - 1 - i : i)];
+    clear_stale_hip_error();
+    return from_hip(sadj::launch_star3d(adjoint, dtype == SADJ_F64, radius, (int)nx, (int)ny, (int)nz, weights[0], w, in0,
+                                        in1, out, current_options(), static_cast<hipStream_t>(stream)));
+}
+
+sadj_status sadj_primal_star3d(sadj_dtype dtype, int radius, long nx, long ny, long nz, const double *weights,
+                               const void *u, const void *c, void *r, void *stream)
+{
+    return star_call(0, dtype, radius, nx, ny, nz, weights, u, c, r, stream);
+}
+
+sadj_status sadj_adjoint_star3d(sadj_dtype dtype, int radius, long nx, long ny, long nz, const double *weights,
+                                const void *c, const void *r_bar, void *u_bar, void *stream)
+{
+    return star_call(1, dtype, radius, nx, ny, nz, weights, c, r_bar, u_bar, stream);
+}
+
 // ------------------------------------------------------------------------- Burgers
 sadj_status sadj_primal_burgers1d(sadj_dtype dtype, long n, double C, double D, const void *u, void *r,
                                   void *stream)

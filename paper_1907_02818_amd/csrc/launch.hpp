@@ -52,6 +52,12 @@ hipError_t launch_burgers1d_functor(int adjoint, int is_f64, long n, double C, d
 hipError_t launch_weighted3_functor(int adjoint, int is_f64, long n, const double *w, const void *u,
                                     const void *c, const void *r_bar, void *out, hipStream_t stream);
 
+// 3-D star stencil with free weights; w0 / w[d][idx] is the gather table (mirrored by the caller
+// for the adjoint), idx enumerating the offsets -R..-1, +1..+R of axis d.
+hipError_t launch_star3d(int adjoint, int is_f64, int radius, int nx, int ny, int nz, double w0,
+                         const double (*w)[8], const void *in0, const void *in1, void *out,
+                         const LaunchOptions &opt, hipStream_t stream);
+
 // Host-side view of how the default 3-D adjoint shape decomposes a grid (for tests): fills
 // plan[0..5] = tiles in x, tiles in y, z-chunks, planes per chunk, tile width, tile height,
 // and, if `tiles` is not null, for every workgroup id its (tile x, tile y, chunk) triple.

@@ -25,7 +25,7 @@ def test_header_declares_the_expected_entry_points():
     names = _declared_functions()
     for n in ("sadj_primal_wave1d", "sadj_adjoint_wave1d", "sadj_primal_wave2d", "sadj_adjoint_wave2d",
               "sadj_primal_wave3d", "sadj_adjoint_wave3d", "sadj_primal_burgers1d",
-              "sadj_adjoint_burgers1d", "sadj_adjoint_wave3d_steps", "sadj_adjoint_wave3d_atomic_scatter", "sadj_primal_burgers1d_steps", "sadj_adjoint_burgers1d_steps", "sadj_primal_box", "sadj_adjoint_box", "sadj_status_string", "sadj_version", "sadj_set_option",
+              "sadj_adjoint_burgers1d", "sadj_adjoint_wave3d_steps", "sadj_adjoint_wave3d_atomic_scatter", "sadj_primal_burgers1d_steps", "sadj_adjoint_burgers1d_steps", "sadj_primal_star3d", "sadj_adjoint_star3d", "sadj_primal_box", "sadj_adjoint_box", "sadj_status_string", "sadj_version", "sadj_set_option",
               "sadj_get_option", "sadj_last_device_error"):
         assert n in names
 
@@ -133,6 +133,12 @@ def test_argument_errors_are_reported_before_any_launch():
     assert lib.sadj_adjoint_wave3d_atomic_scatter(F64, 4, 32, 8, 32, A, B, C_, None) == 2
     assert lib.sadj_adjoint_wave3d_atomic_scatter(F64, 1, 16, 16, 16, A, B, B, None) == 3
     assert lib.sadj_adjoint_wave3d_atomic_scatter(F64, 0, 32, 32, 32, A, B, C_, None) == 4
+    # general star: host table required, radius 1..4, extents, aliasing
+    W25 = (ctypes.c_double * 25)(*([0.5] * 25))
+    assert lib.sadj_adjoint_star3d(F64, 4, 32, 32, 32, None, A, B, C_, None) == 1
+    assert lib.sadj_adjoint_star3d(F64, 0, 32, 32, 32, W25, A, B, C_, None) == 4
+    assert lib.sadj_primal_star3d(F64, 4, 32, 8, 32, W25, A, B, C_, None) == 2
+    assert lib.sadj_primal_star3d(F64, 4, 32, 32, 32, W25, A, B, B, None) == 3
     # unsupported radius / dtype
     assert lib.sadj_adjoint_wave3d(F64, 5, 32, 32, 32, A, B, C_, None, None) == 4
     assert lib.sadj_primal_wave3d(F64, 0, 32, 32, 32, A, B, C_, D_, None) == 4
