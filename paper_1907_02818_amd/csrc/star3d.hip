@@ -30,10 +30,11 @@ struct StarArgs {
     double w[3][8];             // gather weights W[d][idx], idx: offsets -R..-1 -> 0..R-1, +1..+R -> R..2R-1
 };
 
-template <class T, int R, int BX, int BY, int PY, bool ADJ, bool GUARD>
+template <class T, int R, int BX, int BY, int PY, int PX, bool ADJ, bool GUARD>
 __device__ __forceinline__ void star3d_march(const StarArgs &a, int tix, int tiy, int tiz, T *__restrict__ sq)
 {
-    using G = Tile3d<T, R, BX, BY, PY, 1>;
+    using G = Tile3d<T, R, BX, BY, PY, PX>;
+    using V = Vec<T, PX>;
     constexpr int TX = G::TX, TY = G::TY, LX = G::LX, HS = G::HS;
     constexpr int NACC = 2 * R + 1;
     const int tid = threadIdx.x;
@@ -52,15 +53,22 @@ __device__ __forceinline__ void star3d_march(const StarArgs &a, int tix, int tiy
     for (int i = 0; i < 2 * R; ++i) { wx[i] = (T)a.w[0][i]; wy[i] = (T)a.w[1][i]; wz[i] = (T)a.w[2][i]; }
     const uint32_t dummy = (uint32_t)((size_t)y0 * nx + x0) * sizeof(T);   // always inside the grid
 
+    // owned cells: x = x0 + tx*PX + e, y = y0 + ty*PY + p (nx is a multiple of PX, so a vector
+    // of PX cells is entirely inside or entirely outside the grid)
     uint32_t ooff[PY];
-    bool ouse[PY], ostore[PY];                      // ouse: cell in I (x,y); ostore: cell receives output
-    const int x = x0 + tx;
+    bool ouse[PY][PX], ostore[PY][PX], ovec[PY];    // ouse: cell in I (x,y); ostore: cell receives output
+    const int x = x0 + tx * PX;
 #pragma unroll
     for (int p = 0; p < PY; ++p) {
         const int y = y0 + ty * PY + p;
         const bool ingrid = !GUARD || (x < nx && y < ny);
-        ouse[p] = !GUARD || (x >= R && x < nx - R && y >= R && y < ny - R);
-        ostore[p] = ADJ ? ingrid : ouse[p];
+        ovec[p] = true;
+#pragma unroll
+        for (int e = 0; e < PX; ++e) {
+            ouse[p][e] = !GUARD || (x + e >= R && x + e < nx - R && y >= R && y < ny - R);
+            ostore[p][e] = ADJ ? ingrid : ouse[p][e];
+            ovec[p] = ovec[p] && ostore[p][e];
+        }
         ooff[p] = ingrid ? (uint32_t)((size_t)y * nx + x) * sizeof(T) : dummy;
     }
     uint32_t hoff[HS];
@@ -78,14 +86,17 @@ __device__ __forceinline__ void star3d_march(const StarArgs &a, int tix, int tiy
         hlds[s] = slot ? ly * LX + lx : 0;          // cell (0,0) is a corner nobody reads
     }
 
-    T acc[PY][NACC];
+    T acc[PY][PX][NACC];
 #pragma unroll
     for (int p = 0; p < PY; ++p)
 #pragma unroll
-        for (int k = 0; k < NACC; ++k) acc[p][k] = T(0);
-    T n0[PY], n1[PY], nh0[HS], nh1[HS], nout[PY];
+        for (int e = 0; e < PX; ++e)
 #pragma unroll
-    for (int p = 0; p < PY; ++p) n0[p] = n1[p] = nout[p] = T(0);
+            for (int k = 0; k < NACC; ++k) acc[p][e][k] = T(0);
+    V n0[PY], n1[PY], nout[PY];
+    T nh0[HS], nh1[HS];
+#pragma unroll
+    for (int p = 0; p < PY; ++p) { n0[p] = V{}; n1[p] = V{}; nout[p] = V{}; }
 #pragma unroll
     for (int s = 0; s < HS; ++s) nh0[s] = nh1[s] = T(0);
 
@@ -95,7 +106,10 @@ __device__ __forceinline__ void star3d_march(const StarArgs &a, int tix, int tiy
         const T *p0 = g0 + (size_t)z * plane;
         const T *p1 = g1 + (size_t)z * plane;
 #pragma unroll
-        for (int p = 0; p < PY; ++p) { n0[p] = ld_off(p0, ooff[p]); if (ADJ) n1[p] = ld_off(p1, ooff[p]); }
+        for (int p = 0; p < PY; ++p) {
+            n0[p] = ld_vec_off<T, PX, false>(p0, ooff[p]);
+            if (ADJ) n1[p] = ld_vec_off<T, PX, false>(p1, ooff[p]);
+        }
 #pragma unroll
         for (int s = 0; s < HS; ++s) { nh0[s] = ld_off(p0, hoff[s]); if (ADJ) nh1[s] = ld_off(p1, hoff[s]); }
     };
@@ -103,7 +117,7 @@ __device__ __forceinline__ void star3d_march(const StarArgs &a, int tix, int tiy
     auto load_out = [&](int zo) {
         const T *po = (ADJ ? static_cast<const T *>(og) : g1) + (size_t)zo * plane;
 #pragma unroll
-        for (int p = 0; p < PY; ++p) nout[p] = ld_stream<T, true>(po, ooff[p]);
+        for (int p = 0; p < PY; ++p) nout[p] = ld_vec_off<T, PX, true>(po, ooff[p]);
     };
     const int zi0 = zs - R, zi1 = ze - 1 + R;       // source planes that reach outputs [zs, ze)
     if (plane_used(zi0)) load_plane(zi0);
@@ -112,14 +126,16 @@ __device__ __forceinline__ void star3d_march(const StarArgs &a, int tix, int tiy
         const bool zin = plane_used(zi);
         const int zo = zi - R;
         T *sb = sq + buf * G::PLANE;
-        T own[PY];
+        T own[PY][PX];
         if (zin) {
 #pragma unroll
-            for (int p = 0; p < PY; ++p) {
-                if (ADJ) own[p] = ouse[p] ? n0[p] * n1[p] : T(0);
-                else     own[p] = n0[p];
-                sb[(R + ty * PY + p) * LX + R + tx] = own[p];
-            }
+            for (int p = 0; p < PY; ++p)
+#pragma unroll
+                for (int e = 0; e < PX; ++e) {
+                    if (ADJ) own[p][e] = ouse[p][e] ? n0[p].v[e] * n1[p].v[e] : T(0);
+                    else     own[p][e] = n0[p].v[e];
+                    sb[(R + ty * PY + p) * LX + R + tx * PX + e] = own[p][e];
+                }
 #pragma unroll
             for (int s = 0; s < HS; ++s) {
                 T v;
@@ -128,7 +144,7 @@ __device__ __forceinline__ void star3d_march(const StarArgs &a, int tix, int tiy
                 sb[hlds[s]] = v;
             }
         }
-        T cur_out[PY];
+        V cur_out[PY];
 #pragma unroll
         for (int p = 0; p < PY; ++p) cur_out[p] = nout[p];
         if (zi + 1 <= zi1) {
@@ -138,67 +154,97 @@ __device__ __forceinline__ void star3d_march(const StarArgs &a, int tix, int tiy
         if (zin) {
             __syncthreads();
 #pragma unroll
-            for (int p = 0; p < PY; ++p) {
-                const T *row = sb + (R + ty * PY + p) * LX + R + tx;
-                T s = w0 * own[p];
+            for (int p = 0; p < PY; ++p)
 #pragma unroll
-                for (int k = 1; k <= R; ++k) s += wx[R - k] * row[-k] + wx[R + k - 1] * row[k];
+                for (int e = 0; e < PX; ++e) {
+                    const T *row = sb + (R + ty * PY + p) * LX + R + tx * PX + e;
+                    T s = w0 * own[p][e];
 #pragma unroll
-                for (int k = 1; k <= R; ++k) s += wy[R - k] * row[-k * LX] + wy[R + k - 1] * row[k * LX];
-                acc[p][R] += s;
-                // S(zi) sits at offset o = zi - z' of output plane z' = zi - o: running sum R - o
+                    for (int k = 1; k <= R; ++k) s += wx[R - k] * row[-k] + wx[R + k - 1] * row[k];
 #pragma unroll
-                for (int k = 1; k <= R; ++k) {
-                    acc[p][R - k] += wz[R + k - 1] * own[p];     // o = +k
-                    acc[p][R + k] += wz[R - k] * own[p];         // o = -k
+                    for (int k = 1; k <= R; ++k) s += wy[R - k] * row[-k * LX] + wy[R + k - 1] * row[k * LX];
+                    acc[p][e][R] += s;
+                    // S(zi) sits at offset o = zi - z' of output plane z' = zi - o: running sum R - o
+#pragma unroll
+                    for (int k = 1; k <= R; ++k) {
+                        acc[p][e][R - k] += wz[R + k - 1] * own[p][e];     // o = +k
+                        acc[p][e][R + k] += wz[R - k] * own[p][e];         // o = -k
+                    }
                 }
-            }
             buf ^= 1;
         }
         if (zo >= zs && (ADJ || (zo >= R && zo < nz - R))) {
             T *po = og + (size_t)zo * plane;
 #pragma unroll
-            for (int p = 0; p < PY; ++p)
-                if (ostore[p]) st_stream<T, true>(po, ooff[p], ADJ ? cur_out[p] + acc[p][0] : cur_out[p] * acc[p][0]);
+            for (int p = 0; p < PY; ++p) {
+                V o;
+#pragma unroll
+                for (int e = 0; e < PX; ++e)
+                    o.v[e] = ADJ ? cur_out[p].v[e] + acc[p][e][0] : cur_out[p].v[e] * acc[p][e][0];
+                if (!GUARD || ovec[p]) {
+                    st_vec_off<T, PX, true>(po, ooff[p], o);
+                } else {                             // a vector that straddles the boundary of I (primal)
+#pragma unroll
+                    for (int e = 0; e < PX; ++e)
+                        if (ostore[p][e]) st_stream<T, true>(po, ooff[p] + e * (uint32_t)sizeof(T), o.v[e]);
+                }
+            }
         }
 #pragma unroll
-        for (int p = 0; p < PY; ++p) {
+        for (int p = 0; p < PY; ++p)
 #pragma unroll
-            for (int k = 0; k < NACC - 1; ++k) acc[p][k] = acc[p][k + 1];
-            acc[p][NACC - 1] = T(0);
-        }
+            for (int e = 0; e < PX; ++e) {
+#pragma unroll
+                for (int k = 0; k < NACC - 1; ++k) acc[p][e][k] = acc[p][e][k + 1];
+                acc[p][e][NACC - 1] = T(0);
+            }
     }
 }
 
-template <class T, int R, int BX, int BY, int PY, bool ADJ>
+template <class T, int R, int BX, int BY, int PY, int PX, bool ADJ>
 __global__ __launch_bounds__(BX *BY) void star3d_kernel(StarArgs a)
 {
-    using G = Tile3d<T, R, BX, BY, PY, 1>;
+    using G = Tile3d<T, R, BX, BY, PY, PX>;
     __shared__ T sq[2 * G::PLANE];
     int tix, tiy, tiz;
     block_to_tile(a, blockIdx.x, tix, tiy, tiz);
     const int x0 = tix * G::TX, y0 = tiy * G::TY;
     // core tile: own cells and halo cells all inside I in x and y
     const bool core = x0 >= 2 * R && x0 + G::TX + 2 * R <= a.nx && y0 >= 2 * R && y0 + G::TY + 2 * R <= a.ny;
-    if (core) star3d_march<T, R, BX, BY, PY, ADJ, false>(a, tix, tiy, tiz, sq);
-    else      star3d_march<T, R, BX, BY, PY, ADJ, true>(a, tix, tiy, tiz, sq);
+    if (core) star3d_march<T, R, BX, BY, PY, PX, ADJ, false>(a, tix, tiy, tiz, sq);
+    else      star3d_march<T, R, BX, BY, PY, PX, ADJ, true>(a, tix, tiy, tiz, sq);
 }
 
-// 64 x 32 tile, 512 threads, 8 bytes per lane, one workgroup per CU.  (A 64 x 16 tile with two
-// workgroups per CU measured +4 points for the radius-4 primal and -3 for the adjoint.)
-template <class T, int R, bool ADJ>
-static hipError_t launch_star_TR(StarArgs a, const LaunchOptions &opt, hipStream_t stream)
+template <class T, int R, bool ADJ, int BX, int BY, int PY, int PX>
+static hipError_t launch_star_shape(StarArgs a, const LaunchOptions &opt, hipStream_t stream)
 {
-    constexpr int BX = 64, BY = 8, PY = 4;
-    using G = Tile3d<T, R, BX, BY, PY, 1>;
+    using G = Tile3d<T, R, BX, BY, PY, PX>;
     March3dArgs m{};
     m.nx = a.nx; m.ny = a.ny; m.nz = a.nz;
     plan_march(m, G::TX, G::TY, R, opt);
     a.ntx = m.ntx; a.nty = m.nty; a.ntz = m.ntz; a.zchunk = m.zchunk; a.total_blocks = m.total_blocks;
     a.xcd_map = m.xcd_map; a.band = m.band; a.round_blocks = m.round_blocks;
     const unsigned pad = one_workgroup_per_cu_pad(sizeof(T) * 2 * G::PLANE, opt.lds_pad);
-    hipLaunchKernelGGL((star3d_kernel<T, R, BX, BY, PY, ADJ>), dim3(a.total_blocks), dim3(G::NT), pad, stream, a);
+    hipLaunchKernelGGL((star3d_kernel<T, R, BX, BY, PY, PX, ADJ>), dim3(a.total_blocks), dim3(G::NT), pad, stream, a);
     return hipGetLastError();
+}
+
+static inline bool star_aligned(const void *p, size_t n) { return (reinterpret_cast<uintptr_t>(p) % n) == 0; }
+
+// 16 bytes per lane (two doubles / four floats), 32 x 16 threads, two rows per thread, as the
+// wave kernels; needs nx to be a multiple of the vector length and vector-aligned arrays,
+// otherwise 64 x 8 threads with one cell per lane and four rows.  One workgroup per CU.  (A
+// 64 x 16 tile with two workgroups per CU measured +4 points for the radius-4 primal and -3
+// for the adjoint.)
+template <class T, int R, bool ADJ>
+static hipError_t launch_star_TR(const StarArgs &a, const LaunchOptions &opt, hipStream_t stream)
+{
+    constexpr int PXV = 16 / sizeof(T);
+    const bool ok = a.nx % PXV == 0 && star_aligned(a.in0, 16) && star_aligned(a.in1, 16) && star_aligned(a.out, 16);
+    // the primal of radius 1 and 2 measured 2-3 points faster with the one-cell shape
+    const bool wide = ADJ || R >= 3;
+    if (ok && wide && opt.variant != 3) return launch_star_shape<T, R, ADJ, 32, 16, 2, PXV>(a, opt, stream);
+    return launch_star_shape<T, R, ADJ, 64, 8, 4, 1>(a, opt, stream);
 }
 
 template <class T, bool ADJ>
