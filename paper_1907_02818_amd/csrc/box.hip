@@ -198,9 +198,9 @@ __global__ __launch_bounds__(64 * WAVES) void box2d_kernel(BoxArgs a)
 }
 
 // ------------------------------------------------------------------------------ 3-D
-template <class T, int BX, int BY, int PY>
+template <class T, int BX, int BY, int PY, int PX>
 struct BoxTile {
-    static constexpr int TX = BX, TY = BY * PY, NT = BX * BY;
+    static constexpr int TX = BX * PX, TY = BY * PY, NT = BX * BY;
     static constexpr int LX = TX + 2, LY = TY + 2, PLANE = LX * LY;
     static constexpr int NH = PLANE - TX * TY;          // full ring, corners included
     static constexpr int HS = (NH + NT - 1) / NT;
@@ -214,10 +214,13 @@ struct BoxTile {
     }
 };
 
-template <class T, int BX, int BY, int PY, bool ADJ, bool GUARD>
+// A thread owns PX consecutive cells in x (one 16-byte memory instruction where PX > 1; nx is
+// then a multiple of PX, so a vector lies entirely inside or outside the grid) times PY rows.
+template <class T, int BX, int BY, int PY, int PX, bool ADJ, bool GUARD>
 __device__ __forceinline__ void box3d_march(const BoxArgs &a, int tix, int tiy, int tiz, T *__restrict__ sq)
 {
-    using G = BoxTile<T, BX, BY, PY>;
+    using G = BoxTile<T, BX, BY, PY, PX>;
+    using V = Vec<T, PX>;
     constexpr int TX = G::TX, TY = G::TY, LX = G::LX, HS = G::HS;
     const int tid = threadIdx.x;
     const int tx = tid % BX, ty = tid / BX;
@@ -235,14 +238,19 @@ __device__ __forceinline__ void box3d_march(const BoxArgs &a, int tix, int tiy, 
     const uint32_t dummy = (uint32_t)((size_t)y0 * nx + x0) * sizeof(T);
 
     uint32_t ooff[PY];
-    bool ouse[PY], ostore[PY];                      // ouse: cell in I (x,y); ostore: cell receives output
-    const int x = x0 + tx;
+    bool ouse[PY][PX], ostore[PY][PX], ovec[PY];    // ouse: cell in I (x,y); ostore: cell receives output
+    const int x = x0 + tx * PX;
 #pragma unroll
     for (int p = 0; p < PY; ++p) {
         const int y = y0 + ty * PY + p;
-        const bool ingrid = x < nx && y < ny;
-        ouse[p] = x >= 1 && x <= nx - 2 && y >= 1 && y <= ny - 2;
-        ostore[p] = ADJ ? ingrid : ouse[p];
+        const bool ingrid = !GUARD || (x < nx && y < ny);
+        ovec[p] = true;
+#pragma unroll
+        for (int e = 0; e < PX; ++e) {
+            ouse[p][e] = !GUARD || (x + e >= 1 && x + e <= nx - 2 && y >= 1 && y <= ny - 2);
+            ostore[p][e] = ADJ ? ingrid : ouse[p][e];
+            ovec[p] = ovec[p] && ostore[p][e];
+        }
         ooff[p] = ingrid ? (uint32_t)((size_t)y * nx + x) * sizeof(T) : dummy;
     }
     uint32_t hoff[HS];
@@ -253,18 +261,21 @@ __device__ __forceinline__ void box3d_march(const BoxArgs &a, int tix, int tiy, 
         int lx, ly;
         const bool slot = G::halo_cell(tid + s * G::NT, lx, ly);
         const int gx = x0 - 1 + lx, gy = y0 - 1 + ly;
-        const bool ingrid = slot && gx >= 0 && gx < nx && gy >= 0 && gy < ny;
-        huse[s] = ADJ ? (slot && gx >= 1 && gx <= nx - 2 && gy >= 1 && gy <= ny - 2) : ingrid;
+        const bool ingrid = slot && (!GUARD || (gx >= 0 && gx < nx && gy >= 0 && gy < ny));
+        huse[s] = ADJ ? (slot && (!GUARD || (gx >= 1 && gx <= nx - 2 && gy >= 1 && gy <= ny - 2))) : ingrid;
         hoff[s] = ingrid ? (uint32_t)((size_t)gy * nx + gx) * sizeof(T) : dummy;
         hlds[s] = slot ? ly * LX + lx : -1;
     }
 
-    T acc[PY][3];
+    T acc[PY][PX][3];
 #pragma unroll
-    for (int p = 0; p < PY; ++p) acc[p][0] = acc[p][1] = acc[p][2] = T(0);
-    T n0[PY], n1[PY], nh0[HS], nh1[HS], nout[PY];
+    for (int p = 0; p < PY; ++p)
 #pragma unroll
-    for (int p = 0; p < PY; ++p) n0[p] = n1[p] = nout[p] = T(0);
+        for (int e = 0; e < PX; ++e) acc[p][e][0] = acc[p][e][1] = acc[p][e][2] = T(0);
+    V n0[PY], n1[PY], nout[PY];
+    T nh0[HS], nh1[HS];
+#pragma unroll
+    for (int p = 0; p < PY; ++p) { n0[p] = V{}; n1[p] = V{}; nout[p] = V{}; }
 #pragma unroll
     for (int s = 0; s < HS; ++s) nh0[s] = nh1[s] = T(0);
 
@@ -273,14 +284,17 @@ __device__ __forceinline__ void box3d_march(const BoxArgs &a, int tix, int tiy, 
         const T *p0 = g0 + (size_t)z * plane;
         const T *p1 = g1 + (size_t)z * plane;
 #pragma unroll
-        for (int p = 0; p < PY; ++p) { n0[p] = ld_off(p0, ooff[p]); if (ADJ) n1[p] = ld_off(p1, ooff[p]); }
+        for (int p = 0; p < PY; ++p) {
+            n0[p] = ld_vec_off<T, PX, false>(p0, ooff[p]);
+            if (ADJ) n1[p] = ld_vec_off<T, PX, false>(p1, ooff[p]);
+        }
 #pragma unroll
         for (int s = 0; s < HS; ++s) { nh0[s] = ld_off(p0, hoff[s]); if (ADJ) nh1[s] = ld_off(p1, hoff[s]); }
     };
     auto load_out = [&](int zo) {
         const T *po = (ADJ ? static_cast<const T *>(og) : g1) + (size_t)zo * plane;
 #pragma unroll
-        for (int p = 0; p < PY; ++p) nout[p] = ld_stream<T, true>(po, ooff[p]);
+        for (int p = 0; p < PY; ++p) nout[p] = ld_vec_off<T, PX, true>(po, ooff[p]);
     };
     const int zi0 = zs - 1, zi1 = ze;
     if (plane_used(zi0)) load_plane(zi0);
@@ -291,21 +305,23 @@ __device__ __forceinline__ void box3d_march(const BoxArgs &a, int tix, int tiy, 
         T *sb = sq + buf * G::PLANE;
         if (zin) {
 #pragma unroll
-            for (int p = 0; p < PY; ++p) {
-                T s;
-                if (ADJ) s = (!GUARD || ouse[p]) ? n0[p] * n1[p] : T(0);
-                else     s = n0[p];
-                sb[(1 + ty * PY + p) * LX + 1 + tx] = s;
-            }
+            for (int p = 0; p < PY; ++p)
+#pragma unroll
+                for (int e = 0; e < PX; ++e) {
+                    T s;
+                    if (ADJ) s = ouse[p][e] ? n0[p].v[e] * n1[p].v[e] : T(0);
+                    else     s = n0[p].v[e];
+                    sb[(1 + ty * PY + p) * LX + 1 + tx * PX + e] = s;
+                }
 #pragma unroll
             for (int s = 0; s < HS; ++s) {
                 T v;
                 if (ADJ) v = huse[s] ? nh0[s] * nh1[s] : T(0);
-                else     v = nh0[s];
+                else     v = huse[s] ? nh0[s] : T(0);
                 if (hlds[s] >= 0) sb[hlds[s]] = v;
             }
         }
-        T cur_out[PY];
+        V cur_out[PY];
 #pragma unroll
         for (int p = 0; p < PY; ++p) cur_out[p] = nout[p];
         if (zi + 1 <= zi1) {
@@ -314,55 +330,69 @@ __device__ __forceinline__ void box3d_march(const BoxArgs &a, int tix, int tiy, 
         }
         if (zin) {
             __syncthreads();
-            // rows ty*PY .. ty*PY+PY+1 of the LDS plane, three columns each
-            T win[PY + 2][3];
+            // rows ty*PY .. ty*PY+PY+1 of the LDS plane, PX + 2 columns each
+            T win[PY + 2][PX + 2];
 #pragma unroll
             for (int i = 0; i < PY + 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 3; ++j) win[i][j] = sb[(ty * PY + i) * LX + tx + j];
+                for (int j = 0; j < PX + 2; ++j) win[i][j] = sb[(ty * PY + i) * LX + tx * PX + j];
 #pragma unroll
             for (int p = 0; p < PY; ++p)
 #pragma unroll
-                for (int k = 0; k < 3; ++k) {       // k = 0: zo = zi-1 (oz=+1), 1: zo = zi, 2: zo = zi+1 (oz=-1)
-                    const T *w9 = wt + 9 * (2 - k);
-                    T s = T(0);
+                for (int e = 0; e < PX; ++e)
 #pragma unroll
-                    for (int oy = 0; oy < 3; ++oy)
+                    for (int k = 0; k < 3; ++k) {   // k = 0: zo = zi-1 (oz=+1), 1: zo = zi, 2: zo = zi+1 (oz=-1)
+                        const T *w9 = wt + 9 * (2 - k);
+                        T s = T(0);
 #pragma unroll
-                        for (int ox = 0; ox < 3; ++ox) s += w9[ox + 3 * oy] * win[p + oy][ox];
-                    acc[p][k] += s;
-                }
+                        for (int oy = 0; oy < 3; ++oy)
+#pragma unroll
+                            for (int ox = 0; ox < 3; ++ox) s += w9[ox + 3 * oy] * win[p + oy][e + ox];
+                        acc[p][e][k] += s;
+                    }
             buf ^= 1;
         }
         if (zo >= zs && (ADJ || (zo >= 1 && zo <= nz - 2))) {
             T *po = og + (size_t)zo * plane;
 #pragma unroll
-            for (int p = 0; p < PY; ++p)
-                if (ostore[p]) st_stream<T, true>(po, ooff[p], ADJ ? cur_out[p] + acc[p][0] : cur_out[p] * acc[p][0]);
+            for (int p = 0; p < PY; ++p) {
+                V o;
+#pragma unroll
+                for (int e = 0; e < PX; ++e)
+                    o.v[e] = ADJ ? cur_out[p].v[e] + acc[p][e][0] : cur_out[p].v[e] * acc[p][e][0];
+                if (!GUARD || ovec[p]) {
+                    st_vec_off<T, PX, true>(po, ooff[p], o);
+                } else {                             // a vector that straddles the boundary of I (primal)
+#pragma unroll
+                    for (int e = 0; e < PX; ++e)
+                        if (ostore[p][e]) st_stream<T, true>(po, ooff[p] + e * (uint32_t)sizeof(T), o.v[e]);
+                }
+            }
         }
 #pragma unroll
-        for (int p = 0; p < PY; ++p) {
-            acc[p][0] = acc[p][1];
-            acc[p][1] = acc[p][2];
-            acc[p][2] = T(0);
-        }
+        for (int p = 0; p < PY; ++p)
+#pragma unroll
+            for (int e = 0; e < PX; ++e) {
+                acc[p][e][0] = acc[p][e][1];
+                acc[p][e][1] = acc[p][e][2];
+                acc[p][e][2] = T(0);
+            }
     }
 }
 
-template <class T, int BX, int BY, int PY, bool ADJ>
+template <class T, int BX, int BY, int PY, int PX, bool ADJ>
 __global__ __launch_bounds__(BX *BY) void box3d_kernel(BoxArgs a)
 {
-    using G = BoxTile<T, BX, BY, PY>;
+    using G = BoxTile<T, BX, BY, PY, PX>;
     __shared__ T sq[2 * G::PLANE];
     int tix, tiy, tiz;
     block_to_tile(a, blockIdx.x, tix, tiy, tiz);
     const int x0 = tix * G::TX, y0 = tiy * G::TY;
     const bool core = x0 >= 2 && x0 + G::TX + 2 <= a.nx && y0 >= 2 && y0 + G::TY + 2 <= a.ny;
-    if (core) box3d_march<T, BX, BY, PY, ADJ, false>(a, tix, tiy, tiz, sq);
-    else      box3d_march<T, BX, BY, PY, ADJ, true>(a, tix, tiy, tiz, sq);
+    if (core) box3d_march<T, BX, BY, PY, PX, ADJ, false>(a, tix, tiy, tiz, sq);
+    else      box3d_march<T, BX, BY, PY, PX, ADJ, true>(a, tix, tiy, tiz, sq);
 }
 
-// ------------------------------------------------------------------------- launchers
 static inline bool box_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 template <class T, int PX, bool ADJ>
@@ -386,18 +416,29 @@ static hipError_t launch_box2d(BoxArgs a, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <class T, bool ADJ>
-static hipError_t launch_box3d(BoxArgs a, const LaunchOptions &opt, hipStream_t stream)
+template <class T, bool ADJ, int BX, int BY, int PY, int PX>
+static hipError_t launch_box3d_shape(BoxArgs a, const LaunchOptions &opt, hipStream_t stream)
 {
-    using G = BoxTile<T, 64, 8, 4>;
+    using G = BoxTile<T, BX, BY, PY, PX>;
     March3dArgs m{};
     m.nx = a.nx; m.ny = a.ny; m.nz = a.nz;
     plan_march(m, G::TX, G::TY, 1, opt);
     a.ntx = m.ntx; a.nty = m.nty; a.ntz = m.ntz; a.chunk = m.zchunk; a.total_blocks = m.total_blocks;
     a.xcd_map = m.xcd_map; a.band = m.band; a.round_blocks = m.round_blocks;
     const unsigned pad = one_workgroup_per_cu_pad(sizeof(T) * 2 * G::PLANE, opt.lds_pad);
-    hipLaunchKernelGGL((box3d_kernel<T, 64, 8, 4, ADJ>), dim3(a.total_blocks), dim3(G::NT), pad, stream, a);
+    hipLaunchKernelGGL((box3d_kernel<T, BX, BY, PY, PX, ADJ>), dim3(a.total_blocks), dim3(G::NT), pad, stream, a);
     return hipGetLastError();
+}
+
+// Adjoint: 16 bytes per lane where nx and the alignment allow it (as the wave kernels), else one cell.
+template <class T, bool ADJ>
+static hipError_t launch_box3d(const BoxArgs &a, const LaunchOptions &opt, hipStream_t stream)
+{
+    constexpr int PXV = 16 / sizeof(T);
+    const bool ok = a.nx % PXV == 0 && box_aligned16(a.in0) && box_aligned16(a.in1) && box_aligned16(a.out);
+    // the primal (24 bytes per cell) measured 2 points faster with the one-cell shape
+    if (ok && ADJ && opt.variant != 3) return launch_box3d_shape<T, ADJ, 32, 16, 2, PXV>(a, opt, stream);
+    return launch_box3d_shape<T, ADJ, 64, 8, 4, 1>(a, opt, stream);
 }
 
 template <bool ADJ>
