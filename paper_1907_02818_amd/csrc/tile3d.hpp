@@ -127,6 +127,9 @@ static inline void plan_march(March3dArgs &a, int TX, int TY, int R, const Launc
     }
     if (zchunk > a.nz) zchunk = a.nz;
     if (zchunk < 1) zchunk = 1;
+    // the grid is one-dimensional: keep the number of workgroups a valid int
+    while ((long)a.ntx * a.nty * cdiv_i(a.nz, zchunk) > 0x3fffffffL && zchunk < a.nz) zchunk *= 2;
+    if (zchunk > a.nz) zchunk = a.nz;
     a.zchunk = zchunk;
     a.ntz = cdiv_i(a.nz, zchunk);
     a.total_blocks = a.ntx * a.nty * a.ntz;
