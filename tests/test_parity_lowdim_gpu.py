@@ -305,3 +305,15 @@ def test_wave2d_on_drawn_shapes_and_options(sadj, case):
     finally:
         for k in opts:
             sadj.set_option(k, 0)
+
+
+def test_wave2d_at_the_documented_plane_limit(sadj):
+    """16384 x 16384 = 2^28 elements per array, the largest plane the library accepts
+    (in-plane byte offsets are 32-bit): every element against the oracle."""
+    shape = (16384, 16384)
+    d = inputs.wave_inputs(shape, 0.01, 0.2, seed=31, c_mode="iid", fields=("c", "r_bar", "u_bar"))
+    ub = to_gpu(d["u_bar"])
+    sadj.sadj_adjoint_wave2d(to_gpu(d["c"]), to_gpu(d["r_bar"]), ub)
+    _sync()
+    want, _, scale = oracle.wave_adjoint(d["c"], d["r_bar"], d["u_bar"], 1, want_scale=True)
+    assert_close(to_host(ub), want, scale + np.abs(d["u_bar"]), np.float64, "wave2d 16384^2")
