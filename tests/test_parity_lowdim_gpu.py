@@ -317,3 +317,15 @@ def test_wave2d_at_the_documented_plane_limit(sadj):
     _sync()
     want, _, scale = oracle.wave_adjoint(d["c"], d["r_bar"], d["u_bar"], 1, want_scale=True)
     assert_close(to_host(ub), want, scale + np.abs(d["u_bar"]), np.float64, "wave2d 16384^2")
+
+
+def test_burgers_beyond_4_gib_per_array(sadj, path1d):
+    """n = 2^29 + 3 doubles: element offsets pass 2^32 bytes in the 1-D kernels (64-bit
+    indexing), with a ragged last segment; every element against the oracle."""
+    n = (1 << 29) + 3
+    d = inputs.burgers_inputs(n, seed=12)
+    ub = to_gpu(d["u_bar"])
+    sadj.sadj_adjoint_burgers1d(C, D, to_gpu(d["u"]), to_gpu(d["r_bar"]), ub)
+    _sync()
+    want, scale = oracle.burgers_adjoint(d["u"], d["r_bar"], d["u_bar"], C, D, want_scale=True)
+    assert_close(to_host(ub), want, scale + np.abs(d["u_bar"]) + np.abs(d["r_bar"]), np.float64, "burgers n=2^29+3")
