@@ -6,7 +6,6 @@ offsets in the order of their source cell (z-R..z-1, y-R..y-1, x-R..x-1, centre,
 y+1.., z+1..) gives every element exactly the sequence of additions the sequential loop
 performs.  test_oracle_wave.py checks this against the oracle bit for bit in fp64; the
 GPU tests use it as the fp32 reference of the library's scatter-order mode."""
-import numpy as np
 
 from jacobians import star_weights
 
