@@ -223,19 +223,25 @@ sadj_status sadj_adjoint_burgers1d_steps(sadj_dtype dtype, long n, long last, lo
  * Section 3.3.4 requires the loop nests (here: workgroups) to be disjoint and to cover every
  * output index exactly once.  This host-only call reports the decomposition the default tile
  * shape of sadj_adjoint_wave3d would use under the current options, so that a test can check
- * that property without a GPU: plan[0..5] = tiles along x, tiles along y, z-chunks, planes
- * per chunk, tile width, tile height (cells); if `tiles` is not NULL it receives, for each of
- * the first max_blocks workgroup ids, the triple (tile x, tile y, chunk).  `plan` and
- * `tiles` are HOST pointers.  Nothing is launched.
+ * that property without a GPU: plan[0..7] = tiles along x, tiles along y, tile width, tile
+ * height (cells), number of workgroups, and how the tiles are cut along z: the first
+ * plan[5] tiles (in tile numbering order) into plan[6] chunks each, all others into
+ * plan[7] chunks each (plan[5] = 0: every tile alike).  If `tiles` is not NULL it receives,
+ * for each of the first max_blocks workgroup ids, four ints: tile x, tile y, first plane,
+ * one past the last plane.  `plan` and `tiles` are HOST pointers.  Nothing is launched.
  */
 sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, long ny, long nz,
-                                      long *plan /* host, 6 */, int *tiles /* host, 3*max_blocks, nullable */,
+                                      long *plan /* host, 8 */, int *tiles /* host, 4*max_blocks, nullable */,
                                       long max_blocks);
 
 /* ---- launch options -------------------------------------------------------------------
  * Process-wide integer options that select among equivalent launch strategies; they
  * never change what is computed, only how the regions are mapped to kernels.
  *   "wave3d.zchunk"  planes of output per workgroup along z (default 0 = automatic).
+ *   "wave3d.split"   0 (default): where the x-y tiles do not fill whole rounds of one workgroup
+ *                    per compute unit, the left-over tiles may be cut into more z-chunks than
+ *                    the others so that they fill a round of their own; 1: all tiles are cut
+ *                    alike.  Ignored when "wave3d.zchunk" is set.
  *   "wave3d.variant" tile-shape variant index (default 0 = automatic).
  *   "wave2d.ychunk"  rows of output per wave along y (default 0 = automatic).
  *   "wave2d.variant" load-pipeline depth / workgroup size variant (default 0 = automatic).

@@ -172,17 +172,16 @@ def sadj_adjoint_wave3d(radius: int, c, r_bar, u_bar, u_prev_bar=None) -> None:
 
 
 def sadj_describe_wave3d_plan(dtype_code: int, radius: int, nx: int, ny: int, nz: int, with_tiles: bool = True):
-    """Host-only: (plan dict, list of (tile x, tile y, chunk) per workgroup id)."""
-    plan = (ctypes.c_long * 6)()
+    """Host-only: (plan dict, list of (tile x, tile y, first plane, end plane) per workgroup id)."""
+    plan = (ctypes.c_long * 8)()
     _check(load().sadj_describe_wave3d_plan(dtype_code, int(radius), nx, ny, nz, plan, None, 0))
-    ntx, nty, ntz, zchunk, tw, th = (int(v) for v in plan)
-    info = dict(ntx=ntx, nty=nty, ntz=ntz, zchunk=zchunk, tile_w=tw, tile_h=th)
+    ntx, nty, tw, th, total, tiles_a, ntz_a, ntz = (int(v) for v in plan)
+    info = dict(ntx=ntx, nty=nty, tile_w=tw, tile_h=th, workgroups=total, tiles_a=tiles_a, ntz_a=ntz_a, ntz=ntz)
     if not with_tiles:
         return info, None
-    total = ntx * nty * ntz
-    buf = (ctypes.c_int * (3 * total))()
+    buf = (ctypes.c_int * (4 * total))()
     _check(load().sadj_describe_wave3d_plan(dtype_code, int(radius), nx, ny, nz, plan, buf, total))
-    return info, [(buf[3 * b], buf[3 * b + 1], buf[3 * b + 2]) for b in range(total)]
+    return info, [tuple(buf[4 * b:4 * b + 4]) for b in range(total)]
 
 
 def sadj_adjoint_wave3d_atomic_scatter(radius: int, c, r_bar, u_bar) -> None:

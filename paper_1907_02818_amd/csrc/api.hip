@@ -9,7 +9,7 @@
 
 namespace {
 
-std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0}, g_variant2d{0}, g_remainder{0}, g_order{0}, g_functor1d{0}, g_xcdmap{0}, g_band{0}, g_ldspad{0};
+std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0}, g_variant2d{0}, g_remainder{0}, g_order{0}, g_functor1d{0}, g_xcdmap{0}, g_band{0}, g_ldspad{0}, g_split{0};
 
 sadj::LaunchOptions current_options()
 {
@@ -19,6 +19,7 @@ sadj::LaunchOptions current_options()
     o.ychunk2d = g_ychunk2d.load();
     o.variant2d = g_variant2d.load();
     o.remainder = g_remainder.load();
+    o.split = g_split.load();
     o.xcd_map = g_xcdmap.load();
     o.band = g_band.load();
     o.lds_pad = g_ldspad.load();
@@ -120,6 +121,11 @@ sadj_status sadj_set_option(const char *name, long value)
         g_variant2d = value;
         return SADJ_OK;
     }
+    if (!std::strcmp(name, "wave3d.split")) {
+        if (value < 0 || value > 1) return SADJ_ERR_UNSUPPORTED;
+        g_split = value;
+        return SADJ_OK;
+    }
     if (!std::strcmp(name, "wave3d.remainder")) {
         if (value < 0 || value > 2) return SADJ_ERR_UNSUPPORTED;
         g_remainder = value;
@@ -162,6 +168,7 @@ sadj_status sadj_get_option(const char *name, long *value)
     if (!std::strcmp(name, "wave2d.ychunk")) { *value = g_ychunk2d; return SADJ_OK; }
     if (!std::strcmp(name, "wave2d.variant")) { *value = g_variant2d; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.remainder")) { *value = g_remainder; return SADJ_OK; }
+    if (!std::strcmp(name, "wave3d.split")) { *value = g_split; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.order")) { *value = g_order; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.xcdmap")) { *value = g_xcdmap; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.band")) { *value = g_band; return SADJ_OK; }

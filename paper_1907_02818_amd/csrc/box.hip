@@ -29,9 +29,8 @@ struct BoxArgs {
     const void *in0, *in1;      // adjoint: c, r_bar          primal: u, c
     void *out;                  // adjoint: u_bar (accumulated)   primal: r (assigned on I)
     int nx, ny, nz;
-    int chunk;                  // output rows (2-D) / planes (3-D) per march
-    int ntx, nty, ntz, total_blocks;
-    int xcd_map, band, round_blocks;   // workgroup id -> tile mapping of the 3-D march
+    int chunk;                  // 2-D: output rows per march
+    TileMap map;                // 3-D: workgroup id -> tile and planes
     double w[27];               // gather weights W[(ox+1) + 3(oy+1) + 9(oz+1)]
 };
 
@@ -217,7 +216,7 @@ struct BoxTile {
 // A thread owns PX consecutive cells in x (one 16-byte memory instruction where PX > 1; nx is
 // then a multiple of PX, so a vector lies entirely inside or outside the grid) times PY rows.
 template <class T, int BX, int BY, int PY, int PX, bool ADJ, bool GUARD>
-__device__ __forceinline__ void box3d_march(const BoxArgs &a, int tix, int tiy, int tiz, T *__restrict__ sq)
+__device__ __forceinline__ void box3d_march(const BoxArgs &a, int tix, int tiy, int zs, int ze, T *__restrict__ sq)
 {
     using G = BoxTile<T, BX, BY, PY, PX>;
     using V = Vec<T, PX>;
@@ -227,8 +226,6 @@ __device__ __forceinline__ void box3d_march(const BoxArgs &a, int tix, int tiy, 
     const int nx = a.nx, ny = a.ny, nz = a.nz;
     const size_t plane = (size_t)nx * ny;
     const int x0 = tix * TX, y0 = tiy * TY;
-    const int zs = tiz * a.chunk;
-    const int ze = min(zs + a.chunk, nz);
     const T *__restrict__ g0 = static_cast<const T *>(a.in0);
     const T *__restrict__ g1 = static_cast<const T *>(a.in1);
     T *__restrict__ og = static_cast<T *>(a.out);
@@ -385,12 +382,12 @@ __global__ __launch_bounds__(BX *BY) void box3d_kernel(BoxArgs a)
 {
     using G = BoxTile<T, BX, BY, PY, PX>;
     __shared__ T sq[2 * G::PLANE];
-    int tix, tiy, tiz;
-    block_to_tile(a, blockIdx.x, tix, tiy, tiz);
+    int tix, tiy, zs, ze;
+    block_to_tile(a.map, blockIdx.x, tix, tiy, zs, ze);
     const int x0 = tix * G::TX, y0 = tiy * G::TY;
     const bool core = x0 >= 2 && x0 + G::TX + 2 <= a.nx && y0 >= 2 && y0 + G::TY + 2 <= a.ny;
-    if (core) box3d_march<T, BX, BY, PY, PX, ADJ, false>(a, tix, tiy, tiz, sq);
-    else      box3d_march<T, BX, BY, PY, PX, ADJ, true>(a, tix, tiy, tiz, sq);
+    if (core) box3d_march<T, BX, BY, PY, PX, ADJ, false>(a, tix, tiy, zs, ze, sq);
+    else      box3d_march<T, BX, BY, PY, PX, ADJ, true>(a, tix, tiy, zs, ze, sq);
 }
 
 static inline bool box_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -420,13 +417,9 @@ template <class T, bool ADJ, int BX, int BY, int PY, int PX>
 static hipError_t launch_box3d_shape(BoxArgs a, const LaunchOptions &opt, hipStream_t stream)
 {
     using G = BoxTile<T, BX, BY, PY, PX>;
-    March3dArgs m{};
-    m.nx = a.nx; m.ny = a.ny; m.nz = a.nz;
-    plan_march(m, G::TX, G::TY, 1, opt);
-    a.ntx = m.ntx; a.nty = m.nty; a.ntz = m.ntz; a.chunk = m.zchunk; a.total_blocks = m.total_blocks;
-    a.xcd_map = m.xcd_map; a.band = m.band; a.round_blocks = m.round_blocks;
+    plan_march(a.map, a.nx, a.ny, a.nz, G::TX, G::TY, 1, opt);
     const unsigned pad = one_workgroup_per_cu_pad(sizeof(T) * 2 * G::PLANE, opt.lds_pad);
-    hipLaunchKernelGGL((box3d_kernel<T, BX, BY, PY, PX, ADJ>), dim3(a.total_blocks), dim3(G::NT), pad, stream, a);
+    hipLaunchKernelGGL((box3d_kernel<T, BX, BY, PY, PX, ADJ>), dim3(a.map.total_blocks), dim3(G::NT), pad, stream, a);
     return hipGetLastError();
 }
 

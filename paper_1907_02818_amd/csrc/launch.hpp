@@ -12,6 +12,7 @@ struct LaunchOptions {
     long xcd_map = 0;    // wave3d: workgroup id -> logical id (0 = automatic, see block_to_tile)
     long band = 0;       // wave3d: tile rows per band of the tile numbering (0 = rows of tiles)
     long lds_pad = 0;    // 3-D marches: dynamic LDS bytes requested to limit workgroups per CU (0 = automatic, -1 = none)
+    long split = 0;      // 3-D marches: 0 = left-over tiles may be cut finer than the rest, 1 = all tiles cut alike
     long remainder = 0;  // wave3d adjoint: remainder strategy (0 guarded where needed, 1 guarded everywhere, 2 split dispatches)
 };
 

@@ -24,14 +24,13 @@ struct StarArgs {
     const void *in0, *in1;      // adjoint: c, r_bar          primal: u, c
     void *out;                  // adjoint: u_bar (accumulated)   primal: r (assigned on I)
     int nx, ny, nz;
-    int zchunk, ntx, nty, ntz, total_blocks;
-    int xcd_map, band, round_blocks;
+    TileMap map;                // workgroup id -> tile and planes
     double w0;                  // centre weight
     double w[3][8];             // gather weights W[d][idx], idx: offsets -R..-1 -> 0..R-1, +1..+R -> R..2R-1
 };
 
 template <class T, int R, int BX, int BY, int PY, int PX, bool ADJ, bool GUARD>
-__device__ __forceinline__ void star3d_march(const StarArgs &a, int tix, int tiy, int tiz, T *__restrict__ sq)
+__device__ __forceinline__ void star3d_march(const StarArgs &a, int tix, int tiy, int zs, int ze, T *__restrict__ sq)
 {
     using G = Tile3d<T, R, BX, BY, PY, PX>;
     using V = Vec<T, PX>;
@@ -42,8 +41,6 @@ __device__ __forceinline__ void star3d_march(const StarArgs &a, int tix, int tiy
     const int nx = a.nx, ny = a.ny, nz = a.nz;
     const size_t plane = (size_t)nx * ny;
     const int x0 = tix * TX, y0 = tiy * TY;
-    const int zs = tiz * a.zchunk;
-    const int ze = min(zs + a.zchunk, nz);
     const T *__restrict__ g0 = static_cast<const T *>(a.in0);
     const T *__restrict__ g1 = static_cast<const T *>(a.in1);
     T *__restrict__ og = static_cast<T *>(a.out);
@@ -206,26 +203,22 @@ __global__ __launch_bounds__(BX *BY) void star3d_kernel(StarArgs a)
 {
     using G = Tile3d<T, R, BX, BY, PY, PX>;
     __shared__ T sq[2 * G::PLANE];
-    int tix, tiy, tiz;
-    block_to_tile(a, blockIdx.x, tix, tiy, tiz);
+    int tix, tiy, zs, ze;
+    block_to_tile(a.map, blockIdx.x, tix, tiy, zs, ze);
     const int x0 = tix * G::TX, y0 = tiy * G::TY;
     // core tile: own cells and halo cells all inside I in x and y
     const bool core = x0 >= 2 * R && x0 + G::TX + 2 * R <= a.nx && y0 >= 2 * R && y0 + G::TY + 2 * R <= a.ny;
-    if (core) star3d_march<T, R, BX, BY, PY, PX, ADJ, false>(a, tix, tiy, tiz, sq);
-    else      star3d_march<T, R, BX, BY, PY, PX, ADJ, true>(a, tix, tiy, tiz, sq);
+    if (core) star3d_march<T, R, BX, BY, PY, PX, ADJ, false>(a, tix, tiy, zs, ze, sq);
+    else      star3d_march<T, R, BX, BY, PY, PX, ADJ, true>(a, tix, tiy, zs, ze, sq);
 }
 
 template <class T, int R, bool ADJ, int BX, int BY, int PY, int PX>
 static hipError_t launch_star_shape(StarArgs a, const LaunchOptions &opt, hipStream_t stream)
 {
     using G = Tile3d<T, R, BX, BY, PY, PX>;
-    March3dArgs m{};
-    m.nx = a.nx; m.ny = a.ny; m.nz = a.nz;
-    plan_march(m, G::TX, G::TY, R, opt);
-    a.ntx = m.ntx; a.nty = m.nty; a.ntz = m.ntz; a.zchunk = m.zchunk; a.total_blocks = m.total_blocks;
-    a.xcd_map = m.xcd_map; a.band = m.band; a.round_blocks = m.round_blocks;
+    plan_march(a.map, a.nx, a.ny, a.nz, G::TX, G::TY, R, opt);
     const unsigned pad = one_workgroup_per_cu_pad(sizeof(T) * 2 * G::PLANE, opt.lds_pad);
-    hipLaunchKernelGGL((star3d_kernel<T, R, BX, BY, PY, PX, ADJ>), dim3(a.total_blocks), dim3(G::NT), pad, stream, a);
+    hipLaunchKernelGGL((star3d_kernel<T, R, BX, BY, PY, PX, ADJ>), dim3(a.map.total_blocks), dim3(G::NT), pad, stream, a);
     return hipGetLastError();
 }
 

@@ -36,19 +36,29 @@ struct Tile3d {
     }
 };
 
+// Workgroup id -> (x-y tile, range of planes) of a 3-D march; filled by plan_march.
+// The tiles are numbered 0 .. ntx*nty-1 (see `band`).  The first tiles_a of them are cut
+// into ntz_a chunks of zchunk_a planes, the others into ntz chunks of zchunk planes;
+// workgroup ids run over the first group, then over the second, within a group over
+// all tiles of chunk 0, then chunk 1, ...
+struct TileMap {
+    int ntx, nty, nz;
+    int tiles_a, ntz_a, zchunk_a, blocks_a;   // first group (tiles_a = 0: none)
+    int ntz, zchunk;                          // second group
+    int total_blocks;
+    int xcd_map, band;                        // see block_to_tile
+    int round_blocks;                         // workgroups per round of XCD-contiguous ids
+};
+
 struct March3dArgs {
     const void *in0, *in1, *in2;   // adjoint: c, r_bar, -      primal: u, u_prev, c
     void *out0, *out1;             // adjoint: u_bar, u_prev_bar (nullable)   primal: r, -
     int out1_assign;               // adjoint: 1 = u_prev_bar is assigned (-r_bar on I, 0 elsewhere), 0 = accumulated
     int nx, ny, nz;
-    int ntx, nty, ntz;             // tiles along x and y, chunks along z
-    int zchunk;                    // output planes per chunk
-    int total_blocks;
-    int xcd_map, band;             // workgroup id -> tile mapping, see block_to_tile
-    int round_blocks;              // workgroups resident at a time
+    TileMap map;
 };
 
-// Workgroup id -> (tile x, tile y, z-chunk).
+// Workgroup id -> (tile x, tile y, planes zs .. ze-1).
 // Logical ids.  Workgroups are dealt to the 8 XCDs round-robin by hardware id and run in
 // rounds of round_blocks (what the chip holds at a time).  xcd_map 1: within each round
 // every XCD owns a contiguous range of logical ids, so all XCDs work on neighbouring tiles
@@ -57,82 +67,121 @@ struct March3dArgs {
 // there is a single round; with several rounds the XCDs drift to different z-chunks,
 // measured 3-5 % slower).  xcd_map 3: logical id = hardware id (neighbouring tiles on
 // different XCDs).
-// Tiles of a chunk are numbered x fastest (band = 0) or in bands of `band` tile rows with
+// Tiles are numbered x fastest (band = 0) or in bands of `band` tile rows with
 // y fastest inside a band, which makes the 32 tiles an XCD holds a compact patch.
-template <class Args>
-__host__ __device__ __forceinline__ void block_to_tile(const Args &a, int hw_id, int &tix, int &tiy, int &tiz)
+__host__ __device__ __forceinline__ void block_to_tile(const TileMap &m, int hw_id, int &tix, int &tiy, int &zs, int &ze)
 {
     int L;
-    if (a.xcd_map == 3) {
+    if (m.xcd_map == 3) {
         L = hw_id;
-    } else if (a.xcd_map == 2) {
-        L = xcd_contiguous_id(hw_id, a.total_blocks);
+    } else if (m.xcd_map == 2) {
+        L = xcd_contiguous_id(hw_id, m.total_blocks);
     } else {
-        const int round = hw_id / a.round_blocks;
-        const int first = round * a.round_blocks;
-        const int left = a.total_blocks - first;
-        const int m = a.round_blocks < left ? a.round_blocks : left;
-        L = first + xcd_contiguous_id(hw_id - first, m);
+        const int round = hw_id / m.round_blocks;
+        const int first = round * m.round_blocks;
+        const int left = m.total_blocks - first;
+        const int n = m.round_blocks < left ? m.round_blocks : left;
+        L = first + xcd_contiguous_id(hw_id - first, n);
     }
-    const int tiles = a.ntx * a.nty;
-    tiz = L / tiles;
-    const int t = L - tiz * tiles;
-    if (a.band > 0) {
-        const int b = t / (a.ntx * a.band);
-        const int r = t - b * a.ntx * a.band;
-        const int rows_left = a.nty - b * a.band;
-        const int h = a.band < rows_left ? a.band : rows_left;
-        tix = r / h;
-        tiy = b * a.band + (r - tix * h);
+    int t, zchunk;
+    if (L < m.blocks_a) {
+        const int tiz = L / m.tiles_a;
+        t = L - tiz * m.tiles_a;
+        zchunk = m.zchunk_a;
+        zs = tiz * zchunk;
     } else {
-        tiy = t / a.ntx;
-        tix = t - tiy * a.ntx;
+        const int tiles_b = m.ntx * m.nty - m.tiles_a;
+        const int Lb = L - m.blocks_a;
+        const int tiz = Lb / tiles_b;
+        t = m.tiles_a + (Lb - tiz * tiles_b);
+        zchunk = m.zchunk;
+        zs = tiz * zchunk;
+    }
+    ze = zs + zchunk < m.nz ? zs + zchunk : m.nz;
+    if (m.band > 0) {
+        const int b = t / (m.ntx * m.band);
+        const int r = t - b * m.ntx * m.band;
+        const int rows_left = m.nty - b * m.band;
+        const int h = m.band < rows_left ? m.band : rows_left;
+        tix = r / h;
+        tiy = b * m.band + (r - tix * h);
+    } else {
+        tiy = t / m.ntx;
+        tix = t - tiy * m.ntx;
     }
 }
 
 static inline int cdiv_i(int a, int b) { return (a + b - 1) / b; }
 
-// Choose the number of z-chunks.  Each CU holds wg_per_cu workgroups of these kernels at a
+// Cut the grid into workgroups.  Each CU holds wg_per_cu workgroups of these kernels at a
 // time (one, except where a kernel is built to overlap two), so the dispatch runs in rounds
-// of `ncu` = CUs x wg_per_cu workgroups, each marching zchunk + 2R planes
-// (the 2R planes beyond a chunk are read by two chunks).  Minimise rounds * planes per
-// workgroup; ties go to fewer chunks.  With tiles*chunks == ncu this is the single
+// of `ncu` = CUs x wg_per_cu workgroups, each marching its chunk + 2R planes (the 2R planes
+// beyond a chunk are read by two chunks).  The model of the run time is the sum over rounds
+// of the planes a workgroup of that round marches.  Candidates: every tile cut into the same
+// number of chunks; or the tiles that fill whole rounds with few (long) chunks each cut
+// alike and only the left-over tiles cut finer, so that they fill one more round instead of
+// leaving most CUs idle (768^3 with 64 x 32 tiles: 256 tiles march all 768 planes, the
+// other 32 are cut into 8 chunks of 96: 880 + 2*2R plane times instead of 9 rounds of
+// 96 + 2R = 936).  Ties go to fewer workgroups.  With tiles*chunks == ncu this is the single
 // resident wave in which neighbouring tiles move through z in lockstep.
-static inline void plan_march(March3dArgs &a, int TX, int TY, int R, const LaunchOptions &opt, int wg_per_cu = 1)
+static inline void plan_march(TileMap &m, int nx, int ny, int nz, int TX, int TY, int R, const LaunchOptions &opt,
+                              int wg_per_cu = 1)
 {
-    a.ntx = cdiv_i(a.nx, TX);
-    a.nty = cdiv_i(a.ny, TY);
+    m = TileMap{};
+    m.ntx = cdiv_i(nx, TX);
+    m.nty = cdiv_i(ny, TY);
+    m.nz = nz;
     int dev = 0, ncu = 256, v = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
         ncu = v;
-    a.xcd_map = opt.xcd_map > 0 ? (int)opt.xcd_map : 1;
-    a.band = (int)opt.band;
+    m.xcd_map = opt.xcd_map > 0 ? (int)opt.xcd_map : 1;
+    m.band = (int)opt.band;
     // ids are made XCD-contiguous per group of one workgroup per CU, also where two groups
     // are resident together (measured better than one contiguous range per XCD over both)
-    a.round_blocks = ncu >= 8 ? ncu - ncu % 8 : 8;
+    m.round_blocks = ncu >= 8 ? ncu - ncu % 8 : 8;
     ncu *= wg_per_cu;                                  // workgroups resident at a time
+    const long tiles = (long)m.ntx * m.nty;
+    const int max_chunks = nz / (4 * R) > 0 ? (nz / (4 * R) < 64 ? nz / (4 * R) : 64) : 1;   // chunks of at least 4R planes
     int zchunk = (int)opt.zchunk;
     if (zchunk <= 0) {
-        const long tiles = (long)a.ntx * a.nty;
-        long best_cost = -1;
-        int best_chunks = 1;
-        const int max_chunks = a.nz / (4 * R) > 0 ? a.nz / (4 * R) : 1;   // chunks of at least 4R planes
-        for (int c = 1; c <= max_chunks && c <= 64; ++c) {
-            const long rounds = (tiles * c + ncu - 1) / ncu;
-            const long cost = rounds * (cdiv_i(a.nz, c) + 2 * R);
-            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_chunks = c; }
+        long best_cost = -1, best_blocks = 0;
+        int best_a = 0, best_ca = 1, best_cb = 1;
+        auto consider = [&](long tiles_a, int ca, int cb) {
+            const long blocks = tiles_a * ca + (tiles - tiles_a) * cb;
+            const long cost = (tiles_a * ca + ncu - 1) / ncu * (cdiv_i(nz, ca) + 2 * R) +
+                              ((tiles - tiles_a) * cb + ncu - 1) / ncu * (cdiv_i(nz, cb) + 2 * R);
+            if (best_cost < 0 || cost < best_cost || (cost == best_cost && blocks < best_blocks)) {
+                best_cost = cost; best_blocks = blocks; best_a = (int)tiles_a; best_ca = ca; best_cb = cb;
+            }
+        };
+        for (int c = 1; c <= max_chunks; ++c) consider(0, 1, c);
+        if (opt.split == 0 && tiles < 0x3fffffffL / 64) {
+            for (int ca = 1; ca <= max_chunks && ca <= 8; ++ca) {
+                // the largest number of tiles whose ca chunks fill whole rounds
+                long g = ncu, x = ca;
+                while (x) { const long r = g % x; g = x; x = r; }
+                const long step = ncu / g;
+                const long tiles_a = tiles / step * step;
+                if (tiles_a == 0 || tiles_a == tiles) continue;
+                for (int cb = ca + 1; cb <= max_chunks; ++cb) consider(tiles_a, ca, cb);
+            }
         }
-        zchunk = cdiv_i(a.nz, best_chunks);
+        m.tiles_a = best_a;
+        m.ntz_a = best_a ? best_ca : 0;
+        m.zchunk_a = best_a ? cdiv_i(nz, best_ca) : 0;
+        zchunk = cdiv_i(nz, best_cb);
     }
-    if (zchunk > a.nz) zchunk = a.nz;
+    if (zchunk > nz) zchunk = nz;
     if (zchunk < 1) zchunk = 1;
     // the grid is one-dimensional: keep the number of workgroups a valid int
-    while ((long)a.ntx * a.nty * cdiv_i(a.nz, zchunk) > 0x3fffffffL && zchunk < a.nz) zchunk *= 2;
-    if (zchunk > a.nz) zchunk = a.nz;
-    a.zchunk = zchunk;
-    a.ntz = cdiv_i(a.nz, zchunk);
-    a.total_blocks = a.ntx * a.nty * a.ntz;
+    while (tiles * cdiv_i(nz, zchunk) > 0x3fffffffL && zchunk < nz) zchunk *= 2;
+    if (zchunk > nz) zchunk = nz;
+    m.zchunk = zchunk;
+    m.ntz = cdiv_i(nz, zchunk);
+    if (m.tiles_a) m.ntz_a = cdiv_i(nz, m.zchunk_a);
+    m.blocks_a = m.tiles_a * m.ntz_a;
+    m.total_blocks = m.blocks_a + (int)(tiles - m.tiles_a) * m.ntz;
 }
 
 // The marching kernels are planned for one workgroup per CU (rounds of ncu workgroups that

@@ -49,7 +49,7 @@
 namespace sadj {
 
 template <class T, int R, int BX, int BY, int PY, int PX, int D, bool NTU, bool GUARD, int UPREV>
-__device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int tiy, int tiz,
+__device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int tiy, int zs, int ze,
                                             T *__restrict__ sq)
 {
     using G = Tile3d<T, R, BX, BY, PY, PX>;
@@ -61,8 +61,6 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
     const int nx = a.nx, ny = a.ny, nz = a.nz;
     const size_t plane = (size_t)nx * ny;
     const int x0 = tix * TX, y0 = tiy * TY;
-    const int zs = tiz * a.zchunk;
-    const int ze = min(zs + a.zchunk, nz);
 
     const T *__restrict__ cg = static_cast<const T *>(a.in0);
     const T *__restrict__ rg = static_cast<const T *>(a.in1);
@@ -265,20 +263,20 @@ __global__ __launch_bounds__(BX *BY) void adj_wave3d_kernel(March3dArgs a)
 {
     using G = Tile3d<T, R, BX, BY, PY, PX>;
     __shared__ T sq[2 * G::PLANE];
-    int tix, tiy, tiz;
-    block_to_tile(a, blockIdx.x, tix, tiy, tiz);
+    int tix, tiy, zs, ze;
+    block_to_tile(a.map, blockIdx.x, tix, tiy, zs, ze);
     // core tile: own cells and halo cells all inside I in x and y
     const int x0 = tix * G::TX, y0 = tiy * G::TY;
     const bool core = x0 >= 2 * R && x0 + G::TX + 2 * R <= a.nx && y0 >= 2 * R && y0 + G::TY + 2 * R <= a.ny;
     if (REM == 0) {
-        if (core) adj3d_march<T, R, BX, BY, PY, PX, D, NTU, false, UPREV>(a, tix, tiy, tiz, sq);
-        else      adj3d_march<T, R, BX, BY, PY, PX, D, NTU, true, UPREV>(a, tix, tiy, tiz, sq);
+        if (core) adj3d_march<T, R, BX, BY, PY, PX, D, NTU, false, UPREV>(a, tix, tiy, zs, ze, sq);
+        else      adj3d_march<T, R, BX, BY, PY, PX, D, NTU, true, UPREV>(a, tix, tiy, zs, ze, sq);
     } else if (REM == 1) {
-        adj3d_march<T, R, BX, BY, PY, PX, D, NTU, true, UPREV>(a, tix, tiy, tiz, sq);
+        adj3d_march<T, R, BX, BY, PY, PX, D, NTU, true, UPREV>(a, tix, tiy, zs, ze, sq);
     } else if (REM == 2) {
-        if (core) adj3d_march<T, R, BX, BY, PY, PX, D, NTU, false, UPREV>(a, tix, tiy, tiz, sq);
+        if (core) adj3d_march<T, R, BX, BY, PY, PX, D, NTU, false, UPREV>(a, tix, tiy, zs, ze, sq);
     } else {
-        if (!core) adj3d_march<T, R, BX, BY, PY, PX, D, NTU, true, UPREV>(a, tix, tiy, tiz, sq);
+        if (!core) adj3d_march<T, R, BX, BY, PY, PX, D, NTU, true, UPREV>(a, tix, tiy, zs, ze, sq);
     }
 }
 
@@ -296,8 +294,8 @@ static hipError_t launch_cfg(March3dArgs a, const LaunchOptions &opt, hipStream_
                         aligned_to(a.out0, al) && aligned_to(a.out1, al);
         if (!ok) return launch_cfg<T, R, 64, 8, 4, 1, 1, true>(a, opt, stream);
     }
-    plan_march(a, G::TX, G::TY, R, opt);
-    dim3 grid(a.total_blocks), block(G::NT);
+    plan_march(a.map, a.nx, a.ny, a.nz, G::TX, G::TY, R, opt);
+    dim3 grid(a.map.total_blocks), block(G::NT);
     const unsigned pad = one_workgroup_per_cu_pad(sizeof(T) * 2 * G::PLANE, opt.lds_pad);
     if (opt.remainder != 0) {
         // the strategy study is built for the two default shapes and u_bar only
@@ -361,13 +359,15 @@ void describe_march_plan(int is_f64, int radius, int nx, int ny, int nz, const L
     const int TX = is_f64 ? 64 : 128, TY = 32;
     March3dArgs a{};
     a.nx = nx; a.ny = ny; a.nz = nz;
-    plan_march(a, TX, TY, radius, opt);
-    plan[0] = a.ntx; plan[1] = a.nty; plan[2] = a.ntz; plan[3] = a.zchunk; plan[4] = TX; plan[5] = TY;
+    TileMap &m = a.map;
+    plan_march(m, nx, ny, nz, TX, TY, radius, opt);
+    plan[0] = m.ntx; plan[1] = m.nty; plan[2] = TX; plan[3] = TY; plan[4] = m.total_blocks;
+    plan[5] = m.tiles_a; plan[6] = m.ntz_a; plan[7] = m.ntz;
     if (!tiles) return;
-    for (int b = 0; b < a.total_blocks && b < max_blocks; ++b) {
-        int tix, tiy, tiz;
-        block_to_tile(a, b, tix, tiy, tiz);
-        tiles[3 * b] = tix; tiles[3 * b + 1] = tiy; tiles[3 * b + 2] = tiz;
+    for (int b = 0; b < m.total_blocks && b < max_blocks; ++b) {
+        int tix, tiy, zs, ze;
+        block_to_tile(m, b, tix, tiy, zs, ze);
+        tiles[4 * b] = tix; tiles[4 * b + 1] = tiy; tiles[4 * b + 2] = zs; tiles[4 * b + 3] = ze;
     }
 }
 

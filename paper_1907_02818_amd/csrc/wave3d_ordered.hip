@@ -33,7 +33,7 @@
 namespace sadj {
 
 template <class T, int R, int BX, int BY, int PY, bool GUARD, bool UPREV>
-__device__ __forceinline__ void adj3d_march_ordered(const March3dArgs &a, int tix, int tiy, int tiz,
+__device__ __forceinline__ void adj3d_march_ordered(const March3dArgs &a, int tix, int tiy, int zs, int ze,
                                                     T *__restrict__ lds)
 {
     using G = Tile3d<T, R, BX, BY, PY, 1>;
@@ -44,8 +44,6 @@ __device__ __forceinline__ void adj3d_march_ordered(const March3dArgs &a, int ti
     const int nx = a.nx, ny = a.ny, nz = a.nz;
     const size_t plane = (size_t)nx * ny;
     const int x0 = tix * TX, y0 = tiy * TY;
-    const int zs = tiz * a.zchunk;
-    const int ze = min(zs + a.zchunk, nz);
 
     const T *__restrict__ cg = static_cast<const T *>(a.in0);
     const T *__restrict__ rg = static_cast<const T *>(a.in1);
@@ -232,12 +230,12 @@ __global__ __launch_bounds__(BX *BY) void adj_wave3d_ordered_kernel(March3dArgs 
     using G = Tile3d<T, R, BX, BY, PY, 1>;
     constexpr int NBUF = 1;
     __shared__ T lds[NBUF * R * G::PLANE];          // per |k| a plane of finished terms, see the march
-    int tix, tiy, tiz;
-    block_to_tile(a, blockIdx.x, tix, tiy, tiz);
+    int tix, tiy, zs, ze;
+    block_to_tile(a.map, blockIdx.x, tix, tiy, zs, ze);
     const int x0 = tix * G::TX, y0 = tiy * G::TY;
     const bool core = x0 >= 2 * R && x0 + G::TX + 2 * R <= a.nx && y0 >= 2 * R && y0 + G::TY + 2 * R <= a.ny;
-    if (core) adj3d_march_ordered<T, R, BX, BY, PY, false, UPREV>(a, tix, tiy, tiz, lds);
-    else      adj3d_march_ordered<T, R, BX, BY, PY, true, UPREV>(a, tix, tiy, tiz, lds);
+    if (core) adj3d_march_ordered<T, R, BX, BY, PY, false, UPREV>(a, tix, tiy, zs, ze, lds);
+    else      adj3d_march_ordered<T, R, BX, BY, PY, true, UPREV>(a, tix, tiy, zs, ze, lds);
 }
 
 // 64 x 16 tile, 256 threads, one LDS buffer: two workgroups share a CU, so that one computes
@@ -249,8 +247,8 @@ static hipError_t launch_ordered_T(March3dArgs a, const LaunchOptions &opt, hipS
     constexpr int BX = 64, BY = 4, PY = 4;
     using G = Tile3d<T, R, BX, BY, PY, 1>;
     static_assert(sizeof(T) * R * G::PLANE <= 80 * 1024, "two workgroups must fit into the LDS of a CU");
-    plan_march(a, G::TX, G::TY, R, opt, 2);
-    dim3 grid(a.total_blocks), block(G::NT);
+    plan_march(a.map, a.nx, a.ny, a.nz, G::TX, G::TY, R, opt, 2);
+    dim3 grid(a.map.total_blocks), block(G::NT);
     // exactly two per CU: request LDS up to just over a third of a CU's 160 KB
     constexpr size_t static_lds = sizeof(T) * R * G::PLANE, third = 54 * 1024;
     unsigned pad = static_lds < third ? (unsigned)(third - static_lds) : 0;

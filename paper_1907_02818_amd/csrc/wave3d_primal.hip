@@ -33,16 +33,14 @@ __global__ __launch_bounds__(BX *BY) void primal_wave3d_kernel(March3dArgs a)
     constexpr int NB = R + 2;                       // LDS ring of planes
     __shared__ T sq[NB * G::PLANE];
 
-    int tix, tiy, tiz;
-    block_to_tile(a, blockIdx.x, tix, tiy, tiz);
+    int tix, tiy, zs, ze;
+    block_to_tile(a.map, blockIdx.x, tix, tiy, zs, ze);
 
     const int tid = threadIdx.x;
     const int tx = tid % BX, ty = tid / BX;
     const int nx = a.nx, ny = a.ny, nz = a.nz;
     const size_t plane = (size_t)nx * ny;
     const int x0 = tix * TX, y0 = tiy * TY;
-    const int zs = tiz * a.zchunk;
-    const int ze = min(zs + a.zchunk, nz);
     const T *__restrict__ ug = static_cast<const T *>(a.in0);
     const T *__restrict__ pg = static_cast<const T *>(a.in1);
     const T *__restrict__ cg = static_cast<const T *>(a.in2);
@@ -206,9 +204,9 @@ static hipError_t launch_primal_cfg(March3dArgs a, const LaunchOptions &opt, hip
                         aligned_to_p(a.in2, al) && aligned_to_p(a.out0, al);
         if (!ok) return launch_primal_cfg<T, R, 64, 8, 4, 1>(a, opt, stream);
     }
-    plan_march(a, G::TX, G::TY, R, opt);
+    plan_march(a.map, a.nx, a.ny, a.nz, G::TX, G::TY, R, opt);
     const unsigned pad = one_workgroup_per_cu_pad(sizeof(T) * (R + 2) * G::PLANE, opt.lds_pad);
-    hipLaunchKernelGGL((primal_wave3d_kernel<T, R, BX, BY, PY, PX, true>), dim3(a.total_blocks), dim3(G::NT), pad,
+    hipLaunchKernelGGL((primal_wave3d_kernel<T, R, BX, BY, PY, PX, true>), dim3(a.map.total_blocks), dim3(G::NT), pad,
                        stream, a);
     return hipGetLastError();
     }

@@ -175,29 +175,57 @@ def test_every_option_the_library_knows_is_documented_in_the_header():
         assert isinstance(sadj.get_option(name), int)
 
 
-@pytest.mark.parametrize("xcdmap,band,zchunk", [(0, 0, 0), (1, 0, 7), (2, 0, 0), (3, 0, 16), (1, 3, 0), (2, 8, 5), (1, 2, 33)])
+@pytest.mark.parametrize("xcdmap,band,zchunk,split", [(0, 0, 0, 0), (1, 0, 7, 0), (2, 0, 0, 0), (3, 0, 16, 1), (1, 3, 0, 0),
+                                                      (2, 8, 5, 0), (1, 2, 33, 0), (0, 0, 0, 1), (3, 4, 0, 0)])
 @pytest.mark.parametrize("dtype_code,radius,shape", [(1, 4, (512, 512, 512)), (1, 4, (300, 500, 700)), (0, 4, (512, 512, 512)),
                                                      (1, 1, (1000, 1000, 1000)), (1, 2, (9, 9, 9)), (0, 3, (100, 33, 65)),
-                                                     (1, 4, (768, 768, 768)), (1, 1, (3, 3, 3))])
-def test_workgroups_tile_the_grid_exactly_once(dtype_code, radius, shape, xcdmap, band, zchunk):
-    """Disjoint cover (Section 3.3.4): under every mapping option the workgroup ids map
-    one-to-one onto (tile, z-chunk) pairs, and the tiles and chunks cover the grid."""
+                                                     (1, 4, (768, 768, 768)), (1, 1, (3, 3, 3)), (1, 4, (400, 400, 400)),
+                                                     (0, 1, (896, 896, 896)), (1, 4, (640, 640, 640))])
+def test_workgroups_tile_the_grid_exactly_once(dtype_code, radius, shape, xcdmap, band, zchunk, split):
+    """Disjoint cover (Section 3.3.4): under every mapping option the workgroups' (tile,
+    range of planes) pairs are disjoint and cover the grid: every tile of the x-y tiling
+    appears, and the plane ranges of each tile partition 0 .. nz."""
     nz, ny, nx = shape
     try:
         sadj.set_option("wave3d.xcdmap", xcdmap)
         sadj.set_option("wave3d.band", band)
         sadj.set_option("wave3d.zchunk", zchunk)
+        sadj.set_option("wave3d.split", split)
         info, tiles = sadj.sadj_describe_wave3d_plan(dtype_code, radius, nx, ny, nz)
     finally:
         sadj.set_option("wave3d.xcdmap", 0)
         sadj.set_option("wave3d.band", 0)
         sadj.set_option("wave3d.zchunk", 0)
+        sadj.set_option("wave3d.split", 0)
     assert info["ntx"] * info["tile_w"] >= nx > (info["ntx"] - 1) * info["tile_w"]
     assert info["nty"] * info["tile_h"] >= ny > (info["nty"] - 1) * info["tile_h"]
-    assert info["ntz"] * info["zchunk"] >= nz > (info["ntz"] - 1) * info["zchunk"]
-    want = {(x, y, z) for z in range(info["ntz"]) for y in range(info["nty"]) for x in range(info["ntx"])}
-    assert len(tiles) == len(want)
-    assert set(tiles) == want
+    assert len(tiles) == info["workgroups"]
+    ntiles = info["ntx"] * info["nty"]
+    assert info["workgroups"] == info["tiles_a"] * info["ntz_a"] + (ntiles - info["tiles_a"]) * info["ntz"]
+    if split == 1 or zchunk:
+        assert info["tiles_a"] == 0
+    ranges = {}
+    for x, y, zs, ze in tiles:
+        assert 0 <= x < info["ntx"] and 0 <= y < info["nty"] and 0 <= zs < ze <= nz
+        ranges.setdefault((x, y), []).append((zs, ze))
+    assert len(ranges) == ntiles
+    for key, rs in ranges.items():
+        rs.sort()
+        assert rs[0][0] == 0 and rs[-1][1] == nz, key
+        assert all(a[1] == b[0] for a, b in zip(rs, rs[1:])), key
+
+
+def test_left_over_tiles_are_cut_finer_where_that_fills_the_chip():
+    """768^3 in 64 x 32 tiles on 256 compute units (the count the planner assumes without a
+    GPU): 288 tiles = one full round marching all planes + 32 tiles that are cut so that
+    they fill a round too."""
+    info, tiles = sadj.sadj_describe_wave3d_plan(1, 4, 768, 768, 768)
+    assert (info["ntx"], info["nty"]) == (12, 24)
+    assert (info["tiles_a"], info["ntz_a"], info["ntz"]) == (256, 1, 8)
+    assert info["workgroups"] == 512
+    # 512^3: two chunks of every tile fill the chip exactly; nothing is left over
+    info, _ = sadj.sadj_describe_wave3d_plan(1, 4, 512, 512, 512, with_tiles=False)
+    assert (info["tiles_a"], info["ntz"], info["workgroups"]) == (0, 2, 256)
 
 
 def test_gather_kernels_use_no_atomics():

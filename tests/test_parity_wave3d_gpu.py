@@ -54,6 +54,7 @@ def sadj():
     lib.set_option("wave3d.variant", 0)
     lib.set_option("wave3d.remainder", 0)
     lib.set_option("wave3d.order", 0)
+    lib.set_option("wave3d.split", 0)
 
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
@@ -316,6 +317,38 @@ def test_primal_small(sadj, radius, shape, dtype):
     m = interior_mask(shape, radius)
     assert np.array_equal(got[~m], r0[~m])                 # r outside I untouched
     assert_close(got[m], want[m], _primal_scale(d, radius)[m], dtype, "primal R=%d %s" % (radius, shape))
+
+
+# shapes whose x-y tiles do not fill whole rounds of the chip's compute units, so that the
+# left-over tiles are cut into more z-chunks than the others (two groups of workgroups)
+TWO_GROUP = [(np.float64, 4, (64, 580, 520)), (np.float64, 1, (24, 400, 610)), (np.float64, 2, (64, 130, 1150)),
+             (np.float64, 3, (100, 100, 1420)), (np.float32, 1, (24, 400, 1240))]
+
+
+@pytest.mark.parametrize("dtype,radius,shape", TWO_GROUP)
+def test_shapes_whose_left_over_tiles_are_cut_finer(sadj, dtype, radius, shape):
+    nz, ny, nx = shape
+    info, tiles = sadj.sadj_describe_wave3d_plan(1 if dtype == np.float64 else 0, radius, nx, ny, nz)
+    if info["tiles_a"] == 0:
+        pytest.skip("this device's compute-unit count does not leave tiles over at this shape")
+    assert len({ze - zs for _, _, zs, ze in tiles}) >= 2
+    d = inputs.wave_inputs(shape, 0.01, 0.1, seed=sum(shape), dtype=dtype, c_mode="iid")
+    _check_adjoint(sadj, d, radius, dtype, with_prev=True, what="two groups R=%d %s" % (radius, shape))
+    sadj.set_option("wave3d.split", 1)
+    try:
+        alike, _ = _run_adjoint(sadj, d, radius, False)
+    finally:
+        sadj.set_option("wave3d.split", 0)
+    finer, _ = _run_adjoint(sadj, d, radius, False)
+    assert np.array_equal(alike, finer)              # the cut along z does not change any value
+    r0 = inputs.uniform(3, "aux", shape, -1, 1).astype(dtype)
+    r = to_gpu(r0)
+    sadj.sadj_primal_wave3d(radius, to_gpu(d["u"]), to_gpu(d["u_prev"]), to_gpu(d["c"]), r)
+    got = to_host(r)
+    want = oracle.wave_primal(d["u"], d["u_prev"], d["c"], radius, r_init=r0)
+    m = interior_mask(shape, radius)
+    assert np.array_equal(got[~m], r0[~m])
+    assert_close(got[m], want[m], _primal_scale(d, radius)[m], dtype, "primal two groups R=%d %s" % (radius, shape))
 
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
