@@ -226,16 +226,17 @@ static inline bool star_aligned(const void *p, size_t n) { return (reinterpret_c
 
 // 16 bytes per lane (two doubles / four floats), 32 x 16 threads, two rows per thread, as the
 // wave kernels; needs nx to be a multiple of the vector length and vector-aligned arrays,
-// otherwise 64 x 8 threads with one cell per lane and four rows.  One workgroup per CU.  (A
-// 64 x 16 tile with two workgroups per CU measured +4 points for the radius-4 primal and -3
-// for the adjoint.)
+// otherwise 64 x 8 threads with one cell per lane and four rows.  One workgroup per CU (a
+// 64 x 16 tile with two workgroups per CU measured 4-11 points slower for the radius-3 and -4
+// primal at 512^3).
 template <class T, int R, bool ADJ>
 static hipError_t launch_star_TR(const StarArgs &a, const LaunchOptions &opt, hipStream_t stream)
 {
     constexpr int PXV = 16 / sizeof(T);
     const bool ok = a.nx % PXV == 0 && star_aligned(a.in0, 16) && star_aligned(a.in1, 16) && star_aligned(a.out, 16);
-    // the primal of radius 1 and 2 measured 2-3 points faster with the one-cell shape
-    const bool wide = ADJ || R >= 3;
+    // the primal measured 2-6 points faster with the one-cell shape for radius 1 and 2, and for
+    // radius 3 in fp32 (512^3: 63 vs 58 %); 10-12 points slower for radius 4 and radius 3 fp64
+    const bool wide = ADJ || R == 4 || (R == 3 && sizeof(T) == 8);
     if (ok && wide && opt.variant != 3) return launch_star_shape<T, R, ADJ, 32, 16, 2, PXV>(a, opt, stream);
     return launch_star_shape<T, R, ADJ, 64, 8, 4, 1>(a, opt, stream);
 }
