@@ -46,6 +46,8 @@
 #ifndef SADJ_H
 #define SADJ_H
 
+#include <stddef.h>
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -53,10 +55,12 @@ extern "C" {
 typedef enum {
     SADJ_OK = 0,
     SADJ_ERR_NULL = 1,        /* a required pointer is NULL                              */
-    SADJ_ERR_SIZE = 2,        /* an extent is < 2R+1 or above the documented limits      */
+    SADJ_ERR_SIZE = 2,        /* an extent is < 2R+1 or above the documented limits, or
+                                 (sadj_check_array) an array runs past its allocation    */
     SADJ_ERR_ALIAS = 3,       /* an output array overlaps an input array                 */
     SADJ_ERR_UNSUPPORTED = 4, /* dtype or radius not built, unknown option               */
-    SADJ_ERR_DEVICE = 5       /* HIP reported an error when enqueueing                   */
+    SADJ_ERR_DEVICE = 5       /* HIP reported an error when enqueueing, or
+                                 (sadj_check_array) memory the device cannot access      */
 } sadj_status;
 
 typedef enum { SADJ_F32 = 0, SADJ_F64 = 1 } sadj_dtype;
@@ -275,11 +279,28 @@ sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, lon
  *                    bit.  Both orders are deterministic.  "wave3d.variant" and
  *                    "wave3d.remainder" do not apply to order 1; other entry points
  *                    ignore this option.
+ *   "check.pointers" 1: before anything is enqueued, every array argument of every entry
+ *                    point is checked with sadj_check_array (below); a call with a failing
+ *                    array returns that status and launches nothing.  Default 0: pointers
+ *                    are trusted, as the conventions above say (the check costs a few
+ *                    runtime queries per array).
  * Unknown names or out-of-range values give SADJ_ERR_UNSUPPORTED and change nothing.
  * sadj_get_option returns SADJ_OK and stores the value, or SADJ_ERR_UNSUPPORTED.
  */
 sadj_status sadj_set_option(const char *name, long value);
 sadj_status sadj_get_option(const char *name, long *value);
+
+/* ---- diagnostic: can a kernel on the current device use this array? ------------------------
+ * For callers that want wrong pointers or sizes turned into a status instead of a GPU memory
+ * fault.  Queries the HIP runtime; enqueues nothing.  SADJ_OK: [p, p+bytes) lies inside one
+ * allocation of device, managed or pinned host memory that the current device can access.
+ * SADJ_ERR_DEVICE: the runtime does not know the pointer (pageable host memory, a stale or
+ * made-up address), or it belongs to a device the current one cannot access.  SADJ_ERR_SIZE:
+ * the range runs past the end of the allocation p points into.  SADJ_ERR_NULL: p is NULL.
+ * An allocation here is what the runtime handed out: with a caching allocator on top (torch's),
+ * a tensor smaller than its block passes for the block's size.
+ */
+sadj_status sadj_check_array(const void *p /* device or host */, size_t bytes);
 
 #ifdef __cplusplus
 }

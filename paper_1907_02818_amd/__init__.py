@@ -18,6 +18,8 @@ __all__ = [
     "sadj_primal_wave1d", "sadj_adjoint_wave1d", "sadj_primal_wave2d", "sadj_adjoint_wave2d",
     "sadj_primal_wave3d", "sadj_adjoint_wave3d", "sadj_primal_burgers1d", "sadj_adjoint_burgers1d",
     "sadj_adjoint_wave3d_steps", "sadj_primal_box", "sadj_adjoint_box",
+    "sadj_primal_star3d", "sadj_adjoint_star3d", "sadj_primal_burgers1d_steps", "sadj_adjoint_burgers1d_steps",
+    "sadj_adjoint_wave3d_atomic_scatter", "sadj_describe_wave3d_plan", "sadj_check_array",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -76,12 +78,13 @@ def load() -> ctypes.CDLL:
     lib.sadj_adjoint_burgers1d.argtypes = [I, L, D, D, P, P, P, P]
     lib.sadj_primal_burgers1d_steps.argtypes = [I, L, L, D, D, P, P]
     lib.sadj_adjoint_burgers1d_steps.argtypes = [I, L, L, L, D, D, P, P, P, P]
+    lib.sadj_check_array.argtypes = [P, ctypes.c_size_t]
     for name in ("sadj_set_option", "sadj_get_option", "sadj_primal_wave1d", "sadj_adjoint_wave1d",
                  "sadj_primal_wave2d", "sadj_adjoint_wave2d", "sadj_primal_wave3d", "sadj_adjoint_wave3d",
                  "sadj_primal_burgers1d", "sadj_adjoint_burgers1d", "sadj_adjoint_wave3d_steps",
                  "sadj_primal_box", "sadj_adjoint_box", "sadj_adjoint_wave3d_atomic_scatter", "sadj_describe_wave3d_plan",
                  "sadj_primal_star3d", "sadj_adjoint_star3d",
-                 "sadj_primal_burgers1d_steps", "sadj_adjoint_burgers1d_steps"):
+                 "sadj_primal_burgers1d_steps", "sadj_adjoint_burgers1d_steps", "sadj_check_array"):
         getattr(lib, name).restype = I
     _lib = lib
     return lib
@@ -169,6 +172,11 @@ def sadj_primal_wave3d(radius: int, u, u_prev, c, r) -> None:
 def sadj_adjoint_wave3d(radius: int, c, r_bar, u_bar, u_prev_bar=None) -> None:
     code, (nz, ny, nx), p, s = _marshal([c, r_bar, u_bar, u_prev_bar], 3, optional=(3,))
     _check(load().sadj_adjoint_wave3d(code, int(radius), nx, ny, nz, *p, s))
+
+
+def sadj_check_array(address: int, nbytes: int) -> int:
+    """Status (0 = ok) of the library's pointer check for the byte range at `address`."""
+    return int(load().sadj_check_array(ctypes.c_void_p(int(address)), int(nbytes)))
 
 
 def sadj_describe_wave3d_plan(dtype_code: int, radius: int, nx: int, ny: int, nz: int, with_tiles: bool = True):

@@ -41,17 +41,55 @@ bool overlaps(const Span &a, const Span &b)
 bool dtype_ok(sadj_dtype d) { return d == SADJ_F32 || d == SADJ_F64; }
 size_t elem(sadj_dtype d) { return d == SADJ_F64 ? 8 : 4; }
 
-// Outputs must not overlap inputs, nor each other.
+std::atomic<long> g_check_pointers{0};
+
+// Optional argument check (option "check.pointers"): the whole array must lie in memory a
+// kernel on the current device can access (device, managed or pinned host memory) and inside
+// one allocation.  Queries only; nothing is enqueued.
+sadj_status check_span_memory(const Span &a)
+{
+    if (!a.p || a.bytes == 0) return SADJ_OK;
+    hipPointerAttribute_t attr{};
+    hipError_t e = hipPointerGetAttributes(&attr, a.p);
+    if (e != hipSuccess) { (void)hipGetLastError(); return SADJ_ERR_DEVICE; }   // not known to the runtime
+    if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged && attr.type != hipMemoryTypeHost)
+        return SADJ_ERR_DEVICE;                                                  // pageable host memory
+    if (attr.type == hipMemoryTypeDevice) {
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return SADJ_ERR_DEVICE; }
+        if (attr.device != dev) {
+            int peer = 0;
+            if (hipDeviceCanAccessPeer(&peer, dev, attr.device) != hipSuccess || !peer) {
+                (void)hipGetLastError();
+                return SADJ_ERR_DEVICE;
+            }
+        }
+    }
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    e = hipMemGetAddressRange(&base, &size, const_cast<void *>(a.p));
+    if (e != hipSuccess) { (void)hipGetLastError(); return SADJ_ERR_DEVICE; }
+    const uintptr_t b0 = (uintptr_t)base, p0 = (uintptr_t)a.p;
+    if (p0 < b0 || a.bytes > size || p0 - b0 > size - a.bytes) return SADJ_ERR_SIZE;
+    return SADJ_OK;
+}
+
+// Outputs must not overlap inputs, nor each other; with "check.pointers" on, every array must
+// also be memory the device can access, in full.
 template <size_t NI, size_t NO>
-bool any_alias(const Span (&in)[NI], const Span (&out)[NO])
+sadj_status check_arrays(const Span (&in)[NI], const Span (&out)[NO])
 {
     for (size_t o = 0; o < NO; ++o) {
         for (size_t i = 0; i < NI; ++i)
-            if (overlaps(out[o], in[i])) return true;
+            if (overlaps(out[o], in[i])) return SADJ_ERR_ALIAS;
         for (size_t o2 = o + 1; o2 < NO; ++o2)
-            if (overlaps(out[o], out[o2])) return true;
+            if (overlaps(out[o], out[o2])) return SADJ_ERR_ALIAS;
     }
-    return false;
+    if (g_check_pointers.load() == 1) {
+        for (size_t i = 0; i < NI; ++i) { const sadj_status s = check_span_memory(in[i]); if (s != SADJ_OK) return s; }
+        for (size_t o = 0; o < NO; ++o) { const sadj_status s = check_span_memory(out[o]); if (s != SADJ_OK) return s; }
+    }
+    return SADJ_OK;
 }
 
 sadj_status check_extents(int radius, long nx, long ny, long nz, int ndim)
@@ -98,6 +136,13 @@ const char *sadj_version(void) { return "0.1.0"; }
 
 const char *sadj_last_device_error(void) { return hipGetErrorString(g_last_hip_error); }
 
+// Diagnostic: the check that "check.pointers" applies to every array argument.
+sadj_status sadj_check_array(const void *p, size_t bytes)
+{
+    if (!p) return SADJ_ERR_NULL;
+    return check_span_memory({p, bytes});
+}
+
 sadj_status sadj_set_option(const char *name, long value)
 {
     if (!name) return SADJ_ERR_NULL;
@@ -119,6 +164,11 @@ sadj_status sadj_set_option(const char *name, long value)
     if (!std::strcmp(name, "wave2d.variant")) {
         if (value < 0 || value > 15) return SADJ_ERR_UNSUPPORTED;
         g_variant2d = value;
+        return SADJ_OK;
+    }
+    if (!std::strcmp(name, "check.pointers")) {
+        if (value < 0 || value > 1) return SADJ_ERR_UNSUPPORTED;
+        g_check_pointers = value;
         return SADJ_OK;
     }
     if (!std::strcmp(name, "wave3d.split")) {
@@ -169,6 +219,7 @@ sadj_status sadj_get_option(const char *name, long *value)
     if (!std::strcmp(name, "wave2d.variant")) { *value = g_variant2d; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.remainder")) { *value = g_remainder; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.split")) { *value = g_split; return SADJ_OK; }
+    if (!std::strcmp(name, "check.pointers")) { *value = g_check_pointers; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.order")) { *value = g_order; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.xcdmap")) { *value = g_xcdmap; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.band")) { *value = g_band; return SADJ_OK; }
@@ -188,7 +239,7 @@ static sadj_status primal_wave(int ndim, sadj_dtype dtype, int radius, long nx, 
     const size_t bytes = (size_t)nx * ny * nz * elem(dtype);
     const Span in[3] = {{u, bytes}, {u_prev, bytes}, {c, bytes}};
     const Span out[1] = {{r, bytes}};
-    if (any_alias(in, out)) return SADJ_ERR_ALIAS;
+    if (sadj_status al = check_arrays(in, out); al != SADJ_OK) return al;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int f64 = dtype == SADJ_F64;
     clear_stale_hip_error();
@@ -211,7 +262,7 @@ static sadj_status adjoint_wave(int ndim, sadj_dtype dtype, int radius, long nx,
     const size_t bytes = (size_t)nx * ny * nz * elem(dtype);
     const Span in[2] = {{c, bytes}, {r_bar, bytes}};
     const Span out[2] = {{u_bar, bytes}, {u_prev_bar, u_prev_bar ? bytes : 0}};
-    if (any_alias(in, out)) return SADJ_ERR_ALIAS;
+    if (sadj_status al = check_arrays(in, out); al != SADJ_OK) return al;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int f64 = dtype == SADJ_F64;
     clear_stale_hip_error();
@@ -287,7 +338,7 @@ sadj_status sadj_adjoint_wave3d_atomic_scatter(sadj_dtype dtype, int radius, lon
     const size_t bytes = (size_t)nx * ny * nz * elem(dtype);
     const Span in[2] = {{c, bytes}, {r_bar, bytes}};
     const Span out[1] = {{u_bar, bytes}};
-    if (any_alias(in, out)) return SADJ_ERR_ALIAS;
+    if (sadj_status al = check_arrays(in, out); al != SADJ_OK) return al;
     clear_stale_hip_error();
     return from_hip(sadj::launch_adjoint_wave3d_scatter_atomic(dtype == SADJ_F64, radius, (int)nx, (int)ny, (int)nz, c,
                                                                r_bar, u_bar, static_cast<hipStream_t>(stream)));
@@ -306,7 +357,7 @@ sadj_status sadj_adjoint_wave3d_steps(sadj_dtype dtype, int radius, long nx, lon
     const size_t bytes = (size_t)nx * ny * nz * elem(dtype);
     const Span in[1] = {{c, bytes}};
     const Span out[3] = {{lam0, bytes}, {lam1, bytes}, {lam2, bytes}};
-    if (any_alias(in, out)) return SADJ_ERR_ALIAS;
+    if (sadj_status al = check_arrays(in, out); al != SADJ_OK) return al;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int f64 = dtype == SADJ_F64;
     void *lam[3] = {lam0, lam1, lam2};
@@ -336,7 +387,7 @@ static sadj_status box_call(int adjoint, sadj_dtype dtype, int ndim, long nx, lo
     const size_t bytes = (size_t)nx * ny * nz * elem(dtype);
     const Span in[2] = {{in0, bytes}, {in1, bytes}};
     const Span outs[1] = {{out, bytes}};
-    if (any_alias(in, outs)) return SADJ_ERR_ALIAS;
+    if (sadj_status al = check_arrays(in, outs); al != SADJ_OK) return al;
     // expand the caller's 3^ndim table to 27 entries (x fastest); the adjoint gathers with
     // the point-mirrored table W[o] = w[-o] (index shifting)
     double full[27] = {0};
@@ -380,7 +431,7 @@ static sadj_status star_call(int adjoint, sadj_dtype dtype, int radius, long nx,
     const size_t bytes = (size_t)nx * ny * nz * elem(dtype);
     const Span in[2] = {{in0, bytes}, {in1, bytes}};
     const Span outs[1] = {{out, bytes}};
-    if (any_alias(in, outs)) return SADJ_ERR_ALIAS;
+    if (sadj_status al = check_arrays(in, outs); al != SADJ_OK) return al;
     // caller's table: centre, then per axis the offsets -R..-1, +1..+R; the adjoint gathers
     // with the mirrored table W[d][o] = w[d][-o] (index shifting)
     double w[3][8] = {};
@@ -414,7 +465,7 @@ sadj_status sadj_primal_burgers1d(sadj_dtype dtype, long n, double C, double D, 
     const size_t bytes = (size_t)n * elem(dtype);
     const Span in[1] = {{u, bytes}};
     const Span out[1] = {{r, bytes}};
-    if (any_alias(in, out)) return SADJ_ERR_ALIAS;
+    if (sadj_status al = check_arrays(in, out); al != SADJ_OK) return al;
     clear_stale_hip_error();
     if (g_functor1d.load() == 1)
         return from_hip(sadj::launch_burgers1d_functor(0, dtype == SADJ_F64, n, C, D, u, nullptr, r, static_cast<hipStream_t>(stream)));
@@ -430,7 +481,7 @@ sadj_status sadj_adjoint_burgers1d(sadj_dtype dtype, long n, double C, double D,
     const size_t bytes = (size_t)n * elem(dtype);
     const Span in[2] = {{u, bytes}, {r_bar, bytes}};
     const Span out[1] = {{u_bar, bytes}};
-    if (any_alias(in, out)) return SADJ_ERR_ALIAS;
+    if (sadj_status al = check_arrays(in, out); al != SADJ_OK) return al;
     clear_stale_hip_error();
     if (g_functor1d.load() == 1)
         return from_hip(sadj::launch_burgers1d_functor(1, dtype == SADJ_F64, n, C, D, u, r_bar, u_bar,
@@ -447,6 +498,8 @@ sadj_status sadj_primal_burgers1d_steps(sadj_dtype dtype, long n, long nsteps, d
     if (!states) return SADJ_ERR_NULL;
     if (n < 3 || n > kMaxExtent || nsteps < 0 || nsteps > kMaxExtent) return SADJ_ERR_SIZE;
     const size_t row = (size_t)n * elem(dtype);
+    if (g_check_pointers.load() == 1)
+        if (sadj_status m = check_span_memory({states, (size_t)(nsteps + 1) * row}); m != SADJ_OK) return m;
     clear_stale_hip_error();
     char *base = static_cast<char *>(states);
     for (long t = 0; t < nsteps; ++t) {
@@ -467,7 +520,7 @@ sadj_status sadj_adjoint_burgers1d_steps(sadj_dtype dtype, long n, long last, lo
     // states u^{last-nsteps} .. u^{last-1} are read; lam0, lam1 are written
     const Span in[1] = {{static_cast<const char *>(states) + (size_t)(last - nsteps) * row, (size_t)nsteps * row}};
     const Span out[2] = {{lam0, row}, {lam1, row}};
-    if (any_alias(in, out)) return SADJ_ERR_ALIAS;
+    if (sadj_status al = check_arrays(in, out); al != SADJ_OK) return al;
     clear_stale_hip_error();
     void *lam[2] = {lam0, lam1};
     const char *base = static_cast<const char *>(states);

@@ -167,9 +167,9 @@ def test_functor_header_example_is_built_and_exports_its_entry_points():
 def test_every_option_the_library_knows_is_documented_in_the_header():
     """Option names are plain strings; the header's list and the library's must agree."""
     header = open(HEADER).read()
-    documented = set(re.findall(r'"((?:wave[23]d|stencil1d)\.[a-z0-9]+)"', header))
+    documented = set(re.findall(r'"((?:wave[23]d|stencil1d|check)\.[a-z0-9]+)"', header))
     src = open(os.path.join(ROOT, "paper_1907_02818_amd", "csrc", "api.hip")).read()
-    known = set(re.findall(r'"((?:wave[23]d|stencil1d)\.[a-z0-9]+)"', src))
+    known = set(re.findall(r'"((?:wave[23]d|stencil1d|check)\.[a-z0-9]+)"', src))
     assert documented == known
     for name in sorted(known):
         assert isinstance(sadj.get_option(name), int)
@@ -226,6 +226,23 @@ def test_left_over_tiles_are_cut_finer_where_that_fills_the_chip():
     # 512^3: two chunks of every tile fill the chip exactly; nothing is left over
     info, _ = sadj.sadj_describe_wave3d_plan(1, 4, 512, 512, 512, with_tiles=False)
     assert (info["tiles_a"], info["ntz"], info["workgroups"]) == (0, 2, 256)
+
+
+def test_pointer_check_rejects_memory_the_device_cannot_use():
+    """sadj_check_array on pageable host memory, and an entry point with "check.pointers"
+    on: a status comes back and nothing is launched (holds with or without a GPU)."""
+    import numpy as np
+    a = np.zeros(1024)
+    assert sadj.sadj_check_array(a.ctypes.data, a.nbytes) == 5
+    assert sadj.sadj_check_array(0, 8) == 1
+    bufs = [np.zeros(4096) for _ in range(3)]
+    lib = sadj.load()
+    sadj.set_option("check.pointers", 1)
+    try:
+        st = lib.sadj_adjoint_wave1d(1, 4096, bufs[0].ctypes.data, bufs[1].ctypes.data, bufs[2].ctypes.data, None, None)
+    finally:
+        sadj.set_option("check.pointers", 0)
+    assert st == 5
 
 
 def test_gather_kernels_use_no_atomics():

@@ -1,0 +1,59 @@
+"""The optional pointer check (sadj_check_array, option "check.pointers") against real
+allocations.  Only queries are made with bad arguments; every launch here has valid ones."""
+import numpy as np
+import pytest
+
+import inputs
+from parity import to_gpu, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sadj():
+    import paper_1907_02818_amd as lib
+    lib.load()
+    yield lib
+    lib.set_option("check.pointers", 0)
+
+
+def test_check_array_on_device_pinned_and_pageable_memory(sadj):
+    import torch
+    t = torch.zeros(1 << 20, dtype=torch.float64, device="cuda")
+    assert sadj.sadj_check_array(t.data_ptr(), t.numel() * 8) == 0
+    assert sadj.sadj_check_array(t.data_ptr() + 800, t.numel() * 8 - 800) == 0      # a view into it
+    assert sadj.sadj_check_array(t.data_ptr(), 1 << 42) == 2                         # past any allocation
+    pinned = torch.zeros(4096, dtype=torch.float64, pin_memory=True)
+    assert sadj.sadj_check_array(pinned.data_ptr(), pinned.numel() * 8) == 0
+    host = np.zeros(4096)
+    assert sadj.sadj_check_array(host.ctypes.data, host.nbytes) == 5
+    assert sadj.sadj_check_array(0, 8) == 1
+
+
+def test_range_past_the_end_of_its_own_allocation(sadj):
+    """A 64 MiB tensor gets an allocation of its own from torch's allocator (requests above
+    10 MiB are not carved out of a shared block), so one element more does not fit."""
+    import torch
+    nbytes = 64 << 20
+    t = torch.empty(nbytes // 8, dtype=torch.float64, device="cuda")
+    assert sadj.sadj_check_array(t.data_ptr(), nbytes) == 0
+    if sadj.sadj_check_array(t.data_ptr(), nbytes + 8) == 0:
+        pytest.skip("this allocator configuration backs the tensor with a larger allocation")
+    assert sadj.sadj_check_array(t.data_ptr(), nbytes + 8) == 2
+    assert sadj.sadj_check_array(t.data_ptr() + 8, nbytes) == 2
+    assert sadj.sadj_check_array(t.data_ptr() + 8, nbytes - 8) == 0
+
+
+def test_results_do_not_depend_on_the_check(sadj):
+    import torch
+    shape = (20, 33, 70)
+    d = inputs.wave_inputs(shape, 0.01, 0.1, seed=5, dtype=np.float64, c_mode="iid")
+    out = []
+    for on in (0, 1):
+        sadj.set_option("check.pointers", on)
+        ub, up = to_gpu(d["u_bar"]), to_gpu(d["u_prev_bar"])
+        sadj.sadj_adjoint_wave3d(4, to_gpu(d["c"]), to_gpu(d["r_bar"]), ub, up)
+        torch.cuda.synchronize()
+        out.append((to_host(ub), to_host(up)))
+    sadj.set_option("check.pointers", 0)
+    assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
