@@ -105,6 +105,9 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other workloads")
     ap.add_argument("--remainder-study", action="store_true",
                     help="also time the three remainder strategies of the 3-D adjoint")
+    ap.add_argument("--paper-sizes", action="store_true",
+                    help="also time the paper's own two experiments (1000^3 wave step, 10^9-cell Burgers step; "
+                         "needs about 35 GB of device memory)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--size", type=int, default=512, help="grid edge of the headline workload")
     ap.add_argument("--copy-probe", action="store_true",
@@ -287,6 +290,41 @@ def main():
         add("wave1d_f64_adjoint_n4096_in_hip_graph_per_call", graph.replay, n1 * per_graph, 32 * n1 * per_graph, "f64")
         for key in ("ms", "kernel_ms_mean"):
             others["wave1d_f64_adjoint_n4096_in_hip_graph_per_call"][key] /= per_graph
+    if args.paper_sizes:
+        # The paper's experiments (Section 4.1: one step of the 7-point wave solver on 1000^3;
+        # Section 4.2: one Burgers step on 10^9 cells), fp64, synthetic values.  The paper's
+        # best gather-adjoint and primal times are quoted as context with their hardware
+        # (one 12-core Xeon E5-2650 v4 socket; Xeon Phi 7210); they are not a baseline for `value`.
+        s3 = (1000, 1000, 1000)
+        N3 = s3[0] * s3[1] * s3[2]
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(1907)
+        cw = torch.rand(s3, generator=gen, device=dev, dtype=torch.float64) * 0.09 + 0.01
+        a1, a2, a3 = (torch.rand(s3, generator=gen, device=dev, dtype=torch.float64) * 2 - 1 for _ in range(3))
+
+        def add_paper(name, fn, points, nbytes, paper):
+            add(name, fn, points, nbytes, "f64")
+            others[name]["paper_context"] = dict(paper, note="the paper's timing on its own hardware; context only")
+            others[name]["paper_context"]["time_ratio_paper_over_here"] = paper["seconds_best"] / (others[name]["ms"] * 1e-3)
+
+        add_paper("paper_wave3d_7pt_1000^3_f64_adjoint_u_bar_and_u_prev_bar",
+                  lambda: sadj.sadj_adjoint_wave3d(1, cw, a1, a2, a3), N3, wave_adjoint_bytes(s3, 1, 8, True),
+                  {"seconds_best": 1.322396, "hardware": "Xeon E5-2650 v4, 12 threads",
+                   "seconds_best_other": 1.286821, "hardware_other": "Xeon Phi 7210, 64 threads"})
+        add_paper("paper_wave3d_7pt_1000^3_f64_primal",
+                  lambda: sadj.sadj_primal_wave3d(1, a2, a3, cw, a1), N3, 8 * N3 + 24 * interior_points(s3, 1),
+                  {"seconds_best": 0.897188, "hardware": "Xeon E5-2650 v4, 12 threads",
+                   "seconds_best_other": 0.843320, "hardware_other": "Xeon Phi 7210, 32 threads"})
+        ub1d, rb1d, ubar1d, r1d = (t.reshape(-1) for t in (a1, a2, a3, cw))
+        add_paper("paper_burgers1d_1e9_f64_adjoint",
+                  lambda: sadj.sadj_adjoint_burgers1d(0.1, 0.05, ub1d, rb1d, ubar1d), N3, 32 * N3,
+                  {"seconds_best": 1.535777, "hardware": "Xeon E5-2650 v4, 12 threads",
+                   "seconds_best_other": 0.756979, "hardware_other": "Xeon Phi 7210, 128 threads"})
+        add_paper("paper_burgers1d_1e9_f64_primal",
+                  lambda: sadj.sadj_primal_burgers1d(0.1, 0.05, ub1d, r1d), N3, 16 * N3,
+                  {"seconds_best": 0.555659, "hardware": "Xeon E5-2650 v4, 12 threads",
+                   "seconds_best_other": 0.502064, "hardware_other": "Xeon Phi 7210, 128 threads"})
+        del cw, a1, a2, a3, ub1d, rb1d, ubar1d, r1d
     out["others"] = others
     if args.copy_probe:
         ub.copy_(c)

@@ -184,6 +184,23 @@ static inline void plan_march(TileMap &m, int nx, int ny, int nz, int TX, int TY
     m.total_blocks = m.blocks_a + (int)(tiles - m.tiles_a) * m.ntz;
 }
 
+// Radius 1, rows whose length in bytes is not a multiple of the 128-byte cache line (nx = 1000
+// in fp64: every other row starts in the middle of a line).  Tile rows then begin and end
+// inside a line on most rows, and tiles with long rows (fewer row ends per byte) measured
+// 4-10 points faster than the default shapes (500^3, 1000^3, 200 x 700 x 1500, fp64 and
+// fp32, adjoint and primal), while for line-aligned rows they measured equal or slower.  The
+// radius-1 kernels keep three running sums per cell, so eight cells per lane fit the register
+// file.  Returns the tile width in cells to use (512: fp32 adjoint only; 256), or 0 for the
+// default shape; a width qualifies if its tiles cover nx with at most 10 % idle columns.
+static inline int wide_tile_for_unaligned_rows(int nx, size_t elem_bytes, bool allow_512)
+{
+    if (((size_t)nx * elem_bytes) % 128 == 0) return 0;
+    auto fills = [nx](int tx) { return 10L * nx >= 9L * cdiv_i(nx, tx) * tx; };
+    if (allow_512 && fills(512)) return 512;
+    if (fills(256)) return 256;
+    return 0;
+}
+
 // The marching kernels are planned for one workgroup per CU (rounds of ncu workgroups that
 // move through z together).  Kernels that need few registers and little LDS would otherwise
 // be packed two or more to a CU, which measured 2-9 % slower at grid sizes with several

@@ -327,7 +327,14 @@ static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipSt
     long v = opt.variant;
     // measured best: 16 bytes per lane (1 for fp64, 2 for fp32) unless u_prev_bar is read and
     // written as well, where the wider tiles with fewer registers per cell win
-    if (v == 0) v = (a.out1 && !a.out1_assign) ? (sizeof(T) == 8 ? 3 : 8) : (sizeof(T) == 8 ? 1 : 2);
+    if (v == 0) {
+        v = (a.out1 && !a.out1_assign) ? (sizeof(T) == 8 ? 3 : 8) : (sizeof(T) == 8 ? 1 : 2);
+        if (R == 1 && opt.remainder == 0) {
+            const int wide = wide_tile_for_unaligned_rows(a.nx, sizeof(T), sizeof(T) == 4);
+            if (wide == 512) v = 11;
+            else if (wide == 256) v = 10;
+        }
+    }
     if constexpr (R == 2 || R == 3) {            // the default shapes of the dtype only
         if constexpr (sizeof(T) == 8) {
             return v == 3 ? launch_cfg<T, R, 64, 8, 4, 1, 1, true>(a, opt, stream)
@@ -348,6 +355,13 @@ static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipSt
         case 6: return launch_cfg<T, R, 32, 16, 2, 2, 1, false>(a, opt, stream);    // u_bar through L2 (no streaming hint)
         case 7: return launch_cfg<T, R, 64, 4, 4, 1, 1, true>(a, opt, stream);      // 64 x 16 tile, 256 threads
         case 8: return launch_cfg<T, R, 64, 8, 4, 2, 1, true>(a, opt, stream);      // 128 x 32 tile, PX = 2
+        // radius 1 only: 16 rows of 256 or 512 cells (see wide_tile_for_unaligned_rows)
+        case 10:
+            if constexpr (R == 1) return launch_cfg<T, R, 128, 4, 4, 2, 1, true>(a, opt, stream);  // 256 x 16 tile, PX = 2
+            else return launch_cfg<T, R, 32, 16, 2, 2, 1, true>(a, opt, stream);
+        case 11:
+            if constexpr (R == 1 && sizeof(T) == 4) return launch_cfg<T, R, 128, 4, 4, 4, 1, true>(a, opt, stream);   // 512 x 16 tile, PX = 4
+            else return launch_cfg<T, R, 32, 16, 2, 2, 1, true>(a, opt, stream);
         }
     }
 }
@@ -355,8 +369,13 @@ static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipSt
 void describe_march_plan(int is_f64, int radius, int nx, int ny, int nz, const LaunchOptions &opt,
                          long *plan, int *tiles, long max_blocks)
 {
-    // the default shapes: 32 x 16 threads, two rows per thread, 16 bytes per lane
-    const int TX = is_f64 ? 64 : 128, TY = 32;
+    // the default shapes: 32 x 16 threads, two rows per thread, 16 bytes per lane; radius 1
+    // with rows that are not cache-line multiples: 16 rows of 256 or 512 cells
+    int TX = is_f64 ? 64 : 128, TY = 32;
+    if (radius == 1 && opt.remainder == 0 && opt.variant == 0) {
+        const int wide = wide_tile_for_unaligned_rows(nx, is_f64 ? 8 : 4, !is_f64);
+        if (wide) { TX = wide; TY = 16; }
+    }
     March3dArgs a{};
     a.nx = nx; a.ny = ny; a.nz = nz;
     TileMap &m = a.map;

@@ -69,7 +69,7 @@ def test_adjoint_small(sadj, radius, shape, dtype):
     _check_adjoint(sadj, d, radius, dtype, with_prev=True, what="R=%d %s with u_prev_bar" % (radius, shape))
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8, 10, 11])
 @pytest.mark.parametrize("radius", [1, 4])
 def test_adjoint_tile_variants(sadj, radius, variant):
     sadj.set_option("wave3d.variant", variant)
@@ -319,10 +319,35 @@ def test_primal_small(sadj, radius, shape, dtype):
     assert_close(got[m], want[m], _primal_scale(d, radius)[m], dtype, "primal R=%d %s" % (radius, shape))
 
 
+# radius 1 with rows that are not a multiple of the 128-byte cache line: the launcher takes
+# tiles of 256 (fp32 adjoint: 512) cells x 16 rows when they cover nx well; 1002 is not a
+# multiple of four, so the fp32 calls fall back to the one-cell shape there
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("shape", [(20, 37, 250), (9, 40, 500), (6, 20, 1000), (5, 17, 1002), (19, 33, 750), (40, 16, 1500)])
+def test_radius_one_unaligned_rows_take_wide_tiles(sadj, shape, dtype):
+    nz, ny, nx = shape
+    info, _ = sadj.sadj_describe_wave3d_plan(1 if dtype == np.float64 else 0, 1, nx, ny, nz, with_tiles=False)
+    assert info["tile_h"] == 16 and info["tile_w"] in (256, 512)
+    d = inputs.wave_inputs(shape, 0.01, 0.1, seed=sum(shape), dtype=dtype, c_mode="iid")
+    for zchunk in (0, 5):
+        sadj.set_option("wave3d.zchunk", zchunk)
+        _check_adjoint(sadj, d, 1, dtype, with_prev=False, what="wide tiles %s zchunk=%d" % (shape, zchunk))
+    sadj.set_option("wave3d.zchunk", 0)
+    _check_adjoint(sadj, d, 1, dtype, with_prev=True, what="wide tiles %s with u_prev_bar" % (shape,))
+    r0 = inputs.uniform(3, "aux", shape, -1, 1).astype(dtype)
+    r = to_gpu(r0)
+    sadj.sadj_primal_wave3d(1, to_gpu(d["u"]), to_gpu(d["u_prev"]), to_gpu(d["c"]), r)
+    got = to_host(r)
+    want = oracle.wave_primal(d["u"], d["u_prev"], d["c"], 1, r_init=r0)
+    m = interior_mask(shape, 1)
+    assert np.array_equal(got[~m], r0[~m])
+    assert_close(got[m], want[m], _primal_scale(d, 1)[m], dtype, "primal wide tiles %s" % (shape,))
+
+
 # shapes whose x-y tiles do not fill whole rounds of the chip's compute units, so that the
 # left-over tiles are cut into more z-chunks than the others (two groups of workgroups)
 TWO_GROUP = [(np.float64, 4, (64, 580, 520)), (np.float64, 1, (24, 400, 610)), (np.float64, 2, (64, 130, 1150)),
-             (np.float64, 3, (100, 100, 1420)), (np.float32, 1, (24, 400, 1240))]
+             (np.float64, 3, (100, 100, 1420)), (np.float32, 1, (24, 400, 1216))]
 
 
 @pytest.mark.parametrize("dtype,radius,shape", TWO_GROUP)
