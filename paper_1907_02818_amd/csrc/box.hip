@@ -402,8 +402,9 @@ static hipError_t launch_box2d(BoxArgs a, hipStream_t stream)
     if (hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
         ncu = v;
-    // about one workgroup of 8 waves per CU, each wave with two rows in flight
-    const int chunks = bx >= ncu ? 1 : cdiv_i(ncu, bx);
+    // one workgroup of 8 waves per CU, each wave with two rows in flight; never more workgroups
+    // than CUs (a few left for a second round would run almost alone)
+    const int chunks = bx >= ncu ? 1 : ncu / bx;
     int chunk = cdiv_i(a.ny, chunks);
     if (chunk < 16) chunk = 16;
     if (chunk > a.ny) chunk = a.ny;
