@@ -142,7 +142,9 @@ static inline void plan_march(TileMap &m, int nx, int ny, int nz, int TX, int TY
     m.round_blocks = ncu >= 8 ? ncu - ncu % 8 : 8;
     ncu *= wg_per_cu;                                  // workgroups resident at a time
     const long tiles = (long)m.ntx * m.nty;
-    const int max_chunks = nz / (4 * R) > 0 ? (nz / (4 * R) < 64 ? nz / (4 * R) : 64) : 1;   // chunks of at least 4R planes
+    // chunks of at least 4R planes; at most 64 of them, or what fills the chip where the grid has few tiles
+    const long chunk_cap = tiles * 64 >= ncu ? 64 : (ncu + tiles - 1) / tiles;
+    const int max_chunks = nz / (4 * R) > 0 ? (int)(nz / (4 * R) < chunk_cap ? nz / (4 * R) : chunk_cap) : 1;
     int zchunk = (int)opt.zchunk;
     if (zchunk <= 0) {
         long best_cost = -1, best_blocks = 0;
