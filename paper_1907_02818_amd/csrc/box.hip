@@ -430,6 +430,13 @@ static hipError_t launch_box3d(const BoxArgs &a, const LaunchOptions &opt, hipSt
 {
     constexpr int PXV = 16 / sizeof(T);
     const bool ok = a.nx % PXV == 0 && box_aligned16(a.in0) && box_aligned16(a.in1) && box_aligned16(a.out);
+    // rows that are not cache-line multiples: 256 x 16 tiles, as the radius-1 wave kernels
+    // (wide_tile_for_unaligned_rows); 128 x 4 threads, two cells per lane, four rows per thread
+    const uintptr_t all_ptrs = reinterpret_cast<uintptr_t>(a.in0) | reinterpret_cast<uintptr_t>(a.in1) |
+                               reinterpret_cast<uintptr_t>(a.out);
+    const bool ok2 = a.nx % 2 == 0 && all_ptrs % (2 * sizeof(T)) == 0;
+    if (ok2 && opt.variant == 0 && wide_tile_for_unaligned_rows(a.nx, sizeof(T), false) == 256)
+        return launch_box3d_shape<T, ADJ, 128, 4, 4, 2>(a, opt, stream);
     // the primal (24 bytes per cell) measured 2 points faster with the one-cell shape
     if (ok && ADJ && opt.variant != 3) return launch_box3d_shape<T, ADJ, 32, 16, 2, PXV>(a, opt, stream);
     return launch_box3d_shape<T, ADJ, 64, 8, 4, 1>(a, opt, stream);

@@ -14,7 +14,8 @@ pytestmark = pytest.mark.gpu
 SHAPES = [(3,), (4,), (65,), (127,), (128,), (129,), (1000,), (100003,),
           (3, 3), (3, 200), (200, 3), (67, 131), (130, 256), (70, 1030), (300, 301),
           (3, 3, 3), (4, 5, 7), (21, 37, 150), (9, 70, 130), (40, 33, 64), (70, 18, 65),
-          (24, 400, 610)]        # left-over tiles cut finer along z than the rest
+          (24, 400, 610),        # left-over tiles cut finer along z than the rest
+          (6, 20, 1000), (9, 40, 500), (5, 33, 250)]   # rows not cache-line multiples: 256 x 16 tiles
 
 
 @pytest.fixture(scope="module")
