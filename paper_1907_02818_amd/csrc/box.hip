@@ -37,8 +37,16 @@ struct BoxArgs {
 // ------------------------------------------------------------------------------ 2-D
 // D rows of loads in flight per wave; the steady part of the march has no branches so
 // that the wait counters know which loads may still be outstanding.
+template <int D>
+__device__ __forceinline__ RowMarch box2d_rows(int ys, int ye, int ny)
+{
+    // steady steps yi in [lo, hi]: rows yi and yi+D exist and lie in I; output rows yi-1 and
+    // yi+D-1 belong to this chunk and (primal) to I
+    return plan_row_march(ys - 1, ye, max(ys + 1, 2), min(ny - 1, ye) - 1 - D, D);
+}
+
 template <class T, int PX, int D, bool ADJ, bool GUARD>
-__device__ __forceinline__ void box2d_strip(const BoxArgs &a, int xs, int ys, int ye, int lane)
+__device__ __forceinline__ void box2d_strip(const BoxArgs &a, int xs, int ys, int ye, int lane, const RowMarch rm)
 {
     constexpr int W = 64 * PX;
     using V = Vec<T, PX>;
@@ -160,24 +168,19 @@ __device__ __forceinline__ void box2d_strip(const BoxArgs &a, int xs, int ys, in
     };
     issue(yi0, std::integral_constant<int, 0>{}, No{});
     if (D > 1) issue(yi0 + 1, std::integral_constant<int, (D > 1 ? 1 : 0)>{}, No{});
-    // steady steps yi in [lo, hi]: rows yi and yi+D exist and lie in I; output rows yi-1 and
-    // yi+D-1 belong to this chunk and (primal) to I
-    const int lo = max(ys + 1, 2);
-    const int hi = min(ny - 1, ye) - 1 - D;
     int yi = yi0, d = 0;
-    while (yi <= yi1 && (yi < lo || d != 0)) {
+    for (; yi < rm.pre_end; ++yi) {
         step_any(yi, d);
-        ++yi;
         d = d + 1 == D ? 0 : d + 1;
     }
-    while (yi + D - 1 <= hi) {
+    for (int group = 1; group <= rm.steady; ++group) {
         step(yi, std::integral_constant<int, 0>{}, Yes{});
         if (D > 1) step(yi + 1, std::integral_constant<int, (D > 1 ? 1 : 0)>{}, Yes{});
         yi += D;
+        row_march_sync(group);
     }
-    while (yi <= yi1) {
+    for (; yi <= yi1; ++yi) {
         step_any(yi, d);
-        ++yi;
         d = d + 1 == D ? 0 : d + 1;
     }
 }
@@ -188,12 +191,16 @@ __global__ __launch_bounds__(64 * WAVES) void box2d_kernel(BoxArgs a)
     constexpr int W = 64 * PX;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int xs = (blockIdx.x * WAVES + wave) * W;
-    if (xs >= a.nx) return;                         // wave-uniform; no barrier in this kernel
     const int ys = blockIdx.y * a.chunk;
     const int ye = min(ys + a.chunk, a.ny);
+    const RowMarch rm = box2d_rows<2>(ys, ye, a.ny);
+    if (xs >= a.nx) {                               // wave-uniform: a strip outside the grid
+        row_march_idle(rm);
+        return;
+    }
     const bool core = xs >= 2 && xs + W <= a.nx - 2 && ys >= 2 && ye <= a.ny - 2;
-    if (core) box2d_strip<T, PX, 2, ADJ, false>(a, xs, ys, ye, lane);
-    else      box2d_strip<T, PX, 2, ADJ, true>(a, xs, ys, ye, lane);
+    if (core) box2d_strip<T, PX, 2, ADJ, false>(a, xs, ys, ye, lane, rm);
+    else      box2d_strip<T, PX, 2, ADJ, true>(a, xs, ys, ye, lane, rm);
 }
 
 // ------------------------------------------------------------------------------ 3-D

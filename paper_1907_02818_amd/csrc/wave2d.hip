@@ -10,7 +10,8 @@
 // and q itself to the sums of the rows above and below, so a lane keeps three
 // running sums per owned column; x-neighbours travel between lanes with wave
 // shuffles and the two cells beside the strip are loaded by lanes 0 and 63.  There
-// is no LDS and no barrier; waves are independent.  Waves whose reads all lie in I
+// is no LDS; waves exchange nothing, but those of a workgroup meet at a barrier every few
+// rows so that they stream neighbouring pieces of the same rows (plan_row_march).  Waves whose reads all lie in I
 // run the unguarded instantiation (core); waves touching the first/last columns or
 // rows run the guarded one, where unused cells are replaced by zero with a select
 // (the if-guarded remainder variant of Section 3.3.4).
@@ -34,8 +35,16 @@ struct Wave2dArgs {
 // D rows of loads are kept in flight per wave.  In the steady part of the march every
 // row of a step is known to exist, so that part is compiled without branches and the
 // compiler can count exactly which loads may still be outstanding.
+template <int D>
+__device__ __forceinline__ RowMarch adj2d_rows(int ys, int ye, int ny)
+{
+    // steady steps yi in [lo, hi]: rows yi and yi+D lie in I and in this chunk's input
+    // range; output rows yi-1 and yi+D-1 (for u_prev_bar: yi and yi+D) belong to the chunk
+    return plan_row_march(ys - 1, ye, ys + 1, min(ny - 1, ye) - 1 - D, D);
+}
+
 template <class T, int PX, int D, bool GUARD, bool UPREV>
-__device__ __forceinline__ void adj2d_strip(const Wave2dArgs &a, int xs, int ys, int ye, int lane)
+__device__ __forceinline__ void adj2d_strip(const Wave2dArgs &a, int xs, int ys, int ye, int lane, const RowMarch rm)
 {
     constexpr int W = 64 * PX;
     using V = Vec<T, PX>;
@@ -148,26 +157,21 @@ __device__ __forceinline__ void adj2d_strip(const Wave2dArgs &a, int xs, int ys,
     if (D > 2) issue(yi0 + 2, std::integral_constant<int, (D > 2 ? 2 : 0)>{}, No{});
     if (D > 3) issue(yi0 + 3, std::integral_constant<int, (D > 3 ? 3 : 0)>{}, No{});
 
-    // steady steps yi in [lo, hi]: rows yi and yi+D lie in I and in this chunk's input
-    // range; output rows yi-1 and yi+D-1 (for u_prev_bar: yi and yi+D) belong to the chunk
-    const int lo = ys + 1;
-    const int hi = min(ny - 1, ye) - 1 - D;
     int yi = yi0, d = 0;
-    while (yi <= yi1 && (yi < lo || d != 0)) {
+    for (; yi < rm.pre_end; ++yi) {
         step_any(yi, d);
-        ++yi;
         d = d + 1 == D ? 0 : d + 1;
     }
-    while (yi + D - 1 <= hi) {
+    for (int group = 1; group <= rm.steady; ++group) {
         step(yi, std::integral_constant<int, 0>{}, Yes{});
         if (D > 1) step(yi + 1, std::integral_constant<int, (D > 1 ? 1 : 0)>{}, Yes{});
         if (D > 2) step(yi + 2, std::integral_constant<int, (D > 2 ? 2 : 0)>{}, Yes{});
         if (D > 3) step(yi + 3, std::integral_constant<int, (D > 3 ? 3 : 0)>{}, Yes{});
         yi += D;
+        row_march_sync(group);
     }
-    while (yi <= yi1) {
+    for (; yi <= yi1; ++yi) {
         step_any(yi, d);
-        ++yi;
         d = d + 1 == D ? 0 : d + 1;
     }
 }
@@ -178,12 +182,16 @@ __global__ __launch_bounds__(64 * WAVES) void adj_wave2d_kernel(Wave2dArgs a)
     constexpr int W = 64 * PX;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int xs = (blockIdx.x * WAVES + wave) * W;
-    if (xs >= a.nx) return;                     // wave-uniform; the kernel has no barrier
     const int ys = blockIdx.y * a.ychunk;
     const int ye = min(ys + a.ychunk, a.ny);
+    const RowMarch rm = adj2d_rows<D>(ys, ye, a.ny);
+    if (xs >= a.nx) {                           // wave-uniform: a strip outside the grid
+        row_march_idle(rm);
+        return;
+    }
     const bool core = xs >= 2 && xs + W <= a.nx - 2 && ys >= 2 && ye <= a.ny - 2;
-    if (core) adj2d_strip<T, PX, D, false, UPREV>(a, xs, ys, ye, lane);
-    else      adj2d_strip<T, PX, D, true, UPREV>(a, xs, ys, ye, lane);
+    if (core) adj2d_strip<T, PX, D, false, UPREV>(a, xs, ys, ye, lane, rm);
+    else      adj2d_strip<T, PX, D, true, UPREV>(a, xs, ys, ye, lane, rm);
 }
 
 // ------------------------------------------------------------------------- primal
@@ -193,8 +201,14 @@ __global__ __launch_bounds__(64 * WAVES) void adj_wave2d_kernel(Wave2dArgs a)
 // are streamed.  Only cells of I are stored; reads of u never leave the grid.
 // GUARD = false: strips whose columns all lie in I (and hence in the grid): no lane is
 // masked anywhere in the march.  GUARD = true: the first and the last strip of a row.
+template <int D>
+__device__ __forceinline__ RowMarch primal2d_rows(int ys, int ye)
+{
+    return plan_row_march(ys - 1, ye, ys + 1, ye - D, D);   // steady: rows yi-1 >= ys and yi+D <= ye
+}
+
 template <class T, int PX, int D, bool GUARD>
-__device__ __forceinline__ void primal2d_strip(const Wave2dArgs &a, int xs, int ys, int ye, int lane)
+__device__ __forceinline__ void primal2d_strip(const Wave2dArgs &a, int xs, int ys, int ye, int lane, const RowMarch rm)
 {
     constexpr int W = 64 * PX;
     using V = Vec<T, PX>;
@@ -289,21 +303,19 @@ __device__ __forceinline__ void primal2d_strip(const Wave2dArgs &a, int xs, int 
     static_assert(D <= 2, "primal_wave2d_kernel: D is 1 or 2");
     issue(yi0, std::integral_constant<int, 0>{}, No{});
     if (D > 1) issue(yi0 + 1, std::integral_constant<int, (D > 1 ? 1 : 0)>{}, No{});
-    const int lo = ys + 1, hi = ye - D;                    // steady: rows yi-1 >= ys and yi+D <= ye
     int yi = yi0, d = 0;
-    while (yi <= yi1 && (yi < lo || d != 0)) {
+    for (; yi < rm.pre_end; ++yi) {
         step_any(yi, d);
-        ++yi;
         d = d + 1 == D ? 0 : d + 1;
     }
-    while (yi + D - 1 <= hi) {
+    for (int group = 1; group <= rm.steady; ++group) {
         step(yi, std::integral_constant<int, 0>{}, Yes{});
         if (D > 1) step(yi + 1, std::integral_constant<int, (D > 1 ? 1 : 0)>{}, Yes{});
         yi += D;
+        row_march_sync(group);
     }
-    while (yi <= yi1) {
+    for (; yi <= yi1; ++yi) {
         step_any(yi, d);
-        ++yi;
         d = d + 1 == D ? 0 : d + 1;
     }
 }
@@ -314,11 +326,15 @@ __global__ __launch_bounds__(64 * WAVES) void primal_wave2d_kernel(Wave2dArgs a)
     constexpr int W = 64 * PX;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int xs = (blockIdx.x * WAVES + wave) * W;
-    if (xs >= a.nx) return;                               // wave-uniform; no barrier in this kernel
     const int ys = 1 + blockIdx.y * a.ychunk;             // output rows cover [1, ny-1)
     const int ye = min(ys + a.ychunk, a.ny - 1);
-    if (xs >= 1 && xs + W <= a.nx - 1) primal2d_strip<T, PX, D, false>(a, xs, ys, ye, lane);
-    else                               primal2d_strip<T, PX, D, true>(a, xs, ys, ye, lane);
+    const RowMarch rm = primal2d_rows<D>(ys, ye);
+    if (xs >= a.nx) {                                     // wave-uniform: a strip outside the grid
+        row_march_idle(rm);
+        return;
+    }
+    if (xs >= 1 && xs + W <= a.nx - 1) primal2d_strip<T, PX, D, false>(a, xs, ys, ye, lane, rm);
+    else                               primal2d_strip<T, PX, D, true>(a, xs, ys, ye, lane, rm);
 }
 
 // ------------------------------------------------------------------------ launchers
