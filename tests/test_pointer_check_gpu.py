@@ -34,6 +34,7 @@ def test_range_past_the_end_of_its_own_allocation(sadj):
     """A 64 MiB tensor gets an allocation of its own from torch's allocator (requests above
     10 MiB are not carved out of a shared block), so one element more does not fit."""
     import torch
+    torch.cuda.empty_cache()                 # so that the request is served by a fresh allocation, not a cached larger block
     nbytes = 64 << 20
     t = torch.empty(nbytes // 8, dtype=torch.float64, device="cuda")
     assert sadj.sadj_check_array(t.data_ptr(), nbytes) == 0
