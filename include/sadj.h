@@ -253,8 +253,9 @@ sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, lon
  *                    0/1 (default) per round of resident workgroups every XCD (chiplet with
  *                    its own L2) owns a contiguous range of tiles, 2 one contiguous range
  *                    per XCD over the whole dispatch, 3 tiles dealt round-robin to XCDs.
- *   "wave3d.band"    numbering of the tiles of a plane: 0 (default) rows of tiles, k > 0
- *                    bands of k tile rows with y fastest inside a band.
+ *   "wave3d.band"    numbering of the tiles of a plane: k > 0 bands of k tile rows with y
+ *                    fastest inside a band (1: plain rows of tiles, x fastest); 0 (default)
+ *                    automatic: rows of tiles, or bands of 8 where a row has 32 or more tiles.
  *   "wave3d.ldspad"  dynamic LDS bytes requested per workgroup of the 3-D marching kernels,
  *                    which limits how many workgroups share a CU: 0 (default) as much as
  *                    keeps it at one workgroup per CU, -1 none, n > 0 exactly n (<= 65536).

@@ -68,7 +68,8 @@ struct March3dArgs {
 // measured 3-5 % slower).  xcd_map 3: logical id = hardware id (neighbouring tiles on
 // different XCDs).
 // Tiles are numbered x fastest (band = 0) or in bands of `band` tile rows with
-// y fastest inside a band, which makes the 32 tiles an XCD holds a compact patch.
+// y fastest inside a band, which makes the 32 tiles an XCD holds a compact patch
+// (plan_march chooses, see there).
 __host__ __device__ __forceinline__ void block_to_tile(const TileMap &m, int hw_id, int &tix, int &tiy, int &zs, int &ze)
 {
     int L;
@@ -136,7 +137,10 @@ static inline void plan_march(TileMap &m, int nx, int ny, int nz, int TX, int TY
         hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
         ncu = v;
     m.xcd_map = opt.xcd_map > 0 ? (int)opt.xcd_map : 1;
-    m.band = (int)opt.band;
+    // rows of 32 or more tiles: one XCD's 32 tiles would be a single thin strip whose halo rows
+    // are all fetched a second time by the XCDs above and below; bands of 8 rows make the patch
+    // 4 x 8 tiles (2048-wide and wider planes measured 2-4 points faster, others unchanged)
+    m.band = opt.band > 0 ? (int)opt.band : (m.ntx >= 32 ? 8 : 0);
     // ids are made XCD-contiguous per group of one workgroup per CU, also where two groups
     // are resident together (measured better than one contiguous range per XCD over both)
     m.round_blocks = ncu >= 8 ? ncu - ncu % 8 : 8;

@@ -180,7 +180,7 @@ def test_every_option_the_library_knows_is_documented_in_the_header():
 @pytest.mark.parametrize("dtype_code,radius,shape", [(1, 4, (512, 512, 512)), (1, 4, (300, 500, 700)), (0, 4, (512, 512, 512)),
                                                      (1, 1, (1000, 1000, 1000)), (1, 2, (9, 9, 9)), (0, 3, (100, 33, 65)),
                                                      (1, 4, (768, 768, 768)), (1, 1, (3, 3, 3)), (1, 4, (400, 400, 400)),
-                                                     (0, 1, (896, 896, 896)), (1, 4, (640, 640, 640)), (1, 4, (1 << 17, 9, 70))])
+                                                     (0, 1, (896, 896, 896)), (1, 4, (640, 640, 640)), (1, 4, (1 << 17, 9, 70)), (1, 4, (40, 300, 2100))])
 def test_workgroups_tile_the_grid_exactly_once(dtype_code, radius, shape, xcdmap, band, zchunk, split):
     """Disjoint cover (Section 3.3.4): under every mapping option the workgroups' (tile,
     range of planes) pairs are disjoint and cover the grid: every tile of the x-y tiling

@@ -18,6 +18,7 @@ SMALL = [
     (1, (3, 3, 3)), (1, (4, 5, 7)), (1, (21, 37, 150)), (1, (70, 18, 65)), (1, (5, 64, 128)),
     (2, (5, 5, 5)), (2, (9, 11, 70)), (2, (33, 45, 150)), (3, (7, 7, 7)), (3, (13, 15, 17)), (3, (30, 41, 136)),
     (4, (3000, 9, 20)), (1, (5000, 5, 9)),      # one tile, hundreds of z-chunks
+    (4, (12, 300, 2100)), (2, (9, 270, 4100)),  # 32 and more tiles per row: tiles numbered in bands of 8 rows
 ]
 
 
