@@ -255,7 +255,8 @@ sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, lon
  *                    per XCD over the whole dispatch, 3 tiles dealt round-robin to XCDs.
  *   "wave3d.band"    numbering of the tiles of a plane: k > 0 bands of k tile rows with y
  *                    fastest inside a band (1: plain rows of tiles, x fastest); 0 (default)
- *                    automatic: rows of tiles, or bands of 8 where a row has 32 or more tiles.
+ *                    automatic: rows of tiles, or bands of 8 where a row has 32 or more tiles
+ *                    and the plane at least 8 tile rows.
  *   "wave3d.ldspad"  dynamic LDS bytes requested per workgroup of the 3-D marching kernels,
  *                    which limits how many workgroups share a CU: 0 (default) as much as
  *                    keeps it at one workgroup per CU, -1 none, n > 0 exactly n (<= 65536).

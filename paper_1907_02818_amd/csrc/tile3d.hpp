@@ -139,8 +139,9 @@ static inline void plan_march(TileMap &m, int nx, int ny, int nz, int TX, int TY
     m.xcd_map = opt.xcd_map > 0 ? (int)opt.xcd_map : 1;
     // rows of 32 or more tiles: one XCD's 32 tiles would be a single thin strip whose halo rows
     // are all fetched a second time by the XCDs above and below; bands of 8 rows make the patch
-    // 4 x 8 tiles (2048-wide and wider planes measured 2-4 points faster, others unchanged)
-    m.band = opt.band > 0 ? (int)opt.band : (m.ntx >= 32 ? 8 : 0);
+    // 4 x 8 tiles (2048-wide and wider planes measured 2-4 points faster).  Only where the plane
+    // has the 8 tile rows of a full band; with fewer rows no order measured better than another.
+    m.band = opt.band > 0 ? (int)opt.band : (m.ntx >= 32 && m.nty >= 8 ? 8 : 0);
     // ids are made XCD-contiguous per group of one workgroup per CU, also where two groups
     // are resident together (measured better than one contiguous range per XCD over both)
     m.round_blocks = ncu >= 8 ? ncu - ncu % 8 : 8;
