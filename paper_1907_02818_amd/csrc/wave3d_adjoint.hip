@@ -72,7 +72,7 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
 
     // ---- owned cells: x = x0 + tx*PX + e, y = y0 + ty*PY + p  (nx is a multiple of PX,
     //      so a vector of PX cells is entirely inside or entirely outside the grid)
-    uint32_t ooff[PY];
+    uint32_t ooff[PY], coff[PY];
     bool ouse[PY][PX], ostore[PY];
     const int x = x0 + tx * PX;
 #pragma unroll
@@ -83,6 +83,11 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
         for (int e = 0; e < PX; ++e)
             ouse[p][e] = GUARD ? (x + e >= R && x + e < nx - R && y >= R && y < ny - R) : true;
         ooff[p] = ostore[p] ? (uint32_t)((size_t)y * nx + x) * sizeof(T) : dummy;
+        // c and r_bar are not fetched where none of the vector's cells lies in I
+        bool any = false;
+#pragma unroll
+        for (int e = 0; e < PX; ++e) any = any || ouse[p][e];
+        coff[p] = (!GUARD || any) ? ooff[p] : dummy;
     }
     // ---- halo slots
     uint32_t hoff[HS];
@@ -130,8 +135,8 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
             const T *rp = rg + (size_t)z * plane;
 #pragma unroll
             for (int p = 0; p < PY; ++p) {
-                sc[d][p] = ld_vec_off<T, PX, false>(cp, ooff[p]);
-                sr[d][p] = ld_vec_off<T, PX, false>(rp, ooff[p]);
+                sc[d][p] = ld_vec_off<T, PX, false>(cp, coff[p]);
+                sr[d][p] = ld_vec_off<T, PX, false>(rp, coff[p]);
             }
 #pragma unroll
             for (int s = 0; s < HS; ++s) { shc[d][s] = ld_off(cp, hoff[s]); shr[d][s] = ld_off(rp, hoff[s]); }
