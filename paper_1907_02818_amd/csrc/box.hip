@@ -442,7 +442,7 @@ static hipError_t launch_box3d(const BoxArgs &a, const LaunchOptions &opt, hipSt
     const uintptr_t all_ptrs = reinterpret_cast<uintptr_t>(a.in0) | reinterpret_cast<uintptr_t>(a.in1) |
                                reinterpret_cast<uintptr_t>(a.out);
     const bool ok2 = a.nx % 2 == 0 && all_ptrs % (2 * sizeof(T)) == 0;
-    if (ok2 && opt.variant == 0 && wide_tile_for_unaligned_rows(a.nx, sizeof(T), false) == 256)
+    if (ok2 && opt.variant == 0 && wide_tile_for_unaligned_rows(a.nx, sizeof(T), 1, false) == 256)
         return launch_box3d_shape<T, ADJ, 128, 4, 4, 2>(a, opt, stream);
     // the primal (24 bytes per cell) measured 2 points faster with the one-cell shape
     if (ok && ADJ && opt.variant != 3) return launch_box3d_shape<T, ADJ, 32, 16, 2, PXV>(a, opt, stream);

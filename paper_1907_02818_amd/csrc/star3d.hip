@@ -237,12 +237,18 @@ static hipError_t launch_star_TR(const StarArgs &a, const LaunchOptions &opt, hi
     // the primal measured 2-6 points faster with the one-cell shape for radius 1 and 2, and for
     // radius 3 in fp32 (512^3: 63 vs 58 %); 10-12 points slower for radius 4 and radius 3 fp64
     const bool wide = ADJ || R == 4 || (R == 3 && sizeof(T) == 8);
-    if constexpr (R == 1) {
-        // rows that are not cache-line multiples: 256 x 16 tiles, as the radius-1 wave kernels
-        const bool ok2 = a.nx % 2 == 0 && star_aligned(a.in0, 2 * sizeof(T)) && star_aligned(a.in1, 2 * sizeof(T)) &&
-                         star_aligned(a.out, 2 * sizeof(T));
-        if (ok2 && opt.variant == 0 && wide_tile_for_unaligned_rows(a.nx, sizeof(T), false) == 256)
-            return launch_star_shape<T, R, ADJ, 128, 4, 4, 2>(a, opt, stream);
+    // rows that are not cache-line multiples: tiles of 16 rows with long rows, as the wave kernels
+    // (wide_tile_for_unaligned_rows): radius 1 256 cells, two per lane, four rows per thread;
+    // larger radii 1 KB, 16 bytes per lane, two rows per thread
+    if (opt.variant == 0) {
+        const int wide_tx = wide_tile_for_unaligned_rows(a.nx, sizeof(T), R, false);
+        if constexpr (R == 1) {
+            const bool ok2 = a.nx % 2 == 0 && star_aligned(a.in0, 2 * sizeof(T)) && star_aligned(a.in1, 2 * sizeof(T)) &&
+                             star_aligned(a.out, 2 * sizeof(T));
+            if (ok2 && wide_tx == 256) return launch_star_shape<T, R, ADJ, 128, 4, 4, 2>(a, opt, stream);
+        } else {
+            if (ok && wide_tx) return launch_star_shape<T, R, ADJ, 64, 8, 2, PXV>(a, opt, stream);
+        }
     }
     if (ok && wide && opt.variant != 3) return launch_star_shape<T, R, ADJ, 32, 16, 2, PXV>(a, opt, stream);
     return launch_star_shape<T, R, ADJ, 64, 8, 4, 1>(a, opt, stream);

@@ -191,21 +191,30 @@ static inline void plan_march(TileMap &m, int nx, int ny, int nz, int TX, int TY
     m.total_blocks = m.blocks_a + (int)(tiles - m.tiles_a) * m.ntz;
 }
 
-// Radius 1, rows whose length in bytes is not a multiple of the 128-byte cache line (nx = 1000
-// in fp64: every other row starts in the middle of a line).  Tile rows then begin and end
-// inside a line on most rows, and tiles with long rows (fewer row ends per byte) measured
-// 4-10 points faster than the default shapes (500^3, 1000^3, 200 x 700 x 1500, fp64 and
-// fp32, adjoint and primal), while for line-aligned rows they measured equal or slower.  The
-// radius-1 kernels keep three running sums per cell, so eight cells per lane fit the register
-// file.  Returns the tile width in cells to use (512: fp32 adjoint only; 256), or 0 for the
-// default shape; a width qualifies if its tiles cover nx with at most 10 % idle columns.
-static inline int wide_tile_for_unaligned_rows(int nx, size_t elem_bytes, bool allow_512)
+// Rows whose length in bytes is not a multiple of the 128-byte cache line (nx = 1000 in fp64:
+// every other row starts in the middle of a line).  Tile rows then begin and end inside a line
+// on most rows, and tiles with long rows (fewer row ends per byte) measured faster than the
+// default shapes, while for line-aligned rows they measured equal or slower.
+//
+// Radius 1 keeps three running sums per cell, so eight cells per lane fit the register file:
+// tiles of 256 (fp32 adjoint: 512) cells x 16 rows measured 4-10 points faster (500^3, 1000^3,
+// 200 x 700 x 1500, both dtypes, adjoint and primal).  Larger radii stay at four fp64 (eight
+// fp32) cells per lane and trade tile rows for width: 1 KB x 16 rows instead of 512 B x 32
+// (radius 4 fp64 at 500^3, 1000^3, 250 x 900 x 1100, 300 x 300 x 1250: adjoint +2 to +5
+// points, with u_prev_bar +3 to +7, primal +3 to +6).
+//
+// Returns the tile width in cells to use, or 0 for the default shape; a width qualifies if its
+// tiles cover nx with at most 10 % idle columns.
+static inline int wide_tile_for_unaligned_rows(int nx, size_t elem_bytes, int radius, bool allow_512)
 {
     if (((size_t)nx * elem_bytes) % 128 == 0) return 0;
     auto fills = [nx](int tx) { return 10L * nx >= 9L * cdiv_i(nx, tx) * tx; };
-    if (allow_512 && fills(512)) return 512;
-    if (fills(256)) return 256;
-    return 0;
+    if (radius == 1) {
+        if (allow_512 && fills(512)) return 512;
+        return fills(256) ? 256 : 0;
+    }
+    const int tx = (int)(1024 / elem_bytes);
+    return fills(tx) ? tx : 0;
 }
 
 // The marching kernels are planned for one workgroup per CU (rounds of ncu workgroups that

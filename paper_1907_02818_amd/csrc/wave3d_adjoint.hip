@@ -334,18 +334,21 @@ static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipSt
     // written as well, where the wider tiles with fewer registers per cell win
     if (v == 0) {
         v = (a.out1 && !a.out1_assign) ? (sizeof(T) == 8 ? 3 : 8) : (sizeof(T) == 8 ? 1 : 2);
-        if (R == 1 && opt.remainder == 0) {
-            const int wide = wide_tile_for_unaligned_rows(a.nx, sizeof(T), sizeof(T) == 4);
-            if (wide == 512) v = 11;
-            else if (wide == 256) v = 10;
+        if (opt.remainder == 0) {
+            const int wide = wide_tile_for_unaligned_rows(a.nx, sizeof(T), R, sizeof(T) == 4);
+            if (R == 1 && wide == 512) v = 11;
+            else if (R == 1 && wide == 256) v = 10;
+            else if (wide) v = 5;
         }
     }
     if constexpr (R == 2 || R == 3) {            // the default shapes of the dtype only
         if constexpr (sizeof(T) == 8) {
             return v == 3 ? launch_cfg<T, R, 64, 8, 4, 1, 1, true>(a, opt, stream)
+                 : v == 5 ? launch_cfg<T, R, 64, 8, 2, 2, 1, true>(a, opt, stream)
                           : launch_cfg<T, R, 32, 16, 2, 2, 1, true>(a, opt, stream);
         } else {
             return v == 3 ? launch_cfg<T, R, 64, 8, 4, 1, 1, true>(a, opt, stream)
+                 : v == 5 ? launch_cfg<T, R, 64, 8, 2, 4, 1, true>(a, opt, stream)
                  : v == 8 ? launch_cfg<T, R, 64, 8, 4, 2, 1, true>(a, opt, stream)
                           : launch_cfg<T, R, 32, 16, 2, 4, 1, true>(a, opt, stream);
         }
@@ -356,7 +359,9 @@ static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipSt
         case 2: return launch_cfg<T, R, 32, 16, 2, 4, 1, true>(a, opt, stream);     // fp32 default
         case 3: return launch_cfg<T, R, 64, 8, 4, 1, 1, true>(a, opt, stream);      // 8 bytes per lane (fallback shape)
         case 4: return launch_cfg<T, R, 64, 8, 4, 1, 2, true>(a, opt, stream);      // two planes in flight
-        case 5: return launch_cfg<T, R, 64, 8, 2, 2, 1, true>(a, opt, stream);      // 128 x 16 tile
+        case 5:                                                                     // rows of 1 KB, 16 rows
+            if constexpr (sizeof(T) == 8) return launch_cfg<T, R, 64, 8, 2, 2, 1, true>(a, opt, stream);
+            else return launch_cfg<T, R, 64, 8, 2, 4, 1, true>(a, opt, stream);
         case 6: return launch_cfg<T, R, 32, 16, 2, 2, 1, false>(a, opt, stream);    // u_bar through L2 (no streaming hint)
         case 7: return launch_cfg<T, R, 64, 4, 4, 1, 1, true>(a, opt, stream);      // 64 x 16 tile, 256 threads
         case 8: return launch_cfg<T, R, 64, 8, 4, 2, 1, true>(a, opt, stream);      // 128 x 32 tile, PX = 2
@@ -374,11 +379,11 @@ static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipSt
 void describe_march_plan(int is_f64, int radius, int nx, int ny, int nz, const LaunchOptions &opt,
                          long *plan, int *tiles, long max_blocks)
 {
-    // the default shapes: 32 x 16 threads, two rows per thread, 16 bytes per lane; radius 1
-    // with rows that are not cache-line multiples: 16 rows of 256 or 512 cells
+    // the default shapes: 32 x 16 threads, two rows per thread, 16 bytes per lane; with rows
+    // that are not cache-line multiples: 16 rows of 1 KB (radius 1: 256 or 512 cells)
     int TX = is_f64 ? 64 : 128, TY = 32;
-    if (radius == 1 && opt.remainder == 0 && opt.variant == 0) {
-        const int wide = wide_tile_for_unaligned_rows(nx, is_f64 ? 8 : 4, !is_f64);
+    if (opt.remainder == 0 && opt.variant == 0) {
+        const int wide = wide_tile_for_unaligned_rows(nx, is_f64 ? 8 : 4, radius, !is_f64);
         if (wide) { TX = wide; TY = 16; }
     }
     March3dArgs a{};

@@ -219,18 +219,27 @@ static hipError_t launch_primal_T(const March3dArgs &a, const LaunchOptions &opt
     long v = opt.variant;
     if (v == 0) {
         v = sizeof(T) == 8 ? 3 : 8;              // measured best per dtype
-        if (R == 1 && wide_tile_for_unaligned_rows(a.nx, sizeof(T), false) == 256) v = 10;
+        const int wide = wide_tile_for_unaligned_rows(a.nx, sizeof(T), R, false);
+        if (R == 1 && wide == 256) v = 10;
+        else if (R > 1 && wide) v = 5;
     }
     if constexpr (R == 2 || R == 3) {            // the default shapes only
-        if constexpr (sizeof(T) == 8) return launch_primal_cfg<T, R, 64, 8, 4, 1>(a, opt, stream);
-        else return v == 3 ? launch_primal_cfg<T, R, 64, 8, 4, 1>(a, opt, stream) : launch_primal_cfg<T, R, 64, 8, 4, 2>(a, opt, stream);
+        if constexpr (sizeof(T) == 8) {
+            return v == 5 ? launch_primal_cfg<T, R, 64, 8, 2, 2>(a, opt, stream) : launch_primal_cfg<T, R, 64, 8, 4, 1>(a, opt, stream);
+        } else {
+            return v == 3 ? launch_primal_cfg<T, R, 64, 8, 4, 1>(a, opt, stream)
+                 : v == 5 ? launch_primal_cfg<T, R, 64, 8, 2, 4>(a, opt, stream)
+                          : launch_primal_cfg<T, R, 64, 8, 4, 2>(a, opt, stream);
+        }
     } else {
         switch (v) {
         default:
         case 1: return launch_primal_cfg<T, R, 32, 16, 2, 2>(a, opt, stream);
         case 2: return launch_primal_cfg<T, R, 32, 16, 2, 4>(a, opt, stream);
         case 3: return launch_primal_cfg<T, R, 64, 8, 4, 1>(a, opt, stream);
-        case 5: return launch_primal_cfg<T, R, 64, 8, 2, 2>(a, opt, stream);
+        case 5:                                  // rows of 1 KB, 16 rows
+            if constexpr (sizeof(T) == 8) return launch_primal_cfg<T, R, 64, 8, 2, 2>(a, opt, stream);
+            else return launch_primal_cfg<T, R, 64, 8, 2, 4>(a, opt, stream);
         case 8: return launch_primal_cfg<T, R, 64, 8, 4, 2>(a, opt, stream);
         case 10:                                 // radius 1: 256 x 16 tile (see wide_tile_for_unaligned_rows)
             if constexpr (R == 1) return launch_primal_cfg<T, R, 128, 4, 4, 2>(a, opt, stream);

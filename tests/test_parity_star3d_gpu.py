@@ -15,8 +15,9 @@ CASES = [(1, (3, 3, 3)), (1, (4, 5, 7)), (1, (21, 37, 150)), (1, (70, 18, 65)),
          (4, (9, 9, 9)), (4, (16, 17, 19)), (4, (37, 45, 150)), (4, (40, 16, 200)), (4, (70, 20, 129)),
          # left-over tiles cut finer than the rest (two groups of workgroups)
          (1, (24, 400, 610)), (2, (64, 130, 1150)),
-         # radius 1, rows not cache-line multiples: 256 x 16 tiles
-         (1, (6, 20, 1000)), (1, (9, 40, 500)), (1, (5, 33, 250))]
+         # rows not cache-line multiples: tiles of 16 rows with long rows
+         (1, (6, 20, 1000)), (1, (9, 40, 500)), (1, (5, 33, 250)),
+         (4, (20, 37, 250)), (2, (9, 40, 500)), (3, (12, 20, 1000))]
 
 
 @pytest.fixture(scope="module")

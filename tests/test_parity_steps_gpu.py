@@ -26,7 +26,7 @@ def _lams(shape, seed, dtype):
                                                  (4, (12, 33, 131), 4), (1, (21, 37, 150), 5), (1, (3, 3, 3), 4),
                                                  (4, (9, 9, 9), 3), (4, (40, 70, 64), 0), (2, (20, 33, 70), 3),
                                                  (3, (15, 20, 66), 4),
-                                                 (1, (9, 20, 250), 3)])     # radius 1, rows not line multiples: wide tiles
+                                                 (1, (9, 20, 250), 3), (4, (14, 20, 250), 3)])     # rows not line multiples: wide tiles
 def test_steps_match_the_oracle(sadj, radius, shape, nsteps, dtype):
     import torch
     c = inputs.uniform(1, "c", shape, 0.01, 0.1).astype(dtype)

@@ -321,35 +321,39 @@ def test_primal_small(sadj, radius, shape, dtype):
     assert_close(got[m], want[m], _primal_scale(d, radius)[m], dtype, "primal R=%d %s" % (radius, shape))
 
 
-# radius 1 with rows that are not a multiple of the 128-byte cache line: the launcher takes
-# tiles of 256 (fp32 adjoint: 512) cells x 16 rows when they cover nx well; 1002 is not a
-# multiple of four, so the fp32 calls fall back to the one-cell shape there
+# rows that are not a multiple of the 128-byte cache line: the launcher takes tiles of 16 rows
+# with long rows when they cover nx well (radius 1: 256 cells, fp32 adjoint 512; larger radii:
+# 1 KB); 1002 is not a multiple of four, so the fp32 calls fall back to the one-cell shape there
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
-@pytest.mark.parametrize("shape", [(20, 37, 250), (9, 40, 500), (6, 20, 1000), (5, 17, 1002), (19, 33, 750), (40, 16, 1500)])
-def test_radius_one_unaligned_rows_take_wide_tiles(sadj, shape, dtype):
+@pytest.mark.parametrize("radius,shape", [(1, (20, 37, 250)), (1, (9, 40, 500)), (1, (6, 20, 1000)), (1, (5, 17, 1002)),
+                                          (1, (19, 33, 750)), (1, (40, 16, 1500)),
+                                          (4, (20, 37, 250)), (2, (9, 40, 500)), (3, (12, 20, 1000)), (4, (11, 33, 1002)),
+                                          (4, (30, 50, 750)), (2, (5, 5, 1250))])
+def test_unaligned_rows_take_wide_tiles(sadj, radius, shape, dtype):
     nz, ny, nx = shape
-    info, _ = sadj.sadj_describe_wave3d_plan(1 if dtype == np.float64 else 0, 1, nx, ny, nz, with_tiles=False)
-    assert info["tile_h"] == 16 and info["tile_w"] in (256, 512)
+    info, _ = sadj.sadj_describe_wave3d_plan(1 if dtype == np.float64 else 0, radius, nx, ny, nz, with_tiles=False)
+    assert info["tile_h"] == 16
+    assert info["tile_w"] in ((256, 512) if radius == 1 else (1024 // np.dtype(dtype).itemsize,))
     d = inputs.wave_inputs(shape, 0.01, 0.1, seed=sum(shape), dtype=dtype, c_mode="iid")
     for zchunk in (0, 5):
         sadj.set_option("wave3d.zchunk", zchunk)
-        _check_adjoint(sadj, d, 1, dtype, with_prev=False, what="wide tiles %s zchunk=%d" % (shape, zchunk))
+        _check_adjoint(sadj, d, radius, dtype, with_prev=False, what="wide tiles R=%d %s zchunk=%d" % (radius, shape, zchunk))
     sadj.set_option("wave3d.zchunk", 0)
-    _check_adjoint(sadj, d, 1, dtype, with_prev=True, what="wide tiles %s with u_prev_bar" % (shape,))
+    _check_adjoint(sadj, d, radius, dtype, with_prev=True, what="wide tiles R=%d %s with u_prev_bar" % (radius, shape))
     r0 = inputs.uniform(3, "aux", shape, -1, 1).astype(dtype)
     r = to_gpu(r0)
-    sadj.sadj_primal_wave3d(1, to_gpu(d["u"]), to_gpu(d["u_prev"]), to_gpu(d["c"]), r)
+    sadj.sadj_primal_wave3d(radius, to_gpu(d["u"]), to_gpu(d["u_prev"]), to_gpu(d["c"]), r)
     got = to_host(r)
-    want = oracle.wave_primal(d["u"], d["u_prev"], d["c"], 1, r_init=r0)
-    m = interior_mask(shape, 1)
+    want = oracle.wave_primal(d["u"], d["u_prev"], d["c"], radius, r_init=r0)
+    m = interior_mask(shape, radius)
     assert np.array_equal(got[~m], r0[~m])
-    assert_close(got[m], want[m], _primal_scale(d, 1)[m], dtype, "primal wide tiles %s" % (shape,))
+    assert_close(got[m], want[m], _primal_scale(d, radius)[m], dtype, "primal wide tiles R=%d %s" % (radius, shape))
 
 
 # shapes whose x-y tiles do not fill whole rounds of the chip's compute units, so that the
 # left-over tiles are cut into more z-chunks than the others (two groups of workgroups)
-TWO_GROUP = [(np.float64, 4, (64, 580, 520)), (np.float64, 1, (24, 400, 610)), (np.float64, 2, (64, 130, 1150)),
-             (np.float64, 3, (100, 100, 1420)), (np.float32, 1, (24, 400, 1216))]
+TWO_GROUP = [(np.float64, 4, (64, 580, 520)), (np.float64, 1, (24, 400, 610)), (np.float64, 2, (64, 70, 1856)),
+             (np.float64, 3, (24, 610, 832)), (np.float32, 1, (24, 400, 1216))]
 
 
 @pytest.mark.parametrize("dtype,radius,shape", TWO_GROUP)
