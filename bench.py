@@ -163,6 +163,16 @@ def main():
                      "kernel_ms_mean": ev_ms, "kernel_ms_min": ev_min, "algorithmic_bytes": alg_bytes},
     }
 
+    # the paper's own timings of the same method (Section 4, performance tables), with their
+    # hardware: context only, another machine, another stencil radius and grid; `--paper-sizes`
+    # times these two workloads here
+    out["paper_context"] = {
+        "wave_7pt_1000^3_gather_adjoint_best_s": {"Xeon E5-2650 v4, 12 threads": 1.322396, "Xeon Phi 7210, 64 threads": 1.286821},
+        "wave_7pt_1000^3_primal_best_s": {"Xeon E5-2650 v4, 12 threads": 0.897188, "Xeon Phi 7210, 32 threads": 0.843320},
+        "burgers_1e9_gather_adjoint_best_s": {"Xeon E5-2650 v4, 12 threads": 1.535777, "Xeon Phi 7210, 128 threads": 0.756979},
+        "burgers_1e9_primal_best_s": {"Xeon E5-2650 v4, 12 threads": 0.555659, "Xeon Phi 7210, 128 threads": 0.502064},
+    }
+
     others = {}
 
     def add(name, fn, points, nbytes, dtype):
