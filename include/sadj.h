@@ -240,7 +240,13 @@ sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, lon
 
 /* ---- launch options -------------------------------------------------------------------
  * Process-wide integer options that select among equivalent launch strategies; they
- * never change what is computed, only how the regions are mapped to kernels.
+ * never change what is computed, only how the regions are mapped to kernels.  Every
+ * setting is deterministic (same inputs, same bits).  Settings that select another
+ * kernel shape or instruction sequence ("*.variant", "wave2d.ychunk", "wave3d.order",
+ * "stencil1d.functor") may round differently from each other within the usual
+ * floating-point tolerance; "wave3d.zchunk", "wave3d.split", "wave3d.xcdmap",
+ * "wave3d.band" and "wave3d.ldspad" only move work between workgroups and leave every
+ * bit of the 3-D results unchanged.
  *   "wave3d.zchunk"  planes of output per workgroup along z (default 0 = automatic).
  *   "wave3d.split"   0 (default): where the x-y tiles do not fill whole rounds of one workgroup
  *                    per compute unit, the left-over tiles may be cut into more z-chunks than
