@@ -182,6 +182,39 @@ def test_tile_mappings_give_identical_results(sadj, xcdmap, band):
         sadj.set_option("wave3d.zchunk", 0)
 
 
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("radius,shape", [(4, (90, 70, 200)), (1, (64, 130, 140)), (2, (50, 40, 330))])
+def test_cutting_and_placing_the_work_differently_changes_no_bit(sadj, radius, shape, dtype):
+    """z-chunk length, finer cuts of left-over tiles and the LDS request that sets the number
+    of workgroups per CU move work between workgroups; the arithmetic of a cell is the same
+    instruction sequence whichever workgroup runs it, so adjoint and primal results are
+    bit-identical under all of them."""
+    d = inputs.wave_inputs(shape, 0.01, 0.1, seed=sum(shape), dtype=dtype, c_mode="iid")
+    r0 = inputs.uniform(3, "aux", shape, -1, 1).astype(dtype)
+
+    def run():
+        ub, upb = _run_adjoint(sadj, d, radius, True)
+        ub2, _ = _run_adjoint(sadj, d, radius, False)
+        r = to_gpu(r0)
+        sadj.sadj_primal_wave3d(radius, to_gpu(d["u"]), to_gpu(d["u_prev"]), to_gpu(d["c"]), r)
+        return ub, upb, ub2, to_host(r)
+
+    ref = run()
+    try:
+        for opts in ({"wave3d.zchunk": 7}, {"wave3d.zchunk": 33}, {"wave3d.split": 1}, {"wave3d.ldspad": -1},
+                     {"wave3d.zchunk": 16, "wave3d.xcdmap": 3, "wave3d.band": 2}):
+            for k, v in opts.items():
+                sadj.set_option(k, v)
+            got = run()
+            for k in opts:
+                sadj.set_option(k, 0)
+            for a, b in zip(got, ref):
+                assert np.array_equal(a, b), opts
+    finally:
+        for k in ("wave3d.zchunk", "wave3d.split", "wave3d.ldspad", "wave3d.xcdmap", "wave3d.band"):
+            sadj.set_option(k, 0)
+
+
 @pytest.mark.parametrize("case", range(24))
 def test_adjoint_and_primal_on_drawn_shapes_and_options(sadj, case):
     """Shapes, radius, dtype and scheduling options drawn from a seeded generator: ragged
