@@ -46,7 +46,29 @@
 #include "launch.hpp"
 #include "tile3d.hpp"
 
+#include <type_traits>
+
 namespace sadj {
+
+template <class T> __device__ __forceinline__ T mul_rounded(T a, T b)
+{
+#pragma clang fp contract(off)
+    return a * b;
+}
+
+// acc + (2 r + (3 w_0 q + sum_k w_k xs_k + sum_k w_k ys_k)) with every multiply-add explicit
+// and contraction of the remaining operations off.
+template <class T, int R>
+__device__ __forceinline__ T pinned_centre(T q, T r, const T (&xs)[R], const T (&ys)[R], T acc)
+{
+#pragma clang fp contract(off)
+    T s = T(3.0 * star_w<R>(0)) * q;
+#pragma unroll
+    for (int k = 1; k <= R; ++k) s = __builtin_fmaf(T(star_w<R>(k)), xs[k - 1], s);
+#pragma unroll
+    for (int k = 1; k <= R; ++k) s = __builtin_fmaf(T(star_w<R>(k)), ys[k - 1], s);
+    return acc + __builtin_fmaf(T(2), r, s);
+}
 
 template <class T, int R, int BX, int BY, int PY, int PX, int D, bool NTU, bool GUARD, int UPREV>
 __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int tiy, int zs, int ze,
@@ -56,6 +78,17 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
     using V = Vec<T, PX>;
     constexpr int TX = G::TX, TY = G::TY, LX = G::LX, LY = G::LY, HS = G::HS;
     constexpr int NACC = 2 * R + 1;
+    // A branch-free middle part of the march.  With a branch around the stores the number of
+    // outstanding stores at the next wait for loads is unknown, and the compiler waits for all
+    // memory operations, the stores of the previous plane included, before it touches the
+    // loaded values; without the branch two stores stay in flight across the loop end.
+    // Measured at 512^3 .. 1000^3: fp32 with u_bar only gains 1-6 points; fp64 loses 1-8 (the
+    // wait keeps waves and workgroups closer together, which is worth more there) and the
+    // u_prev_bar variants lose more, so only the fp32 u_bar-only kernels have it.  Their
+    // arithmetic is written with explicit fused multiply-adds (PINNED), so that the two
+    // instantiations of a step round alike and no bit depends on where the z-chunks are cut.
+    constexpr bool STEADY_PHASE = D == 1 && sizeof(T) == 4 && UPREV == 0;
+    constexpr bool PINNED = STEADY_PHASE;
     const int tid = threadIdx.x;
     const int tx = tid % BX, ty = tid / BX;
     const int nx = a.nx, ny = a.ny, nz = a.nz;
@@ -128,9 +161,13 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
     auto plane_in_I = [&](int z) { return z >= R && z < nz - R; };
 
     // Request everything step `z` will consume into stage d.
-    auto issue = [&](int z, int d) {
-        if (z > zi1) return;
-        if (plane_in_I(z)) {
+    // `steady` (a std::bool_constant): the caller knows that every condition below holds, so
+    // the code has no branches and the compiler can count exactly which loads and stores are
+    // outstanding at each wait (see the loop at the end).
+    auto issue = [&](int z, int d, auto steady) {
+        constexpr bool ST = decltype(steady)::value;
+        if (!ST && z > zi1) return;
+        if (ST || plane_in_I(z)) {
             const T *cp = cg + (size_t)z * plane;
             const T *rp = rg + (size_t)z * plane;
 #pragma unroll
@@ -141,7 +178,7 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
 #pragma unroll
             for (int s = 0; s < HS; ++s) { shc[d][s] = ld_off(cp, hoff[s]); shr[d][s] = ld_off(rp, hoff[s]); }
             if (UPREV == 1) {                      // accumulate mode reads u_prev_bar; assign mode does not
-                if (z >= zs && z < ze) {
+                if (ST || (z >= zs && z < ze)) {
                     const T *pp = upg + (size_t)z * plane;
 #pragma unroll
                     for (int p = 0; p < PY; ++p) sp[d][p] = ld_vec_off<T, PX, NTU>(pp, ooff[p]);
@@ -149,7 +186,7 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
             }
         }
         const int zo = z - R;
-        if (zo >= zs) {                            // zo <= ze-1 because z <= zi1
+        if (ST || zo >= zs) {                      // zo <= ze-1 because z <= zi1
             const T *up = ug + (size_t)zo * plane;
 #pragma unroll
             for (int p = 0; p < PY; ++p) su[d][p] = ld_vec_off<T, PX, NTU>(up, ooff[p]);
@@ -157,8 +194,9 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
     };
 
     int buf = 0;
-    auto step = [&](int zi, int d) {
-        const bool zin = plane_in_I(zi);
+    auto step = [&](int zi, int d, auto steady) {
+        constexpr bool ST = decltype(steady)::value;
+        const bool zin = ST || plane_in_I(zi);
         const int zo = zi - R;
         T *sb = sq + buf * (LY * LX);
         T qo[PY][PX], ro[PY][PX];
@@ -172,7 +210,10 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
                 for (int e = 0; e < PX; ++e) {
                     const T cc = sc[d][p].v[e], rv = sr[d][p].v[e];
                     ro[p][e] = GUARD ? (ouse[p][e] ? rv : T(0)) : rv;
-                    qo[p][e] = GUARD ? (ouse[p][e] ? cc * rv : T(0)) : cc * rv;
+                    // PINNED: a product rounded on its own, never fused into a later addition
+                    // (for radius 1 the z-terms are acc + 1.0 * q, which would otherwise invite it)
+                    const T cr = PINNED ? mul_rounded(cc, rv) : cc * rv;
+                    qo[p][e] = GUARD ? (ouse[p][e] ? cr : T(0)) : cr;
                     sb[(R + ty * PY + p) * LX + R + tx * PX + e] = qo[p][e];
                 }
 #pragma unroll
@@ -181,7 +222,7 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
                 sb[hlds[s]] = qq;
             }
             if (UPREV) {
-                if (zi >= zs && zi < ze) {
+                if (ST || (zi >= zs && zi < ze)) {
                     T *pp = upg + (size_t)zi * plane;
 #pragma unroll
                     for (int p = 0; p < PY; ++p) {
@@ -202,7 +243,7 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
             }
         }
         // the registers of stage d are free again: request plane zi+D
-        issue(zi + D, d);
+        issue(zi + D, d, steady);
         if (zin) {
             __syncthreads();
 #pragma unroll
@@ -213,22 +254,36 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
 #pragma unroll
                 for (int p = 0; p < PY; ++p) {
                     const T *row = sb + (R + ty * PY + p) * LX + R + tx * PX + e;
-                    T s = T(3.0 * star_w<R>(0)) * qo[p][e];
+                    if constexpr (PINNED) {
+                        // every multiply-add written out, so that the generic and the branch-free
+                        // instantiation of this step round alike
+                        T xs[R], ys[R];
 #pragma unroll
-                    for (int k = 1; k <= R; ++k) s += T(star_w<R>(k)) * (row[-k] + row[k]);
+                        for (int k = 1; k <= R; ++k) { xs[k - 1] = row[-k] + row[k]; ys[k - 1] = col[R + p - k] + col[R + p + k]; }
+                        acc[p][e][R] = pinned_centre<T, R>(qo[p][e], ro[p][e], xs, ys, acc[p][e][R]);
 #pragma unroll
-                    for (int k = 1; k <= R; ++k) s += T(star_w<R>(k)) * (col[R + p - k] + col[R + p + k]);
-                    acc[p][e][R] += s + T(2) * ro[p][e];
+                        for (int k = 1; k <= R; ++k) {
+                            acc[p][e][R - k] = __builtin_fmaf(T(star_w<R>(k)), qo[p][e], acc[p][e][R - k]);
+                            acc[p][e][R + k] = __builtin_fmaf(T(star_w<R>(k)), qo[p][e], acc[p][e][R + k]);
+                        }
+                    } else {
+                        T s = T(3.0 * star_w<R>(0)) * qo[p][e];
 #pragma unroll
-                    for (int k = 1; k <= R; ++k) {
-                        acc[p][e][R - k] += T(star_w<R>(k)) * qo[p][e];
-                        acc[p][e][R + k] += T(star_w<R>(k)) * qo[p][e];
+                        for (int k = 1; k <= R; ++k) s += T(star_w<R>(k)) * (row[-k] + row[k]);
+#pragma unroll
+                        for (int k = 1; k <= R; ++k) s += T(star_w<R>(k)) * (col[R + p - k] + col[R + p + k]);
+                        acc[p][e][R] += s + T(2) * ro[p][e];
+#pragma unroll
+                        for (int k = 1; k <= R; ++k) {
+                            acc[p][e][R - k] += T(star_w<R>(k)) * qo[p][e];
+                            acc[p][e][R + k] += T(star_w<R>(k)) * qo[p][e];
+                        }
                     }
                 }
             }
             buf ^= 1;
         }
-        if (zo >= zs) {
+        if (ST || zo >= zs) {
             T *up = ug + (size_t)zo * plane;
 #pragma unroll
             for (int p = 0; p < PY; ++p) {
@@ -248,12 +303,30 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
             }
     };
 
+    using Generic = std::false_type;
+    using Steady = std::true_type;
 #pragma unroll
-    for (int d = 0; d < D; ++d) issue(zi0 + d, d);
-    for (int zb = zi0; zb <= zi1; zb += D) {
+    for (int d = 0; d < D; ++d) issue(zi0 + d, d, Generic{});
+    if constexpr (STEADY_PHASE) {
+        // Steady steps zi in [lo, hi]: planes zi and zi+1 lie in I and in this chunk's input
+        // range, and the output planes zi-R and zi+1-R belong to the chunk.
+        const int lo = zs + R;
+        const int hi = min(nz - R - 2, ze - 2);
+        int zi = zi0;
+        for (; zi <= zi1 && zi < lo; ++zi) step(zi, 0, Generic{});
+        // Enter the steady loop with nothing outstanding: otherwise the unknown number of loads
+        // that the generic steps may have left pending is carried into the loop header, and
+        // every iteration waits for all its memory operations there (vmcnt(0); expcnt and
+        // lgkmcnt untouched).
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        for (; zi <= hi; ++zi) step(zi, 0, Steady{});
+        for (; zi <= zi1; ++zi) step(zi, 0, Generic{});
+    } else {
+        for (int zb = zi0; zb <= zi1; zb += D) {
 #pragma unroll
-        for (int d = 0; d < D; ++d)
-            if (zb + d <= zi1) step(zb + d, d);
+            for (int d = 0; d < D; ++d)
+                if (zb + d <= zi1) step(zb + d, d, Generic{});
+        }
     }
 }
 
