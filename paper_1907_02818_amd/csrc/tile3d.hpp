@@ -122,8 +122,8 @@ static inline int cdiv_i(int a, int b) { return (a + b - 1) / b; }
 // number of chunks; or the tiles that fill whole rounds with few (long) chunks each cut
 // alike and only the left-over tiles cut finer, so that they fill one more round instead of
 // leaving most CUs idle (768^3 with 64 x 32 tiles: 256 tiles march all 768 planes, the
-// other 32 are cut into 8 chunks of 96: 880 + 2*2R plane times instead of 9 rounds of
-// 96 + 2R = 936).  Ties go to fewer workgroups.  With tiles*chunks == ncu this is the single
+// other 32 are cut into 8 chunks of 96: 768 + 96 + 2*2R = 880 plane times instead of 9 rounds
+// of 96 + 2R, 936).  Ties go to fewer workgroups.  With tiles*chunks == ncu this is the single
 // resident wave in which neighbouring tiles move through z in lockstep.
 static inline void plan_march(TileMap &m, int nx, int ny, int nz, int TX, int TY, int R, const LaunchOptions &opt,
                               int wg_per_cu = 1)
