@@ -403,10 +403,11 @@ template <class T, int R>
 static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipStream_t stream)
 {
     long v = opt.variant;
-    // measured best: 16 bytes per lane (1 for fp64, 2 for fp32) unless u_prev_bar is read and
-    // written as well, where the wider tiles with fewer registers per cell win
+    // measured best: 16 bytes per lane (1 for fp64, 2 for fp32); fp64 with u_prev_bar read and
+    // written as well: the one-cell shape with fewer registers per cell (3).  (fp32 with
+    // u_prev_bar: shape 2 measured 3-16 points faster than the 8-byte shape 8 at 256^3 .. 896^3.)
     if (v == 0) {
-        v = (a.out1 && !a.out1_assign) ? (sizeof(T) == 8 ? 3 : 8) : (sizeof(T) == 8 ? 1 : 2);
+        v = sizeof(T) == 8 ? ((a.out1 && !a.out1_assign) ? 3 : 1) : 2;
         if (opt.remainder == 0) {
             const int wide = wide_tile_for_unaligned_rows(a.nx, sizeof(T), R, sizeof(T) == 4);
             if (R == 1 && wide == 512) v = 11;
