@@ -1,27 +1,42 @@
 #!/usr/bin/env python3
 """Benchmark of the adjoint-stencil hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--all] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--all] [--only NAME] [--no-cpu-baseline]
 
 A step is one call of sadj_adjoint_wave3d (core region + remainder regions) on the
 headline workload: 3-D variable-coefficient wave stencil, 25-point star (radius 4),
 512^3 grid, fp64, u_bar accumulated, inputs already resident in HBM.  Prints ONE
 JSON line.  `value` = grid points of u_bar updated per second (Gpoints/s).
 
+Timing protocol.  After a load step from idle the GPU's firmware lowers the shader
+clock for some 20 ms (2.43 -> about 1.5 GHz, restored in steps; the memory clock stays
+put), and a kernel that is not purely memory-bound runs up to 20 % slower meanwhile.
+Every timed leg is therefore preceded by a disclosed SETTLE phase: the call is launched
+in groups of ten until the per-launch times of a group agree within 1 % (its slowest
+and fastest launch set aside) and the group's mean is within 1 % of the previous
+group's (at most `--settle-cap` launches).
+Then come the W warm-up and the K timed steps exactly as the flags say; nothing inside
+the timed region differs from a run without the settle phase.  The JSON carries
+`settle_launches` and the mean of the first (unsettled) launches next to the timed mean.
+
 roofline: HBM-bound.  achieved = algorithmic bytes per call / mean kernel time
 measured with HIP events on the launch stream; algorithmic bytes = read c and r_bar
 once on the primal interior, read and write u_bar once on the whole grid
-(16 N + 16 |I| bytes in fp64).  peak = 8000 GB/s (MI355X HBM3E).
+(16 N + 16 |I| bytes in fp64).  peak = 8000 GB/s (MI355X HBM3E).  stream_ceiling =
+what the library's plain streaming kernel with the same mix of streams (two arrays
+read, one read and written, no halo) reaches in the same process.
 
-cpu_baseline: the CPU oracle (scatter adjoint, one core, gcc -O2) timed on the
-leading z-planes of the same arrays (about 15 s of work, at most the whole grid).
+cpu_baseline: the CPU oracle (scatter adjoint, one core, gcc -O2) on the same arrays,
+median of three runs.
 
-With --all the same JSON line carries an "others" object with the remaining
-workloads (fp32, radius 1, primal, 2-D, Burgers, 1-D), each timed the same way.
+`others` carries the remaining workloads of the benchmark definition (fp32, with
+u_prev_bar, primal, radius 1, 2-D, Burgers, 1-D), each timed the same way; --all adds
+the further stencil families, --only NAME times a single workload (for profiling).
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -34,6 +49,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 METRIC = "adjoint stencil Gpoints/s + % of peak HBM GB/s, 3D wave r=4 512^3 fp64"
+HEADLINE = "wave3d_r4_f64_adjoint"
 
 
 def cpu_model():
@@ -63,38 +79,97 @@ def wave_adjoint_bytes(shape, radius, esize, with_prev=False):
     return b
 
 
-def time_calls(fn, steps, warmup):
-    """Returns (wall ms per step, mean HIP-event ms per call).  Events are recorded
-    on torch's current stream, which is the stream the binding launches on."""
-    import torch
-    for _ in range(warmup):
-        fn()
-    torch.cuda.synchronize()
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
-    stops = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
-    t0 = time.perf_counter()
-    for i in range(steps):
-        starts[i].record()
-        fn()
-        stops[i].record()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ev = [s.elapsed_time(e) for s, e in zip(starts, stops)]
-    return (t1 - t0) * 1e3 / steps, float(np.mean(ev)), float(np.min(ev))
+def library_sources_sha256():
+    """Hash of the kernel sources and headers libsadj.so is built from; the counter
+    summaries under profiles/ record it, so that a summary taken from other sources is
+    recognised as stale."""
+    h = hashlib.sha256()
+    files = []
+    for sub in (os.path.join("paper_1907_02818_amd", "csrc"), "include"):
+        d = os.path.join(ROOT, sub)
+        for name in sorted(os.listdir(d)):
+            if name.endswith((".hip", ".hpp", ".h")):
+                files.append(os.path.join(d, name))
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
 
 
-def read_traffic(name):
-    """HBM bytes per launch derived from rocprofv3 --pmc runs, kept as text under
-    profiles/ (line 'traffic_bytes_per_launch: N'); None when not recorded."""
-    path = os.path.join(ROOT, "profiles", name)
+def read_traffic(workload):
+    """HBM bytes per launch from the rocprofv3 --pmc summary profiles/<workload>_pmc.txt
+    (lines 'traffic_bytes_per_launch: N' and 'library_sources_sha256: H').  Returns
+    (bytes or None, note): the value is reported only if the summary was taken from the
+    sources this library was built from."""
+    path = os.path.join(ROOT, "profiles", workload + "_pmc.txt")
+    val = sha = None
     try:
         with open(path) as fh:
             for ln in fh:
                 if ln.startswith("traffic_bytes_per_launch:"):
-                    return float(ln.split(":", 1)[1])
+                    val = float(ln.split(":", 1)[1])
+                elif ln.startswith("library_sources_sha256:"):
+                    sha = ln.split(":", 1)[1].strip()
     except OSError:
-        pass
-    return None
+        return None, "no counter summary recorded for this workload"
+    if val is None:
+        return None, "summary holds no traffic line"
+    if sha != library_sources_sha256():
+        return None, "recorded summary profiles/%s_pmc.txt is from other kernel sources (stale)" % workload
+    return val, "recorded: profiles/%s_pmc.txt, same kernel sources (sha256 %s)" % (workload, sha[:12])
+
+
+class Timer:
+    def __init__(self, settle_cap):
+        self.settle_cap = settle_cap
+
+    def settle(self, fn):
+        """Launch in groups of ten until the clocks have settled (see module docstring).
+        Returns (launches done, mean ms of the first up to 25 launches, settled?)."""
+        import torch
+        group, tol = 10, 0.01
+        done, first, prev_mean, ok = 0, [], None, False
+        while done < self.settle_cap:
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(group + 1)]
+            ev[0].record()
+            for i in range(group):
+                fn()
+                ev[i + 1].record()
+            torch.cuda.synchronize()
+            t = [ev[i].elapsed_time(ev[i + 1]) for i in range(group)]
+            done += group
+            if len(first) < 25:
+                first.extend(t[: 25 - len(first)])
+            mean = float(np.mean(t))
+            mid = sorted(t)[1:-1]                     # one outlier on either side is tolerated
+            if mid[-1] <= mid[0] * (1 + tol) and prev_mean is not None and abs(mean - prev_mean) <= tol * prev_mean:
+                ok = True
+                break
+            prev_mean = mean
+        return done, (float(np.mean(first)) if first else None), ok
+
+    def time_calls(self, fn, steps, warmup):
+        """Returns a dict: wall ms per step, mean / min HIP-event ms per call (events are
+        recorded on torch's current stream, the stream the binding launches on), and the
+        settle phase's figures."""
+        import torch
+        starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+        stops = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+        settle_launches, first_ms, settled = self.settle(fn) if self.settle_cap > 0 else (0, None, False)
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            starts[i].record()
+            fn()
+            stops[i].record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ev = [s.elapsed_time(e) for s, e in zip(starts, stops)]
+        return {"wall_ms": (t1 - t0) * 1e3 / steps, "ev_mean": float(np.mean(ev)), "ev_min": float(np.min(ev)),
+                "settle_launches": settle_launches, "settled": settled, "unsettled_first_ms": first_ms}
 
 
 def main():
@@ -102,13 +177,16 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--all", action="store_true", help="also time the other workloads")
+    ap.add_argument("--all", action="store_true", help="also time the further stencil families and modes")
+    ap.add_argument("--only", default=None, help="time this one workload only (a key of `others`, or the headline)")
     ap.add_argument("--remainder-study", action="store_true",
                     help="also time the three remainder strategies of the 3-D adjoint")
     ap.add_argument("--paper-sizes", action="store_true",
                     help="also time the paper's own two experiments (1000^3 wave step, 10^9-cell Burgers step; "
                          "needs about 35 GB of device memory)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--settle-cap", type=int, default=300,
+                    help="upper limit of launches in the settle phase before each timed leg (0 = no settle phase)")
     ap.add_argument("--size", type=int, default=512, help="grid edge of the headline workload")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed region run one plain device copy of a whole array (the known-size "
@@ -129,39 +207,212 @@ def main():
     sadj.load()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    timer = Timer(args.settle_cap)
 
     n = args.size
     shape = (n, n, n)
     R = 4
+    N = n ** 3
     d = inputs.config_inputs("wave3d_r4", shape=shape, fields=("c", "r_bar", "u_bar"))
     c, rb, ub = (torch.from_numpy(d[k]).to(dev) for k in ("c", "r_bar", "u_bar"))
     torch.cuda.synchronize()
 
-    wall_ms, ev_ms, ev_min = time_calls(lambda: sadj.sadj_adjoint_wave3d(R, c, rb, ub), args.steps, args.warmup)
-    N = n ** 3
-    alg_bytes = wave_adjoint_bytes(shape, R, 8)
-    achieved = alg_bytes / (ev_ms * 1e-3) / 1e9
-    out = {
-        "metric": METRIC,
-        "value": N / (wall_ms * 1e-3) / 1e9,
-        "unit": "Gpoints/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": wall_ms,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "f64",
-        "data": "synthetic",
-        "config": {"workload": "wave3d adjoint, 25-point star r=4, %d^3, fp64, u_bar only" % n,
-                   "variant": sadj.get_option("wave3d.variant"),
-                   "zchunk": sadj.get_option("wave3d.zchunk")},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": read_traffic("adjoint_wave3d_r4_f64_512_pmc.txt") if n == 512 else None,
-                     "kernel_ms_mean": ev_ms, "kernel_ms_min": ev_min, "algorithmic_bytes": alg_bytes},
+    others = {}
+    steps_o, warm_o = max(5, args.steps // 4), max(3, args.warmup // 4)
+
+    def add(name, fn, points, nbytes, dtype, per=1, steps=None, warmup=None):
+        """Time one further workload; `per` = inner steps one call performs.  One untimed
+        call first, so that arrays the workload creates on first use exist."""
+        fn()
+        torch.cuda.synchronize()
+        t = timer.time_calls(fn, steps or steps_o, warmup or warm_o)
+        gbs = nbytes / (t["ev_mean"] * 1e-3) / 1e9
+        traffic, tnote = read_traffic(name)
+        others[name] = {"Gpoints/s": points / (t["wall_ms"] * 1e-3) / 1e9, "ms": t["wall_ms"] / per,
+                        "kernel_ms_mean": t["ev_mean"] / per, "kernel_ms_min": t["ev_min"] / per,
+                        "GB/s": gbs, "frac": gbs / HBM_PEAK_GBS, "dtype": dtype,
+                        "algorithmic_bytes": nbytes // per,
+                        "settle_launches": t["settle_launches"], "settled": t["settled"],
+                        "kernel_ms_unsettled_first25": (t["unsettled_first_ms"] / per) if t["unsettled_first_ms"] else None}
+        if traffic is not None:
+            others[name]["traffic"] = traffic
+            others[name]["traffic_source"] = tnote
+        return others[name]
+
+    # ---------------------------------------------------------------- workload table
+    # Arrays of the further workloads are views of / conversions from the headline's
+    # seeded arrays (values do not change a streaming kernel's speed).
+    lazy = {}
+
+    def get(key, make):
+        if key not in lazy:
+            lazy[key] = make()
+        return lazy[key]
+
+    def upb():
+        return get("upb", lambda: torch.from_numpy(
+            inputs.config_inputs("wave3d_r4", shape=shape, fields=("u_prev_bar",))["u_prev_bar"]).to(dev))
+
+    def rbuf():
+        return get("r", lambda: torch.empty_like(ub))
+
+    def r2d():
+        return get("r2d", lambda: rbuf().reshape(-1)[: s2[0] * s2[1]].reshape(s2))
+
+    def f32set():
+        return get("f32", lambda: (c.float(), rb.float(), ub.float()))
+
+    s2 = (8192, 8192)
+    nb = 1 << 24
+    n1 = 4096
+
+    def views2d():
+        return get("v2d", lambda: tuple(t.reshape(-1)[: s2[0] * s2[1]].reshape(s2) for t in (c, rb, ub)))
+
+    def views1d():
+        return get("v1d", lambda: tuple(t.reshape(-1)[:n1] for t in (c, rb, ub)))
+
+    burg_state = {"i": 0}
+
+    def burg_sets():
+        # three rotating buffer sets so that the 128 MiB arrays do not stay in the 256 MB last-level cache
+        return get("burg", lambda: [tuple(t.reshape(-1)[k * nb:(k + 1) * nb] for t in (rb, c, ub)) for k in range(3)])
+
+    def burg_adj():
+        u_, r_, b_ = burg_sets()[burg_state["i"] % 3]
+        burg_state["i"] += 1
+        sadj.sadj_adjoint_burgers1d(0.1, 0.05, u_, r_, b_)
+
+    def burg_pri():
+        u_, r_, b_ = burg_sets()[burg_state["i"] % 3]
+        burg_state["i"] += 1
+        sadj.sadj_primal_burgers1d(0.1, 0.05, u_, b_)
+
+    I4, I1 = interior_points(shape, 4), interior_points(shape, 1)
+    table = {
+        # the benchmark definition's five configurations and the forms the paper differentiates
+        "wave3d_r4_f32_adjoint": lambda: add("wave3d_r4_f32_adjoint", lambda: sadj.sadj_adjoint_wave3d(R, *f32set()), N,
+                                             wave_adjoint_bytes(shape, R, 4), "f32"),
+        "wave3d_r4_f64_adjoint_with_u_prev_bar": lambda: add(
+            "wave3d_r4_f64_adjoint_with_u_prev_bar", lambda: sadj.sadj_adjoint_wave3d(R, c, rb, ub, upb()), N,
+            wave_adjoint_bytes(shape, R, 8, True), "f64"),
+        "wave3d_r4_f64_primal": lambda: add("wave3d_r4_f64_primal", lambda: sadj.sadj_primal_wave3d(R, ub, upb(), c, rbuf()),
+                                            N, 8 * N + 24 * I4, "f64"),
+        "wave3d_r1_f64_adjoint": lambda: add("wave3d_r1_f64_adjoint", lambda: sadj.sadj_adjoint_wave3d(1, c, rb, ub), N,
+                                             wave_adjoint_bytes(shape, 1, 8), "f64"),
+        "wave3d_r1_f64_adjoint_with_u_prev_bar": lambda: add(
+            "wave3d_r1_f64_adjoint_with_u_prev_bar", lambda: sadj.sadj_adjoint_wave3d(1, c, rb, ub, upb()), N,
+            wave_adjoint_bytes(shape, 1, 8, True), "f64"),
+        "wave2d_f64_adjoint": lambda: add("wave2d_f64_adjoint", lambda: sadj.sadj_adjoint_wave2d(*views2d()),
+                                          s2[0] * s2[1], wave_adjoint_bytes(s2, 1, 8), "f64"),
+        "burgers1d_f64_adjoint": lambda: add("burgers1d_f64_adjoint", burg_adj, nb, 32 * nb, "f64"),
+        "wave1d_f64_adjoint_n4096_latency": lambda: add(
+            "wave1d_f64_adjoint_n4096_latency",
+            lambda: sadj.sadj_adjoint_wave1d(*views1d()), n1, 32 * n1, "f64"),
     }
+    default_names = list(table)
+
+    def more():
+        wbox = [[[0.1 * (i + 3 * j + 9 * k) - 1.0 for i in range(3)] for j in range(3)] for k in range(3)]
+        wbox2 = [[0.1 * (i + 3 * j) - 0.4 for i in range(3)] for j in range(3)]
+        wstar = [0.3] + [0.05 * (i % 7) - 0.12 for i in range(24)]
+        ksteps = 6
+        t = {
+            # reverse sweep of a time loop: per step read c and lam_a on I, read+write lam_b, write lam_p
+            "wave3d_r4_f64_adjoint_steps_per_step": lambda: add(
+                "wave3d_r4_f64_adjoint_steps_per_step", lambda: sadj.sadj_adjoint_wave3d_steps(R, ksteps, c, rb, ub, upb()),
+                N * ksteps, ksteps * (16 * I4 + 16 * N + 8 * N), "f64", per=ksteps),
+            "wave3d_r1_f64_primal": lambda: add("wave3d_r1_f64_primal", lambda: sadj.sadj_primal_wave3d(1, ub, upb(), c, rbuf()),
+                                                N, 8 * N + 24 * I1, "f64"),
+            "wave3d_r2_f64_adjoint": lambda: add("wave3d_r2_f64_adjoint", lambda: sadj.sadj_adjoint_wave3d(2, c, rb, ub), N,
+                                                 wave_adjoint_bytes(shape, 2, 8), "f64"),
+            "wave3d_r3_f64_adjoint": lambda: add("wave3d_r3_f64_adjoint", lambda: sadj.sadj_adjoint_wave3d(3, c, rb, ub), N,
+                                                 wave_adjoint_bytes(shape, 3, 8), "f64"),
+            # dense 3x3x3 box stencil with asymmetric weights (27 terms), same grid
+            "box3d_f64_adjoint": lambda: add("box3d_f64_adjoint", lambda: sadj.sadj_adjoint_box(wbox, c, rb, ub), N,
+                                             wave_adjoint_bytes(shape, 1, 8), "f64"),
+            "box3d_f64_primal": lambda: add("box3d_f64_primal", lambda: sadj.sadj_primal_box(wbox, ub, c, rbuf()), N,
+                                            8 * N + 16 * I1, "f64"),
+            # general star of radius 4 with an asymmetric weight table (25 free weights)
+            "star3d_r4_f64_adjoint": lambda: add("star3d_r4_f64_adjoint", lambda: sadj.sadj_adjoint_star3d(4, wstar, c, rb, ub),
+                                                 N, wave_adjoint_bytes(shape, 4, 8), "f64"),
+            "star3d_r4_f64_primal": lambda: add("star3d_r4_f64_primal", lambda: sadj.sadj_primal_star3d(4, wstar, ub, c, rbuf()),
+                                                N, 8 * N + 16 * I4, "f64"),
+            "wave2d_f64_primal": lambda: add(
+                "wave2d_f64_primal",
+                lambda: sadj.sadj_primal_wave2d(views2d()[2], views2d()[1], views2d()[0], r2d()),
+                s2[0] * s2[1], 8 * s2[0] * s2[1] + 24 * interior_points(s2, 1), "f64"),
+            "box2d_f64_adjoint": lambda: add("box2d_f64_adjoint", lambda: sadj.sadj_adjoint_box(wbox2, *views2d()),
+                                             s2[0] * s2[1], wave_adjoint_bytes(s2, 1, 8), "f64"),
+            "burgers1d_f64_primal": lambda: add("burgers1d_f64_primal", burg_pri, nb, 16 * nb, "f64"),
+        }
+        return t
+
+    if args.all or (args.only and args.only not in table and args.only != HEADLINE):
+        table.update(more())
+
+    def burgers_steps_leg():
+        # reverse sweep over stored Burgers states: per step read u^t and lam, write lam (24 B/pt)
+        ks = 12
+        states = torch.rand(ks + 1, nb, device=dev, dtype=torch.float64)
+        la, lb = torch.rand(nb, device=dev, dtype=torch.float64), torch.zeros(nb, device=dev, dtype=torch.float64)
+        add("burgers1d_f64_adjoint_steps_per_step", lambda: sadj.sadj_adjoint_burgers1d_steps(0.1, 0.05, ks, ks, states, la, lb),
+            nb * ks, 32 * nb + (ks - 1) * 24 * nb, "f64", per=ks)
+
+    def functor_leg():
+        sadj.set_option("stencil1d.functor", 1)      # same stencil through the generic functor kernel
+        add("burgers1d_f64_adjoint_functor", burg_adj, nb, 32 * nb, "f64")
+        sadj.set_option("stencil1d.functor", 0)
+
+    def graph_leg():
+        # the n = 4096 call recorded 100 times into a HIP graph: the launch-bound size without host launch cost
+        c1, rb1, ub1 = views1d()
+        per_graph = 100
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            sadj.sadj_adjoint_wave1d(c1, rb1, ub1)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(per_graph):
+                sadj.sadj_adjoint_wave1d(c1, rb1, ub1)
+        add("wave1d_f64_adjoint_n4096_in_hip_graph_per_call", graph.replay, n1 * per_graph, 32 * n1 * per_graph, "f64",
+            per=per_graph)
+
+    if args.all:
+        table["burgers1d_f64_adjoint_steps_per_step"] = burgers_steps_leg
+        table["burgers1d_f64_adjoint_functor"] = functor_leg
+        table["wave1d_f64_adjoint_n4096_in_hip_graph_per_call"] = graph_leg
+
+    # ---------------------------------------------------------------- headline
+    out = {"metric": METRIC, "unit": "Gpoints/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic"}
+    if args.only is None or args.only == HEADLINE:
+        t = timer.time_calls(lambda: sadj.sadj_adjoint_wave3d(R, c, rb, ub), args.steps, args.warmup)
+        alg_bytes = wave_adjoint_bytes(shape, R, 8)
+        achieved = alg_bytes / (t["ev_mean"] * 1e-3) / 1e9
+        traffic, tnote = read_traffic(HEADLINE) if n == 512 else (None, "recorded for 512^3 only")
+        out.update({
+            "value": N / (t["wall_ms"] * 1e-3) / 1e9,
+            "ms_per_step": t["wall_ms"],
+            "config": {"workload": "wave3d adjoint, 25-point star r=4, %d^3, fp64, u_bar only" % n,
+                       "variant": sadj.get_option("wave3d.variant"),
+                       "zchunk": sadj.get_option("wave3d.zchunk")},
+            "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": tnote,
+                         "kernel_ms_mean": t["ev_mean"], "kernel_ms_min": t["ev_min"], "algorithmic_bytes": alg_bytes},
+            "settle": {"launches": t["settle_launches"], "settled": t["settled"], "cap": args.settle_cap,
+                       "kernel_ms_unsettled_first25": t["unsettled_first_ms"],
+                       "rule": "groups of 10 launches until the times of a group agree within 1 % (slowest and fastest "
+                               "set aside) and the group mean is within 1 % of the previous group's; then the W warm-up "
+                               "and K timed steps as flagged",
+                       "why": "after a load step from idle the shader clock drops from 2.43 to about 1.5 GHz for some "
+                              "20 ms (memory clock unchanged); the first launches of a process run up to 20 % slower"},
+        })
+    else:
+        out.update({"value": None, "ms_per_step": None, "config": {"workload": "only " + args.only}})
 
     # the paper's own timings of the same method (Section 4, performance tables), with their
     # hardware: context only, another machine, another stencil radius and grid; `--paper-sizes`
@@ -173,19 +424,41 @@ def main():
         "burgers_1e9_primal_best_s": {"Xeon E5-2650 v4, 12 threads": 0.555659, "Xeon Phi 7210, 128 threads": 0.502064},
     }
 
-    others = {}
+    # ---------------------------------------------------------------- streaming ceiling
+    def stream_ceiling(dtype_name):
+        a_, b_, o_ = ((c, rb, ub) if dtype_name == "f64" else f32set())
+        a_, b_, o_ = (t.reshape(-1) for t in (a_, b_, o_))
+        esize = 8 if dtype_name == "f64" else 4
+        best = None
+        for shp in (0, 1):
+            t = timer.time_calls(lambda: sadj.sadj_stream_probe(shp, a_, b_, o_), steps_o, warm_o)
+            gbs = 4 * esize * N / (t["ev_mean"] * 1e-3) / 1e9
+            if best is None or gbs > best["GB/s"]:
+                best = {"GB/s": gbs, "kernel_ms_mean": t["ev_mean"], "shape": shp, "bytes": 4 * esize * N,
+                        "what": "out[i] += a[i]*b[i] over the same %d^3 %s arrays (sadj_stream_probe), best of two launch shapes"
+                                % (n, dtype_name)}
+        return best
 
-    def add(name, fn, points, nbytes, dtype):
-        w, e, emin = time_calls(fn, max(5, args.steps // 4), max(3, args.warmup // 4))
-        others[name] = {"Gpoints/s": points / (w * 1e-3) / 1e9, "ms": w, "kernel_ms_mean": e,
-                        "GB/s": nbytes / (e * 1e-3) / 1e9, "frac": nbytes / (e * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                        "dtype": dtype}
-
-    # fp32 run of the same workload (same draws rounded to float)
-    c32, rb32, ub32 = c.float(), rb.float(), ub.float()
-    add("wave3d_r4_f32_adjoint", lambda: sadj.sadj_adjoint_wave3d(R, c32, rb32, ub32), N,
-        wave_adjoint_bytes(shape, R, 4), "f32")
-    del c32, rb32, ub32
+    if args.only is None:
+        sc = stream_ceiling("f64")
+        out["roofline"]["stream_ceiling"] = sc
+        out["roofline"]["frac_of_ceiling"] = out["roofline"]["achieved"] / sc["GB/s"]
+        names = list(table) if args.all else default_names
+        for name in names:
+            table[name]()
+            if name == "wave3d_r4_f32_adjoint":
+                sc32 = stream_ceiling("f32")
+                others[name]["stream_ceiling"] = sc32
+                others[name]["frac_of_ceiling"] = others[name]["GB/s"] / sc32["GB/s"]
+                lazy.pop("f32", None)
+        for name, o in others.items():
+            if o["dtype"] == "f64" and "latency" not in name and "graph" not in name:
+                o["frac_of_ceiling"] = o["GB/s"] / sc["GB/s"]
+    elif args.only != HEADLINE:
+        if args.only not in table:
+            print("bench.py: unknown workload %r; known: %s" % (args.only, ", ".join([HEADLINE] + sorted(table))), file=sys.stderr)
+            sys.exit(2)
+        table[args.only]()
 
     if args.remainder_study:
         # Section 3.3.4's alternatives on the GPU: 0 guarded only where needed (default),
@@ -207,99 +480,7 @@ def main():
             add("atomic_scatter_r%d_f64_adjoint" % rad, lambda: sadj.sadj_adjoint_wave3d_atomic_scatter(rad, c, rb, ub),
                 N, wave_adjoint_bytes(shape, rad, 8), "f64")
 
-    if args.all:
-        upb = torch.from_numpy(inputs.config_inputs("wave3d_r4", shape=shape, fields=("u_prev_bar",))["u_prev_bar"]).to(dev)
-        add("wave3d_r4_f64_adjoint_with_u_prev_bar", lambda: sadj.sadj_adjoint_wave3d(R, c, rb, ub, upb), N,
-            wave_adjoint_bytes(shape, R, 8, True), "f64")
-        # reverse sweep of a time loop: per step read c and lam_a on I, read+write lam_b, write lam_p
-        ksteps = 6
-        I4 = interior_points(shape, R)
-        add("wave3d_r4_f64_adjoint_steps_per_step", lambda: sadj.sadj_adjoint_wave3d_steps(R, ksteps, c, rb, ub, upb),
-            N * ksteps, ksteps * (16 * I4 + 16 * N + 8 * N), "f64")
-        others["wave3d_r4_f64_adjoint_steps_per_step"]["ms"] /= ksteps
-        others["wave3d_r4_f64_adjoint_steps_per_step"]["kernel_ms_mean"] /= ksteps
-        # primal: reads u, u_prev, c, writes r (u_bar/u_prev_bar buffers reused as u/u_prev)
-        r = torch.empty_like(ub)
-        I = interior_points(shape, R)
-        add("wave3d_r4_f64_primal", lambda: sadj.sadj_primal_wave3d(R, ub, upb, c, r), N, 8 * N + 24 * I, "f64")
-        add("wave3d_r1_f64_adjoint", lambda: sadj.sadj_adjoint_wave3d(1, c, rb, ub), N,
-            wave_adjoint_bytes(shape, 1, 8), "f64")
-        add("wave3d_r1_f64_primal", lambda: sadj.sadj_primal_wave3d(1, ub, upb, c, r), N,
-            8 * N + 24 * interior_points(shape, 1), "f64")
-        for rad in (2, 3):
-            add("wave3d_r%d_f64_adjoint" % rad, lambda: sadj.sadj_adjoint_wave3d(rad, c, rb, ub), N,
-                wave_adjoint_bytes(shape, rad, 8), "f64")
-        # dense 3x3x3 box stencil with asymmetric weights (27 terms), same grid
-        wbox = [[[0.1 * (i + 3 * j + 9 * k) - 1.0 for i in range(3)] for j in range(3)] for k in range(3)]
-        add("box3d_f64_adjoint", lambda: sadj.sadj_adjoint_box(wbox, c, rb, ub), N,
-            wave_adjoint_bytes(shape, 1, 8), "f64")
-        add("box3d_f64_primal", lambda: sadj.sadj_primal_box(wbox, ub, c, r), N,
-            8 * N + 16 * interior_points(shape, 1), "f64")
-        # general star of radius 4 with an asymmetric weight table (25 free weights)
-        wstar = [0.3] + [0.05 * (i % 7) - 0.12 for i in range(24)]
-        add("star3d_r4_f64_adjoint", lambda: sadj.sadj_adjoint_star3d(4, wstar, c, rb, ub), N,
-            wave_adjoint_bytes(shape, 4, 8), "f64")
-        add("star3d_r4_f64_primal", lambda: sadj.sadj_primal_star3d(4, wstar, ub, c, r), N,
-            8 * N + 16 * interior_points(shape, 4), "f64")
-        del upb, r
-        # 2-D 8192^2
-        s2 = (8192, 8192)
-        c2, rb2, ub2 = (t.reshape(-1)[: s2[0] * s2[1]].reshape(s2) for t in (c, rb, ub))
-        add("wave2d_f64_adjoint", lambda: sadj.sadj_adjoint_wave2d(c2, rb2, ub2), s2[0] * s2[1],
-            wave_adjoint_bytes(s2, 1, 8), "f64")
-        r2 = torch.empty_like(ub2)
-        add("wave2d_f64_primal", lambda: sadj.sadj_primal_wave2d(ub2, rb2, c2, r2), s2[0] * s2[1],
-            8 * s2[0] * s2[1] + 24 * interior_points(s2, 1), "f64")
-        wbox2 = [[0.1 * (i + 3 * j) - 0.4 for i in range(3)] for j in range(3)]
-        add("box2d_f64_adjoint", lambda: sadj.sadj_adjoint_box(wbox2, c2, rb2, ub2), s2[0] * s2[1],
-            wave_adjoint_bytes(s2, 1, 8), "f64")
-        del r2
-        # Burgers 2^24, rotating three buffer sets so the arrays do not stay in the 256 MB last-level cache
-        nb = 1 << 24
-        sets = [tuple(t.reshape(-1)[k * nb:(k + 1) * nb] for t in (rb, c, ub)) for k in range(3)]
-        state = {"i": 0}
-
-        def burg():
-            u_, r_, b_ = sets[state["i"] % 3]
-            state["i"] += 1
-            sadj.sadj_adjoint_burgers1d(0.1, 0.05, u_, r_, b_)
-        add("burgers1d_f64_adjoint", burg, nb, 32 * nb, "f64")
-        # reverse sweep over stored Burgers states: per step read u^t and lam, write lam (24 B/pt)
-        ks = 12
-        states = torch.rand(ks + 1, nb, device=dev, dtype=torch.float64)
-        la, lb = torch.rand(nb, device=dev, dtype=torch.float64), torch.zeros(nb, device=dev, dtype=torch.float64)
-        add("burgers1d_f64_adjoint_steps_per_step", lambda: sadj.sadj_adjoint_burgers1d_steps(0.1, 0.05, ks, ks, states, la, lb),
-            nb * ks, 32 * nb + (ks - 1) * 24 * nb, "f64")
-        others["burgers1d_f64_adjoint_steps_per_step"]["ms"] /= ks
-        others["burgers1d_f64_adjoint_steps_per_step"]["kernel_ms_mean"] /= ks
-        del states, la, lb
-        sadj.set_option("stencil1d.functor", 1)      # same stencil through the generic functor kernel
-        add("burgers1d_f64_adjoint_functor", burg, nb, 32 * nb, "f64")
-        sadj.set_option("stencil1d.functor", 0)
-
-        def burg_primal():
-            u_, r_, b_ = sets[state["i"] % 3]
-            state["i"] += 1
-            sadj.sadj_primal_burgers1d(0.1, 0.05, u_, b_)
-        add("burgers1d_f64_primal", burg_primal, nb, 16 * nb, "f64")
-        n1 = 4096
-        c1, rb1, ub1 = (t.reshape(-1)[:n1] for t in (c, rb, ub))
-        add("wave1d_f64_adjoint_n4096_latency", lambda: sadj.sadj_adjoint_wave1d(c1, rb1, ub1), n1, 32 * n1, "f64")
-        # the same call recorded 100 times into a HIP graph: the launch-bound size without host launch cost
-        per_graph = 100
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            sadj.sadj_adjoint_wave1d(c1, rb1, ub1)
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            for _ in range(per_graph):
-                sadj.sadj_adjoint_wave1d(c1, rb1, ub1)
-        add("wave1d_f64_adjoint_n4096_in_hip_graph_per_call", graph.replay, n1 * per_graph, 32 * n1 * per_graph, "f64")
-        for key in ("ms", "kernel_ms_mean"):
-            others["wave1d_f64_adjoint_n4096_in_hip_graph_per_call"][key] /= per_graph
+    lazy.clear()
     if args.paper_sizes:
         # The paper's experiments (Section 4.1: one step of the 7-point wave solver on 1000^3;
         # Section 4.2: one Burgers step on 10^9 cells), fp64, synthetic values.  The paper's
@@ -340,7 +521,7 @@ def main():
         ub.copy_(c)
         torch.cuda.synchronize()
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.only is None:
         import oracle
         oracle.build()
 
@@ -352,11 +533,12 @@ def main():
 
         probe = min(n, 32)
         rate = probe / run_oracle(probe)                 # planes per second on this host
-        nzs = int(min(n, max(probe, rate * 15.0)))      # about 15 s of CPU work, at most the whole grid
-        dt = run_oracle(nzs)
+        nzs = int(min(n, max(probe, rate * 8.0)))       # about 8 s of CPU work per run, at most the whole grid
+        runs = sorted(run_oracle(nzs) for _ in range(3))
+        dt = runs[1]
         out["cpu_baseline"] = {"value": nzs * n * n / dt / 1e9, "unit": "Gpoints/s", "cores": 1, "kind": "oracle",
-                               "sample": "first %d z-planes of the same %d^3 arrays (%d x %d x %d grid), one run, "
-                                         "%.1f s" % (nzs, n, n, n, nzs, dt),
+                               "sample": "first %d z-planes of the same %d^3 arrays (%d x %d x %d grid), median of 3 runs "
+                                         "(%.1f / %.1f / %.1f s)" % (nzs, n, n, n, nzs, runs[0], runs[1], runs[2]),
                                "host_cpus": os.cpu_count(), "host_cpu_model": cpu_model()}
     print(json.dumps(out))
 

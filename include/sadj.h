@@ -298,6 +298,19 @@ sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, lon
 sadj_status sadj_set_option(const char *name, long value);
 sadj_status sadj_get_option(const char *name, long *value);
 
+/* ---- measurement yardstick: a plain streaming kernel with the adjoint's access mix -----------
+ * out[i] += a[i] * b[i] for i in [0, n): two arrays read, one array read and written, every
+ * element touched once -- the streams of a wave adjoint call (c, r_bar, u_bar; Section 4.1's
+ * gather listing) without any stencil, halo or reuse.  Its rate is the ceiling this memory
+ * system offers to that mix of streams; the benchmark quotes the adjoint kernels against it as
+ * well as against the nominal HBM peak.  `shape` selects the launch shape: 0 = 8 bytes per lane,
+ * one access per thread; 1 = 16 bytes per lane, four accesses per thread, streaming hints.
+ * a, b, out: DEVICE arrays of n elements, 16-byte aligned (else SADJ_ERR_UNSUPPORTED), out not
+ * overlapping a or b.  n < 1 or n > 2^40 -> SADJ_ERR_SIZE.  Asynchronous on `stream`.
+ */
+sadj_status sadj_stream_probe(sadj_dtype dtype, int shape, long n,
+                              const void *a, const void *b, void *out, void *stream);
+
 /* ---- diagnostic: can a kernel on the current device use this array? ------------------------
  * For callers that want wrong pointers or sizes turned into a status instead of a GPU memory
  * fault.  Queries the HIP runtime; enqueues nothing.  SADJ_OK: [p, p+bytes) lies inside one

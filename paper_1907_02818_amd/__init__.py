@@ -20,6 +20,7 @@ __all__ = [
     "sadj_adjoint_wave3d_steps", "sadj_primal_box", "sadj_adjoint_box",
     "sadj_primal_star3d", "sadj_adjoint_star3d", "sadj_primal_burgers1d_steps", "sadj_adjoint_burgers1d_steps",
     "sadj_adjoint_wave3d_atomic_scatter", "sadj_describe_wave3d_plan", "sadj_check_array",
+    "sadj_stream_probe",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -79,12 +80,14 @@ def load() -> ctypes.CDLL:
     lib.sadj_primal_burgers1d_steps.argtypes = [I, L, L, D, D, P, P]
     lib.sadj_adjoint_burgers1d_steps.argtypes = [I, L, L, L, D, D, P, P, P, P]
     lib.sadj_check_array.argtypes = [P, ctypes.c_size_t]
+    lib.sadj_stream_probe.argtypes = [I, I, L, P, P, P, P]
     for name in ("sadj_set_option", "sadj_get_option", "sadj_primal_wave1d", "sadj_adjoint_wave1d",
                  "sadj_primal_wave2d", "sadj_adjoint_wave2d", "sadj_primal_wave3d", "sadj_adjoint_wave3d",
                  "sadj_primal_burgers1d", "sadj_adjoint_burgers1d", "sadj_adjoint_wave3d_steps",
                  "sadj_primal_box", "sadj_adjoint_box", "sadj_adjoint_wave3d_atomic_scatter", "sadj_describe_wave3d_plan",
                  "sadj_primal_star3d", "sadj_adjoint_star3d",
-                 "sadj_primal_burgers1d_steps", "sadj_adjoint_burgers1d_steps", "sadj_check_array"):
+                 "sadj_primal_burgers1d_steps", "sadj_adjoint_burgers1d_steps", "sadj_check_array",
+                 "sadj_stream_probe"):
         getattr(lib, name).restype = I
     _lib = lib
     return lib
@@ -177,6 +180,12 @@ def sadj_adjoint_wave3d(radius: int, c, r_bar, u_bar, u_prev_bar=None) -> None:
 def sadj_check_array(address: int, nbytes: int) -> int:
     """Status (0 = ok) of the library's pointer check for the byte range at `address`."""
     return int(load().sadj_check_array(ctypes.c_void_p(int(address)), int(nbytes)))
+
+
+def sadj_stream_probe(shape: int, a, b, out) -> None:
+    """out += a * b over flat tensors (the streaming yardstick of the header)."""
+    code, (n,), p, s = _marshal([a, b, out], 1)
+    _check(load().sadj_stream_probe(code, int(shape), n, *p, s))
 
 
 def sadj_describe_wave3d_plan(dtype_code: int, radius: int, nx: int, ny: int, nz: int, with_tiles: bool = True):

@@ -374,6 +374,24 @@ sadj_status sadj_adjoint_wave3d_steps(sadj_dtype dtype, int radius, long nx, lon
     return SADJ_OK;
 }
 
+// Streaming yardstick with the adjoint's access mix (two arrays read, one read and written).
+sadj_status sadj_stream_probe(sadj_dtype dtype, int shape, long n, const void *a, const void *b, void *out,
+                              void *stream)
+{
+    if (!dtype_ok(dtype) || shape < 0 || shape > 1) return SADJ_ERR_UNSUPPORTED;
+    if (!a || !b || !out) return SADJ_ERR_NULL;
+    if (n < 1 || n > (1L << 40)) return SADJ_ERR_SIZE;
+    const size_t bytes = (size_t)n * elem(dtype);
+    const Span in[2] = {{a, bytes}, {b, bytes}};
+    const Span outs[1] = {{out, bytes}};
+    if (sadj_status al = check_arrays(in, outs); al != SADJ_OK) return al;
+    // vector accesses need 16-byte aligned arrays
+    if (((uintptr_t)a | (uintptr_t)b | (uintptr_t)out) % 16 != 0) return SADJ_ERR_UNSUPPORTED;
+    clear_stale_hip_error();
+    return from_hip(sadj::launch_stream_probe(dtype == SADJ_F64, shape, (size_t)n, a, b, out,
+                                              static_cast<hipStream_t>(stream)));
+}
+
 // ------------------------------------------------------------ dense 3^d box stencils
 static sadj_status box_call(int adjoint, sadj_dtype dtype, int ndim, long nx, long ny, long nz,
                             const double *weights, const void *in0, const void *in1, void *out, void *stream)

@@ -59,11 +59,16 @@ hipError_t launch_star3d(int adjoint, int is_f64, int radius, int nx, int ny, in
                          const double (*w)[8], const void *in0, const void *in1, void *out,
                          const LaunchOptions &opt, hipStream_t stream);
 
-// Host-side view of how the default 3-D adjoint shape decomposes a grid (for tests): fills
-// plan[0..5] = tiles in x, tiles in y, z-chunks, planes per chunk, tile width, tile height,
-// and, if `tiles` is not null, for every workgroup id its (tile x, tile y, chunk) triple.
+// Host-side view of how the 3-D adjoint decomposes a grid (for tests): fills plan[0..7] =
+// tiles in x, tiles in y, tile width, tile height, workgroups, tiles of the first group,
+// z-chunks per tile of the first group, z-chunks per tile of the others; and, if `tiles` is
+// not null, for every workgroup id (tile x, tile y, first plane, one past the last plane).
 void describe_march_plan(int is_f64, int radius, int nx, int ny, int nz, const LaunchOptions &opt,
                          long *plan, int *tiles, long max_blocks);
+
+// Streaming yardstick out[i] += a[i]*b[i] over n elements (two launch shapes, see probe.hip).
+hipError_t launch_stream_probe(int is_f64, int shape, size_t n, const void *a, const void *b, void *out,
+                               hipStream_t stream);
 
 // Dense 3^d box stencils; w = gather weights (mirrored by the caller for the adjoint).
 hipError_t launch_box1d(int adjoint, int is_f64, long n, const double *w, const void *in0, const void *in1,
