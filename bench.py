@@ -36,7 +36,6 @@ the further stencil families, --only NAME times a single workload (for profiling
 from __future__ import annotations
 
 import argparse
-import hashlib
 import json
 import os
 import sys
@@ -79,24 +78,6 @@ def wave_adjoint_bytes(shape, radius, esize, with_prev=False):
     return b
 
 
-def library_sources_sha256():
-    """Hash of the kernel sources and headers libsadj.so is built from; the counter
-    summaries under profiles/ record it, so that a summary taken from other sources is
-    recognised as stale."""
-    h = hashlib.sha256()
-    files = []
-    for sub in (os.path.join("paper_1907_02818_amd", "csrc"), "include"):
-        d = os.path.join(ROOT, sub)
-        for name in sorted(os.listdir(d)):
-            if name.endswith((".hip", ".hpp", ".h")):
-                files.append(os.path.join(d, name))
-    for f in files:
-        h.update(os.path.basename(f).encode())
-        with open(f, "rb") as fh:
-            h.update(fh.read())
-    return h.hexdigest()
-
-
 def read_traffic(workload):
     """HBM bytes per launch from the rocprofv3 --pmc summary profiles/<workload>_pmc.txt
     (lines 'traffic_bytes_per_launch: N' and 'library_sources_sha256: H').  Returns
@@ -115,6 +96,7 @@ def read_traffic(workload):
         return None, "no counter summary recorded for this workload"
     if val is None:
         return None, "summary holds no traffic line"
+    from paper_1907_02818_amd.profile_summary import library_sources_sha256
     if sha != library_sources_sha256():
         return None, "recorded summary profiles/%s_pmc.txt is from other kernel sources (stale)" % workload
     return val, "recorded: profiles/%s_pmc.txt, same kernel sources (sha256 %s)" % (workload, sha[:12])
@@ -227,7 +209,7 @@ def main():
         torch.cuda.synchronize()
         t = timer.time_calls(fn, steps or steps_o, warmup or warm_o)
         gbs = nbytes / (t["ev_mean"] * 1e-3) / 1e9
-        traffic, tnote = read_traffic(name)
+        traffic, tnote = read_traffic(name) if n == 512 else (None, "")
         others[name] = {"Gpoints/s": points / (t["wall_ms"] * 1e-3) / 1e9, "ms": t["wall_ms"] / per,
                         "kernel_ms_mean": t["ev_mean"] / per, "kernel_ms_min": t["ev_min"] / per,
                         "GB/s": gbs, "frac": gbs / HBM_PEAK_GBS, "dtype": dtype,
@@ -388,7 +370,8 @@ def main():
 
     # ---------------------------------------------------------------- headline
     out = {"metric": METRIC, "unit": "Gpoints/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic"}
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+           "size": n}
     if args.only is None or args.only == HEADLINE:
         t = timer.time_calls(lambda: sadj.sadj_adjoint_wave3d(R, c, rb, ub), args.steps, args.warmup)
         alg_bytes = wave_adjoint_bytes(shape, R, 8)
@@ -518,7 +501,10 @@ def main():
         del cw, a1, a2, a3, ub1d, rb1d, ubar1d, r1d
     out["others"] = others
     if args.copy_probe:
-        ub.copy_(c)
+        src = torch.ones(1 << 27, device=dev, dtype=torch.float64)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                                   # exactly 1 GiB read and 1 GiB written
         torch.cuda.synchronize()
 
     if not args.no_cpu_baseline and args.only is None:
