@@ -283,3 +283,48 @@ def stencil1d_adjoint(df, u, p, r_bar, u_bar, want_scale: bool = False):
     _check(_load().oracle_stencil1d_adjoint(_L(u.size), cb, _ptr(u), _ptr(p), _ptr(r_bar), _ptr(ub), _ptr(scale)),
            "stencil1d_adjoint")
     return (ub, scale) if want_scale else ub
+
+
+_STAR_BODY = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.POINTER(ctypes.c_double), ctypes.c_double)
+_STAR_PARTIALS = ctypes.CFUNCTYPE(None, ctypes.POINTER(ctypes.c_double), ctypes.c_double,
+                                  ctypes.POINTER(ctypes.c_double))
+
+
+def starfn_reads(ndim: int, radius: int) -> int:
+    """Number of reads of a star-shaped body: the centre and 2*radius per axis."""
+    return 1 + 2 * radius * ndim
+
+
+def starfn_primal(f, u, p, radius: int, r_init=None) -> np.ndarray:
+    """r[i] = f(v, p[i]) on I for a star-shaped body in u.ndim dimensions; f takes a list of the
+    reads (centre, then per axis x, y, z the offsets -R..-1, +1..+R) and p[i].  One Python
+    callback per cell: for small grids."""
+    u = _f64(u)
+    p = _f64(p) if p is not None else None
+    r = _f64(r_init).copy() if r_init is not None else np.zeros_like(u)
+    nread = starfn_reads(u.ndim, radius)
+    cb = _STAR_BODY(lambda v, pp: float(f([v[k] for k in range(nread)], pp)))
+    ndim, nx, ny, nz = _dims(u.shape)
+    _check(_load().oracle_starfn_primal(_I(ndim), _I(int(radius)), _L(nx), _L(ny), _L(nz), cb, _ptr(u), _ptr(p), _ptr(r)),
+           "starfn_primal")
+    return r
+
+
+def starfn_adjoint(df, u, p, r_bar, u_bar, radius: int, want_scale: bool = False):
+    """Scatter adjoint of the loop above; df(v, p) returns the partials with respect to the reads."""
+    u, r_bar = _f64(u), _f64(r_bar)
+    p = _f64(p) if p is not None else None
+    ub = _f64(u_bar).copy()
+    scale = np.zeros_like(ub) if want_scale else None
+    nread = starfn_reads(u.ndim, radius)
+
+    def partials(v, pp, d):
+        out = df([v[k] for k in range(nread)], pp)
+        for k in range(nread):
+            d[k] = float(out[k])
+
+    cb = _STAR_PARTIALS(partials)
+    ndim, nx, ny, nz = _dims(u.shape)
+    _check(_load().oracle_starfn_adjoint(_I(ndim), _I(int(radius)), _L(nx), _L(ny), _L(nz), cb, _ptr(u), _ptr(p),
+                                         _ptr(r_bar), _ptr(ub), _ptr(scale)), "starfn_adjoint")
+    return (ub, scale) if want_scale else ub

@@ -457,3 +457,82 @@ int oracle_stencil1d_adjoint(long n, oracle_body_partials_fn df, const double *u
     }
     return ORACLE_OK;
 }
+
+/* ---- star-shaped loop body supplied by the caller, 1 to 3 dimensions (paper Section 3.3.1:
+ * the loop body as an uninterpreted function of its reads, its partial derivatives as
+ * uninterpreted functions too; the paper's example there is two-dimensional).
+ *   primal   r[i] = f(v, p[i])   for i in I,   v[0] = u[i], and for the axes x, y, z in turn
+ *            v[1 + a*2R + m], m = 0..2R-1, = u at the offsets -R..-1, +1..+R along axis a
+ *   adjoint  for i in I (ascending): for every read k:  u_bar[i + o_k] += d_k * r_bar[i],
+ *            (d_0 .. d_{2R*ndim}) = the partials of f with respect to v at iteration i
+ * `parity unpinned` does not apply: pinned against the wave, free-weight star and three-point
+ * callback loops of this file and against finite differences (tests/test_oracle_starfn.py). */
+typedef double (*oracle_star_body_fn)(const double *v, double p);
+typedef void (*oracle_star_partials_fn)(const double *v, double p, double *d);
+
+static long star_offsets(int ndim, int R, long nx, long ny, long *off)
+{
+    long stride[3] = {1, nx, nx * ny};
+    long n = 0;
+    off[n++] = 0;
+    for (int a = 0; a < ndim; ++a) {
+        for (int k = -R; k <= R; ++k)
+            if (k != 0) off[n++] = k * stride[a];
+    }
+    return n;
+}
+
+int oracle_starfn_primal(int ndim, int radius, long nx, long ny, long nz, oracle_star_body_fn f,
+                         const double *u, const double *p, double *r)
+{
+    if (!f || !u || !r || ndim < 1 || ndim > 3 || radius < 1 || radius > 4) return ORACLE_BAD_ARG;
+    if (ndim < 3 && nz != 1) return ORACLE_BAD_ARG;
+    if (ndim < 2 && ny != 1) return ORACLE_BAD_ARG;
+    const long R = radius;
+    const long n[3] = {nx, ny, nz};
+    for (int a = 0; a < ndim; ++a)
+        if (n[a] < 2 * R + 1) return ORACLE_BAD_ARG;
+    long off[25];
+    const long nread = star_offsets(ndim, radius, nx, ny, off);
+    const long zlo = ndim >= 3 ? R : 0, zhi = ndim >= 3 ? nz - 1 - R : 0;
+    const long ylo = ndim >= 2 ? R : 0, yhi = ndim >= 2 ? ny - 1 - R : 0;
+    double v[25];
+    for (long z = zlo; z <= zhi; ++z)
+        for (long y = ylo; y <= yhi; ++y)
+            for (long x = R; x <= nx - 1 - R; ++x) {
+                const long i = x + nx * (y + ny * z);
+                for (long k = 0; k < nread; ++k) v[k] = u[i + off[k]];
+                r[i] = f(v, p ? p[i] : 0.0);
+            }
+    return ORACLE_OK;
+}
+
+int oracle_starfn_adjoint(int ndim, int radius, long nx, long ny, long nz, oracle_star_partials_fn df,
+                          const double *u, const double *p, const double *r_bar, double *u_bar, double *scale)
+{
+    if (!df || !u || !r_bar || !u_bar || ndim < 1 || ndim > 3 || radius < 1 || radius > 4) return ORACLE_BAD_ARG;
+    if (ndim < 3 && nz != 1) return ORACLE_BAD_ARG;
+    if (ndim < 2 && ny != 1) return ORACLE_BAD_ARG;
+    const long R = radius;
+    const long n[3] = {nx, ny, nz};
+    for (int a = 0; a < ndim; ++a)
+        if (n[a] < 2 * R + 1) return ORACLE_BAD_ARG;
+    long off[25];
+    const long nread = star_offsets(ndim, radius, nx, ny, off);
+    const long zlo = ndim >= 3 ? R : 0, zhi = ndim >= 3 ? nz - 1 - R : 0;
+    const long ylo = ndim >= 2 ? R : 0, yhi = ndim >= 2 ? ny - 1 - R : 0;
+    double v[25], d[25];
+    for (long z = zlo; z <= zhi; ++z)
+        for (long y = ylo; y <= yhi; ++y)
+            for (long x = R; x <= nx - 1 - R; ++x) {
+                const long i = x + nx * (y + ny * z);
+                for (long k = 0; k < nread; ++k) v[k] = u[i + off[k]];
+                df(v, p ? p[i] : 0.0, d);
+                const double rb = r_bar[i];
+                for (long k = 0; k < nread; ++k) {
+                    u_bar[i + off[k]] += d[k] * rb;
+                    if (scale) scale[i + off[k]] += fabs(d[k] * rb);
+                }
+            }
+    return ORACLE_OK;
+}
