@@ -320,6 +320,10 @@ def main():
                                                  N, wave_adjoint_bytes(shape, 4, 8), "f64"),
             "star3d_r4_f64_primal": lambda: add("star3d_r4_f64_primal", lambda: sadj.sadj_primal_star3d(4, wstar, ub, c, rbuf()),
                                                 N, 8 * N + 16 * I4, "f64"),
+            "star3d_r1_f64_adjoint": lambda: add("star3d_r1_f64_adjoint", lambda: sadj.sadj_adjoint_star3d(1, wstar[:7], c, rb, ub),
+                                                 N, wave_adjoint_bytes(shape, 1, 8), "f64"),
+            "star3d_r1_f64_primal": lambda: add("star3d_r1_f64_primal", lambda: sadj.sadj_primal_star3d(1, wstar[:7], ub, c, rbuf()),
+                                                N, 8 * N + 16 * I1, "f64"),
             "wave2d_f64_primal": lambda: add(
                 "wave2d_f64_primal",
                 lambda: sadj.sadj_primal_wave2d(views2d()[2], views2d()[1], views2d()[0], r2d()),
@@ -363,6 +367,22 @@ def main():
         add("wave1d_f64_adjoint_n4096_in_hip_graph_per_call", graph.replay, n1 * per_graph, 32 * n1 * per_graph, "f64",
             per=per_graph)
 
+    def star_functor_leg(name, fn, nbytes):
+        # the same 7-point star through the generic functor kernels (include/sadj_stencil_star.hpp)
+        def leg():
+            sadj.set_option("star3d.functor", 1)
+            try:
+                add(name, fn, N, nbytes, "f64")
+            finally:
+                sadj.set_option("star3d.functor", 0)
+        return leg
+
+    w7 = [0.3] + [0.05 * (i % 7) - 0.12 for i in range(6)]
+    if args.all or args.only in ("star3d_r1_f64_adjoint_functor", "star3d_r1_f64_primal_functor"):
+        table["star3d_r1_f64_adjoint_functor"] = star_functor_leg(
+            "star3d_r1_f64_adjoint_functor", lambda: sadj.sadj_adjoint_star3d(1, w7, c, rb, ub), wave_adjoint_bytes(shape, 1, 8))
+        table["star3d_r1_f64_primal_functor"] = star_functor_leg(
+            "star3d_r1_f64_primal_functor", lambda: sadj.sadj_primal_star3d(1, w7, ub, c, rbuf()), 8 * N + 16 * I1)
     if args.all:
         table["burgers1d_f64_adjoint_steps_per_step"] = burgers_steps_leg
         table["burgers1d_f64_adjoint_functor"] = functor_leg

@@ -243,7 +243,7 @@ sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, lon
  * never change what is computed, only how the regions are mapped to kernels.  Every
  * setting is deterministic (same inputs, same bits).  Settings that select another
  * kernel shape or instruction sequence ("*.variant", "wave2d.ychunk", "wave3d.order",
- * "stencil1d.functor") may round differently from each other within the usual
+ * "stencil1d.functor", "star3d.functor") may round differently from each other within the usual
  * floating-point tolerance; "wave3d.zchunk", "wave3d.split", "wave3d.xcdmap",
  * "wave3d.band" and "wave3d.ldspad" only move work between workgroups and leave every
  * bit of the 3-D results unchanged.
@@ -276,6 +276,9 @@ sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, lon
  *                    elements and 16-byte aligned arrays, else SADJ_ERR_UNSUPPORTED.
  *   "stencil1d.functor" 1: sadj_*_burgers1d and the 1-D sadj_*_box run through the generic
  *                    functor kernel of sadj_stencil1d.hpp instead of their own (default 0).
+ *   "star3d.functor" 1: radius-1 calls of sadj_*_star3d run through the generic functor kernels of
+ *                    sadj_stencil_star.hpp where nx and the arrays' alignment allow 16-byte
+ *                    accesses (default 0: their own kernel).
  *   "wave3d.order"   order in which sadj_adjoint_wave3d adds the terms of one u_bar[j]
  *                    (Section 3.5: a gather can respect an order the user chooses and
  *                    stay parallel).  0 (default): the kernel's own fixed order, fastest.

@@ -9,7 +9,7 @@
 
 namespace {
 
-std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0}, g_variant2d{0}, g_remainder{0}, g_order{0}, g_functor1d{0}, g_xcdmap{0}, g_band{0}, g_ldspad{0}, g_split{0};
+std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0}, g_variant2d{0}, g_remainder{0}, g_order{0}, g_functor1d{0}, g_functor_star{0}, g_xcdmap{0}, g_band{0}, g_ldspad{0}, g_split{0};
 
 sadj::LaunchOptions current_options()
 {
@@ -206,6 +206,11 @@ sadj_status sadj_set_option(const char *name, long value)
         g_functor1d = value;
         return SADJ_OK;
     }
+    if (!std::strcmp(name, "star3d.functor")) {
+        if (value < 0 || value > 1) return SADJ_ERR_UNSUPPORTED;
+        g_functor_star = value;
+        return SADJ_OK;
+    }
 
     return SADJ_ERR_UNSUPPORTED;
 }
@@ -225,6 +230,7 @@ sadj_status sadj_get_option(const char *name, long *value)
     if (!std::strcmp(name, "wave3d.band")) { *value = g_band; return SADJ_OK; }
     if (!std::strcmp(name, "wave3d.ldspad")) { *value = g_ldspad; return SADJ_OK; }
     if (!std::strcmp(name, "stencil1d.functor")) { *value = g_functor1d; return SADJ_OK; }
+    if (!std::strcmp(name, "star3d.functor")) { *value = g_functor_star; return SADJ_OK; }
     return SADJ_ERR_UNSUPPORTED;
 }
 
@@ -457,6 +463,11 @@ static sadj_status star_call(int adjoint, sadj_dtype dtype, int radius, long nx,
     for (int d = 0; d < 3; ++d)
         for (int i = 0; i < n; ++i) w[d][i] = weights[1 + d * n + (adjoint ? n - 1 - i : i)];
     clear_stale_hip_error();
+    if (radius == 1 && g_functor_star.load() == 1) {
+        const hipError_t e = sadj::launch_star7_functor(adjoint, dtype == SADJ_F64, (int)nx, (int)ny, (int)nz, weights, in0,
+                                                        in1, out, static_cast<hipStream_t>(stream));
+        if (e != hipErrorNotSupported) return from_hip(e);      // else: the hand-written kernel takes the call
+    }
     return from_hip(sadj::launch_star3d(adjoint, dtype == SADJ_F64, radius, (int)nx, (int)ny, (int)nz, weights[0], w, in0,
                                         in1, out, current_options(), static_cast<hipStream_t>(stream)));
 }

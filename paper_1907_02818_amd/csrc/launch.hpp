@@ -53,6 +53,12 @@ hipError_t launch_burgers1d_functor(int adjoint, int is_f64, long n, double C, d
 hipError_t launch_weighted3_functor(int adjoint, int is_f64, long n, const double *w, const void *u,
                                     const void *c, const void *r_bar, void *out, hipStream_t stream);
 
+// The radius-1 free-weight star through the generic functor kernels of
+// include/sadj_stencil_star.hpp; w = the caller's PRIMAL weights (centre, x-1, x+1, y-1, y+1,
+// z-1, z+1).  hipErrorNotSupported (nothing enqueued) if nx or the alignment rule it out.
+hipError_t launch_star7_functor(int adjoint, int is_f64, int nx, int ny, int nz, const double *w, const void *in0,
+                                const void *in1, void *out, hipStream_t stream);
+
 // 3-D star stencil with free weights; w0 / w[d][idx] is the gather table (mirrored by the caller
 // for the adjoint), idx enumerating the offsets -R..-1, +1..+R of axis d.
 hipError_t launch_star3d(int adjoint, int is_f64, int radius, int nx, int ny, int nz, double w0,

@@ -45,10 +45,23 @@ def _abs_star(w, radius, a):
     return ndi.correlate(np.abs(a), k, mode="constant")
 
 
+@pytest.fixture(params=[0, 1], ids=["handwritten", "functor"])
+def star_path(request, sadj):
+    """Radius-1 calls also run through the generic functor kernels of
+    include/sadj_stencil_star.hpp (a linear 7-point functor with a passive coefficient); both
+    paths must meet the same bar.  Other radii and shapes that rule out 16-byte accesses fall
+    back to the hand-written kernel."""
+    sadj.set_option("star3d.functor", request.param)
+    yield request.param
+    sadj.set_option("star3d.functor", 0)
+
+
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 @pytest.mark.parametrize("radius,shape", CASES)
-def test_star_adjoint_and_primal(sadj, radius, shape, dtype):
+def test_star_adjoint_and_primal(sadj, star_path, radius, shape, dtype):
     import torch
+    if star_path == 1 and radius != 1:
+        pytest.skip("the functor path exists for radius 1")
     w = _table(radius, sum(shape))
     wq = w.astype(dtype).astype(np.float64)             # the library converts the weights to dtype
     u = inputs.uniform(1, "u", shape, -1, 1).astype(dtype)
