@@ -223,6 +223,33 @@ sadj_status sadj_primal_burgers1d_steps(sadj_dtype dtype, long n, long nsteps, d
 sadj_status sadj_adjoint_burgers1d_steps(sadj_dtype dtype, long n, long last, long nsteps, double C, double D,
                                          const void *states, void *lam0, void *lam1, void *stream);
 
+/* ---- time loop of Burgers steps with checkpoints: keep every k-th state, recompute the rest ------
+ * At the size of the paper's own Burgers experiment (10^9 cells, Section 4.2) one state is 8 GB,
+ * so a long time loop cannot keep every state; the standard remedy stores every `every`-th state
+ * (a checkpoint) and recomputes the states in between, one segment at a time, while sweeping
+ * backwards.  Both calls run the kernels of the single-step calls; the reverse sweep's result
+ * equals that of sadj_adjoint_burgers1d_steps over a full history bit for bit.
+ * Boundary data: elements 0 and n-1 of every state equal those of u^0 (held fixed in time).
+ *
+ * sadj_primal_burgers1d_ckpt: `ckpt` holds nsteps/every + 1 rows of n elements; row 0 = u^0 on
+ *   entry; on return row j = u^{j*every}.  `work`: 2 rows of scratch.  u_final (nullable, n
+ *   elements) receives u^{nsteps}.  nsteps+1 kernels (and one copy) are enqueued.
+ *
+ * sadj_adjoint_burgers1d_ckpt: reverse sweep over the steps nsteps-1 .. 0.  On entry lam0 =
+ *   adjoint of u^{nsteps}, lam1 = what the objective contributes directly to the adjoint of
+ *   u^{nsteps-1} (often zero); rotation and assign/accumulate rules as in
+ *   sadj_adjoint_burgers1d_steps; after the call lam[nsteps%2] holds the adjoint of u^0.  `work`:
+ *   scratch of at least (every-1)*n elements (work_bytes states its size; may be NULL when
+ *   every == 1) that receives the recomputed states of one segment at a time.
+ *   Errors: every < 1, work_bytes too small -> SADJ_ERR_SIZE; ckpt, lam0, lam1, work overlapping
+ *   -> SADJ_ERR_ALIAS.  Roughly (2 - 1/every) kernels per step are enqueued.
+ */
+sadj_status sadj_primal_burgers1d_ckpt(sadj_dtype dtype, long n, long nsteps, long every, double C, double D,
+                                       void *ckpt, void *work, void *u_final /* nullable */, void *stream);
+sadj_status sadj_adjoint_burgers1d_ckpt(sadj_dtype dtype, long n, long nsteps, long every, double C, double D,
+                                        const void *ckpt, void *work, size_t work_bytes,
+                                        void *lam0, void *lam1, void *stream);
+
 /* ---- diagnostic: how a 3-D adjoint call is cut into workgroups ----------------------------
  * Section 3.3.4 requires the loop nests (here: workgroups) to be disjoint and to cover every
  * output index exactly once.  This host-only call reports the decomposition the default tile

@@ -20,7 +20,7 @@ __all__ = [
     "sadj_adjoint_wave3d_steps", "sadj_primal_box", "sadj_adjoint_box",
     "sadj_primal_star3d", "sadj_adjoint_star3d", "sadj_primal_burgers1d_steps", "sadj_adjoint_burgers1d_steps",
     "sadj_adjoint_wave3d_atomic_scatter", "sadj_describe_wave3d_plan", "sadj_check_array",
-    "sadj_stream_probe",
+    "sadj_stream_probe", "sadj_primal_burgers1d_ckpt", "sadj_adjoint_burgers1d_ckpt",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -81,13 +81,15 @@ def load() -> ctypes.CDLL:
     lib.sadj_adjoint_burgers1d_steps.argtypes = [I, L, L, L, D, D, P, P, P, P]
     lib.sadj_check_array.argtypes = [P, ctypes.c_size_t]
     lib.sadj_stream_probe.argtypes = [I, I, L, P, P, P, P]
+    lib.sadj_primal_burgers1d_ckpt.argtypes = [I, L, L, L, D, D, P, P, P, P]
+    lib.sadj_adjoint_burgers1d_ckpt.argtypes = [I, L, L, L, D, D, P, P, ctypes.c_size_t, P, P, P]
     for name in ("sadj_set_option", "sadj_get_option", "sadj_primal_wave1d", "sadj_adjoint_wave1d",
                  "sadj_primal_wave2d", "sadj_adjoint_wave2d", "sadj_primal_wave3d", "sadj_adjoint_wave3d",
                  "sadj_primal_burgers1d", "sadj_adjoint_burgers1d", "sadj_adjoint_wave3d_steps",
                  "sadj_primal_box", "sadj_adjoint_box", "sadj_adjoint_wave3d_atomic_scatter", "sadj_describe_wave3d_plan",
                  "sadj_primal_star3d", "sadj_adjoint_star3d",
                  "sadj_primal_burgers1d_steps", "sadj_adjoint_burgers1d_steps", "sadj_check_array",
-                 "sadj_stream_probe"):
+                 "sadj_stream_probe", "sadj_primal_burgers1d_ckpt", "sadj_adjoint_burgers1d_ckpt"):
         getattr(lib, name).restype = I
     _lib = lib
     return lib
@@ -283,3 +285,35 @@ def sadj_adjoint_burgers1d_steps(C: float, D: float, last: int, nsteps: int, sta
     if rows < int(last):
         raise ValueError("states needs at least `last` rows")
     _check(load().sadj_adjoint_burgers1d_steps(code, n, int(last), int(nsteps), float(C), float(D), *ps, *pl, s))
+
+
+def sadj_primal_burgers1d_ckpt(C: float, D: float, nsteps: int, every: int, ckpt, work, u_final=None) -> None:
+    """ckpt: (rows, n) tensor with rows >= nsteps // every + 1, row 0 = initial state; work: (2, n)."""
+    code, (rows, n), pc, s = _marshal([ckpt], 2)
+    if rows < int(nsteps) // int(every) + 1:
+        raise ValueError("ckpt needs nsteps // every + 1 rows")
+    _, (wr, wn), pw, _ = _marshal([work], 2)
+    if wr < 2 or wn != n or work.dtype != ckpt.dtype:
+        raise ValueError("work needs two rows of n elements of the same dtype")
+    pf = [None]
+    if u_final is not None:
+        _, (nf,), pf, _ = _marshal([u_final], 1)
+        if nf != n or u_final.dtype != ckpt.dtype:
+            raise ValueError("u_final: n elements of the same dtype")
+    _check(load().sadj_primal_burgers1d_ckpt(code, n, int(nsteps), int(every), float(C), float(D), *pc, *pw, *pf, s))
+
+
+def sadj_adjoint_burgers1d_ckpt(C: float, D: float, nsteps: int, every: int, ckpt, work, lam0, lam1) -> None:
+    """ckpt as written by sadj_primal_burgers1d_ckpt; work: a tensor of at least (every-1)*n elements
+    (None when every == 1); lam0, lam1: (n,) tensors."""
+    code, (rows, n), pc, s = _marshal([ckpt], 2)
+    code2, (n2,), pl, _ = _marshal([lam0, lam1], 1)
+    if code2 != code or n2 != n:
+        raise ValueError("ckpt and lam buffers share dtype and row length")
+    if work is not None:
+        if not work.is_cuda or work.dtype != ckpt.dtype or not work.is_contiguous():
+            raise ValueError("work: contiguous GPU tensor of the same dtype")
+        pw, wbytes = ctypes.c_void_p(work.data_ptr()), work.numel() * work.element_size()
+    else:
+        pw, wbytes = None, 0
+    _check(load().sadj_adjoint_burgers1d_ckpt(code, n, int(nsteps), int(every), float(C), float(D), *pc, pw, wbytes, *pl, s))

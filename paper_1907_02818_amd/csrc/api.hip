@@ -117,6 +117,51 @@ void clear_stale_hip_error() { (void)hipGetLastError(); }
 
 }  // namespace
 
+namespace {
+
+// Reverse sweep over all nsteps steps with recomputation; `work` holds every-1 rows.
+sadj_status burgers_ckpt_reverse(sadj_dtype dtype, long n, long nsteps, long every, double C, double D,
+                                 const void *ckpt, void *work, void *lam0, void *lam1, hipStream_t st)
+{
+    const size_t row = (size_t)n * elem(dtype);
+    const int f64 = dtype == SADJ_F64;
+    void *lam[2] = {lam0, lam1};
+    const char *cb = static_cast<const char *>(ckpt);
+    char *wb = static_cast<char *>(work);
+    long s = 0;                                             // reverse steps done
+    for (long seg = (nsteps - 1) / every; seg >= 0 && nsteps > 0; --seg) {
+        const long t0 = seg * every, t1 = t0 + every < nsteps ? t0 + every : nsteps;
+        // states u^{t0+1} .. u^{t1-1} into work rows 0 .. t1-t0-2 (u^{t0} is the checkpoint itself)
+        auto state = [&](long t) -> const char * { return t == t0 ? cb + (size_t)seg * row : wb + (size_t)(t - t0 - 1) * row; };
+        for (long t = t0; t + 1 < t1; ++t) {
+            hipError_t e = sadj::launch_primal_burgers1d(f64, n, C, D, state(t), wb + (size_t)(t - t0) * row, st, 1);
+            if (e != hipSuccess) return from_hip(e);
+        }
+        for (long t = t1 - 1; t >= t0; --t, ++s) {
+            hipError_t e = sadj::launch_adjoint_burgers1d(f64, n, C, D, state(t), lam[s % 2], lam[(s + 1) % 2], s > 0 ? 1 : 0, st);
+            if (e != hipSuccess) return from_hip(e);
+        }
+    }
+    return SADJ_OK;
+}
+
+sadj_status burgers_ckpt_args(sadj_dtype dtype, long n, long nsteps, long every, const void *ckpt, const void *work,
+                              size_t work_bytes, void *lam0, void *lam1)
+{
+    if (!dtype_ok(dtype)) return SADJ_ERR_UNSUPPORTED;
+    if (!ckpt || !lam0 || !lam1) return SADJ_ERR_NULL;
+    if (n < 3 || n > kMaxExtent || nsteps < 0 || nsteps > kMaxExtent || every < 1 || every > kMaxExtent) return SADJ_ERR_SIZE;
+    const size_t row = (size_t)n * elem(dtype);
+    const size_t need = (size_t)(every - 1) * row;
+    if (need > 0 && !work) return SADJ_ERR_NULL;
+    if (work_bytes < need) return SADJ_ERR_SIZE;
+    const Span in[1] = {{ckpt, (size_t)((nsteps - 1 > 0 ? nsteps - 1 : 0) / every + 1) * row}};
+    const Span out[3] = {{lam0, row}, {lam1, row}, {work, need}};
+    return check_arrays(in, out);
+}
+
+}  // namespace
+
 extern "C" {
 
 const char *sadj_status_string(sadj_status s)
@@ -561,6 +606,47 @@ sadj_status sadj_adjoint_burgers1d_steps(sadj_dtype dtype, long n, long last, lo
         if (e != hipSuccess) return from_hip(e);
     }
     return SADJ_OK;
+}
+
+// Time loop with checkpoints: every `every`-th state is kept, the others are recomputed
+// segment by segment during the reverse sweep.
+sadj_status sadj_primal_burgers1d_ckpt(sadj_dtype dtype, long n, long nsteps, long every, double C, double D,
+                                       void *ckpt, void *work, void *u_final, void *stream)
+{
+    if (!dtype_ok(dtype)) return SADJ_ERR_UNSUPPORTED;
+    if (!ckpt || !work) return SADJ_ERR_NULL;
+    if (n < 3 || n > kMaxExtent || nsteps < 0 || nsteps > kMaxExtent || every < 1 || every > kMaxExtent) return SADJ_ERR_SIZE;
+    const size_t row = (size_t)n * elem(dtype);
+    const long rows = nsteps / every + 1;
+    const Span in[1] = {{ckpt, (size_t)rows * row}};
+    const Span out[2] = {{work, 2 * row}, {u_final, u_final ? row : 0}};
+    if (sadj_status al = check_arrays(in, out); al != SADJ_OK) return al;
+    clear_stale_hip_error();
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int f64 = dtype == SADJ_F64;
+    char *cb = static_cast<char *>(ckpt), *wb = static_cast<char *>(work);
+    const char *cur = cb;                                   // u^0
+    for (long t = 0; t < nsteps; ++t) {
+        // u^{t+1} goes to its checkpoint row if it has one, else to the work row not holding u^t
+        char *dst = (t + 1) % every == 0 ? cb + (size_t)((t + 1) / every) * row : wb + (size_t)((t + 1) % 2) * row;
+        hipError_t e = sadj::launch_primal_burgers1d(f64, n, C, D, cur, dst, st, 1);
+        if (e != hipSuccess) return from_hip(e);
+        cur = dst;
+    }
+    if (u_final) {
+        hipError_t e = hipMemcpyAsync(u_final, cur, row, hipMemcpyDeviceToDevice, st);
+        if (e != hipSuccess) return from_hip(e);
+    }
+    return SADJ_OK;
+}
+
+sadj_status sadj_adjoint_burgers1d_ckpt(sadj_dtype dtype, long n, long nsteps, long every, double C, double D,
+                                        const void *ckpt, void *work, size_t work_bytes, void *lam0, void *lam1,
+                                        void *stream)
+{
+    if (sadj_status s = burgers_ckpt_args(dtype, n, nsteps, every, ckpt, work, work_bytes, lam0, lam1); s != SADJ_OK) return s;
+    clear_stale_hip_error();
+    return burgers_ckpt_reverse(dtype, n, nsteps, every, C, D, ckpt, work, lam0, lam1, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

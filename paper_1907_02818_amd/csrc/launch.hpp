@@ -43,8 +43,9 @@ hipError_t launch_primal_wave1d(int is_f64, long n, const void *u, const void *u
 // assign != 0: u_bar = J^T r_bar (u_bar is not read) instead of u_bar += J^T r_bar
 hipError_t launch_adjoint_burgers1d(int is_f64, long n, double C, double D, const void *u,
                                     const void *r_bar, void *u_bar, int assign, hipStream_t stream);
+// keep_ends != 0: r[0] = u[0] and r[n-1] = u[n-1] as well (boundary data carried to the next state)
 hipError_t launch_primal_burgers1d(int is_f64, long n, double C, double D, const void *u, void *r,
-                                   hipStream_t stream);
+                                   hipStream_t stream, int keep_ends = 0);
 
 // The same 1-D stencils as instantiations of the generic functor kernel
 // (include/sadj_stencil1d.hpp); w = PRIMAL weights at offsets -1, 0, +1.

@@ -33,7 +33,7 @@ struct Args1d {
 constexpr int kWaves1d = 4;
 constexpr bool kStreamStores = true;
 enum Op1d { OP_ADJ_WAVE, OP_ADJ_WAVE_UPREV, OP_PRI_WAVE, OP_PRI_BURGERS, OP_ADJ_BURGERS, OP_ADJ_BOX, OP_PRI_BOX,
-            OP_ADJ_BURGERS_ASSIGN };
+            OP_ADJ_BURGERS_ASSIGN, OP_PRI_BURGERS_KEEP_ENDS };
 
 // Load PX consecutive cells starting at x.  Unguarded: one vector load.  Guarded:
 // element-wise, indices clamped to [0, n-1].
@@ -204,7 +204,9 @@ __device__ __forceinline__ void box1d_segment(const Args1d &a, long xs, int lane
 template <class T> __device__ __forceinline__ T pos_part(T v) { return v > T(0) ? v : T(0); }
 template <class T> __device__ __forceinline__ T neg_part(T v) { return v < T(0) ? v : T(0); }
 
-template <class T, int PX, bool GUARD>
+// KEEP_ENDS: the two end cells, which no iteration writes, receive the input's end values
+// (boundary data held fixed from one state of a time loop to the next).
+template <class T, int PX, bool GUARD, bool KEEP_ENDS = false>
 __device__ __forceinline__ void pri_burgers_segment(const Args1d &a, long xs, int lane)
 {
     constexpr int W = 64 * PX;
@@ -226,9 +228,11 @@ __device__ __forceinline__ void pri_burgers_segment(const Args1d &a, long xs, in
         const T um = e == 0 ? left : uv[e - 1];
         const T up = e == PX - 1 ? right : uv[e + 1];
         const T u0 = uv[e];
-        ok[e] = GUARD ? (x + e >= 1 && x + e <= n - 2) : true;
+        const bool in = GUARD ? (x + e >= 1 && x + e <= n - 2) : true;
+        ok[e] = (GUARD && KEEP_ENDS) ? (x + e < n) : in;
         const T conv = pos_part(u0) * (u0 - um) + neg_part(u0) * (up - u0);
-        out[e] = u0 - C * conv + D * (um - T(2) * u0 + up);
+        const T val = u0 - C * conv + D * (um - T(2) * u0 + up);
+        out[e] = (GUARD && KEEP_ENDS) ? (in ? val : u0) : val;
     }
     store_cells<T, PX, GUARD>(rg, x, n, out, ok);
 }
@@ -295,6 +299,7 @@ __device__ __forceinline__ void run_segment(const Args1d &a, long xs, int lane)
     else if (OP == OP_ADJ_WAVE_UPREV) adj_wave1d_segment<T, PX, GUARD, true>(a, xs, lane);
     else if (OP == OP_PRI_WAVE) pri_wave1d_segment<T, PX, GUARD>(a, xs, lane);
     else if (OP == OP_PRI_BURGERS) pri_burgers_segment<T, PX, GUARD>(a, xs, lane);
+    else if (OP == OP_PRI_BURGERS_KEEP_ENDS) pri_burgers_segment<T, PX, GUARD, true>(a, xs, lane);
     else if (OP == OP_ADJ_BOX) box1d_segment<T, PX, GUARD, true>(a, xs, lane);
     else if (OP == OP_PRI_BOX) box1d_segment<T, PX, GUARD, false>(a, xs, lane);
     else if (OP == OP_ADJ_BURGERS_ASSIGN) adj_burgers_segment<T, PX, GUARD, true>(a, xs, lane);
@@ -371,11 +376,11 @@ hipError_t launch_adjoint_burgers1d(int is_f64, long n, double C, double D, cons
     return assign ? dispatch_1d<OP_ADJ_BURGERS_ASSIGN>(is_f64, a, stream) : dispatch_1d<OP_ADJ_BURGERS>(is_f64, a, stream);
 }
 hipError_t launch_primal_burgers1d(int is_f64, long n, double C, double D, const void *u, void *r,
-                                   hipStream_t stream)
+                                   hipStream_t stream, int keep_ends)
 {
     Args1d a{};
     a.a0 = u; a.o0 = r; a.n = n; a.C = C; a.D = D;
-    return dispatch_1d<OP_PRI_BURGERS>(is_f64, a, stream);
+    return keep_ends ? dispatch_1d<OP_PRI_BURGERS_KEEP_ENDS>(is_f64, a, stream) : dispatch_1d<OP_PRI_BURGERS>(is_f64, a, stream);
 }
 
 hipError_t launch_box1d(int adjoint, int is_f64, long n, const double *w, const void *in0, const void *in1,
