@@ -250,6 +250,24 @@ sadj_status sadj_adjoint_burgers1d_ckpt(sadj_dtype dtype, long n, long nsteps, l
                                         const void *ckpt, void *work, size_t work_bytes,
                                         void *lam0, void *lam1, void *stream);
 
+/* ---- the checkpointed reverse sweep for callers that cannot allocate ------------------------
+ * For callers that may not obtain device memory at the time of the call -- code recorded into a
+ * HIP graph, tight serving loops, harnesses that forbid allocation -- and therefore cannot hand
+ * over a `work` array: sadj_adjoint_burgers1d_ckpt with its scratch taken from a fixed array
+ * that lives in the library's device image (sadj_static_scratch_bytes() bytes, 64 MiB; every GPU
+ * that loads the library holds its own copy until the process ends).  The call allocates and
+ * frees nothing; the first call on a device looks up that device's copy of the array.
+ * Arguments, result and errors as sadj_adjoint_burgers1d_ckpt without `work`/`work_bytes`;
+ * additionally (every-1)*n*sizeof(element) > sadj_static_scratch_bytes() -> SADJ_ERR_SIZE, nothing
+ * enqueued.  The scratch keeps the last call's contents; every element a call reads it has
+ * written before, so nothing needs clearing.  All calls on one GPU share the one array: calls
+ * whose work overlaps in time on the same GPU (different streams or threads) race and must be
+ * serialised by the caller.
+ */
+sadj_status sadj_adjoint_burgers1d_ckpt_static(sadj_dtype dtype, long n, long nsteps, long every, double C, double D,
+                                               const void *ckpt, void *lam0, void *lam1, void *stream);
+size_t sadj_static_scratch_bytes(void);
+
 /* ---- diagnostic: how a 3-D adjoint call is cut into workgroups ----------------------------
  * Section 3.3.4 requires the loop nests (here: workgroups) to be disjoint and to cover every
  * output index exactly once.  This host-only call reports the decomposition the default tile

@@ -21,6 +21,7 @@ __all__ = [
     "sadj_primal_star3d", "sadj_adjoint_star3d", "sadj_primal_burgers1d_steps", "sadj_adjoint_burgers1d_steps",
     "sadj_adjoint_wave3d_atomic_scatter", "sadj_describe_wave3d_plan", "sadj_check_array",
     "sadj_stream_probe", "sadj_primal_burgers1d_ckpt", "sadj_adjoint_burgers1d_ckpt",
+    "sadj_adjoint_burgers1d_ckpt_static", "sadj_static_scratch_bytes",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -83,13 +84,17 @@ def load() -> ctypes.CDLL:
     lib.sadj_stream_probe.argtypes = [I, I, L, P, P, P, P]
     lib.sadj_primal_burgers1d_ckpt.argtypes = [I, L, L, L, D, D, P, P, P, P]
     lib.sadj_adjoint_burgers1d_ckpt.argtypes = [I, L, L, L, D, D, P, P, ctypes.c_size_t, P, P, P]
+    lib.sadj_adjoint_burgers1d_ckpt_static.argtypes = [I, L, L, L, D, D, P, P, P, P]
+    lib.sadj_static_scratch_bytes.argtypes = []
+    lib.sadj_static_scratch_bytes.restype = ctypes.c_size_t
     for name in ("sadj_set_option", "sadj_get_option", "sadj_primal_wave1d", "sadj_adjoint_wave1d",
                  "sadj_primal_wave2d", "sadj_adjoint_wave2d", "sadj_primal_wave3d", "sadj_adjoint_wave3d",
                  "sadj_primal_burgers1d", "sadj_adjoint_burgers1d", "sadj_adjoint_wave3d_steps",
                  "sadj_primal_box", "sadj_adjoint_box", "sadj_adjoint_wave3d_atomic_scatter", "sadj_describe_wave3d_plan",
                  "sadj_primal_star3d", "sadj_adjoint_star3d",
                  "sadj_primal_burgers1d_steps", "sadj_adjoint_burgers1d_steps", "sadj_check_array",
-                 "sadj_stream_probe", "sadj_primal_burgers1d_ckpt", "sadj_adjoint_burgers1d_ckpt"):
+                 "sadj_stream_probe", "sadj_primal_burgers1d_ckpt", "sadj_adjoint_burgers1d_ckpt",
+                 "sadj_adjoint_burgers1d_ckpt_static"):
         getattr(lib, name).restype = I
     _lib = lib
     return lib
@@ -317,3 +322,16 @@ def sadj_adjoint_burgers1d_ckpt(C: float, D: float, nsteps: int, every: int, ckp
     else:
         pw, wbytes = None, 0
     _check(load().sadj_adjoint_burgers1d_ckpt(code, n, int(nsteps), int(every), float(C), float(D), *pc, pw, wbytes, *pl, s))
+
+
+def sadj_static_scratch_bytes() -> int:
+    return int(load().sadj_static_scratch_bytes())
+
+
+def sadj_adjoint_burgers1d_ckpt_static(C: float, D: float, nsteps: int, every: int, ckpt, lam0, lam1) -> None:
+    """sadj_adjoint_burgers1d_ckpt with the library's fixed scratch array (no allocation)."""
+    code, (rows, n), pc, s = _marshal([ckpt], 2)
+    code2, (n2,), pl, _ = _marshal([lam0, lam1], 1)
+    if code2 != code or n2 != n:
+        raise ValueError("ckpt and lam buffers share dtype and row length")
+    _check(load().sadj_adjoint_burgers1d_ckpt_static(code, n, int(nsteps), int(every), float(C), float(D), *pc, *pl, s))

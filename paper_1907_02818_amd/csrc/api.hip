@@ -6,6 +6,7 @@
 #include <atomic>
 #include <cstdint>
 #include <cstring>
+#include <mutex>
 
 namespace {
 
@@ -145,8 +146,40 @@ sadj_status burgers_ckpt_reverse(sadj_dtype dtype, long n, long nsteps, long eve
     return SADJ_OK;
 }
 
+// Scratch memory of the entry point that must not allocate: a fixed array in device memory,
+// one copy per GPU that loads the library, held until the process ends.  The array's name is
+// a host-side handle only; the device address of the current GPU's copy is looked up once per
+// device and used from then on.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+sadj_status static_scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { g_last_hip_error = e; (void)hipGetLastError(); return SADJ_ERR_DEVICE; }
+    if (dev < 0 || dev >= kMaxDevices) return SADJ_ERR_UNSUPPORTED;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+        if (!p) {
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));       // of the current device's copy
+            if (e != hipSuccess || !p) { g_last_hip_error = e; (void)hipGetLastError(); return SADJ_ERR_DEVICE; }
+            g_scratch_ptr[dev].store(p, std::memory_order_release);
+        }
+    }
+    *out = p;
+    return SADJ_OK;
+}
+
+// library_work: `work` is the library's own scratch array (not an argument of the caller, so
+// the optional pointer check does not apply to it; overlap with the caller's arrays cannot occur)
 sadj_status burgers_ckpt_args(sadj_dtype dtype, long n, long nsteps, long every, const void *ckpt, const void *work,
-                              size_t work_bytes, void *lam0, void *lam1)
+                              size_t work_bytes, void *lam0, void *lam1, bool library_work = false)
 {
     if (!dtype_ok(dtype)) return SADJ_ERR_UNSUPPORTED;
     if (!ckpt || !lam0 || !lam1) return SADJ_ERR_NULL;
@@ -156,7 +189,7 @@ sadj_status burgers_ckpt_args(sadj_dtype dtype, long n, long nsteps, long every,
     if (need > 0 && !work) return SADJ_ERR_NULL;
     if (work_bytes < need) return SADJ_ERR_SIZE;
     const Span in[1] = {{ckpt, (size_t)((nsteps - 1 > 0 ? nsteps - 1 : 0) / every + 1) * row}};
-    const Span out[3] = {{lam0, row}, {lam1, row}, {work, need}};
+    const Span out[3] = {{lam0, row}, {lam1, row}, {work, library_work ? 0 : need}};
     return check_arrays(in, out);
 }
 
@@ -648,5 +681,24 @@ sadj_status sadj_adjoint_burgers1d_ckpt(sadj_dtype dtype, long n, long nsteps, l
     clear_stale_hip_error();
     return burgers_ckpt_reverse(dtype, n, nsteps, every, C, D, ckpt, work, lam0, lam1, static_cast<hipStream_t>(stream));
 }
+
+// The same reverse sweep for callers that cannot allocate: the recomputed states go to the
+// library's fixed scratch array.
+sadj_status sadj_adjoint_burgers1d_ckpt_static(sadj_dtype dtype, long n, long nsteps, long every, double C, double D,
+                                               const void *ckpt, void *lam0, void *lam1, void *stream)
+{
+    if (!dtype_ok(dtype)) return SADJ_ERR_UNSUPPORTED;
+    if (n < 3 || n > kMaxExtent || every < 1 || every > kMaxExtent) return SADJ_ERR_SIZE;
+    const size_t need = (size_t)(every - 1) * (size_t)n * elem(dtype);
+    if (need > kStaticScratchBytes) return SADJ_ERR_SIZE;
+    void *work = nullptr;
+    if (sadj_status s = static_scratch_of_current_device(&work); s != SADJ_OK) return s;
+    if (sadj_status s = burgers_ckpt_args(dtype, n, nsteps, every, ckpt, work, kStaticScratchBytes, lam0, lam1, true); s != SADJ_OK)
+        return s;
+    clear_stale_hip_error();
+    return burgers_ckpt_reverse(dtype, n, nsteps, every, C, D, ckpt, work, lam0, lam1, static_cast<hipStream_t>(stream));
+}
+
+size_t sadj_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 }  // extern "C"
