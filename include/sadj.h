@@ -216,7 +216,8 @@ sadj_status sadj_adjoint_star3d(sadj_dtype dtype, int radius, long nx, long ny, 
  *   consumed; adjoints of earlier states start from zero).  As in every adjoint call, values
  *   of lam[s%2] outside I are never used.  After the call lam[nsteps%2] holds the adjoint of
  *   u^{last-nsteps}.  nsteps = 0 does nothing; nsteps > last -> SADJ_ERR_SIZE.  lam0, lam1 and
- *   the rows read must not overlap.  One kernel per step is enqueued.
+ *   the rows read must not overlap.  One kernel per step is enqueued (fewer where steps are fused, see
+ *   option "burgers1d.fuse").
  */
 sadj_status sadj_primal_burgers1d_steps(sadj_dtype dtype, long n, long nsteps, double C, double D,
                                         void *states, void *stream);
@@ -324,6 +325,11 @@ sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, lon
  *   "star3d.functor" 1: radius-1 calls of sadj_*_star3d run through the generic functor kernels of
  *                    sadj_stencil_star.hpp where nx and the arrays' alignment allow 16-byte
  *                    accesses (default 0: their own kernel).
+ *   "burgers1d.fuse" 0 (default): the reverse sweeps of the Burgers time loop
+ *                    (sadj_adjoint_burgers1d_steps, sadj_adjoint_burgers1d_ckpt*) apply runs of five
+ *                    assigned steps in one pass over the data (lam read and written once per
+ *                    five states read, instead of once per state) where all arrays are 16-byte
+ *                    aligned; 1: one kernel per step.  Same result bit for bit.
  *   "wave3d.order"   order in which sadj_adjoint_wave3d adds the terms of one u_bar[j]
  *                    (Section 3.5: a gather can respect an order the user chooses and
  *                    stay parallel).  0 (default): the kernel's own fixed order, fastest.

@@ -10,7 +10,7 @@
 
 namespace {
 
-std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0}, g_variant2d{0}, g_remainder{0}, g_order{0}, g_functor1d{0}, g_functor_star{0}, g_xcdmap{0}, g_band{0}, g_ldspad{0}, g_split{0};
+std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0}, g_variant2d{0}, g_remainder{0}, g_order{0}, g_functor1d{0}, g_functor_star{0}, g_burgers_fuse{0}, g_xcdmap{0}, g_band{0}, g_ldspad{0}, g_split{0};
 
 sadj::LaunchOptions current_options()
 {
@@ -120,13 +120,43 @@ void clear_stale_hip_error() { (void)hipGetLastError(); }
 
 namespace {
 
+// Reverse steps s0, s0+1, ... of a sweep over the states state(0), state(1), ... (in the order
+// they are applied).  Step s reads lam[s%2] and updates lam[(s+1)%2]: accumulated for s = 0,
+// assigned from then on.  Runs of assigned steps are fused, several steps per pass over the
+// data, unless option "burgers1d.fuse" is 1 or the arrays' alignment rules it out; the result is
+// the same bit for bit.  Returns the number of steps done in `s0`.
+template <class StateOf>
+sadj_status burgers_reverse_steps(sadj_dtype dtype, long n, double C, double D, long count, StateOf state, void *const (&lam)[2],
+                                  long &s0, hipStream_t st)
+{
+    const int f64 = dtype == SADJ_F64;
+    const int M = sadj::burgers_fused_steps();
+    const bool fuse = g_burgers_fuse.load() == 0;
+    long k = 0;
+    while (k < count) {
+        const long s = s0 + k;
+        if (fuse && s > 0 && count - k >= M) {
+            const void *u[16];
+            for (int i = 0; i < M; ++i) u[i] = state(k + i);
+            const hipError_t e = sadj::launch_adjoint_burgers1d_fused(f64, n, C, D, u, lam[s % 2], lam[(s + M) % 2], st);
+            if (e == hipSuccess) { k += M; continue; }
+            if (e != hipErrorNotSupported) return from_hip(e);
+        }
+        const hipError_t e = sadj::launch_adjoint_burgers1d(f64, n, C, D, state(k), lam[s % 2], lam[(s + 1) % 2], s > 0 ? 1 : 0, st);
+        if (e != hipSuccess) return from_hip(e);
+        ++k;
+    }
+    s0 += count;
+    return SADJ_OK;
+}
+
 // Reverse sweep over all nsteps steps with recomputation; `work` holds every-1 rows.
 sadj_status burgers_ckpt_reverse(sadj_dtype dtype, long n, long nsteps, long every, double C, double D,
                                  const void *ckpt, void *work, void *lam0, void *lam1, hipStream_t st)
 {
     const size_t row = (size_t)n * elem(dtype);
     const int f64 = dtype == SADJ_F64;
-    void *lam[2] = {lam0, lam1};
+    void *const lam[2] = {lam0, lam1};
     const char *cb = static_cast<const char *>(ckpt);
     char *wb = static_cast<char *>(work);
     long s = 0;                                             // reverse steps done
@@ -138,10 +168,9 @@ sadj_status burgers_ckpt_reverse(sadj_dtype dtype, long n, long nsteps, long eve
             hipError_t e = sadj::launch_primal_burgers1d(f64, n, C, D, state(t), wb + (size_t)(t - t0) * row, st, 1);
             if (e != hipSuccess) return from_hip(e);
         }
-        for (long t = t1 - 1; t >= t0; --t, ++s) {
-            hipError_t e = sadj::launch_adjoint_burgers1d(f64, n, C, D, state(t), lam[s % 2], lam[(s + 1) % 2], s > 0 ? 1 : 0, st);
-            if (e != hipSuccess) return from_hip(e);
-        }
+        // reverse steps t1-1 .. t0 over these states
+        auto applied = [&](long k) -> const void * { return state(t1 - 1 - k); };
+        if (sadj_status rs = burgers_reverse_steps(dtype, n, C, D, t1 - t0, applied, lam, s, st); rs != SADJ_OK) return rs;
     }
     return SADJ_OK;
 }
@@ -289,6 +318,11 @@ sadj_status sadj_set_option(const char *name, long value)
         g_functor_star = value;
         return SADJ_OK;
     }
+    if (!std::strcmp(name, "burgers1d.fuse")) {
+        if (value < 0 || value > 1) return SADJ_ERR_UNSUPPORTED;
+        g_burgers_fuse = value;
+        return SADJ_OK;
+    }
 
     return SADJ_ERR_UNSUPPORTED;
 }
@@ -309,6 +343,7 @@ sadj_status sadj_get_option(const char *name, long *value)
     if (!std::strcmp(name, "wave3d.ldspad")) { *value = g_ldspad; return SADJ_OK; }
     if (!std::strcmp(name, "stencil1d.functor")) { *value = g_functor1d; return SADJ_OK; }
     if (!std::strcmp(name, "star3d.functor")) { *value = g_functor_star; return SADJ_OK; }
+    if (!std::strcmp(name, "burgers1d.fuse")) { *value = g_burgers_fuse; return SADJ_OK; }
     return SADJ_ERR_UNSUPPORTED;
 }
 
@@ -629,16 +664,13 @@ sadj_status sadj_adjoint_burgers1d_steps(sadj_dtype dtype, long n, long last, lo
     const Span out[2] = {{lam0, row}, {lam1, row}};
     if (sadj_status al = check_arrays(in, out); al != SADJ_OK) return al;
     clear_stale_hip_error();
-    void *lam[2] = {lam0, lam1};
+    void *const lam[2] = {lam0, lam1};
     const char *base = static_cast<const char *>(states);
-    for (long s = 0; s < nsteps; ++s) {
-        const long t = last - 1 - s;                 // the primal step u^t -> u^{t+1}
-        // lam[(s+1)%2] receives lam^t; from s = 1 on it is the consumed buffer and is assigned
-        hipError_t e = sadj::launch_adjoint_burgers1d(dtype == SADJ_F64, n, C, D, base + (size_t)t * row, lam[s % 2],
-                                                      lam[(s + 1) % 2], s > 0 ? 1 : 0, static_cast<hipStream_t>(stream));
-        if (e != hipSuccess) return from_hip(e);
-    }
-    return SADJ_OK;
+    // reverse step s undoes the primal step u^t -> u^{t+1}, t = last-1-s; lam[(s+1)%2] receives
+    // lam^t; from s = 1 on it is the consumed buffer and is assigned
+    auto applied = [&](long s) -> const void * { return base + (size_t)(last - 1 - s) * row; };
+    long done = 0;
+    return burgers_reverse_steps(dtype, n, C, D, nsteps, applied, lam, done, static_cast<hipStream_t>(stream));
 }
 
 // Time loop with checkpoints: every `every`-th state is kept, the others are recomputed

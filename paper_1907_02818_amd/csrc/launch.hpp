@@ -43,6 +43,14 @@ hipError_t launch_primal_wave1d(int is_f64, long n, const void *u, const void *u
 // assign != 0: u_bar = J^T r_bar (u_bar is not read) instead of u_bar += J^T r_bar
 hipError_t launch_adjoint_burgers1d(int is_f64, long n, double C, double D, const void *u,
                                     const void *r_bar, void *u_bar, int assign, hipStream_t stream);
+// burgers_fused_steps() consecutive reverse steps of a time loop in one pass, all in assign mode:
+// lam_out = J(u[M-1])^T ... J(u[0])^T lam_in (u[0] is the state of the step applied first).
+// lam_in and lam_out must differ.  hipErrorNotSupported (nothing enqueued) if an array is not
+// 16-byte aligned.
+int burgers_fused_steps();
+hipError_t launch_adjoint_burgers1d_fused(int is_f64, long n, double C, double D, const void *const *u,
+                                          const void *lam_in, void *lam_out, hipStream_t stream);
+
 // keep_ends != 0: r[0] = u[0] and r[n-1] = u[n-1] as well (boundary data carried to the next state)
 hipError_t launch_primal_burgers1d(int is_f64, long n, double C, double D, const void *u, void *r,
                                    hipStream_t stream, int keep_ends = 0);

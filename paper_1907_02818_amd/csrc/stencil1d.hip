@@ -244,6 +244,22 @@ __device__ __forceinline__ void pri_burgers_segment(const Args1d &a, long xs, in
 // The primal u is read at j-1, j, j+1 (shifted reads, Section 3.3.2).
 // ASSIGN: u_bar[j] = (the three terms) instead of +=, for a time loop that recycles a
 // buffer whose accumulated value is known to be zero (u_bar is then not read).
+// The three terms of one u_bar[j]; (um, u0, up) = u[j-1], u[j], u[j+1], (rm, r0, rp) = r_bar at
+// the same cells with zeros where the iteration does not exist.  One function with
+// contraction into fused multiply-adds switched off, shared by the single-step kernel and the
+// kernel that fuses several reverse steps of a time loop, so that both round every cell alike
+// and the fused sweep reproduces the step-by-step sweep bit for bit.
+template <class T> __device__ __forceinline__ T burgers_adjoint_terms(T um, T u0, T up, T rm, T r0, T rp, T C, T D, bool in0)
+{
+#pragma clang fp contract(off)
+    const T dpos = u0 >= T(0) ? T(1) : T(0);
+    const T dneg = -u0 >= T(0) ? T(1) : T(0);
+    const T g0 = T(1) - C * (dpos * (u0 - um) + pos_part(u0) + dneg * (up - u0) - neg_part(u0)) - T(2) * D;
+    const T from_right = (C * pos_part(up) + D) * rp;      // iteration j+1 read u[j] as its left cell
+    const T from_left = (-C * neg_part(um) + D) * rm;      // iteration j-1 read u[j] as its right cell
+    return from_right + (in0 ? g0 * r0 : T(0)) + from_left;
+}
+
 template <class T, int PX, bool GUARD, bool ASSIGN>
 __device__ __forceinline__ void adj_burgers_segment(const Args1d &a, long xs, int lane)
 {
@@ -279,16 +295,168 @@ __device__ __forceinline__ void adj_burgers_segment(const Args1d &a, long xs, in
         const T up = e == PX - 1 ? ur : uv[e + 1];
         const T rm = e == 0 ? rl : rv[e - 1];
         const T rp = e == PX - 1 ? rr : rv[e + 1];
-        const T u0 = uv[e];
-        const T dpos = u0 >= T(0) ? T(1) : T(0);
-        const T dneg = -u0 >= T(0) ? T(1) : T(0);
-        const T g0 = T(1) - C * (dpos * (u0 - um) + pos_part(u0) + dneg * (up - u0) - neg_part(u0)) - T(2) * D;
-        const T from_right = (C * pos_part(up) + D) * rp;      // iteration j+1 read u[j] as its left cell
-        const T from_left = (-C * neg_part(um) + D) * rm;      // iteration j-1 read u[j] as its right cell
-        const T terms = from_right + (in[e] ? g0 * rv[e] : T(0)) + from_left;
+        const T terms = burgers_adjoint_terms(um, uv[e], up, rm, rv[e], rp, C, D, in[e]);
         out[e] = ASSIGN ? terms : bv[e] + terms;
     }
     store_cells<T, PX, GUARD>(bg, x, n, out, ok);
+}
+
+// ------------------------------------------- Burgers, several reverse steps in one pass
+// A reverse sweep over stored states applies lam <- J(u^t)^T lam for t = T, T-1, ...; done
+// step by step each application reads u^t and lam and writes lam: 24 bytes per cell and step
+// (fp64).  Here a wave applies M consecutive steps to a window of cells held in registers:
+// lam is read once, the M states once each, lam written once -- (16 + 8M)/M bytes per cell and
+// step.  A cell's value after k steps depends on k cells to either side, so a window of W cells
+// yields W - 2H finished cells (H >= M, a multiple of the cells per lane so that whole lanes
+// are either finished or not); neighbouring windows overlap by 2H cells, which are computed
+// twice.  All M steps are in assign mode (the target starts from zero), as from the second
+// step of a sweep on; lam outside I is never used (masked to zero at every step).  Input and
+// output must be different buffers (windows read cells their neighbours write): M is odd, so
+// the alternating buffers of the sweep stay in step.
+constexpr int kFuseM = 5;        // reverse steps per pass
+constexpr int kFuseH = 8;        // cells recomputed on either side of a window
+
+struct FusedArgs {
+    const void *u[kFuseM];       // states of the steps in the order they are applied: u^t, u^{t-1}, ...
+    const void *lam_in;
+    void *lam_out;
+    long n;
+    double C, D;
+    long core_lo, core_hi;       // windows core_lo .. core_hi-1 need no guard
+    long core_blocks, nwin;
+};
+
+template <class T, bool GUARD>
+__device__ __forceinline__ void adj_burgers_fused_window(const FusedArgs &a, long w, int lane)
+{
+    constexpr int PXL = 32 / (int)sizeof(T);            // cells per lane: two 16-byte accesses
+    constexpr int PXV = 16 / (int)sizeof(T);
+    constexpr int W = 64 * PXL, V = W - 2 * kFuseH;
+    const long n = a.n;
+    const T C = (T)a.C, D = (T)a.D;
+    const long x = w * V - kFuseH + (long)lane * PXL;  // first cell of this lane (may lie outside the array)
+    auto load = [&](const void *base, T (&v)[PXL]) {
+        const T *p = static_cast<const T *>(base);
+        if (!GUARD) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const Vec<T, PXV> t = ld_vec_stream<T, PXV>(p + x + h * PXV);
+#pragma unroll
+                for (int e = 0; e < PXV; ++e) v[h * PXV + e] = t.v[e];
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < PXL; ++e) {
+                long i = x + e;
+                i = i < 0 ? 0 : (i > n - 1 ? n - 1 : i);
+                v[e] = p[i];
+            }
+        }
+    };
+    bool in[PXL];
+#pragma unroll
+    for (int e = 0; e < PXL; ++e) in[e] = GUARD ? (x + e >= 1 && x + e <= n - 2) : true;
+    T lam[PXL], uv[kFuseM][PXL];
+    load(a.lam_in, lam);
+#pragma unroll
+    for (int s = 0; s < kFuseM; ++s) load(a.u[s], uv[s]);
+#pragma unroll
+    for (int s = 0; s < kFuseM; ++s) {
+#pragma unroll
+        for (int e = 0; e < PXL; ++e) lam[e] = in[e] ? lam[e] : T(0);      // lam outside I is never used
+        // neighbours across lanes; the window's two end lanes get zeros, which only reach cells
+        // that are discarded
+        T ul = __shfl_up(uv[s][PXL - 1], 1), ur = __shfl_down(uv[s][0], 1);
+        T ll = __shfl_up(lam[PXL - 1], 1), lr = __shfl_down(lam[0], 1);
+        ul = lane == 0 ? T(0) : ul;  ll = lane == 0 ? T(0) : ll;
+        ur = lane == 63 ? T(0) : ur; lr = lane == 63 ? T(0) : lr;
+        T next[PXL];
+#pragma unroll
+        for (int e = 0; e < PXL; ++e) {
+            const T um = e == 0 ? ul : uv[s][e - 1];
+            const T up = e == PXL - 1 ? ur : uv[s][e + 1];
+            const T rm = e == 0 ? ll : lam[e - 1];
+            const T rp = e == PXL - 1 ? lr : lam[e + 1];
+            next[e] = burgers_adjoint_terms(um, uv[s][e], up, rm, lam[e], rp, C, D, in[e]);
+        }
+#pragma unroll
+        for (int e = 0; e < PXL; ++e) lam[e] = next[e];
+    }
+    T *out = static_cast<T *>(a.lam_out);
+    if (!GUARD) {
+        if (lane >= kFuseH / PXL && lane < 64 - kFuseH / PXL) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                Vec<T, PXV> t;
+#pragma unroll
+                for (int e = 0; e < PXV; ++e) t.v[e] = lam[h * PXV + e];
+                st_vec_stream<T, PXV>(out + x + h * PXV, t);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < PXL; ++e) {
+            const long i = x + e;
+            if (i >= w * V && i < (w + 1) * V && i < n) out[i] = lam[e];
+        }
+    }
+}
+
+template <class T>
+__global__ __launch_bounds__(64 * kWaves1d) void adj_burgers_fused_kernel(FusedArgs a)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long b = blockIdx.x;
+    if (b < a.core_blocks) {                       // block-uniform; no barrier in this kernel
+        const long w = a.core_lo + b * kWaves1d + wave;
+        if (w >= a.core_hi) return;
+        adj_burgers_fused_window<T, false>(a, w, lane);
+    } else {
+        // remainder windows: 0 .. core_lo-1 and core_hi .. nwin-1
+        long k = (b - a.core_blocks) * kWaves1d + wave;
+        const long w = k < a.core_lo ? k : a.core_hi + (k - a.core_lo);
+        if (w >= a.nwin) return;
+        adj_burgers_fused_window<T, true>(a, w, lane);
+    }
+}
+
+static inline bool aligned16_1d(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+template <class T>
+static hipError_t launch_fused_T(FusedArgs a, hipStream_t stream)
+{
+    constexpr int PXL = 32 / (int)sizeof(T);
+    constexpr int W = 64 * PXL, V = W - 2 * kFuseH;
+    a.nwin = (a.n + V - 1) / V;
+    // core window w: all its cells w*V-H .. w*V-H+W-1 lie in I = [1, n-2]
+    a.core_lo = 1;
+    a.core_hi = (a.n - 2 - W + 1 + kFuseH) / V + 1;          // largest w with w*V - H + W - 1 <= n-2, plus one
+    if (a.n - 2 - W + 1 + kFuseH < V) a.core_hi = 1;         // no core window
+    if (a.core_hi > a.nwin) a.core_hi = a.nwin;
+    if (a.core_hi < a.core_lo) a.core_hi = a.core_lo;
+    a.core_blocks = (a.core_hi - a.core_lo + kWaves1d - 1) / kWaves1d;
+    const long rem = a.nwin - (a.core_hi - a.core_lo);
+    const long blocks = a.core_blocks + (rem + kWaves1d - 1) / kWaves1d;
+    if (blocks > 0x7fffffffL) return hipErrorNotSupported;
+    hipLaunchKernelGGL((adj_burgers_fused_kernel<T>), dim3((unsigned)blocks), dim3(64 * kWaves1d), 0, stream, a);
+    return hipGetLastError();
+}
+
+int burgers_fused_steps() { return kFuseM; }
+
+// kFuseM reverse steps in assign mode: lam_out = J(u[M-1])^T ... J(u[0])^T lam_in.
+// hipErrorNotSupported (nothing enqueued) if an array is not 16-byte aligned.
+hipError_t launch_adjoint_burgers1d_fused(int is_f64, long n, double C, double D, const void *const *u,
+                                          const void *lam_in, void *lam_out, hipStream_t stream)
+{
+    FusedArgs a{};
+    for (int s = 0; s < kFuseM; ++s) {
+        a.u[s] = u[s];
+        if (!aligned16_1d(u[s])) return hipErrorNotSupported;
+    }
+    if (!aligned16_1d(lam_in) || !aligned16_1d(lam_out)) return hipErrorNotSupported;
+    a.lam_in = lam_in; a.lam_out = lam_out; a.n = n; a.C = C; a.D = D;
+    return is_f64 ? launch_fused_T<double>(a, stream) : launch_fused_T<float>(a, stream);
 }
 
 // -------------------------------------------------------------------------- kernels

@@ -118,6 +118,49 @@ def test_burgers_forward_and_reverse_sweeps(sadj, n, nsteps, dtype):
     assert_close(got, want, scale, dtype, "burgers reverse sweep n=%d steps=%d" % (n, nsteps))
 
 
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("n", [3, 17, 64, 239, 240, 241, 257, 495, 496, 497, 1000, 4099, 100003])
+@pytest.mark.parametrize("nsteps", [6, 11, 17])
+def test_fused_reverse_steps_equal_single_steps_bit_for_bit(sadj, n, nsteps, dtype):
+    """Runs of five assigned steps go through one kernel that keeps a window of cells in
+    registers (option burgers1d.fuse = 0, the default); the step-by-step sweep is the reference.
+    Sizes around the window widths (240 / 496 finished cells per wave) and the clamped ends."""
+    import torch
+    st = to_gpu(_burgers_states(n, nsteps, 3 * n + nsteps, dtype))
+    lam0 = inputs.uniform(n, "r_bar", (n,), -1, 1).astype(dtype)
+    lam1 = inputs.uniform(n, "u_bar", (n,), -1, 1).astype(dtype)
+    lam0[0] = lam0[-1] = np.nan                                        # outside I: never used
+    out = []
+    for fuse in (1, 0):
+        sadj.set_option("burgers1d.fuse", fuse)
+        g0, g1 = to_gpu(lam0), to_gpu(lam1)
+        sadj.sadj_adjoint_burgers1d_steps(BC, BD, nsteps, nsteps, st, g0, g1)
+        torch.cuda.synchronize()
+        out.append(to_host((g0, g1)[nsteps % 2]))
+    sadj.set_option("burgers1d.fuse", 0)
+    assert np.isfinite(out[0]).all()
+    assert np.array_equal(out[0], out[1])
+
+
+def test_fused_reverse_steps_with_unaligned_rows_fall_back(sadj):
+    """Rows of an odd length start at addresses that are not 16-byte aligned: those steps run
+    one by one; the result is unchanged."""
+    import torch
+    n, nsteps = 1001, 12
+    st = to_gpu(_burgers_states(n, nsteps, 5, np.float64))
+    lam0 = inputs.uniform(n, "r_bar", (n,), -1, 1)
+    lam1 = inputs.uniform(n, "u_bar", (n,), -1, 1)
+    out = []
+    for fuse in (1, 0):
+        sadj.set_option("burgers1d.fuse", fuse)
+        g0, g1 = to_gpu(lam0), to_gpu(lam1)
+        sadj.sadj_adjoint_burgers1d_steps(BC, BD, nsteps, nsteps, st, g0, g1)
+        torch.cuda.synchronize()
+        out.append(to_host((g0, g1)[nsteps % 2]))
+    sadj.set_option("burgers1d.fuse", 0)
+    assert np.array_equal(out[0], out[1])
+
+
 def test_burgers_sweep_argument_checks(sadj):
     import paper_1907_02818_amd as lib
     st = to_gpu(np.zeros((4, 100)))
