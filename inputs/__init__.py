@@ -89,6 +89,16 @@ def uniform(seed: int, name: str, shape, lo: float, hi: float) -> np.ndarray:
     return a.reshape(shape)
 
 
+def uniform_planes(seed: int, name: str, shape, lo: float, hi: float, z0: int, nplanes: int) -> np.ndarray:
+    """Planes z0 .. z0+nplanes-1 (slowest axis) of the array uniform(seed, name, shape, lo, hi)
+    would return, without generating the rest: the generator is counter-based."""
+    per = int(np.prod(shape[1:]))
+    a = unit(seed, STREAMS[name], nplanes * per, start=z0 * per)
+    a *= (hi - lo)
+    a += lo
+    return a.reshape((nplanes,) + tuple(shape[1:]))
+
+
 def layered_profile(seed: int, n_axis: int, nlayers: int, blend: int,
                     lo: float, hi: float) -> np.ndarray:
     """1-D piecewise-constant profile with linear blends across layer interfaces.

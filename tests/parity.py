@@ -50,3 +50,23 @@ def assert_close(got, want, scale, dtype, what=""):
     plain = norm_err(got, want)
     assert plain <= tol, "%s: max|g-o|/max|o| = %.3e > %.1e" % (what, plain, tol)
     return err
+
+
+def wave_primal_scale(u, u_prev, c, radius):
+    """sum of the magnitudes of the terms of r[i] = 2u[i] - u_prev[i] + c[i] sum_o w_o u[i+o]: the
+    scale against which a differently ordered evaluation of the primal is compared."""
+    import scipy.ndimage as ndi
+    from jacobians import star_weights
+    u = np.abs(np.asarray(u, dtype=np.float64))
+    w = np.abs(star_weights(radius))
+    nd = u.ndim
+    k = np.zeros((2 * radius + 1,) * nd)
+    k[(radius,) * nd] = nd * w[0]
+    for axis in range(nd):
+        for o in range(1, radius + 1):
+            for sgn in (-1, 1):
+                pos = [radius] * nd
+                pos[axis] += sgn * o
+                k[tuple(pos)] = w[o]
+    star = ndi.correlate(u, k, mode="constant")
+    return 2.0 * u + np.abs(np.asarray(u_prev, dtype=np.float64)) + np.abs(np.asarray(c, dtype=np.float64)) * star

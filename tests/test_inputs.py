@@ -74,3 +74,10 @@ def test_burgers_profile_changes_sign_and_is_bounded():
     assert u.min() > -1 and u.max() < 1
     assert (u > 0.2).sum() > 500 and (u < -0.2).sum() > 500
     assert set(d) == {"u", "r_bar", "u_bar"}
+
+
+def test_planes_of_a_field_can_be_generated_on_their_own():
+    shape = (9, 6, 5)
+    full = inputs.uniform(11, "r_bar", shape, -1.0, 1.0)
+    for z0, k in ((0, 1), (3, 4), (8, 1)):
+        assert np.array_equal(inputs.uniform_planes(11, "r_bar", shape, -1.0, 1.0, z0, k), full[z0:z0 + k])
