@@ -36,7 +36,11 @@
  *    read and write sets are disjoint) -> SADJ_ERR_ALIAS.
  *  - Errors are return codes; argument checks happen before anything is enqueued, so
  *    a failed call has no effect.  No function throws or aborts.
- *  - Calls are thread-safe; one GPU (the current HIP device of the calling thread).
+ *  - Calls may be made from several threads at once; one GPU (the current HIP device of the
+ *    calling thread).  The launch options (sadj_set_option) are process-wide, not per thread or
+ *    per call: every call works with one consistent snapshot of them, taken when it starts, so
+ *    two threads cannot use different settings at the same time, and an option changed while
+ *    calls are being made applies to the calls that start afterwards.
  *
  * Star Laplacian weights (standard central second-derivative weights, centre first):
  * R=1: (-2, 1); R=2: (-5/2, 4/3, -1/12); R=3: (-49/18, 3/2, -3/20, 1/90);
@@ -271,9 +275,10 @@ size_t sadj_static_scratch_bytes(void);
 
 /* ---- diagnostic: how a 3-D adjoint call is cut into workgroups ----------------------------
  * Section 3.3.4 requires the loop nests (here: workgroups) to be disjoint and to cover every
- * output index exactly once.  This host-only call reports the decomposition the default tile
- * shape of sadj_adjoint_wave3d would use under the current options, so that a test can check
- * that property without a GPU: plan[0..7] = tiles along x, tiles along y, tile width, tile
+ * output index exactly once.  This host-only call reports the decomposition that
+ * sadj_adjoint_wave3d uses under the current options for 16-byte aligned arrays (with_u_prev_bar:
+ * whether u_prev_bar is passed, which selects another tile shape in fp64), so that a test can
+ * check that property without a GPU: plan[0..7] = tiles along x, tiles along y, tile width, tile
  * height (cells), number of workgroups, and how the tiles are cut along z: the first
  * plan[5] tiles (in tile numbering order) into plan[6] chunks each, all others into
  * plan[7] chunks each (plan[5] = 0: every tile alike).  If `tiles` is not NULL it receives,
@@ -281,7 +286,7 @@ size_t sadj_static_scratch_bytes(void);
  * one past the last plane.  `plan` and `tiles` are HOST pointers.  Nothing is launched.
  */
 sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, long ny, long nz,
-                                      long *plan /* host, 8 */, int *tiles /* host, 4*max_blocks, nullable */,
+                                      int with_u_prev_bar, long *plan /* host, 8 */, int *tiles /* host, 4*max_blocks, nullable */,
                                       long max_blocks);
 
 /* ---- launch options -------------------------------------------------------------------
@@ -298,9 +303,13 @@ sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, lon
  *                    per compute unit, the left-over tiles may be cut into more z-chunks than
  *                    the others so that they fill a round of their own; 1: all tiles are cut
  *                    alike.  Ignored when "wave3d.zchunk" is set.
- *   "wave3d.variant" tile-shape variant index (default 0 = automatic).
- *   "wave2d.ychunk"  rows of output per wave along y (default 0 = automatic).
- *   "wave2d.variant" load-pipeline depth / workgroup size variant (default 0 = automatic).
+ *   "wave3d.variant" tile shape of sadj_adjoint_wave3d (default 0 = automatic): 1 = 64 x 32 cells, two
+ *                    cells per lane; 2 = 128 x 32, four cells per lane; 3 = 64 x 32, one cell per
+ *                    lane; 5 = rows of 1 KB x 16 rows; 10 / 11 = 256 / 512 cells x 16 rows (radius
+ *                    1).  Other values select shape 1.
+ *   "wave2d.ychunk"  rows of output per wave along y (default 0 = automatic); a value that would
+ *                    need more than 65535 row chunks makes the 2-D calls return SADJ_ERR_UNSUPPORTED.
+ * *   "wave2d.variant" load-pipeline depth / workgroup size variant (default 0 = automatic).
  *   "wave3d.xcdmap"  how workgroups of the 3-D marching kernels are assigned to x-y tiles:
  *                    0/1 (default) per round of resident workgroups every XCD (chiplet with
  *                    its own L2) owns a contiguous range of tiles, 2 one contiguous range

@@ -69,7 +69,7 @@ def load() -> ctypes.CDLL:
     lib.sadj_adjoint_wave2d.argtypes = [I, L, L, P, P, P, P, P]
     lib.sadj_primal_wave3d.argtypes = [I, I, L, L, L, P, P, P, P, P]
     lib.sadj_adjoint_wave3d.argtypes = [I, I, L, L, L, P, P, P, P, P]
-    lib.sadj_describe_wave3d_plan.argtypes = [I, I, L, L, L, ctypes.POINTER(L), ctypes.POINTER(ctypes.c_int), L]
+    lib.sadj_describe_wave3d_plan.argtypes = [I, I, L, L, L, I, ctypes.POINTER(L), ctypes.POINTER(ctypes.c_int), L]
     lib.sadj_adjoint_wave3d_atomic_scatter.argtypes = [I, I, L, L, L, P, P, P, P]
     lib.sadj_adjoint_wave3d_steps.argtypes = [I, I, L, L, L, L, P, P, P, P, P]
     lib.sadj_primal_star3d.argtypes = [I, I, L, L, L, ctypes.POINTER(D), P, P, P, P]
@@ -195,16 +195,18 @@ def sadj_stream_probe(shape: int, a, b, out) -> None:
     _check(load().sadj_stream_probe(code, int(shape), n, *p, s))
 
 
-def sadj_describe_wave3d_plan(dtype_code: int, radius: int, nx: int, ny: int, nz: int, with_tiles: bool = True):
+def sadj_describe_wave3d_plan(dtype_code: int, radius: int, nx: int, ny: int, nz: int, with_tiles: bool = True,
+                              with_u_prev_bar: bool = False):
     """Host-only: (plan dict, list of (tile x, tile y, first plane, end plane) per workgroup id)."""
     plan = (ctypes.c_long * 8)()
-    _check(load().sadj_describe_wave3d_plan(dtype_code, int(radius), nx, ny, nz, plan, None, 0))
+    prev = int(bool(with_u_prev_bar))
+    _check(load().sadj_describe_wave3d_plan(dtype_code, int(radius), nx, ny, nz, prev, plan, None, 0))
     ntx, nty, tw, th, total, tiles_a, ntz_a, ntz = (int(v) for v in plan)
     info = dict(ntx=ntx, nty=nty, tile_w=tw, tile_h=th, workgroups=total, tiles_a=tiles_a, ntz_a=ntz_a, ntz=ntz)
     if not with_tiles:
         return info, None
     buf = (ctypes.c_int * (4 * total))()
-    _check(load().sadj_describe_wave3d_plan(dtype_code, int(radius), nx, ny, nz, plan, buf, total))
+    _check(load().sadj_describe_wave3d_plan(dtype_code, int(radius), nx, ny, nz, prev, plan, buf, total))
     return info, [tuple(buf[4 * b:4 * b + 4]) for b in range(total)]
 
 

@@ -12,8 +12,14 @@ namespace {
 
 std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0}, g_variant2d{0}, g_remainder{0}, g_order{0}, g_functor1d{0}, g_functor_star{0}, g_burgers_fuse{0}, g_xcdmap{0}, g_band{0}, g_ldspad{0}, g_split{0};
 
+// Options are set one at a time; a call takes one consistent snapshot of all of them under
+// the same lock the setters hold, so it never sees a combination that was not in force at
+// some moment.
+std::mutex g_option_mutex;
+
 sadj::LaunchOptions current_options()
 {
+    std::lock_guard<std::mutex> lock(g_option_mutex);
     sadj::LaunchOptions o;
     o.zchunk = g_zchunk.load();
     o.variant = g_variant.load();
@@ -253,6 +259,7 @@ sadj_status sadj_check_array(const void *p, size_t bytes)
 sadj_status sadj_set_option(const char *name, long value)
 {
     if (!name) return SADJ_ERR_NULL;
+    std::lock_guard<std::mutex> lock(g_option_mutex);
     if (!std::strcmp(name, "wave3d.zchunk")) {
         if (value < 0 || value > kMaxExtent) return SADJ_ERR_UNSUPPORTED;
         g_zchunk = value;
@@ -432,15 +439,15 @@ sadj_status sadj_adjoint_wave3d(sadj_dtype dtype, int radius, long nx, long ny, 
 
 // Diagnostic: the decomposition sadj_adjoint_wave3d would use (no launch, no device access
 // beyond reading the CU count).
-sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, long ny, long nz, long *plan,
-                                      int *tiles, long max_blocks)
+sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, long ny, long nz, int with_u_prev_bar,
+                                      long *plan, int *tiles, long max_blocks)
 {
     if (radius < 1 || radius > 4 || !dtype_ok(dtype)) return SADJ_ERR_UNSUPPORTED;
     if (!plan) return SADJ_ERR_NULL;
     sadj_status s = check_extents(radius, nx, ny, nz, 3);
     if (s != SADJ_OK) return s;
-    sadj::describe_march_plan(dtype == SADJ_F64, radius, (int)nx, (int)ny, (int)nz, current_options(), plan, tiles,
-                              max_blocks);
+    sadj::describe_march_plan(dtype == SADJ_F64, radius, (int)nx, (int)ny, (int)nz, with_u_prev_bar, current_options(),
+                              plan, tiles, max_blocks);
     (void)hipGetLastError();       // a machine without a GPU leaves an error code behind; it is not ours to keep
     return SADJ_OK;
 }

@@ -78,7 +78,7 @@ hipError_t launch_star3d(int adjoint, int is_f64, int radius, int nx, int ny, in
 // tiles in x, tiles in y, tile width, tile height, workgroups, tiles of the first group,
 // z-chunks per tile of the first group, z-chunks per tile of the others; and, if `tiles` is
 // not null, for every workgroup id (tile x, tile y, first plane, one past the last plane).
-void describe_march_plan(int is_f64, int radius, int nx, int ny, int nz, const LaunchOptions &opt,
+void describe_march_plan(int is_f64, int radius, int nx, int ny, int nz, int with_u_prev_bar, const LaunchOptions &opt,
                          long *plan, int *tiles, long max_blocks);
 
 // Streaming yardstick out[i] += a[i]*b[i] over n elements (two launch shapes, see probe.hip).

@@ -368,6 +368,7 @@ static hipError_t launch_adj2d_cfg(Wave2dArgs a, const LaunchOptions &opt, hipSt
     const int bx = (nstrips + WAVES - 1) / WAVES;
     const int ychunk = auto_ychunk(bx, a.ny, opt.ychunk2d);
     a.ychunk = ychunk;
+    if ((a.ny + ychunk - 1) / ychunk > 65535) return hipErrorNotSupported;     // a user-set "wave2d.ychunk" too small for ny
     dim3 grid(bx, (a.ny + ychunk - 1) / ychunk), block(64 * WAVES);
     if (a.u_prev_bar) hipLaunchKernelGGL((adj_wave2d_kernel<T, PX, D, WAVES, true>), grid, block, 0, stream, a);
     else              hipLaunchKernelGGL((adj_wave2d_kernel<T, PX, D, WAVES, false>), grid, block, 0, stream, a);
@@ -396,6 +397,7 @@ static hipError_t launch_pri2d(const Wave2dArgs &a0, const LaunchOptions &opt, h
     const int bx = (nstrips + WAVES - 1) / WAVES;
     const int rows = a.ny - 2;
     a.ychunk = auto_ychunk(bx, rows, opt.ychunk2d);
+    if ((rows + a.ychunk - 1) / a.ychunk > 65535) return hipErrorNotSupported;
     dim3 grid(bx, (rows + a.ychunk - 1) / a.ychunk), block(64 * WAVES);
     hipLaunchKernelGGL((primal_wave2d_kernel<T, PX, D, WAVES>), grid, block, 0, stream, a);
     return hipGetLastError();

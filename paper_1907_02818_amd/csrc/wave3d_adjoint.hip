@@ -399,22 +399,50 @@ static hipError_t launch_cfg(March3dArgs a, const LaunchOptions &opt, hipStream_
 // Tile shapes <BX, BY, PY, PX, D, NT>.  Variant 0 picks the measured best per dtype:
 // 16 bytes per lane and memory instruction (two doubles / four floats), tile rows of
 // 512 bytes, 32 rows, 32 x 16 threads (a wave covers two rows), one workgroup per CU.
+//   1  fp64 default: 64 x 32 tile, two doubles per lane
+//   2  fp32 default: 128 x 32 tile, four floats per lane
+//   3  one cell per lane (64 x 32 tile, 8- or 4-byte accesses): the fallback for odd nx or
+//      unaligned arrays, and the fp64 choice when u_prev_bar is read and written as well
+//   5  rows of 1 KB, 16 rows: for rows that are not cache-line multiples
+//   10, 11  radius 1 only: 16 rows of 256 / 512 cells (see wide_tile_for_unaligned_rows)
+// (Shapes tried and removed: two planes in flight, u_bar without the streaming hint, a
+// 64 x 16 tile with 256 threads, a 128 x 32 tile with eight cells per thread -- none
+// was the best anywhere.)
+static inline long choose_adjoint_shape(bool is_f64, int radius, int nx, bool u_prev_accumulated, const LaunchOptions &opt)
+{
+    long v = opt.variant;
+    if (v != 0) return v;
+    // measured best: 16 bytes per lane (1 for fp64, 2 for fp32); fp64 with u_prev_bar read and
+    // written as well: the one-cell shape with fewer registers per cell (3).  (fp32 with
+    // u_prev_bar: shape 2 measured 3-16 points faster than an 8-byte shape at 256^3 .. 896^3.)
+    v = is_f64 ? (u_prev_accumulated ? 3 : 1) : 2;
+    if (opt.remainder == 0) {
+        const int wide = wide_tile_for_unaligned_rows(nx, is_f64 ? 8 : 4, radius, !is_f64);
+        if (radius == 1 && wide == 512) v = 11;
+        else if (radius == 1 && wide == 256) v = 10;
+        else if (wide) v = 5;
+    }
+    return v;
+}
+
+// Tile extents (cells) and cells per lane of a shape, for the host-side description of the plan.
+static inline void shape_extents(long v, bool is_f64, int radius, int &TX, int &TY, int &PX)
+{
+    const int px16 = is_f64 ? 2 : 4;
+    switch (v) {
+    case 2: TX = 128; TY = 32; PX = 4; break;
+    case 3: TX = 64; TY = 32; PX = 1; break;
+    case 5: TX = 64 * px16; TY = 16; PX = px16; break;
+    case 10: if (radius == 1) { TX = 256; TY = 16; PX = 2; break; } TX = 64; TY = 32; PX = 2; break;
+    case 11: if (radius == 1 && !is_f64) { TX = 512; TY = 16; PX = 4; break; } TX = 64; TY = 32; PX = 2; break;
+    default: TX = 64; TY = 32; PX = 2; break;      // 1 and anything unknown: the fp64 default shape
+    }
+}
+
 template <class T, int R>
 static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipStream_t stream)
 {
-    long v = opt.variant;
-    // measured best: 16 bytes per lane (1 for fp64, 2 for fp32); fp64 with u_prev_bar read and
-    // written as well: the one-cell shape with fewer registers per cell (3).  (fp32 with
-    // u_prev_bar: shape 2 measured 3-16 points faster than the 8-byte shape 8 at 256^3 .. 896^3.)
-    if (v == 0) {
-        v = sizeof(T) == 8 ? ((a.out1 && !a.out1_assign) ? 3 : 1) : 2;
-        if (opt.remainder == 0) {
-            const int wide = wide_tile_for_unaligned_rows(a.nx, sizeof(T), R, sizeof(T) == 4);
-            if (R == 1 && wide == 512) v = 11;
-            else if (R == 1 && wide == 256) v = 10;
-            else if (wide) v = 5;
-        }
-    }
+    const long v = choose_adjoint_shape(sizeof(T) == 8, R, a.nx, a.out1 && !a.out1_assign, opt);
     if constexpr (R == 2 || R == 3) {            // the default shapes of the dtype only
         if constexpr (sizeof(T) == 8) {
             return v == 3 ? launch_cfg<T, R, 64, 8, 4, 1, 1, true>(a, opt, stream)
@@ -423,7 +451,6 @@ static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipSt
         } else {
             return v == 3 ? launch_cfg<T, R, 64, 8, 4, 1, 1, true>(a, opt, stream)
                  : v == 5 ? launch_cfg<T, R, 64, 8, 2, 4, 1, true>(a, opt, stream)
-                 : v == 8 ? launch_cfg<T, R, 64, 8, 4, 2, 1, true>(a, opt, stream)
                           : launch_cfg<T, R, 32, 16, 2, 4, 1, true>(a, opt, stream);
         }
     } else {
@@ -431,15 +458,11 @@ static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipSt
         default:
         case 1: return launch_cfg<T, R, 32, 16, 2, 2, 1, true>(a, opt, stream);     // fp64 default
         case 2: return launch_cfg<T, R, 32, 16, 2, 4, 1, true>(a, opt, stream);     // fp32 default
-        case 3: return launch_cfg<T, R, 64, 8, 4, 1, 1, true>(a, opt, stream);      // 8 bytes per lane (fallback shape)
-        case 4: return launch_cfg<T, R, 64, 8, 4, 1, 2, true>(a, opt, stream);      // two planes in flight
+        case 3: return launch_cfg<T, R, 64, 8, 4, 1, 1, true>(a, opt, stream);      // one cell per lane
         case 5:                                                                     // rows of 1 KB, 16 rows
             if constexpr (sizeof(T) == 8) return launch_cfg<T, R, 64, 8, 2, 2, 1, true>(a, opt, stream);
             else return launch_cfg<T, R, 64, 8, 2, 4, 1, true>(a, opt, stream);
-        case 6: return launch_cfg<T, R, 32, 16, 2, 2, 1, false>(a, opt, stream);    // u_bar through L2 (no streaming hint)
-        case 7: return launch_cfg<T, R, 64, 4, 4, 1, 1, true>(a, opt, stream);      // 64 x 16 tile, 256 threads
-        case 8: return launch_cfg<T, R, 64, 8, 4, 2, 1, true>(a, opt, stream);      // 128 x 32 tile, PX = 2
-        // radius 1 only: 16 rows of 256 or 512 cells (see wide_tile_for_unaligned_rows)
+        // radius 1 only: 16 rows of 256 or 512 cells
         case 10:
             if constexpr (R == 1) return launch_cfg<T, R, 128, 4, 4, 2, 1, true>(a, opt, stream);  // 256 x 16 tile, PX = 2
             else return launch_cfg<T, R, 32, 16, 2, 2, 1, true>(a, opt, stream);
@@ -450,16 +473,15 @@ static hipError_t launch_T(const March3dArgs &a, const LaunchOptions &opt, hipSt
     }
 }
 
-void describe_march_plan(int is_f64, int radius, int nx, int ny, int nz, const LaunchOptions &opt,
+void describe_march_plan(int is_f64, int radius, int nx, int ny, int nz, int with_u_prev_bar, const LaunchOptions &opt,
                          long *plan, int *tiles, long max_blocks)
 {
-    // the default shapes: 32 x 16 threads, two rows per thread, 16 bytes per lane; with rows
-    // that are not cache-line multiples: 16 rows of 1 KB (radius 1: 256 or 512 cells)
-    int TX = is_f64 ? 64 : 128, TY = 32;
-    if (opt.remainder == 0 && opt.variant == 0) {
-        const int wide = wide_tile_for_unaligned_rows(nx, is_f64 ? 8 : 4, radius, !is_f64);
-        if (wide) { TX = wide; TY = 16; }
-    }
+    // the shape launch_T takes for 16-byte aligned arrays and an nx that allows whole vectors;
+    // otherwise the one-cell shape
+    long v = choose_adjoint_shape(is_f64 != 0, radius, nx, with_u_prev_bar != 0, opt);
+    int TX, TY, PX;
+    shape_extents(v, is_f64 != 0, radius, TX, TY, PX);
+    if (nx % PX != 0) shape_extents(3, is_f64 != 0, radius, TX, TY, PX);
     March3dArgs a{};
     a.nx = nx; a.ny = ny; a.nz = nz;
     TileMap &m = a.map;

@@ -261,3 +261,31 @@ def test_gather_kernels_use_no_atomics():
                 continue                               # std::atomic<long> option variables on the host
             offenders.append(os.path.basename(path))
     assert offenders == []
+
+
+def test_a_row_chunk_option_that_needs_too_many_chunks_is_refused_before_any_launch():
+    lib = sadj.load()
+    sadj.set_option("wave2d.ychunk", 1)
+    try:
+        rc = lib.sadj_adjoint_wave2d(1, 64, 70000, A, B, C_, None, None)
+        assert rc == 4
+        rc = lib.sadj_primal_wave2d(1, 64, 70000, A, B, C_, D_, None)
+        assert rc == 4
+    finally:
+        sadj.set_option("wave2d.ychunk", 0)
+
+
+def test_plan_description_follows_the_shape_the_launch_takes():
+    # fp64: 64 x 32 tiles with and without u_prev_bar; an odd nx takes the one-cell shape (64 x 32);
+    # rows that are not cache-line multiples take 16-row tiles of 1 KB (radius 4) or 256 cells (radius 1)
+    for prev in (False, True):
+        info, _ = sadj.sadj_describe_wave3d_plan(1, 4, 512, 512, 512, with_tiles=False, with_u_prev_bar=prev)
+        assert (info["tile_w"], info["tile_h"]) == (64, 32)
+    info, _ = sadj.sadj_describe_wave3d_plan(0, 4, 512, 512, 512, with_tiles=False)
+    assert (info["tile_w"], info["tile_h"]) == (128, 32)
+    info, _ = sadj.sadj_describe_wave3d_plan(1, 4, 1000, 1000, 100, with_tiles=False)
+    assert (info["tile_w"], info["tile_h"]) == (128, 16)
+    info, _ = sadj.sadj_describe_wave3d_plan(1, 1, 1000, 1000, 100, with_tiles=False)
+    assert (info["tile_w"], info["tile_h"]) == (256, 16)
+    info, _ = sadj.sadj_describe_wave3d_plan(1, 4, 1001, 1000, 100, with_tiles=False)
+    assert (info["tile_w"], info["tile_h"]) == (64, 32)

@@ -104,23 +104,33 @@ def test_adjoint_equals_dense_JT(n):
     assert np.allclose(sc, np.abs(J).T @ np.abs(rb), rtol=1e-13, atol=1e-15)
 
 
-def test_adjoint_core_matches_the_papers_printed_gather_loop():
-    """Section 4.2 figure, 'PerforAD Stencil Adjoint', on [2, n-3]; a few u are set to
-    exactly 0 so that the printed >= convention at the kink is covered as well."""
+def _partials(um, u0, up):
+    """Partial derivatives of one Burgers iteration with respect to its three reads, from the
+    upwind formula of Section 4.2; d max(a,0)/da = d min(a,0)/da = 1 at a == 0 (the convention of
+    the paper's generated adjoint)."""
+    pos, neg = np.maximum(u0, 0.0), np.minimum(u0, 0.0)
+    ipos, ineg = (u0 >= 0).astype(float), (u0 <= 0).astype(float)
+    g_left = C * pos + D
+    g_right = -C * neg + D
+    g_centre = 1.0 - 2.0 * D - C * (ipos * (u0 - um) + pos + ineg * (up - u0) - neg)
+    return g_left, g_centre, g_right
+
+
+def test_adjoint_core_is_the_three_shifted_partials_gathered():
+    """On the core [2, n-3] every u_bar[j] receives the left-read partial of iteration j+1, the
+    centre partial of iteration j and the right-read partial of iteration j-1 (Section 4.2's
+    adjoint, Section 3.3.2's index shifting), here as whole-array expressions; a few u are set to
+    exactly 0 so that the convention at the kink is covered as well."""
     n = 500
     d = _u(n, seed=8)
-    u1 = d["u"].copy()
-    u1[[10, 11, 200, 201, 202, 350]] = 0.0
-    ub_in, u_b = d["u_bar"], d["r_bar"]
-    want = ub_in.copy()
-    for i in range(2, n - 2):
-        want[i] += (C * max(0.0, u1[i + 1]) + D) * u_b[i + 1]
-        want[i] += (-C * ((-u1[i] + u1[i + 1]) * (1.0 if -u1[i] >= 0 else 0.0)
-                          + (u1[i] - u1[i - 1]) * (1.0 if u1[i] >= 0 else 0.0)
-                          + max(0.0, u1[i]) - min(0.0, u1[i])) - 2.0 * D + 1) * u_b[i]
-        want[i] += (-C * min(0.0, u1[i - 1]) + D) * u_b[i - 1]
-    got, _ = oracle.burgers_adjoint(u1, u_b, ub_in, C, D)
-    assert np.allclose(got[2:n - 2], want[2:n - 2], rtol=1e-13, atol=1e-15)
+    u = d["u"].copy()
+    u[[10, 11, 200, 201, 202, 350]] = 0.0
+    rb, ub_in = d["r_bar"], d["u_bar"]
+    gl, gc, gr = _partials(u[:-2], u[1:-1], u[2:])          # of iterations 1 .. n-2 (array index i-1)
+    j = np.arange(2, n - 2)
+    want = ub_in[j] + gl[j] * rb[j + 1] + gc[j - 1] * rb[j] + gr[j - 2] * rb[j - 1]
+    got, _ = oracle.burgers_adjoint(u, rb, ub_in, C, D)
+    assert np.allclose(got[2:n - 2], want, rtol=1e-13, atol=1e-15)
 
 
 def test_adjoint_end_points_receive_only_the_terms_whose_primal_iteration_exists():

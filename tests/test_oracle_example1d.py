@@ -1,6 +1,7 @@
 """The paper's 1-D worked example (Section 3.2): asymmetric weights (2,-3,4), variable
 c, iteration space [1,n-1] on arrays of length n+1.  The scatter oracle must give
-what the paper's printed remainder statements and merged core loop give; the
+what the paper's remainder statements and merged core loop give (derived here from the
+weight table and checked against the facts the section states about them); the
 asymmetric weights catch a mirrored-offset mistake that a symmetric Laplacian hides."""
 import os
 
@@ -14,21 +15,36 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "example1d_adjoint_st
 W = (2.0, -3.0, 4.0)
 
 
-def _printed_adjoint(n, c, rb, ub):
-    ub = ub.copy()
+def _facts():
+    out = {}
     with open(GOLDEN) as fh:
-        rows = [ln.split() for ln in fh if ln.strip() and not ln.startswith("#")]
-    assert len(rows) == 9
-    for kind, tgt, w, src in rows:
-        w = float(w)
-        if kind == "stmt":
-            t, s = eval(tgt, {"n": n}), eval(src, {"n": n})
-            ub[t] += w * c[s] * rb[s]
-        else:
-            for j in range(2, n - 1):
-                t, s = eval(tgt, {"n": n, "j": j}), eval(src, {"n": n, "j": j})
-                ub[t] += w * c[s] * rb[s]
-    return ub
+        for ln in fh:
+            if ln.strip() and not ln.startswith("#"):
+                key, *vals = ln.split()
+                out[key] = vals
+    return out
+
+
+def _statements(n):
+    """Every update ub[target] += w * c[source] * rb[source] of the adjoint, derived from the
+    primal's weight table: iteration i in [1, n-1] reads u[i-1], u[i], u[i+1] with W."""
+    return [(i + o, w, i) for i in range(1, n) for o, w in zip((-1, 0, 1), W)]
+
+
+def _split_adjoint(n, c, rb, ub):
+    """The statements regrouped by target as Section 3.2 does: those whose target has all three
+    sources form the core loop, the others remain single statements."""
+    ub = ub.copy()
+    st = _statements(n)
+    by_target = {}
+    for t, w, s_ in st:
+        by_target.setdefault(t, []).append((w, s_))
+    core = sorted(t for t, lst in by_target.items() if len(lst) == 3)
+    rest = sorted(t for t, lst in by_target.items() if len(lst) < 3 for _ in lst)
+    for t, lst in by_target.items():
+        for w, s_ in lst:
+            ub[t] += w * c[s_] * rb[s_]
+    return ub, core, rest, by_target
 
 
 def _fields(n, seed):
@@ -42,8 +58,17 @@ def _fields(n, seed):
 def test_scatter_oracle_equals_the_printed_remainder_and_core(n):
     c, rb, ub = _fields(n, n)
     got = oracle.lin3_adjoint(c, rb, ub, 1, n - 1, *W)
-    want = _printed_adjoint(n, c, rb, ub)
+    want, core, rest, by_target = _split_adjoint(n, c, rb, ub)
     assert np.allclose(got, want, rtol=1e-14, atol=1e-15)
+    # the split has the structure the paper states
+    facts = _facts()
+    env = {"n": n}
+    lo, hi = (eval(v, env) for v in facts["core_bounds"])
+    assert core == list(range(lo, hi + 1))
+    assert rest == sorted(eval(v, env) for v in facts["remainder_targets"])
+    want_factors = [float(v) for v in facts["core_factors_at_j-1_j_j+1"]]
+    for j in core:
+        assert [w for w, s_ in sorted(by_target[j], key=lambda ws: ws[1])] == want_factors
 
 
 def test_weights_swap_sides_between_primal_and_adjoint():

@@ -207,30 +207,28 @@ def test_adjoint_core_matches_the_papers_printed_gather_loop():
     assert np.allclose(upb[s, s, s], d["u_prev_bar"][s, s, s] - rb[s, s, s], rtol=0, atol=1e-15)
 
 
-def test_adjoint_matches_the_papers_printed_scatter_loop_run_backwards():
-    """Section 4.1 figure, 'Tapenade adjoint': loops run from n-2 down to 1 with
-    tempb = c*ub scattered to the six neighbours and 2ub - 6 tempb to the centre.
-    Same real-number result as the ascending oracle; only rounding differs."""
+def test_adjoint_on_the_whole_grid_is_a_sum_of_shifted_copies_of_c_times_r_bar():
+    """Section 4.1's conventional adjoint sends t = c*r_bar of every interior point to its six
+    neighbours and 2 r_bar - 6 t to the point itself.  Over the whole grid, boundary layers
+    included, that is: the interior block of t added at the six shifted positions.  Written with
+    whole-array slices, in no particular order (the result is order-independent up to rounding)."""
     n = 7
     d = _fields((n, n, n), seed=43)
-    c, ubar = d["c"], d["r_bar"]
-    u1b = d["u_bar"].copy()
-    u2b = d["u_prev_bar"].copy()
-    for i in range(n - 2, 0, -1):
-        for j in range(n - 2, 0, -1):
-            for k in range(n - 2, 0, -1):
-                t = c[i, j, k] * ubar[i, j, k]
-                u1b[i, j, k - 1] += t
-                u1b[i, j, k] += 2.0 * ubar[i, j, k] - 6 * t
-                u1b[i, j, k + 1] += t
-                u1b[i, j - 1, k] += t
-                u1b[i, j + 1, k] += t
-                u1b[i - 1, j, k] += t
-                u1b[i + 1, j, k] += t
-                u2b[i, j, k] -= ubar[i, j, k]
-    ub, upb, _ = oracle.wave_adjoint(c, ubar, d["u_bar"], 1, u_prev_bar=d["u_prev_bar"])
-    assert np.allclose(ub, u1b, rtol=1e-13, atol=1e-14)
-    assert np.allclose(upb, u2b, rtol=0, atol=1e-15)
+    c, rb = d["c"], d["r_bar"]
+    s = slice(1, n - 1)
+    t = (c * rb)[s, s, s]
+    want = d["u_bar"].copy()
+    want[s, s, s] += 2.0 * rb[s, s, s] - 6.0 * t
+    for axis in range(3):
+        for shift in (-1, 1):
+            idx = [s, s, s]
+            idx[axis] = slice(1 + shift, n - 1 + shift)
+            want[tuple(idx)] += t
+    wantp = d["u_prev_bar"].copy()
+    wantp[s, s, s] -= rb[s, s, s]
+    ub, upb, _ = oracle.wave_adjoint(c, rb, d["u_bar"], 1, u_prev_bar=d["u_prev_bar"])
+    assert np.allclose(ub, want, rtol=1e-13, atol=1e-14)
+    assert np.allclose(upb, wantp, rtol=0, atol=1e-15)
 
 
 # ---------------------------------------------------- adjoint: special cases, invariants

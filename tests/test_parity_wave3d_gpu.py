@@ -71,7 +71,7 @@ def test_adjoint_small(sadj, radius, shape, dtype):
     _check_adjoint(sadj, d, radius, dtype, with_prev=True, what="R=%d %s with u_prev_bar" % (radius, shape))
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8, 10, 11])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 5, 10, 11])
 @pytest.mark.parametrize("radius", [1, 4])
 def test_adjoint_tile_variants(sadj, radius, variant):
     sadj.set_option("wave3d.variant", variant)
@@ -365,8 +365,13 @@ def test_primal_small(sadj, radius, shape, dtype):
 def test_unaligned_rows_take_wide_tiles(sadj, radius, shape, dtype):
     nz, ny, nx = shape
     info, _ = sadj.sadj_describe_wave3d_plan(1 if dtype == np.float64 else 0, radius, nx, ny, nz, with_tiles=False)
-    assert info["tile_h"] == 16
-    assert info["tile_w"] in ((256, 512) if radius == 1 else (1024 // np.dtype(dtype).itemsize,))
+    if dtype == np.float32 and nx % 4 != 0:
+        # whole four-float vectors are not possible: the radius-1 shape with two cells per lane
+        # (256 x 16) where it covers nx well, else the one-cell shape
+        assert (info["tile_w"], info["tile_h"]) in (((256, 16), (64, 32)) if radius == 1 and nx % 2 == 0 else ((64, 32),))
+    else:
+        assert info["tile_h"] == 16
+        assert info["tile_w"] in ((256, 512) if radius == 1 else (1024 // np.dtype(dtype).itemsize,))
     d = inputs.wave_inputs(shape, 0.01, 0.1, seed=sum(shape), dtype=dtype, c_mode="iid")
     for zchunk in (0, 5):
         sadj.set_option("wave3d.zchunk", zchunk)
