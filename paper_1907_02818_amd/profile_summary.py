@@ -12,7 +12,9 @@ DIR holds what three rocprofv3 runs of the same workload wrote (csv output, `-o 
     DIR/write/   the same with WRITE_SIZE
     DIR/stats.json   stdout of the first run (bench.py's JSON line: algorithmic bytes of the workload)
 
-and, optionally, DIR/sq/ from a run with SQ_* counters.  Writes profiles/WORKLOAD_stats.txt
+and, optionally, DIR/sq/ from a run with SQ_* counters.  With `--all DIR` instead of a workload
+it writes profiles/all_workloads_stats.txt from DIR/stats/ and DIR/stats.json of a
+`bench.py --all --remainder-study` run under rocprofv3 --kernel-trace --stats.  Writes profiles/WORKLOAD_stats.txt
 and profiles/WORKLOAD_pmc.txt.  The counters are calibrated on the run's last dispatch, the
 plain device copy of one 1 GiB array that `--copy-probe` appends (2^30 bytes read, 2^30
 written).  The pmc summary records a hash of the kernel sources, so that bench.py reports its
@@ -41,7 +43,7 @@ def library_sources_sha256() -> str:
     files = []
     for d in (os.path.join(HERE, "csrc"), os.path.join(ROOT, "include")):
         for name in sorted(os.listdir(d)):
-            if name.endswith((".hip", ".hpp", ".h")):
+            if name.endswith((".hip", ".hpp")):          # kernel sources; sadj.h holds declarations only
                 files.append(os.path.join(d, name))
     for f in files:
         h.update(os.path.basename(f).encode())
@@ -172,7 +174,43 @@ def summarise(workload, d):
     return stats_txt, pmc_txt
 
 
+def summarise_all(d):
+    """Summary of a `bench.py --all --remainder-study` run under rocprofv3 --kernel-trace --stats:
+    DIR/stats/ (csv) and DIR/stats.json (bench.py's JSON line)."""
+    js = _bench_json(os.path.join(d, "stats.json"))
+    lines = ["rocprofv3 kernel-trace summary of every benchmark workload, one MI355X",
+             "command (from the repository root; DIR is any scratch directory):",
+             "  rocprofv3 --kernel-trace --stats -d DIR/stats -o p --output-format csv -- python3 bench.py --all "
+             "--remainder-study --steps %d --warmup %d --no-cpu-baseline" % (js["steps"], js["warmup"]), "",
+             "bench.py's figures (HIP-event mean of the timed calls after the settle phase; fraction of 8000 GB/s on",
+             "algorithmic bytes; per step where a call performs several steps):", "",
+             "%-52s %10s %9s %8s" % ("workload", "ms", "GB/s", "% peak")]
+    rows = [(HEADLINE, js["roofline"]["kernel_ms_mean"], js["roofline"]["achieved"], js["roofline"]["frac"])]
+    rows += [(k, v["kernel_ms_mean"], v["GB/s"], v["frac"]) for k, v in js["others"].items()]
+    for k, ms, gbs, frac in rows:
+        lines.append("%-52s %10.4f %9.0f %8.1f" % (k, ms, gbs, 100 * frac))
+    sc = js["roofline"].get("stream_ceiling")
+    if sc:
+        lines.append("%-52s %10.4f %9.0f %8.1f" % ("streaming ceiling (out += a*b, same arrays)", sc["kernel_ms_mean"], sc["GB/s"], sc["GB/s"] / 80))
+    stats = _rows(os.path.join(d, "stats", "**", "*kernel_stats.csv"))
+    lines += ["", "rocprofv3 --stats, library kernels (avg over ALL launches of a kernel, settle and warm-up included):", "",
+              "%-100s %6s %10s %10s" % ("kernel", "calls", "avg_us", "min_us")]
+    for r in stats:
+        if _is_ours(r["Name"]):
+            lines.append("%-100s %6s %10.1f %10.1f" % (_short(r["Name"])[:100], r["Calls"], float(r["AverageNs"]) / 1e3, float(r["MinNs"]) / 1e3))
+    return "\n".join(lines) + "\n"
+
+
+HEADLINE = "wave3d_r4_f64_adjoint"
+
+
 def main(argv):
+    if len(argv) == 3 and argv[1] == "--all":
+        txt = summarise_all(argv[2])
+        with open(os.path.join(ROOT, "profiles", "all_workloads_stats.txt"), "w") as fh:
+            fh.write(txt)
+        sys.stdout.write(txt)
+        return 0
     if len(argv) != 3:
         print(__doc__, file=sys.stderr)
         return 2
