@@ -239,36 +239,32 @@ __device__ __forceinline__ void box3d_march(const BoxArgs &a, int tix, int tiy, 
     T wt[27];
 #pragma unroll
     for (int i = 0; i < 27; ++i) wt[i] = (T)a.w[i];
-    const uint32_t dummy = (uint32_t)((size_t)y0 * nx + x0) * sizeof(T);
-
+    // owned cells and halo slots (tile3d.hpp); the halo is the full ring of width 1, corners included.
+    // ouse: cell in I (x,y); ostore: cell receives output
+    TileAddr<PX, PY, HS, GUARD> ad;
+    ad.init(tx, ty, x0, y0, nx, ny, 1, 1, LX, -1, (uint32_t)sizeof(T),
+            [&](int s, int &lx, int &ly) { return G::halo_cell(tid + s * G::NT, lx, ly); });
     uint32_t ooff[PY];
-    bool ouse[PY][PX], ostore[PY][PX], ovec[PY];    // ouse: cell in I (x,y); ostore: cell receives output
-    const int x = x0 + tx * PX;
+    bool ouse[PY][PX], ostore[PY][PX], ovec[PY];
 #pragma unroll
     for (int p = 0; p < PY; ++p) {
-        const int y = y0 + ty * PY + p;
-        const bool ingrid = !GUARD || (x < nx && y < ny);
         ovec[p] = true;
 #pragma unroll
         for (int e = 0; e < PX; ++e) {
-            ouse[p][e] = !GUARD || (x + e >= 1 && x + e <= nx - 2 && y >= 1 && y <= ny - 2);
-            ostore[p][e] = ADJ ? ingrid : ouse[p][e];
+            ouse[p][e] = ad.own_I[p][e];
+            ostore[p][e] = ADJ ? ad.own_grid[p] : ouse[p][e];
             ovec[p] = ovec[p] && ostore[p][e];
         }
-        ooff[p] = ingrid ? (uint32_t)((size_t)y * nx + x) * sizeof(T) : dummy;
+        ooff[p] = ad.own_off[p];
     }
     uint32_t hoff[HS];
     int hlds[HS];
     bool huse[HS];
 #pragma unroll
     for (int s = 0; s < HS; ++s) {
-        int lx, ly;
-        const bool slot = G::halo_cell(tid + s * G::NT, lx, ly);
-        const int gx = x0 - 1 + lx, gy = y0 - 1 + ly;
-        const bool ingrid = slot && (!GUARD || (gx >= 0 && gx < nx && gy >= 0 && gy < ny));
-        huse[s] = ADJ ? (slot && (!GUARD || (gx >= 1 && gx <= nx - 2 && gy >= 1 && gy <= ny - 2))) : ingrid;
-        hoff[s] = ingrid ? (uint32_t)((size_t)gy * nx + gx) * sizeof(T) : dummy;
-        hlds[s] = slot ? ly * LX + lx : -1;
+        huse[s] = ADJ ? ad.halo_I[s] : ad.halo_grid[s];
+        hoff[s] = ad.halo_off[s];
+        hlds[s] = ad.halo_lds[s];
     }
 
     T acc[PY][PX][3];

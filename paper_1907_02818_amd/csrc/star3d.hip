@@ -48,39 +48,33 @@ __device__ __forceinline__ void star3d_march(const StarArgs &a, int tix, int tiy
     T wx[2 * R], wy[2 * R], wz[2 * R];
 #pragma unroll
     for (int i = 0; i < 2 * R; ++i) { wx[i] = (T)a.w[0][i]; wy[i] = (T)a.w[1][i]; wz[i] = (T)a.w[2][i]; }
-    const uint32_t dummy = (uint32_t)((size_t)y0 * nx + x0) * sizeof(T);   // always inside the grid
-
-    // owned cells: x = x0 + tx*PX + e, y = y0 + ty*PY + p (nx is a multiple of PX, so a vector
-    // of PX cells is entirely inside or entirely outside the grid)
+    // owned cells x = x0 + tx*PX + e, y = y0 + ty*PY + p and halo slots (tile3d.hpp).  ouse: cell in I
+    // (x,y); ostore: cell receives output; the primal reads u wherever it lies in the grid (outside it
+    // reads as 0, never used by cells of I), the adjoint uses c and r_bar on I only
+    TileAddr<PX, PY, HS, GUARD> ad;
+    ad.init(tx, ty, x0, y0, nx, ny, R, R, LX, 0 /* cell (0,0) is a corner nobody reads */, (uint32_t)sizeof(T),
+            [&](int s, int &lx, int &ly) { return G::halo_cell(tid, s, lx, ly); });
     uint32_t ooff[PY];
-    bool ouse[PY][PX], ostore[PY][PX], ovec[PY];    // ouse: cell in I (x,y); ostore: cell receives output
-    const int x = x0 + tx * PX;
+    bool ouse[PY][PX], ostore[PY][PX], ovec[PY];
 #pragma unroll
     for (int p = 0; p < PY; ++p) {
-        const int y = y0 + ty * PY + p;
-        const bool ingrid = !GUARD || (x < nx && y < ny);
         ovec[p] = true;
 #pragma unroll
         for (int e = 0; e < PX; ++e) {
-            ouse[p][e] = !GUARD || (x + e >= R && x + e < nx - R && y >= R && y < ny - R);
-            ostore[p][e] = ADJ ? ingrid : ouse[p][e];
+            ouse[p][e] = ad.own_I[p][e];
+            ostore[p][e] = ADJ ? ad.own_grid[p] : ouse[p][e];
             ovec[p] = ovec[p] && ostore[p][e];
         }
-        ooff[p] = ingrid ? (uint32_t)((size_t)y * nx + x) * sizeof(T) : dummy;
+        ooff[p] = ad.own_off[p];
     }
     uint32_t hoff[HS];
     int hlds[HS];
     bool huse[HS];
 #pragma unroll
     for (int s = 0; s < HS; ++s) {
-        int lx, ly;
-        const bool slot = G::halo_cell(tid, s, lx, ly);
-        const int gx = x0 - R + lx, gy = y0 - R + ly;
-        const bool ingrid = slot && (!GUARD || (gx >= 0 && gx < nx && gy >= 0 && gy < ny));
-        const bool inI = slot && (!GUARD || (gx >= R && gx < nx - R && gy >= R && gy < ny - R));
-        huse[s] = ADJ ? inI : ingrid;               // primal: u outside the grid reads as 0 (never used by cells of I)
-        hoff[s] = ingrid ? (uint32_t)((size_t)gy * nx + gx) * sizeof(T) : dummy;
-        hlds[s] = slot ? ly * LX + lx : 0;          // cell (0,0) is a corner nobody reads
+        huse[s] = ADJ ? ad.halo_I[s] : ad.halo_grid[s];
+        hoff[s] = ad.halo_off[s];
+        hlds[s] = ad.halo_lds[s];
     }
 
     T acc[PY][PX][NACC];

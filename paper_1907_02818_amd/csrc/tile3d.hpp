@@ -36,6 +36,55 @@ struct Tile3d {
     }
 };
 
+// Per-thread addressing of a marching kernel's tile, computed once before the march and shared
+// by the 3-D kernels (wave adjoint and primal, free-weight star, box, scatter-order adjoint).
+// A thread owns PX consecutive cells in x times PY consecutive rows and HS halo slots.  For
+// each it gets the byte offset inside an x-y plane and two predicates: "lies in the grid" and
+// "lies in the primal iteration space I in x and y" (at least `margin` cells from the grid's
+// edge).  Offsets of owned vectors outside the grid and of halo slots that are unused or
+// outside the grid point at `dummy`, a cell that is always inside the grid, so that a load
+// through them is harmless; which of the two predicates decides about a cell's value is the
+// kernel's business (an adjoint uses c and r_bar on I only, a primal reads u on the whole
+// grid).  GUARD = false (core tiles: everything lies in I) folds all predicates to constants.
+template <int PX, int PY, int HS, bool GUARD> struct TileAddr {
+    uint32_t dummy;
+    uint32_t own_off[PY];     // owned vector of row p (nx is a multiple of PX: inside or outside the grid as a whole)
+    bool own_grid[PY];
+    bool own_I[PY][PX];
+    uint32_t halo_off[HS];
+    bool halo_grid[HS], halo_I[HS];
+    int halo_lds[HS];
+
+    // halo_cell(s, lx, ly) -> does slot s of this thread exist, and its LDS coordinates; the LDS
+    // plane has row length LX and its origin `halo` cells left of and above the tile.
+    template <class HaloCell>
+    __device__ __forceinline__ void init(int tx, int ty, int x0, int y0, int nx, int ny, int margin, int halo, int LX,
+                                         int unused_lds, uint32_t elem_bytes, HaloCell halo_cell)
+    {
+        dummy = (uint32_t)((size_t)y0 * nx + x0) * elem_bytes;
+        const int x = x0 + tx * PX;
+#pragma unroll
+        for (int p = 0; p < PY; ++p) {
+            const int y = y0 + ty * PY + p;
+            own_grid[p] = GUARD ? (x < nx && y < ny) : true;
+#pragma unroll
+            for (int e = 0; e < PX; ++e)
+                own_I[p][e] = GUARD ? (x + e >= margin && x + e < nx - margin && y >= margin && y < ny - margin) : true;
+            own_off[p] = own_grid[p] ? (uint32_t)((size_t)y * nx + x) * elem_bytes : dummy;
+        }
+#pragma unroll
+        for (int s = 0; s < HS; ++s) {
+            int lx, ly;
+            const bool slot = halo_cell(s, lx, ly);
+            const int gx = x0 - halo + lx, gy = y0 - halo + ly;
+            halo_grid[s] = slot && (!GUARD || (gx >= 0 && gx < nx && gy >= 0 && gy < ny));
+            halo_I[s] = slot && (!GUARD || (gx >= margin && gx < nx - margin && gy >= margin && gy < ny - margin));
+            halo_off[s] = halo_grid[s] ? (uint32_t)((size_t)gy * nx + gx) * elem_bytes : dummy;
+            halo_lds[s] = slot ? ly * LX + lx : unused_lds;
+        }
+    }
+};
+
 // Workgroup id -> (x-y tile, range of planes) of a 3-D march; filled by plan_march.
 // The tiles are numbered 0 .. ntx*nty-1 (see `band`).  The first tiles_a of them are cut
 // into ntz_a chunks of zchunk_a planes, the others into ntz chunks of zchunk planes;

@@ -100,42 +100,31 @@ __device__ __forceinline__ void adj3d_march(const March3dArgs &a, int tix, int t
     T *__restrict__ ug = static_cast<T *>(a.out0);
     T *__restrict__ upg = static_cast<T *>(a.out1);
 
-    // A cell that is always inside the grid: unused slots load it and discard it.
-    const uint32_t dummy = (uint32_t)((size_t)y0 * nx + x0) * sizeof(T);
-
-    // ---- owned cells: x = x0 + tx*PX + e, y = y0 + ty*PY + p  (nx is a multiple of PX,
-    //      so a vector of PX cells is entirely inside or entirely outside the grid)
+    // owned cells x = x0 + tx*PX + e, y = y0 + ty*PY + p and halo slots (tile3d.hpp); c and r_bar are
+    // used on I only, and not fetched at all where none of a vector's cells lies in I
+    TileAddr<PX, PY, HS, GUARD> ad;
+    ad.init(tx, ty, x0, y0, nx, ny, R, R, LX, 0 /* cell (0,0) is a corner nobody reads */, (uint32_t)sizeof(T),
+            [&](int s, int &lx, int &ly) { return G::halo_cell(tid, s, lx, ly); });
+    const uint32_t dummy = ad.dummy;
     uint32_t ooff[PY], coff[PY];
     bool ouse[PY][PX], ostore[PY];
-    const int x = x0 + tx * PX;
 #pragma unroll
     for (int p = 0; p < PY; ++p) {
-        const int y = y0 + ty * PY + p;
-        ostore[p] = GUARD ? (x < nx && y < ny) : true;
-#pragma unroll
-        for (int e = 0; e < PX; ++e)
-            ouse[p][e] = GUARD ? (x + e >= R && x + e < nx - R && y >= R && y < ny - R) : true;
-        ooff[p] = ostore[p] ? (uint32_t)((size_t)y * nx + x) * sizeof(T) : dummy;
-        // c and r_bar are not fetched where none of the vector's cells lies in I
+        ostore[p] = ad.own_grid[p];
+        ooff[p] = ad.own_off[p];
         bool any = false;
 #pragma unroll
-        for (int e = 0; e < PX; ++e) any = any || ouse[p][e];
+        for (int e = 0; e < PX; ++e) { ouse[p][e] = ad.own_I[p][e]; any = any || ouse[p][e]; }
         coff[p] = (!GUARD || any) ? ooff[p] : dummy;
     }
-    // ---- halo slots
     uint32_t hoff[HS];
     int hlds[HS];
     bool huse[HS];
 #pragma unroll
     for (int s = 0; s < HS; ++s) {
-        int lx, ly;
-        const bool slot = G::halo_cell(tid, s, lx, ly);
-        const int gx = x0 - R + lx, gy = y0 - R + ly;
-        bool use = slot;
-        if (GUARD) use = use && gx >= R && gx < nx - R && gy >= R && gy < ny - R;
-        huse[s] = use;
-        hoff[s] = use ? (uint32_t)((size_t)gy * nx + gx) * sizeof(T) : dummy;
-        hlds[s] = slot ? ly * LX + lx : 0;        // cell (0,0) is a corner nobody reads
+        huse[s] = ad.halo_I[s];
+        hoff[s] = huse[s] ? ad.halo_off[s] : dummy;
+        hlds[s] = ad.halo_lds[s];
     }
 
     T acc[PY][PX][NACC];

@@ -50,10 +50,12 @@ __device__ __forceinline__ void adj3d_march_ordered(const March3dArgs &a, int ti
     T *__restrict__ ug = static_cast<T *>(a.out0);
     T *__restrict__ upg = static_cast<T *>(a.out1);
 
-    const uint32_t dummy = (uint32_t)((size_t)y0 * nx + x0) * sizeof(T);   // always inside the grid
-
-    // owned cells (x, y0 + ty*PY + p) and, per cell, which of its sources lie in I:
-    // bit R+d of xbits: x+d in I_x;  bit R+d of ybits[p]: y_p+d in I_y
+    // owned cells (x, y0 + ty*PY + p) and halo slots (tile3d.hpp; halo slots are loaded wherever the
+    // cell lies in the grid, their use is decided per term); per owned cell, which of its sources
+    // lie in I: bit R+d of xbits: x+d in I_x;  bit R+d of ybits[p]: y_p+d in I_y
+    TileAddr<1, PY, HS, GUARD> ad;
+    ad.init(tx, ty, x0, y0, nx, ny, R, R, LX, 0 /* cell (0,0) is a corner nobody reads */, (uint32_t)sizeof(T),
+            [&](int s, int &lx, int &ly) { return G::halo_cell(tid, s, lx, ly); });
     const int x = x0 + tx;
     uint32_t ooff[PY], ybits[PY], xbits = 0;
     bool ostore[PY];
@@ -63,28 +65,19 @@ __device__ __forceinline__ void adj3d_march_ordered(const March3dArgs &a, int ti
 #pragma unroll
     for (int p = 0; p < PY; ++p) {
         const int y = y0 + ty * PY + p;
-        ostore[p] = GUARD ? (x < nx && y < ny) : true;
-        ooff[p] = ostore[p] ? (uint32_t)((size_t)y * nx + x) * sizeof(T) : dummy;
+        ostore[p] = ad.own_grid[p];
+        ooff[p] = ad.own_off[p];
         ybits[p] = 0;
 #pragma unroll
         for (int d = -R; d <= R; ++d)
             if (!GUARD || (y + d >= R && y + d < ny - R)) ybits[p] |= 1u << (R + d);
     }
-    auto xin = [&](int d) { return !GUARD || ((xbits >> (R + d)) & 1u); };
-    auto yin = [&](int p, int d) { return !GUARD || ((ybits[p] >> (R + d)) & 1u); };
-
-    // halo slots: loaded only where the cell lies in the grid (its use is decided per term)
     uint32_t hoff[HS];
     int hlds[HS];
 #pragma unroll
-    for (int s = 0; s < HS; ++s) {
-        int lx, ly;
-        const bool slot = G::halo_cell(tid, s, lx, ly);
-        const int gx = x0 - R + lx, gy = y0 - R + ly;
-        const bool ingrid = slot && (!GUARD || (gx >= 0 && gx < nx && gy >= 0 && gy < ny));
-        hoff[s] = ingrid ? (uint32_t)((size_t)gy * nx + gx) * sizeof(T) : dummy;
-        hlds[s] = slot ? ly * LX + lx : 0;          // cell (0,0) is a corner nobody reads
-    }
+    for (int s = 0; s < HS; ++s) { hoff[s] = ad.halo_off[s]; hlds[s] = ad.halo_lds[s]; }
+    auto xin = [&](int d) { return !GUARD || ((xbits >> (R + d)) & 1u); };
+    auto yin = [&](int p, int d) { return !GUARD || ((ybits[p] >> (R + d)) & 1u); };
 
     T acc[PY][NACC];
 #pragma unroll

@@ -45,34 +45,24 @@ __global__ __launch_bounds__(BX *BY) void primal_wave3d_kernel(March3dArgs a)
     const T *__restrict__ pg = static_cast<const T *>(a.in1);
     const T *__restrict__ cg = static_cast<const T *>(a.in2);
     T *__restrict__ rg = static_cast<T *>(a.out0);
-    const uint32_t dummy = (uint32_t)((size_t)y0 * nx + x0) * sizeof(T);
-
-    // owned cells: x = x0 + tx*PX + e, y = y0 + ty*PY + p (nx is a multiple of PX)
+    // owned cells x = x0 + tx*PX + e, y = y0 + ty*PY + p and halo slots (tile3d.hpp): r is written on I,
+    // u is read wherever it lies in the grid
+    TileAddr<PX, PY, HS, true> ad;
+    ad.init(tx, ty, x0, y0, nx, ny, R, R, LX, 0 /* cell (0,0) is a corner nobody reads */, (uint32_t)sizeof(T),
+            [&](int s, int &lx, int &ly) { return G::halo_cell(tid, s, lx, ly); });
     uint32_t ooff[PY];
     bool ostore[PY][PX], oall[PY];
-    const int x = x0 + tx * PX;
 #pragma unroll
     for (int p = 0; p < PY; ++p) {
-        const int y = y0 + ty * PY + p;
         oall[p] = true;
 #pragma unroll
-        for (int e = 0; e < PX; ++e) {
-            ostore[p][e] = x + e >= R && x + e < nx - R && y >= R && y < ny - R;
-            oall[p] = oall[p] && ostore[p][e];
-        }
-        ooff[p] = (x < nx && y < ny) ? (uint32_t)((size_t)y * nx + x) * sizeof(T) : dummy;
+        for (int e = 0; e < PX; ++e) { ostore[p][e] = ad.own_I[p][e]; oall[p] = oall[p] && ostore[p][e]; }
+        ooff[p] = ad.own_off[p];
     }
     uint32_t hoff[HS];
     int hlds[HS];
 #pragma unroll
-    for (int s = 0; s < HS; ++s) {
-        int lx, ly;
-        const bool slot = G::halo_cell(tid, s, lx, ly);
-        const int gx = x0 - R + lx, gy = y0 - R + ly;
-        const bool ingrid = slot && gx >= 0 && gx < nx && gy >= 0 && gy < ny;
-        hoff[s] = ingrid ? (uint32_t)((size_t)gy * nx + gx) * sizeof(T) : dummy;
-        hlds[s] = slot ? ly * LX + lx : 0;          // cell (0,0) is a corner nobody reads
-    }
+    for (int s = 0; s < HS; ++s) { hoff[s] = ad.halo_off[s]; hlds[s] = ad.halo_lds[s]; }
 
     T acc[PY][PX][NACC];
 #pragma unroll
