@@ -58,3 +58,23 @@ def test_results_do_not_depend_on_the_check(sadj):
         out.append((to_host(ub), to_host(up)))
     sadj.set_option("check.pointers", 0)
     assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 255, 256, 257, 1024, 4099, 1 << 20, (1 << 20) + 3])
+@pytest.mark.parametrize("shape", [0, 1])
+def test_stream_probe_computes_out_plus_a_times_b(n, dtype, shape):
+    """The streaming yardstick of the benchmark is a kernel like any other: out[i] += a[i]*b[i],
+    both launch shapes, sizes around the vector width and the workgroup's piece, ragged tails."""
+    import torch
+    import paper_1907_02818_amd as sadj
+    from parity import to_gpu, to_host
+    sadj.load()
+    rng = np.random.default_rng(n)
+    a, b, o = (rng.uniform(-1, 1, n).astype(dtype) for _ in range(3))
+    og = to_gpu(o)
+    sadj.sadj_stream_probe(shape, to_gpu(a), to_gpu(b), og)
+    torch.cuda.synchronize()
+    want = o.astype(np.float64) + a.astype(np.float64) * b.astype(np.float64)
+    tol = 1e-15 if dtype == np.float64 else 1e-6
+    assert np.max(np.abs(to_host(og) - want)) <= tol * 3.0
