@@ -355,6 +355,20 @@ def main():
         o["note"] = ("fraction is against the step-by-step compulsory bytes (24 B/pt/step); the fused passes themselves move "
                      "(16 + 8*5)/5 = 11.2 B/pt/step plus 6.7 % recomputed window overlap")
 
+    def wave_steps_leg():
+        # reverse sweep of a time loop of 7-point wave steps, 25 steps per call: one kernel per step, then
+        # with pairs of steps fused (step 0 alone, then 12 pairs); both against the step-by-step bytes
+        ks = 25
+        per_step_bytes = 16 * I1 + 24 * N
+        work = get("work", lambda: torch.empty_like(c))
+        add("wave3d_r1_f64_adjoint_steps_per_step", lambda: sadj.sadj_adjoint_wave3d_steps(1, ks, c, rb, ub, upb()),
+            N * ks, ks * per_step_bytes, "f64", per=ks)
+        o = add("wave3d_r1_f64_adjoint_steps_fused_per_step",
+                lambda: sadj.sadj_adjoint_wave3d_steps_fused(1, ks, c, rb, ub, upb(), work), N * ks, ks * per_step_bytes, "f64",
+                per=ks)
+        o["note"] = ("fraction is against the step-by-step compulsory bytes (40 B/pt/step); a fused pair of steps itself "
+                     "moves 40 B/pt (a, b, c read, two results written)")
+
     def functor_leg():
         sadj.set_option("stencil1d.functor", 1)      # same stencil through the generic functor kernel
         add("burgers1d_f64_adjoint_functor", burg_adj, nb, 32 * nb, "f64")
@@ -396,8 +410,12 @@ def main():
     if args.all or args.only in ("burgers1d_f64_adjoint_steps_per_step", "burgers1d_f64_adjoint_steps_fused_per_step"):
         table["burgers1d_f64_adjoint_steps_per_step"] = burgers_steps_leg
         table["burgers1d_f64_adjoint_steps_fused_per_step"] = burgers_steps_leg
+    if args.all or args.only in ("wave3d_r1_f64_adjoint_steps_per_step", "wave3d_r1_f64_adjoint_steps_fused_per_step"):
+        table["wave3d_r1_f64_adjoint_steps_per_step"] = wave_steps_leg
+        table["wave3d_r1_f64_adjoint_steps_fused_per_step"] = wave_steps_leg
     if args.all:
         del table["burgers1d_f64_adjoint_steps_fused_per_step"]
+        del table["wave3d_r1_f64_adjoint_steps_fused_per_step"]
         table["burgers1d_f64_adjoint_functor"] = functor_leg
         table["wave1d_f64_adjoint_n4096_in_hip_graph_per_call"] = graph_leg
 

@@ -147,6 +147,38 @@ sadj_status sadj_adjoint_wave3d_steps(sadj_dtype dtype, int radius, long nx, lon
                                       long nsteps, const void *c,
                                       void *lam0, void *lam1, void *lam2, void *stream);
 
+/* The same reverse sweep with a fourth array to work in, so that two steps can share one pass
+ * over the data.  Writing a = lam^{k+1}, b = lam^k and m for the indicator of I, one reverse step
+ * is a' = b + 2 a m + S(c a m), b' = -a m (S: the gather of sadj_adjoint_wave3d without its
+ * centre term 2 r_bar); two steps are a'' = -a m + 2 a' m + S(c a' m), b'' = -a' m, and a' need
+ * not reach memory: a, b and c are read once and a'', b'' written once per two steps (40 bytes
+ * per cell in fp64 instead of 80).  a'' and b'' cannot be written over a or b, because other
+ * workgroups still read their halo cells; hence the fourth array.
+ *   Arguments, entry and exit state of lam0, lam1, lam2 and errors are those of
+ * sadj_adjoint_wave3d_steps; `work` is a device array of the same size and dtype, not overlapping
+ * the others (NULL -> SADJ_ERR_NULL), whose contents on entry are ignored and on exit undefined,
+ * as are those of lam[(nsteps+2)%3].  Step 0 accumulates into lam2 and runs alone; from then on
+ * pairs of steps are fused, and the last few launches are chosen such that the results land in
+ * the documented buffers (at most three single steps after the first; sadj_describe_wave3d_sweep
+ * shows the choice).  Fused pairs exist for radius 1 where nx is a multiple of 16 bytes' worth
+ * of elements and all five arrays are 16-byte aligned; otherwise, with nsteps < 3, or with
+ * option "wave3d.fuse" 1, the call is sadj_adjoint_wave3d_steps and `work` is not touched.
+ * Fused and single steps add the same terms in a different order: results agree to rounding,
+ * not bit for bit.
+ */
+sadj_status sadj_adjoint_wave3d_steps_fused(sadj_dtype dtype, int radius, long nx, long ny, long nz,
+                                            long nsteps, const void *c,
+                                            void *lam0, void *lam1, void *lam2, void *work, void *stream);
+
+/* Diagnostic (host only, no device access): the launches of sadj_adjoint_wave3d_steps_fused
+ * after step 0 when pairs can be fused.  Buffers are numbered 0..2 = lam0..lam2, 3 = work.
+ * *body_pairs fused pairs alternate (a, b) = (1, 2) -> results in (0, 3) -> results in (1, 2)
+ * ...; then *tail_len launches follow, five ints each in `tail` (room for 12 launches):
+ * fused (1 or 0), a, b, and the output buffers (fused: a'', b''; single: the buffer that
+ * receives -a m, then -1).  *body_pairs = -1: single steps over lam0..lam2 only (nsteps < 3).
+ */
+sadj_status sadj_describe_wave3d_sweep(long nsteps, long *body_pairs, int *tail_len, int *tail);
+
 /* ---- dense 3^d box stencils with arbitrary weights --------------------------------------
  * Primal:   r[i] = c[i] * sum_{o in {-1,0,1}^ndim} w[o] u[i+o]              for i in I = prod [1, n_d-2]
  * Adjoint:  u_bar[j] += sum_o w[o] * c[j-o] r_bar[j-o] [j-o in I]           for all j
@@ -339,6 +371,8 @@ sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, lon
  *                    assigned steps in one pass over the data (lam read and written once per
  *                    five states read, instead of once per state) where all arrays are 16-byte
  *                    aligned; 1: one kernel per step.  Same result bit for bit.
+ *   "wave3d.fuse"    0 (default): sadj_adjoint_wave3d_steps_fused fuses pairs of steps where it can;
+ *                    1: it runs single steps only.
  *   "wave3d.order"   order in which sadj_adjoint_wave3d adds the terms of one u_bar[j]
  *                    (Section 3.5: a gather can respect an order the user chooses and
  *                    stay parallel).  0 (default): the kernel's own fixed order, fastest.

@@ -22,6 +22,7 @@ __all__ = [
     "sadj_adjoint_wave3d_atomic_scatter", "sadj_describe_wave3d_plan", "sadj_check_array",
     "sadj_stream_probe", "sadj_primal_burgers1d_ckpt", "sadj_adjoint_burgers1d_ckpt",
     "sadj_adjoint_burgers1d_ckpt_static", "sadj_static_scratch_bytes",
+    "sadj_adjoint_wave3d_steps_fused", "sadj_describe_wave3d_sweep",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -85,6 +86,8 @@ def load() -> ctypes.CDLL:
     lib.sadj_primal_burgers1d_ckpt.argtypes = [I, L, L, L, D, D, P, P, P, P]
     lib.sadj_adjoint_burgers1d_ckpt.argtypes = [I, L, L, L, D, D, P, P, ctypes.c_size_t, P, P, P]
     lib.sadj_adjoint_burgers1d_ckpt_static.argtypes = [I, L, L, L, D, D, P, P, P, P]
+    lib.sadj_adjoint_wave3d_steps_fused.argtypes = [I, I, L, L, L, L, P, P, P, P, P, P]
+    lib.sadj_describe_wave3d_sweep.argtypes = [L, ctypes.POINTER(L), ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
     lib.sadj_static_scratch_bytes.argtypes = []
     lib.sadj_static_scratch_bytes.restype = ctypes.c_size_t
     for name in ("sadj_set_option", "sadj_get_option", "sadj_primal_wave1d", "sadj_adjoint_wave1d",
@@ -94,7 +97,8 @@ def load() -> ctypes.CDLL:
                  "sadj_primal_star3d", "sadj_adjoint_star3d",
                  "sadj_primal_burgers1d_steps", "sadj_adjoint_burgers1d_steps", "sadj_check_array",
                  "sadj_stream_probe", "sadj_primal_burgers1d_ckpt", "sadj_adjoint_burgers1d_ckpt",
-                 "sadj_adjoint_burgers1d_ckpt_static"):
+                 "sadj_adjoint_burgers1d_ckpt_static", "sadj_adjoint_wave3d_steps_fused",
+                 "sadj_describe_wave3d_sweep"):
         getattr(lib, name).restype = I
     _lib = lib
     return lib
@@ -218,6 +222,21 @@ def sadj_adjoint_wave3d_atomic_scatter(radius: int, c, r_bar, u_bar) -> None:
 def sadj_adjoint_wave3d_steps(radius: int, nsteps: int, c, lam0, lam1, lam2) -> None:
     code, (nz, ny, nx), p, s = _marshal([c, lam0, lam1, lam2], 3)
     _check(load().sadj_adjoint_wave3d_steps(code, int(radius), nx, ny, nz, int(nsteps), *p, s))
+
+
+def sadj_adjoint_wave3d_steps_fused(radius: int, nsteps: int, c, lam0, lam1, lam2, work) -> None:
+    code, (nz, ny, nx), p, s = _marshal([c, lam0, lam1, lam2, work], 3)
+    _check(load().sadj_adjoint_wave3d_steps_fused(code, int(radius), nx, ny, nz, int(nsteps), *p, s))
+
+
+def sadj_describe_wave3d_sweep(nsteps: int):
+    """(body_pairs, [(pair, a, b, o0, o1), ...]) of the launches after step 0; body_pairs = -1: single
+    steps over the caller's three buffers only."""
+    body = ctypes.c_long(0)
+    n = ctypes.c_int(0)
+    tail = (ctypes.c_int * 60)()
+    _check(load().sadj_describe_wave3d_sweep(int(nsteps), ctypes.byref(body), ctypes.byref(n), tail))
+    return body.value, [tuple(tail[5 * i:5 * i + 5]) for i in range(n.value)]
 
 
 def _box(fn_name, weights, tensors):

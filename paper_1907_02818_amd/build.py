@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsadj.so")
-SOURCES = ["api.hip", "wave3d_adjoint.hip", "wave3d_ordered.hip", "wave3d_scatter_atomic.hip", "wave3d_primal.hip", "wave2d.hip", "stencil1d.hip", "functor1d.hip", "functor_star.hip", "box.hip", "star3d.hip", "probe.hip"]
+SOURCES = ["api.hip", "wave3d_adjoint.hip", "wave3d_ordered.hip", "wave3d_scatter_atomic.hip", "wave3d_primal.hip", "wave2d.hip", "stencil1d.hip", "functor1d.hip", "functor_star.hip", "box.hip", "star3d.hip", "probe.hip", "wave3d_pair.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -10,7 +10,7 @@
 
 namespace {
 
-std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0}, g_variant2d{0}, g_remainder{0}, g_order{0}, g_functor1d{0}, g_functor_star{0}, g_burgers_fuse{0}, g_xcdmap{0}, g_band{0}, g_ldspad{0}, g_split{0};
+std::atomic<long> g_zchunk{0}, g_variant{0}, g_ychunk2d{0}, g_variant2d{0}, g_remainder{0}, g_order{0}, g_functor1d{0}, g_functor_star{0}, g_burgers_fuse{0}, g_wave_fuse{0}, g_xcdmap{0}, g_band{0}, g_ldspad{0}, g_split{0};
 
 // Options are set one at a time; a call takes one consistent snapshot of all of them under
 // the same lock the setters hold, so it never sees a combination that was not in force at
@@ -181,6 +181,79 @@ sadj_status burgers_ckpt_reverse(sadj_dtype dtype, long n, long nsteps, long eve
     return SADJ_OK;
 }
 
+// Order of launches of a reverse sweep of wave steps that may use a fourth array.
+// Buffers 0..2 are the caller's lam arrays, 3 is the work array.  A state is the pair (A, B) of
+// buffers that hold lam^{k+1} and lam^k.  A single step updates B in place and assigns -A m to
+// a buffer F outside {A, B}: (A, B) -> (B, F).  A fused pair of steps writes both results to the
+// two buffers outside {A, B}: (A, B) -> (F, G).  After the first step (which accumulates into
+// lam2 and is always single) the state is (1, 2); the sweep must end in (n%3, (n+1)%3).  The
+// body alternates pairs (1,2) -> (0,3) -> (1,2) ...; the last few steps are chosen by exhaustive
+// dynamic programming so that the end state is met with as many pairs as possible.
+struct WaveStepLaunch { int pair, a, b, o0, o1; };   // single: o0 = F;  pair: o0 <- a'', o1 <- b''
+
+constexpr int kTailMax = 12;
+
+struct WaveSweepPlan {
+    bool plain = true;                 // single steps rotating the caller's three buffers, work unused
+    long body_pairs = 0;               // else: pairs alternating (1,2) -> (0,3) -> (1,2) ..., then the tail
+    int tail_len = 0;
+    WaveStepLaunch tail[kTailMax];
+};
+
+inline int state_id(int a, int b) { return a * 4 + b; }
+
+// Launches for steps 1 .. nsteps-1 (step 0 is not part of the plan).
+WaveSweepPlan plan_wave_sweep(long nsteps)
+{
+    WaveSweepPlan plan;
+    const long m = nsteps - 1;
+    if (m < 2) return plan;
+    const int ta = (int)(nsteps % 3), tb = (int)((nsteps + 1) % 3);
+    const int tmax = (int)(m < kTailMax ? m : kTailMax);
+    // best[t][state]: most pairs on a way from state to the target in exactly t steps, -1 if none
+    int best[kTailMax + 1][16], choice[kTailMax + 1][16][3];
+    for (int t = 0; t <= tmax; ++t)
+        for (int s = 0; s < 16; ++s) best[t][s] = -1;
+    best[0][state_id(ta, tb)] = 0;
+    for (int t = 1; t <= tmax; ++t)
+        for (int a = 0; a < 4; ++a)
+            for (int b = 0; b < 4; ++b) {
+                if (a == b) continue;
+                int fr[2], nf = 0;
+                for (int f = 0; f < 4; ++f)
+                    if (f != a && f != b) fr[nf++] = f;
+                int &bst = best[t][state_id(a, b)];
+                int *ch = choice[t][state_id(a, b)];
+                for (int i = 0; i < 2; ++i) {
+                    const int v = best[t - 1][state_id(b, fr[i])];
+                    if (v >= 0 && v > bst) { bst = v; ch[0] = 0; ch[1] = fr[i]; ch[2] = -1; }
+                    if (t >= 2) {
+                        const int w = best[t - 2][state_id(fr[i], fr[1 - i])];
+                        if (w >= 0 && w + 1 > bst) { bst = w + 1; ch[0] = 1; ch[1] = fr[i]; ch[2] = fr[1 - i]; }
+                    }
+                }
+            }
+    auto body_state = [](long pairs, int &a, int &b) { if (pairs % 2 == 0) { a = 1; b = 2; } else { a = 0; b = 3; } };
+    long q = m / 2;
+    int t = 0, a = 1, b = 2;
+    bool found = false;
+    for (; q >= 0 && m - 2 * q <= tmax; --q) {
+        t = (int)(m - 2 * q);
+        body_state(q, a, b);
+        if (best[t][state_id(a, b)] >= 0) { found = true; break; }
+    }
+    if (!found) return plan;           // plain stays set: single steps over three buffers
+    plan.plain = false;
+    plan.body_pairs = q;
+    while (t > 0) {
+        const int *ch = choice[t][state_id(a, b)];
+        WaveStepLaunch &l = plan.tail[plan.tail_len++];
+        if (ch[0] == 0) { l = {0, a, b, ch[1], -1}; const int nb = ch[1]; a = b; b = nb; t -= 1; }
+        else            { l = {1, a, b, ch[1], ch[2]}; a = ch[1]; b = ch[2]; t -= 2; }
+    }
+    return plan;
+}
+
 // Scratch memory of the entry point that must not allocate: a fixed array in device memory,
 // one copy per GPU that loads the library, held until the process ends.  The array's name is
 // a host-side handle only; the device address of the current GPU's copy is looked up once per
@@ -330,6 +403,11 @@ sadj_status sadj_set_option(const char *name, long value)
         g_burgers_fuse = value;
         return SADJ_OK;
     }
+    if (!std::strcmp(name, "wave3d.fuse")) {
+        if (value < 0 || value > 1) return SADJ_ERR_UNSUPPORTED;
+        g_wave_fuse = value;
+        return SADJ_OK;
+    }
 
     return SADJ_ERR_UNSUPPORTED;
 }
@@ -351,6 +429,7 @@ sadj_status sadj_get_option(const char *name, long *value)
     if (!std::strcmp(name, "stencil1d.functor")) { *value = g_functor1d; return SADJ_OK; }
     if (!std::strcmp(name, "star3d.functor")) { *value = g_functor_star; return SADJ_OK; }
     if (!std::strcmp(name, "burgers1d.fuse")) { *value = g_burgers_fuse; return SADJ_OK; }
+    if (!std::strcmp(name, "wave3d.fuse")) { *value = g_wave_fuse; return SADJ_OK; }
     return SADJ_ERR_UNSUPPORTED;
 }
 
@@ -471,8 +550,8 @@ sadj_status sadj_adjoint_wave3d_atomic_scatter(sadj_dtype dtype, int radius, lon
 }
 
 // Reverse sweep of a time loop of wave steps.
-sadj_status sadj_adjoint_wave3d_steps(sadj_dtype dtype, int radius, long nx, long ny, long nz, long nsteps,
-                                      const void *c, void *lam0, void *lam1, void *lam2, void *stream)
+static sadj_status wave_steps_args(sadj_dtype dtype, int radius, long nx, long ny, long nz, long nsteps, const void *c,
+                                   void *lam0, void *lam1, void *lam2, void *work)
 {
     if (radius < 1 || radius > 4) return SADJ_ERR_UNSUPPORTED;
     if (!dtype_ok(dtype)) return SADJ_ERR_UNSUPPORTED;
@@ -482,20 +561,81 @@ sadj_status sadj_adjoint_wave3d_steps(sadj_dtype dtype, int radius, long nx, lon
     if (s != SADJ_OK) return s;
     const size_t bytes = (size_t)nx * ny * nz * elem(dtype);
     const Span in[1] = {{c, bytes}};
-    const Span out[3] = {{lam0, bytes}, {lam1, bytes}, {lam2, bytes}};
-    if (sadj_status al = check_arrays(in, out); al != SADJ_OK) return al;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int f64 = dtype == SADJ_F64;
-    void *lam[3] = {lam0, lam1, lam2};
-    clear_stale_hip_error();
-    sadj::LaunchOptions opt = current_options();
-    opt.remainder = 0;   // the strategy variants exist for the single-step call only
-    for (long k = 0; k < nsteps; ++k) {
+    const Span out[4] = {{lam0, bytes}, {lam1, bytes}, {lam2, bytes}, {work, work ? bytes : 0}};
+    return check_arrays(in, out);
+}
+
+// Single steps k0 .. nsteps-1 rotating three buffers.
+static sadj_status wave_steps_plain(int f64, int radius, long nx, long ny, long nz, long k0, long nsteps, const void *c,
+                                    void *const (&lam)[3], const sadj::LaunchOptions &opt, hipStream_t st)
+{
+    for (long k = k0; k < nsteps; ++k) {
         void *a = lam[k % 3], *b = lam[(k + 1) % 3], *p = lam[(k + 2) % 3];
         // the buffer that receives -a was the r_bar of the previous step: it is dead and is assigned
         hipError_t e = sadj::launch_adjoint_wave3d(f64, radius, (int)nx, (int)ny, (int)nz, c, a, b, p, k > 0 ? 1 : 0,
                                                    opt, st);
         if (e != hipSuccess) return from_hip(e);
+    }
+    return SADJ_OK;
+}
+
+sadj_status sadj_adjoint_wave3d_steps(sadj_dtype dtype, int radius, long nx, long ny, long nz, long nsteps,
+                                      const void *c, void *lam0, void *lam1, void *lam2, void *stream)
+{
+    if (sadj_status s = wave_steps_args(dtype, radius, nx, ny, nz, nsteps, c, lam0, lam1, lam2, nullptr); s != SADJ_OK) return s;
+    void *const lam[3] = {lam0, lam1, lam2};
+    clear_stale_hip_error();
+    sadj::LaunchOptions opt = current_options();
+    opt.remainder = 0;   // the strategy variants exist for the single-step call only
+    return wave_steps_plain(dtype == SADJ_F64, radius, nx, ny, nz, 0, nsteps, c, lam, opt, static_cast<hipStream_t>(stream));
+}
+
+// The same sweep with a fourth array to work in: pairs of steps run fused where the kernel exists.
+sadj_status sadj_adjoint_wave3d_steps_fused(sadj_dtype dtype, int radius, long nx, long ny, long nz, long nsteps,
+                                            const void *c, void *lam0, void *lam1, void *lam2, void *work, void *stream)
+{
+    if (!work) return SADJ_ERR_NULL;
+    if (sadj_status s = wave_steps_args(dtype, radius, nx, ny, nz, nsteps, c, lam0, lam1, lam2, work); s != SADJ_OK) return s;
+    void *const lam[3] = {lam0, lam1, lam2};
+    void *const buf[4] = {lam0, lam1, lam2, work};
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int f64 = dtype == SADJ_F64;
+    clear_stale_hip_error();
+    sadj::LaunchOptions opt = current_options();
+    opt.remainder = 0;
+    const bool fusable = radius == 1 && g_wave_fuse.load() == 0 &&
+                         sadj::adjoint_wave3d_pair_supported(f64, (int)nx, c, lam0, lam1, lam2, work);
+    const WaveSweepPlan plan = fusable ? plan_wave_sweep(nsteps) : WaveSweepPlan{};
+    if (plan.plain) return wave_steps_plain(f64, radius, nx, ny, nz, 0, nsteps, c, lam, opt, st);
+    // step 0 accumulates into lam2, which may hold the objective's own contribution
+    if (sadj_status s = wave_steps_plain(f64, radius, nx, ny, nz, 0, 1, c, lam, opt, st); s != SADJ_OK) return s;
+    auto run = [&](const WaveStepLaunch &l) {
+        return l.pair ? sadj::launch_adjoint_wave3d_pair(f64, (int)nx, (int)ny, (int)nz, c, buf[l.a], buf[l.b], buf[l.o0],
+                                                         buf[l.o1], opt, st)
+                      : sadj::launch_adjoint_wave3d(f64, radius, (int)nx, (int)ny, (int)nz, c, buf[l.a], buf[l.b], buf[l.o0], 1,
+                                                    opt, st);
+    };
+    for (long i = 0; i < plan.body_pairs; ++i) {
+        const WaveStepLaunch l = i % 2 == 0 ? WaveStepLaunch{1, 1, 2, 0, 3} : WaveStepLaunch{1, 0, 3, 1, 2};
+        if (hipError_t e = run(l); e != hipSuccess) return from_hip(e);
+    }
+    for (int i = 0; i < plan.tail_len; ++i)
+        if (hipError_t e = run(plan.tail[i]); e != hipSuccess) return from_hip(e);
+    return SADJ_OK;
+}
+
+// Diagnostic: the launches sadj_adjoint_wave3d_steps_fused makes after step 0 when pairs can be fused.
+sadj_status sadj_describe_wave3d_sweep(long nsteps, long *body_pairs, int *tail_len, int *tail /* 5 ints per launch, 12 launches */)
+{
+    if (!body_pairs || !tail_len || !tail) return SADJ_ERR_NULL;
+    if (nsteps < 0) return SADJ_ERR_SIZE;
+    const WaveSweepPlan plan = plan_wave_sweep(nsteps);
+    *body_pairs = plan.plain ? -1 : plan.body_pairs;
+    *tail_len = plan.tail_len;
+    for (int i = 0; i < plan.tail_len; ++i) {
+        const WaveStepLaunch &l = plan.tail[i];
+        const int v[5] = {l.pair, l.a, l.b, l.o0, l.o1};
+        for (int k = 0; k < 5; ++k) tail[5 * i + k] = v[k];
     }
     return SADJ_OK;
 }

@@ -26,6 +26,14 @@ hipError_t launch_adjoint_wave3d_ordered(int is_f64, int radius, int nx, int ny,
 // Contrast baseline: conventional scatter with atomic updates (not the method).
 hipError_t launch_adjoint_wave3d_scatter_atomic(int is_f64, int radius, int nx, int ny, int nz, const void *c,
                                                 const void *r_bar, void *u_bar, hipStream_t stream);
+// Two reverse steps of a time loop of radius-1 wave steps in one pass: with a = lam^{k+1},
+// b = lam^k: out_a = lam^{k-1}, out_b = -(lam^k after the first step) on I, 0 elsewhere.  out_a and
+// out_b must be arrays other than a and b.  hipErrorNotSupported (nothing enqueued) where
+// adjoint_wave3d_pair_supported is false.
+bool adjoint_wave3d_pair_supported(int is_f64, int nx, const void *c, const void *p0, const void *p1, const void *p2,
+                                   const void *p3);
+hipError_t launch_adjoint_wave3d_pair(int is_f64, int nx, int ny, int nz, const void *c, const void *a, const void *b,
+                                      void *out_a, void *out_b, const LaunchOptions &opt, hipStream_t stream);
 hipError_t launch_primal_wave3d(int is_f64, int radius, int nx, int ny, int nz, const void *u,
                                 const void *u_prev, const void *c, void *r,
                                 const LaunchOptions &opt, hipStream_t stream);

@@ -289,3 +289,32 @@ def test_plan_description_follows_the_shape_the_launch_takes():
     assert (info["tile_w"], info["tile_h"]) == (256, 16)
     info, _ = sadj.sadj_describe_wave3d_plan(1, 4, 1001, 1000, 100, with_tiles=False)
     assert (info["tile_w"], info["tile_h"]) == (64, 32)
+
+
+def test_wave_sweep_plan_ends_in_the_documented_buffers():
+    """Host logic of sadj_adjoint_wave3d_steps_fused: whatever mix of fused pairs and single steps
+    the plan holds, every launch writes to buffers it does not read, the steps add up, and the
+    sweep ends with lam^{K+1-n} in buffer n%3 and lam^{K-n} in buffer (n+1)%3."""
+    import paper_1907_02818_amd as lib
+    lib.load()
+    for n in list(range(0, 80)) + [1000, 1001, 1002, 1003, 1004, 1005, 12345678]:
+        body, tail = lib.sadj_describe_wave3d_sweep(n)
+        if n < 3:
+            assert body == -1 and tail == []
+            continue
+        assert body >= 0
+        a, b = (1, 2) if body % 2 == 0 else (0, 3)         # the body alternates (1,2) -> (0,3) -> (1,2)
+        steps = 1 + 2 * body
+        for pair, la, lb, o0, o1 in tail:
+            assert (la, lb) == (a, b)
+            if pair:
+                assert len({la, lb, o0, o1}) == 4
+                a, b = o0, o1
+                steps += 2
+            else:
+                assert o0 not in (la, lb) and 0 <= o0 <= 3
+                a, b = lb, o0
+                steps += 1
+        assert steps == n
+        assert (a, b) == (n % 3, (n + 1) % 3)
+        assert n - 1 - 2 * (body + sum(t[0] for t in tail)) <= 3      # at most three unfused steps after the first
