@@ -355,19 +355,24 @@ def main():
         o["note"] = ("fraction is against the step-by-step compulsory bytes (24 B/pt/step); the fused passes themselves move "
                      "(16 + 8*5)/5 = 11.2 B/pt/step plus 6.7 % recomputed window overlap")
 
+    # reverse sweep of a time loop of 7-point wave steps, 25 steps per call: one kernel per step, or with
+    # pairs of steps fused (step 0 alone, then 12 pairs); both priced at the step-by-step bytes
+    wave_ks = 25
+    wave_step_bytes = 16 * I1 + 24 * N
+
     def wave_steps_leg():
-        # reverse sweep of a time loop of 7-point wave steps, 25 steps per call: one kernel per step, then
-        # with pairs of steps fused (step 0 alone, then 12 pairs); both against the step-by-step bytes
-        ks = 25
-        per_step_bytes = 16 * I1 + 24 * N
+        add("wave3d_r1_f64_adjoint_steps_per_step", lambda: sadj.sadj_adjoint_wave3d_steps(1, wave_ks, c, rb, ub, upb()),
+            N * wave_ks, wave_ks * wave_step_bytes, "f64", per=wave_ks)
+
+    def wave_steps_fused_leg():
         work = get("work", lambda: torch.empty_like(c))
-        add("wave3d_r1_f64_adjoint_steps_per_step", lambda: sadj.sadj_adjoint_wave3d_steps(1, ks, c, rb, ub, upb()),
-            N * ks, ks * per_step_bytes, "f64", per=ks)
         o = add("wave3d_r1_f64_adjoint_steps_fused_per_step",
-                lambda: sadj.sadj_adjoint_wave3d_steps_fused(1, ks, c, rb, ub, upb(), work), N * ks, ks * per_step_bytes, "f64",
-                per=ks)
-        o["note"] = ("fraction is against the step-by-step compulsory bytes (40 B/pt/step); a fused pair of steps itself "
-                     "moves 40 B/pt (a, b, c read, two results written)")
+                lambda: sadj.sadj_adjoint_wave3d_steps_fused(1, wave_ks, c, rb, ub, upb(), work), N * wave_ks,
+                wave_ks * wave_step_bytes, "f64", per=wave_ks)
+        o["kernel_algorithmic_bytes"] = 24 * I1 + 16 * N
+        o["note"] = ("fraction is against the step-by-step compulsory bytes (40 B/pt/step); a call is one single step and 12 "
+                     "launches of the pair kernel, each of which moves kernel_algorithmic_bytes for two steps "
+                     "(a, b, c read on I, two results written)")
 
     def functor_leg():
         sadj.set_option("stencil1d.functor", 1)      # same stencil through the generic functor kernel
@@ -410,12 +415,11 @@ def main():
     if args.all or args.only in ("burgers1d_f64_adjoint_steps_per_step", "burgers1d_f64_adjoint_steps_fused_per_step"):
         table["burgers1d_f64_adjoint_steps_per_step"] = burgers_steps_leg
         table["burgers1d_f64_adjoint_steps_fused_per_step"] = burgers_steps_leg
-    if args.all or args.only in ("wave3d_r1_f64_adjoint_steps_per_step", "wave3d_r1_f64_adjoint_steps_fused_per_step"):
-        table["wave3d_r1_f64_adjoint_steps_per_step"] = wave_steps_leg
-        table["wave3d_r1_f64_adjoint_steps_fused_per_step"] = wave_steps_leg
+    table["wave3d_r1_f64_adjoint_steps_per_step"] = wave_steps_leg
+    table["wave3d_r1_f64_adjoint_steps_fused_per_step"] = wave_steps_fused_leg
+    default_names += ["wave3d_r1_f64_adjoint_steps_per_step", "wave3d_r1_f64_adjoint_steps_fused_per_step"]
     if args.all:
         del table["burgers1d_f64_adjoint_steps_fused_per_step"]
-        del table["wave3d_r1_f64_adjoint_steps_fused_per_step"]
         table["burgers1d_f64_adjoint_functor"] = functor_leg
         table["wave1d_f64_adjoint_n4096_in_hip_graph_per_call"] = graph_leg
 

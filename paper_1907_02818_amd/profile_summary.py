@@ -80,6 +80,8 @@ def _bench_json(path):
 def _workload_figures(js, workload):
     if workload in js.get("others", {}):
         o = js["others"][workload]
+        if "kernel_algorithmic_bytes" in o:          # a call launches several kernels: bytes of the dominant kernel's launch
+            return int(o["kernel_algorithmic_bytes"]), None, o.get("settle_launches")
         return int(o["algorithmic_bytes"]), o["kernel_ms_mean"], o.get("settle_launches")
     r = js["roofline"]
     return int(r["algorithmic_bytes"]), r["kernel_ms_mean"], js.get("settle", {}).get("launches")
@@ -121,7 +123,8 @@ def summarise(workload, d):
              "first 25 launches:   avg %.1f us (shader clock still settling after the load step)" % statistics.mean(dur[:25]),
              "the %d timed launches: avg %.1f us, min %.1f us, max %.1f us" % (
                  len(timed), statistics.mean(timed), min(timed), max(timed)),
-             "bench.py's own HIP-event mean for the same launches: %.1f us" % (bench_ms * 1e3),
+             ("bench.py's own HIP-event mean for the same launches: %.1f us" % (bench_ms * 1e3)) if bench_ms is not None else
+             "(a call of this workload launches several kernels; bench.py times calls, this summary the dominant kernel)",
              "algorithmic bytes per launch: %d" % alg,
              "=> achieved %.0f GB/s = %.1f %% of 8000 GB/s (timed launches)" % (
                  alg / statistics.mean(timed) / 1e3, alg / statistics.mean(timed) / 1e3 / 80), ""]
