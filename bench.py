@@ -370,6 +370,8 @@ def main():
                 lambda: sadj.sadj_adjoint_wave3d_steps_fused(1, wave_ks, c, rb, ub, upb(), work), N * wave_ks,
                 wave_ks * wave_step_bytes, "f64", per=wave_ks)
         o["kernel_algorithmic_bytes"] = 24 * I1 + 16 * N
+        if "traffic" in o:                       # the recorded counters are those of one launch of the pair kernel
+            o["kernel_traffic"] = o.pop("traffic")
         o["note"] = ("fraction is against the step-by-step compulsory bytes (40 B/pt/step); a call is one single step and 12 "
                      "launches of the pair kernel, each of which moves kernel_algorithmic_bytes for two steps "
                      "(a, b, c read on I, two results written)")
