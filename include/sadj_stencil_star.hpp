@@ -66,8 +66,12 @@
 namespace sadj {
 namespace star_detail {
 
-template <class T> struct Shape {
-    static constexpr int PX = 16 / (int)sizeof(T), PY = 2, BX = 32, BY = 16;
+// Cells per thread and threads per workgroup.  A 3-D march overlaps the loads of the next plane
+// with the arithmetic of this one inside a workgroup; a 2-D grid has a single plane per tile, so
+// there the tile is half as high, which lets three workgroups share a compute unit and overlap
+// each other instead.
+template <class T, int ND> struct Shape {
+    static constexpr int PX = 16 / (int)sizeof(T), PY = ND == 3 ? 2 : 1, BX = 32, BY = 16;
     static constexpr int TX = BX * PX, TY = BY * PY, NT = BX * BY;
     static constexpr int ULX = TX + 4, ULY = TY + 4, UPLANE = ULX * ULY;     // u: tile + border of 2
     static constexpr int TLX = TX + 2, TLY = TY + 2, TPLANE = TLX * TLY;     // terms: tile + ring of 1
@@ -117,7 +121,7 @@ template <class T, int N> __device__ __forceinline__ void stv(T *p, const Vec<T,
 template <class T, class F, bool ADJ, bool GUARD>
 __device__ __forceinline__ void march(const Args<T, F> &a, int tix, int tiy, int zs, int ze, T *su, T *st)
 {
-    using S = Shape<T>;
+    using S = Shape<T, F::ndim>;
     constexpr int ND = F::ndim, NREAD = 1 + 2 * ND;
     constexpr int PX = S::PX, PY = S::PY, TX = S::TX, TY = S::TY, NT = S::NT;
     constexpr int ULX = S::ULX, TLX = S::TLX, US = S::US, RS = S::RS;
@@ -393,9 +397,9 @@ __device__ __forceinline__ void march(const Args<T, F> &a, int tix, int tiy, int
 }
 
 template <class T, class F, bool ADJ>
-__global__ __launch_bounds__(Shape<T>::NT) void kernel(Args<T, F> a)
+__global__ __launch_bounds__((Shape<T, F::ndim>::NT)) void kernel(Args<T, F> a)
 {
-    using S = Shape<T>;
+    using S = Shape<T, F::ndim>;
     constexpr int NU = F::ndim == 3 ? (ADJ ? 3 : 4) : 1;
     constexpr bool NEED_U = !ADJ || F::df_uses_u;
     __shared__ T su[NEED_U ? NU * S::UPLANE : 1];
@@ -418,7 +422,7 @@ inline bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 
 template <class T, class F, bool ADJ>
 hipError_t launch(Args<T, F> a, hipStream_t stream)
 {
-    using S = Shape<T>;
+    using S = Shape<T, F::ndim>;
     if (a.nx < 3 || a.ny < 3 || (F::ndim == 3 && a.nz < 3)) return hipErrorInvalidValue;
     if ((long)a.nx * a.ny >= (1L << 28) || a.nx % S::PX != 0) return hipErrorInvalidValue;
     if (!aligned16(a.u) || !aligned16(a.p) || !aligned16(a.r_bar) || !aligned16(a.out)) return hipErrorInvalidValue;
