@@ -339,9 +339,12 @@ sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, lon
  *                    cells per lane; 2 = 128 x 32, four cells per lane; 3 = 64 x 32, one cell per
  *                    lane; 5 = rows of 1 KB x 16 rows; 10 / 11 = 256 / 512 cells x 16 rows (radius
  *                    1).  Other values select shape 1.
- *   "wave2d.ychunk"  rows of output per wave along y (default 0 = automatic); a value that would
- *                    need more than 65535 row chunks makes the 2-D calls return SADJ_ERR_UNSUPPORTED.
- * *   "wave2d.variant" load-pipeline depth / workgroup size variant (default 0 = automatic).
+ *   "wave2d.variant" kernel form of the 2-D wave calls: 0 (default) one workgroup per tile of 8 rows,
+ *                    no march; 1 the strip march (a wave marches down y over a strip of columns);
+ *                    2 tiles of 16 rows.
+ *   "wave2d.ychunk"  strip march only: rows of output per wave along y (default 0 = automatic); a
+ *                    value that would need more than 65535 row chunks makes the 2-D calls return
+ *                    SADJ_ERR_UNSUPPORTED.
  *   "wave3d.xcdmap"  how workgroups of the 3-D marching kernels are assigned to x-y tiles:
  *                    0/1 (default) per round of resident workgroups every XCD (chiplet with
  *                    its own L2) owns a contiguous range of tiles, 2 one contiguous range

@@ -349,7 +349,7 @@ sadj_status sadj_set_option(const char *name, long value)
         return SADJ_OK;
     }
     if (!std::strcmp(name, "wave2d.variant")) {
-        if (value < 0 || value > 15) return SADJ_ERR_UNSUPPORTED;
+        if (value < 0 || value > 2) return SADJ_ERR_UNSUPPORTED;
         g_variant2d = value;
         return SADJ_OK;
     }

@@ -17,6 +17,7 @@
 // (the if-guarded remainder variant of Section 3.3.4).
 #include "common.hpp"
 #include "launch.hpp"
+#include "tile3d.hpp"
 
 #include <type_traits>
 
@@ -337,6 +338,172 @@ __global__ __launch_bounds__(64 * WAVES) void primal_wave2d_kernel(Wave2dArgs a)
     else                               primal2d_strip<T, PX, D, true>(a, xs, ys, ye, lane, rm);
 }
 
+
+// ------------------------------------------------------------ tile form of the adjoint
+// One workgroup per tile of TX x TY outputs, no march: q on the tile and the ring around it is
+// staged in LDS once, and the loads of one workgroup overlap the arithmetic of the others that
+// share its compute unit (small tiles, several workgroups per CU).  Every tile re-reads a ring of
+// c and r_bar (found in L2 where the neighbour runs on the same XCD).  Measured a few points
+// slower than the strip march where that is at its best and a little faster where it is not
+// (see launch_adj2d).
+template <class T, int PX, int TY, bool GUARD, bool UPREV>
+__device__ __forceinline__ void adj2d_tile(const Wave2dArgs &a, int tix, int tiy, T *__restrict__ sq)
+{
+    using G = Tile3d<T, 1, 32, TY, 1, PX>;
+    using V = Vec<T, PX>;
+    constexpr int TX = G::TX, LX = G::LX, HS = G::HS;
+    const int tid = threadIdx.x, tx = tid % 32, ty = tid / 32;
+    const int x0 = tix * TX, y0 = tiy * TY;
+    const T *__restrict__ cg = static_cast<const T *>(a.c);
+    const T *__restrict__ rg = static_cast<const T *>(a.r_bar);
+    T *__restrict__ ug = static_cast<T *>(a.u_bar);
+    T *__restrict__ pg = static_cast<T *>(a.u_prev_bar);
+
+    TileAddr<PX, 1, HS, GUARD> ad;
+    ad.init(tx, ty, x0, y0, a.nx, a.ny, 1, 1, LX, 0 /* a corner nobody reads */, (uint32_t)sizeof(T),
+            [&](int s, int &lx, int &ly) { return G::halo_cell(tid, s, lx, ly); });
+    bool any = false;
+#pragma unroll
+    for (int e = 0; e < PX; ++e) any = any || ad.own_I[0][e];
+    const uint32_t ooff = ad.own_off[0], coff = (!GUARD || any) ? ooff : ad.dummy;
+    const V vc = ld_vec_off<T, PX, false>(cg, coff), vr = ld_vec_off<T, PX, false>(rg, coff);
+    T hc[HS], hr[HS];
+#pragma unroll
+    for (int s = 0; s < HS; ++s) {
+        const uint32_t off = ad.halo_I[s] ? ad.halo_off[s] : ad.dummy;
+        hc[s] = ld_off(cg, off);
+        hr[s] = ld_off(rg, off);
+    }
+    const V vu = ld_vec_off<T, PX, true>(ug, ooff);
+    V vp{};
+    if (UPREV) vp = ld_vec_off<T, PX, true>(pg, ooff);
+    T q[PX], rm[PX];
+#pragma unroll
+    for (int e = 0; e < PX; ++e) {
+        const bool in = ad.own_I[0][e];
+        rm[e] = GUARD ? (in ? vr.v[e] : T(0)) : vr.v[e];
+        q[e] = GUARD ? (in ? vc.v[e] * vr.v[e] : T(0)) : vc.v[e] * vr.v[e];
+        sq[(1 + ty) * LX + 1 + tx * PX + e] = q[e];
+    }
+#pragma unroll
+    for (int s = 0; s < HS; ++s) sq[ad.halo_lds[s]] = GUARD ? (ad.halo_I[s] ? hc[s] * hr[s] : T(0)) : hc[s] * hr[s];
+    __syncthreads();
+    V o, op;
+#pragma unroll
+    for (int e = 0; e < PX; ++e) {
+        const T *at = sq + (1 + ty) * LX + 1 + tx * PX + e;
+        const T left = e > 0 ? q[e - 1] : at[-1], right = e < PX - 1 ? q[e + 1] : at[1];
+        const T s = T(2.0 * star_w<1>(0)) * q[e] + T(star_w<1>(1)) * (left + right) + T(star_w<1>(1)) * (at[-LX] + at[LX]);
+        o.v[e] = vu.v[e] + (s + T(2) * rm[e]);
+        op.v[e] = vp.v[e] - rm[e];
+    }
+    if (!GUARD || ad.own_grid[0]) {
+        st_vec_off<T, PX, true>(ug, ooff, o);
+        if (UPREV) st_vec_off<T, PX, true>(pg, ooff, op);
+    }
+}
+
+template <class T, int PX, int TY, bool UPREV>
+__global__ __launch_bounds__(32 * TY) void adj_wave2d_tile_kernel(Wave2dArgs a, int ntx, int total)
+{
+    using G = Tile3d<T, 1, 32, TY, 1, PX>;
+    __shared__ T sq[G::PLANE];
+    const int L = xcd_contiguous_id(blockIdx.x, total);
+    const int tiy = L / ntx, tix = L - tiy * ntx;
+    const int x0 = tix * G::TX, y0 = tiy * TY;
+    const bool core = x0 >= 2 && x0 + G::TX + 2 <= a.nx && y0 >= 2 && y0 + TY + 2 <= a.ny;
+    if (core) adj2d_tile<T, PX, TY, false, UPREV>(a, tix, tiy, sq);
+    else      adj2d_tile<T, PX, TY, true, UPREV>(a, tix, tiy, sq);
+}
+
+template <class T, int PX, int TY>
+static hipError_t launch_adj2d_tile(const Wave2dArgs &a, hipStream_t stream)
+{
+    constexpr int TX = 32 * PX;
+    const long ntx = (a.nx + TX - 1) / TX, nty = (a.ny + TY - 1) / TY;
+    if (ntx * nty > 0x3fffffffL) return hipErrorNotSupported;
+    const int total = (int)(ntx * nty);
+    dim3 grid(total), block(32 * TY);
+    if (a.u_prev_bar) hipLaunchKernelGGL((adj_wave2d_tile_kernel<T, PX, TY, true>), grid, block, 0, stream, a, (int)ntx, total);
+    else              hipLaunchKernelGGL((adj_wave2d_tile_kernel<T, PX, TY, false>), grid, block, 0, stream, a, (int)ntx, total);
+    return hipGetLastError();
+}
+
+
+// Tile form of the primal: u on the tile and its ring staged in LDS, one workgroup per tile.
+template <class T, int PX, int TY, bool GUARD>
+__device__ __forceinline__ void primal2d_tile(const Wave2dArgs &a, int tix, int tiy, T *__restrict__ sq)
+{
+    using G = Tile3d<T, 1, 32, TY, 1, PX>;
+    using V = Vec<T, PX>;
+    constexpr int TX = G::TX, LX = G::LX, HS = G::HS;
+    const int tid = threadIdx.x, tx = tid % 32, ty = tid / 32;
+    const int x0 = tix * TX, y0 = tiy * TY;
+    const T *__restrict__ ug = static_cast<const T *>(a.u);
+    const T *__restrict__ pg = static_cast<const T *>(a.u_prev);
+    const T *__restrict__ cg = static_cast<const T *>(a.c);
+    T *__restrict__ rg = static_cast<T *>(a.r);
+
+    TileAddr<PX, 1, HS, GUARD> ad;
+    ad.init(tx, ty, x0, y0, a.nx, a.ny, 1, 1, LX, 0 /* a corner nobody reads */, (uint32_t)sizeof(T),
+            [&](int s, int &lx, int &ly) { return G::halo_cell(tid, s, lx, ly); });
+    bool any = false, all = true;
+#pragma unroll
+    for (int e = 0; e < PX; ++e) { any = any || ad.own_I[0][e]; all = all && ad.own_I[0][e]; }
+    const uint32_t ooff = ad.own_off[0], coff = (!GUARD || any) ? ooff : ad.dummy;
+    const V vu = ld_vec_off<T, PX, false>(ug, ooff);       // u is read on the whole grid
+    T hu[HS];
+#pragma unroll
+    for (int s = 0; s < HS; ++s) hu[s] = ld_off(ug, ad.halo_off[s]);
+    const V vc = ld_vec_off<T, PX, true>(cg, coff), vp = ld_vec_off<T, PX, true>(pg, coff);
+#pragma unroll
+    for (int e = 0; e < PX; ++e) sq[(1 + ty) * LX + 1 + tx * PX + e] = vu.v[e];
+#pragma unroll
+    for (int s = 0; s < HS; ++s) sq[ad.halo_lds[s]] = hu[s];
+    __syncthreads();
+    if (GUARD && !any) return;
+    V o;
+#pragma unroll
+    for (int e = 0; e < PX; ++e) {
+        const T *at = sq + (1 + ty) * LX + 1 + tx * PX + e;
+        const T left = e > 0 ? vu.v[e - 1] : at[-1], right = e < PX - 1 ? vu.v[e + 1] : at[1];
+        const T lap = T(2.0 * star_w<1>(0)) * vu.v[e] + T(star_w<1>(1)) * (left + right) + T(star_w<1>(1)) * (at[-LX] + at[LX]);
+        o.v[e] = T(2) * vu.v[e] - vp.v[e] + vc.v[e] * lap;
+    }
+    if (!GUARD || all) {
+        st_vec_off<T, PX, true>(rg, ooff, o);
+    } else {                                               // r outside I stays untouched
+        T *rp = reinterpret_cast<T *>(reinterpret_cast<char *>(rg) + ooff);
+#pragma unroll
+        for (int e = 0; e < PX; ++e)
+            if (ad.own_I[0][e]) rp[e] = o.v[e];
+    }
+}
+
+template <class T, int PX, int TY>
+__global__ __launch_bounds__(32 * TY) void primal_wave2d_tile_kernel(Wave2dArgs a, int ntx, int total)
+{
+    using G = Tile3d<T, 1, 32, TY, 1, PX>;
+    __shared__ T sq[G::PLANE];
+    const int L = xcd_contiguous_id(blockIdx.x, total);
+    const int tiy = L / ntx, tix = L - tiy * ntx;
+    const int x0 = tix * G::TX, y0 = tiy * TY;
+    const bool core = x0 >= 1 && x0 + G::TX + 1 <= a.nx && y0 >= 1 && y0 + TY + 1 <= a.ny;
+    if (core) primal2d_tile<T, PX, TY, false>(a, tix, tiy, sq);
+    else      primal2d_tile<T, PX, TY, true>(a, tix, tiy, sq);
+}
+
+template <class T, int PX, int TY>
+static hipError_t launch_pri2d_tile(const Wave2dArgs &a, hipStream_t stream)
+{
+    constexpr int TX = 32 * PX;
+    const long ntx = (a.nx + TX - 1) / TX, nty = (a.ny + TY - 1) / TY;
+    if (ntx * nty > 0x3fffffffL) return hipErrorNotSupported;
+    const int total = (int)(ntx * nty);
+    hipLaunchKernelGGL((primal_wave2d_tile_kernel<T, PX, TY>), dim3(total), dim3(32 * TY), 0, stream, a, (int)ntx, total);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------ launchers
 static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -375,21 +542,30 @@ static hipError_t launch_adj2d_cfg(Wave2dArgs a, const LaunchOptions &opt, hipSt
     return hipGetLastError();
 }
 
+// "wave2d.variant": 0 (automatic) the tile form with 8 rows per tile; 1 the strip march (two rows
+// of loads in flight per wave, eight waves per workgroup; "wave2d.ychunk" applies); 2 the tile
+// form with 16 rows per tile.  Measured fp64 adjoint, % of 8 TB/s, strip march / tiles of 8 rows:
+// 8192^2 72.5 / 76, 9000^2 65 / 72, 10000^2 65 / 73, 7000^2 64.5 / 70-73, 6144^2 61 / 73,
+// 8192 x 9216 66.5 / 73-76, 2048^2 65 / 72, 9001^2 (one cell per lane) 62 / 65; primal the same
+// picture (8192^2 72.8 / 73.4, 7000^2 63.6 / 75.4); tiles of 16 rows within 2 points of 8 rows,
+// tiles of 4 and of 32 rows 1-3 points lower.  Other strip-march shapes that were tried (one or
+// four rows in flight, four or sixteen waves per workgroup) were never better than the one kept.
 template <class T, int PX>
 static hipError_t launch_adj2d(const Wave2dArgs &a, const LaunchOptions &opt, hipStream_t stream)
 {
     switch (opt.variant2d) {
     default:
-    case 0: return launch_adj2d_cfg<T, PX, 2, 8>(a, opt, stream);
-    case 1: return launch_adj2d_cfg<T, PX, 1, 4>(a, opt, stream);
-    case 2: return launch_adj2d_cfg<T, PX, 4, 8>(a, opt, stream);
-    case 3: return launch_adj2d_cfg<T, PX, 2, 16>(a, opt, stream);
+    case 0: return launch_adj2d_tile<T, PX, 8>(a, stream);
+    case 1: return launch_adj2d_cfg<T, PX, 2, 8>(a, opt, stream);
+    case 2: return launch_adj2d_tile<T, PX, 16>(a, stream);
     }
 }
 
 template <class T, int PX>
 static hipError_t launch_pri2d(const Wave2dArgs &a0, const LaunchOptions &opt, hipStream_t stream)
 {
+    if (opt.variant2d == 2) return launch_pri2d_tile<T, PX, 16>(a0, stream);
+    if (opt.variant2d != 1) return launch_pri2d_tile<T, PX, 8>(a0, stream);
     constexpr int WAVES = 8, D = 2;
     Wave2dArgs a = a0;
     constexpr int W = 64 * PX;

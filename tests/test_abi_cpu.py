@@ -265,6 +265,7 @@ def test_gather_kernels_use_no_atomics():
 
 def test_a_row_chunk_option_that_needs_too_many_chunks_is_refused_before_any_launch():
     lib = sadj.load()
+    sadj.set_option("wave2d.variant", 1)          # the strip march is the form that cuts y into chunks
     sadj.set_option("wave2d.ychunk", 1)
     try:
         rc = lib.sadj_adjoint_wave2d(1, 64, 70000, A, B, C_, None, None)
@@ -273,6 +274,7 @@ def test_a_row_chunk_option_that_needs_too_many_chunks_is_refused_before_any_lau
         assert rc == 4
     finally:
         sadj.set_option("wave2d.ychunk", 0)
+        sadj.set_option("wave2d.variant", 0)
 
 
 def test_plan_description_follows_the_shape_the_launch_takes():

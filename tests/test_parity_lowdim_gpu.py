@@ -174,7 +174,7 @@ def test_wave2d_adjoint_and_primal(sadj, shape, dtype):
     assert_close(got[m], want[m], wave_primal_scale(d["u"], d["u_prev"], d["c"], 1)[m], dtype, "wave2d primal %s" % (shape,))
 
 
-@pytest.mark.parametrize("variant,ychunk", [(0, 0), (0, 5), (1, 16), (2, 7), (2, 0), (3, 33)])
+@pytest.mark.parametrize("variant,ychunk", [(0, 0), (1, 0), (1, 5), (1, 16), (1, 33), (2, 0)])
 def test_wave2d_variants(sadj, variant, ychunk):
     shape = (131, 523)
     d = inputs.wave_inputs(shape, 0.01, 0.2, seed=variant + ychunk)
@@ -211,12 +211,18 @@ def test_wave2d_nan_outside_interior_and_reproducible(sadj):
 
 
 def test_wave2d_full_size(sadj):
+    """8192^2, every element, in the default (tile) form and in the strip-march form."""
     d = inputs.config_inputs("wave2d")
-    ub = to_gpu(d["u_bar"])
-    sadj.sadj_adjoint_wave2d(to_gpu(d["c"]), to_gpu(d["r_bar"]), ub)
-    _sync()
     want, _, scale = oracle.wave_adjoint(d["c"], d["r_bar"], d["u_bar"], 1, want_scale=True)
-    assert_close(to_host(ub), want, scale + np.abs(d["u_bar"]), np.float64, "wave2d 8192^2")
+    for variant in (0, 1):
+        sadj.set_option("wave2d.variant", variant)
+        try:
+            ub = to_gpu(d["u_bar"])
+            sadj.sadj_adjoint_wave2d(to_gpu(d["c"]), to_gpu(d["r_bar"]), ub)
+            _sync()
+        finally:
+            sadj.set_option("wave2d.variant", 0)
+        assert_close(to_host(ub), want, scale + np.abs(d["u_bar"]), np.float64, "wave2d 8192^2 variant %d" % variant)
 
 
 # ------------------------------------------------------------------ graph capture
@@ -278,7 +284,7 @@ def test_wave2d_on_drawn_shapes_and_options(sadj, case):
     rng = np.random.default_rng(700 + case)
     dtype = [np.float64, np.float32][int(rng.integers(0, 2))]
     shape = (int(rng.integers(3, 300)), int(rng.integers(3, 1200)))
-    opts = {"wave2d.variant": int(rng.integers(0, 4)), "wave2d.ychunk": int(rng.choice([0, 0, 4, 9, 50]))}
+    opts = {"wave2d.variant": int(rng.integers(0, 3)), "wave2d.ychunk": int(rng.choice([0, 0, 4, 9, 50]))}
     d = inputs.wave_inputs(shape, 0.01, 0.2, seed=case, dtype=dtype, c_mode="iid")
     m = interior_mask(shape, 1)
     try:
