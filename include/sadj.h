@@ -403,8 +403,9 @@ sadj_status sadj_get_option(const char *name, long *value);
  * element touched once -- the streams of a wave adjoint call (c, r_bar, u_bar; Section 4.1's
  * gather listing) without any stencil, halo or reuse.  Its rate is the ceiling this memory
  * system offers to that mix of streams; the benchmark quotes the adjoint kernels against it as
- * well as against the nominal HBM peak.  `shape` selects the launch shape: 0 = 8 bytes per lane,
- * one access per thread; 1 = 16 bytes per lane, four accesses per thread, streaming hints.
+ * well as against the nominal HBM peak.  `shape` selects the launch shape: 0 = 256 threads, 8 bytes
+ * per lane, one access per thread; 1 = 256 threads, 16 bytes per lane, four accesses per thread,
+ * streaming hints; 2 = single-wave workgroups, one 16-byte access per lane, the fastest found.
  * a, b, out: DEVICE arrays of n elements, 16-byte aligned (else SADJ_ERR_UNSUPPORTED), out not
  * overlapping a or b.  n < 1 or n > 2^40 -> SADJ_ERR_SIZE.  Asynchronous on `stream`.
  */

@@ -644,7 +644,7 @@ sadj_status sadj_describe_wave3d_sweep(long nsteps, long *body_pairs, int *tail_
 sadj_status sadj_stream_probe(sadj_dtype dtype, int shape, long n, const void *a, const void *b, void *out,
                               void *stream)
 {
-    if (!dtype_ok(dtype) || shape < 0 || shape > 1) return SADJ_ERR_UNSUPPORTED;
+    if (!dtype_ok(dtype) || shape < 0 || shape > 2) return SADJ_ERR_UNSUPPORTED;
     if (!a || !b || !out) return SADJ_ERR_NULL;
     if (n < 1 || n > (1L << 40)) return SADJ_ERR_SIZE;
     const size_t bytes = (size_t)n * elem(dtype);

@@ -62,10 +62,10 @@ def test_results_do_not_depend_on_the_check(sadj):
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 @pytest.mark.parametrize("n", [1, 2, 3, 5, 255, 256, 257, 1024, 4099, 1 << 20, (1 << 20) + 3])
-@pytest.mark.parametrize("shape", [0, 1])
+@pytest.mark.parametrize("shape", [0, 1, 2])
 def test_stream_probe_computes_out_plus_a_times_b(n, dtype, shape):
     """The streaming yardstick of the benchmark is a kernel like any other: out[i] += a[i]*b[i],
-    both launch shapes, sizes around the vector width and the workgroup's piece, ragged tails."""
+    every launch shape, sizes around the vector width and the workgroup's piece, ragged tails."""
     import torch
     import paper_1907_02818_amd as sadj
     from parity import to_gpu, to_host
