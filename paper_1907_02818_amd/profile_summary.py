@@ -91,9 +91,12 @@ def summarise(workload, d):
     js = _bench_json(os.path.join(d, "stats.json"))
     alg, bench_ms, settle = _workload_figures(js, workload)
     steps, warmup = js["steps"], js["warmup"]
+    if workload in js.get("others", {}):            # bench.py times the further workloads with a quarter of the steps
+        steps, warmup = max(5, steps // 4), max(3, warmup // 4)
+    flag_steps, flag_warmup = js["steps"], js["warmup"]
     only = "--only %s " % workload + ("--size %d " % js["size"] if js.get("size", 512) != 512 else "")
     cmd_stats = ("rocprofv3 --kernel-trace --stats -d DIR/stats -o p --output-format csv -- python3 bench.py "
-                 + only + "--steps %d --warmup %d --no-cpu-baseline" % (steps, warmup))
+                 + only + "--steps %d --warmup %d --no-cpu-baseline" % (flag_steps, flag_warmup))
     cmd_pmc = ("rocprofv3 --pmc %s --kernel-trace -d DIR/%s -o p --output-format csv -- python3 bench.py "
                + only + "--steps 5 --warmup 2 --settle-cap 0 --no-cpu-baseline --copy-probe")
 
@@ -117,8 +120,8 @@ def summarise(workload, d):
              "workgroups %d x %s threads, LDS %s B per workgroup, %s VGPRs" % (
                  int(first["Grid_Size_X"]) // max(1, int(first["Workgroup_Size_X"])), first["Workgroup_Size_X"],
                  first["LDS_Block_Size"], first.get("VGPR_Count", "?")),
-             "launches in the run: %d (settle phase %s, warm-up %d, timed %d; one kernel per call unless noted)" % (
-                 len(dur), settle, warmup, steps),
+             "launches in the run: %d (one untimed first call where the workload is not the headline, settle phase %s, "
+             "warm-up %d, timed %d; one kernel per call unless noted)" % (len(dur), settle, warmup, steps),
              "all launches:        avg %.1f us, min %.1f us, max %.1f us" % (statistics.mean(dur), min(dur), max(dur)),
              "first 25 launches:   avg %.1f us (shader clock still settling after the load step)" % statistics.mean(dur[:25]),
              "the %d timed launches: avg %.1f us, min %.1f us, max %.1f us" % (
