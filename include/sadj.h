@@ -339,7 +339,7 @@ sadj_status sadj_describe_wave3d_plan(sadj_dtype dtype, int radius, long nx, lon
  *                    cells per lane; 2 = 128 x 32, four cells per lane; 3 = 64 x 32, one cell per
  *                    lane; 5 = rows of 1 KB x 16 rows; 10 / 11 = 256 / 512 cells x 16 rows (radius
  *                    1).  Other values select shape 1.
- *   "wave2d.variant" kernel form of the 2-D wave calls: 0 (default) one workgroup per tile of 8 rows,
+ *   "wave2d.variant" kernel form of the 2-D wave and 2-D box calls: 0 (default) one workgroup per tile of 8 rows,
  *                    no march; 1 the strip march (a wave marches down y over a strip of columns);
  *                    2 tiles of 16 rows.
  *   "wave2d.ychunk"  strip march only: rows of output per wave along y (default 0 = automatic); a

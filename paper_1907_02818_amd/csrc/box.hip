@@ -11,8 +11,9 @@
 // to I.  The launcher mirrors the table on the host, so primal and adjoint are the same
 // gather  out[j] <- sum_o W[o] S[j+o]  over a staged field S (u, or q), and share one
 // kernel body per dimension:
-//   2-D: a wave owns a strip of columns and marches down y; an arriving row of S feeds
-//        three running sums (output rows y-1, y, y+1); x-neighbours by wave shuffles.
+//   2-D: one workgroup per small tile, S on the tile and its ring staged in LDS once (default);
+//        or (option "wave2d.variant" 1) a wave owns a strip of columns and marches down y, an
+//        arriving row of S feeding three running sums, x-neighbours by wave shuffles.
 //   3-D: a workgroup owns an x-y tile and marches along z; an arriving plane of S is
 //        staged in LDS with a full halo ring (a box reads the corners) and feeds three
 //        running sums per owned cell.
@@ -219,6 +220,106 @@ struct BoxTile {
         return h < NH;
     }
 };
+
+// Tile form of the 2-D kernels (the default; see wave2d.hip for the measurements that made it
+// so): one workgroup per tile of TX x TY outputs, no march.  The staged field S (u, or q) on the
+// tile and the full ring around it goes to LDS once; a thread owns PX cells of one row.
+template <class T, int PX, int TY, bool ADJ, bool GUARD>
+__device__ __forceinline__ void box2d_tile(const BoxArgs &a, int tix, int tiy, T *__restrict__ sq)
+{
+    using G = BoxTile<T, 32, TY, 1, PX>;
+    using V = Vec<T, PX>;
+    constexpr int TX = G::TX, LX = G::LX, HS = G::HS;
+    const int tid = threadIdx.x, tx = tid % 32, ty = tid / 32;
+    const int x0 = tix * TX, y0 = tiy * TY;
+    const T *__restrict__ g0 = static_cast<const T *>(a.in0);
+    const T *__restrict__ g1 = static_cast<const T *>(a.in1);
+    T *__restrict__ og = static_cast<T *>(a.out);
+    T wt[3][3];                                     // wt[oy+1][ox+1]
+#pragma unroll
+    for (int j = 0; j < 3; ++j)
+#pragma unroll
+        for (int i = 0; i < 3; ++i) wt[j][i] = (T)a.w[i + 3 * j + 9];
+
+    TileAddr<PX, 1, HS, GUARD> ad;
+    ad.init(tx, ty, x0, y0, a.nx, a.ny, 1, 1, LX, -1, (uint32_t)sizeof(T),
+            [&](int s, int &lx, int &ly) { return G::halo_cell(tid + s * G::NT, lx, ly); });
+    bool any = false, all = true;
+#pragma unroll
+    for (int e = 0; e < PX; ++e) { any = any || ad.own_I[0][e]; all = all && ad.own_I[0][e]; }
+    const uint32_t ooff = ad.own_off[0];
+    // adjoint: c and r_bar are used on I only; primal: u is read on the whole grid, c on I
+    const uint32_t ioff = (!GUARD || any) ? ooff : ad.dummy;
+    const V v0 = ld_vec_off<T, PX, false>(g0, ADJ ? ioff : ooff);
+    const V v1 = ld_vec_off<T, PX, !ADJ>(g1, ioff);
+    T h0[HS], h1[HS];
+#pragma unroll
+    for (int s = 0; s < HS; ++s) {
+        const bool use = ADJ ? ad.halo_I[s] : ad.halo_grid[s];
+        const uint32_t off = use ? ad.halo_off[s] : ad.dummy;
+        h0[s] = ld_off(g0, off);
+        h1[s] = ADJ ? ld_off(g1, off) : T(0);
+    }
+    V vo{};
+    if (ADJ) vo = ld_vec_off<T, PX, true>(og, ooff);
+    T sv[PX];
+#pragma unroll
+    for (int e = 0; e < PX; ++e) {
+        if (ADJ) sv[e] = (!GUARD || ad.own_I[0][e]) ? v0.v[e] * v1.v[e] : T(0);
+        else     sv[e] = v0.v[e];
+        sq[(1 + ty) * LX + 1 + tx * PX + e] = sv[e];
+    }
+#pragma unroll
+    for (int s = 0; s < HS; ++s)
+        if (ad.halo_lds[s] >= 0) sq[ad.halo_lds[s]] = ADJ ? ((!GUARD || ad.halo_I[s]) ? h0[s] * h1[s] : T(0)) : h0[s];
+    __syncthreads();
+    if (!ADJ && GUARD && !any) return;
+    V o;
+#pragma unroll
+    for (int e = 0; e < PX; ++e) {
+        const T *at = sq + (1 + ty) * LX + 1 + tx * PX + e;
+        T s = T(0);
+#pragma unroll
+        for (int j = 0; j < 3; ++j)
+#pragma unroll
+            for (int i = 0; i < 3; ++i) s += wt[j][i] * at[(j - 1) * LX + (i - 1)];
+        o.v[e] = ADJ ? vo.v[e] + s : v1.v[e] * s;
+    }
+    if (ADJ) {
+        if (!GUARD || ad.own_grid[0]) st_vec_off<T, PX, true>(og, ooff, o);
+    } else if (!GUARD || all) {
+        st_vec_off<T, PX, true>(og, ooff, o);
+    } else {                                               // r outside I stays untouched
+        T *rp = reinterpret_cast<T *>(reinterpret_cast<char *>(og) + ooff);
+#pragma unroll
+        for (int e = 0; e < PX; ++e)
+            if (ad.own_I[0][e]) rp[e] = o.v[e];
+    }
+}
+
+template <class T, int PX, int TY, bool ADJ>
+__global__ __launch_bounds__(32 * TY) void box2d_tile_kernel(BoxArgs a, int ntx, int total)
+{
+    using G = BoxTile<T, 32, TY, 1, PX>;
+    __shared__ T sq[G::PLANE];
+    const int L = xcd_contiguous_id(blockIdx.x, total);
+    const int tiy = L / ntx, tix = L - tiy * ntx;
+    const int x0 = tix * G::TX, y0 = tiy * TY;
+    const bool core = x0 >= 2 && x0 + G::TX + 2 <= a.nx && y0 >= 2 && y0 + TY + 2 <= a.ny;
+    if (core) box2d_tile<T, PX, TY, ADJ, false>(a, tix, tiy, sq);
+    else      box2d_tile<T, PX, TY, ADJ, true>(a, tix, tiy, sq);
+}
+
+template <class T, int PX, bool ADJ>
+static hipError_t launch_box2d_tile(const BoxArgs &a, hipStream_t stream)
+{
+    constexpr int TY = 8, TX = 32 * PX;
+    const long ntx = cdiv_i(a.nx, TX), nty = cdiv_i(a.ny, TY);
+    if (ntx * nty > 0x3fffffffL) return hipErrorNotSupported;
+    const int total = (int)(ntx * nty);
+    hipLaunchKernelGGL((box2d_tile_kernel<T, PX, TY, ADJ>), dim3(total), dim3(32 * TY), 0, stream, a, (int)ntx, total);
+    return hipGetLastError();
+}
 
 // A thread owns PX consecutive cells in x (one 16-byte memory instruction where PX > 1; nx is
 // then a multiple of PX, so a vector lies entirely inside or outside the grid) times PY rows.
@@ -450,8 +551,12 @@ static hipError_t launch_box_nd(int is_f64, int ndim, const BoxArgs &a, const La
 {
     if (ndim == 3) return is_f64 ? launch_box3d<double, ADJ>(a, opt, stream) : launch_box3d<float, ADJ>(a, opt, stream);
     const bool al = box_aligned16(a.in0) && box_aligned16(a.in1) && box_aligned16(a.out);
-    if (is_f64) return (al && a.nx % 2 == 0) ? launch_box2d<double, 2, ADJ>(a, stream) : launch_box2d<double, 1, ADJ>(a, stream);
-    return (al && a.nx % 4 == 0) ? launch_box2d<float, 4, ADJ>(a, stream) : launch_box2d<float, 1, ADJ>(a, stream);
+    if (opt.variant2d == 1) {                       // the strip march
+        if (is_f64) return (al && a.nx % 2 == 0) ? launch_box2d<double, 2, ADJ>(a, stream) : launch_box2d<double, 1, ADJ>(a, stream);
+        return (al && a.nx % 4 == 0) ? launch_box2d<float, 4, ADJ>(a, stream) : launch_box2d<float, 1, ADJ>(a, stream);
+    }
+    if (is_f64) return (al && a.nx % 2 == 0) ? launch_box2d_tile<double, 2, ADJ>(a, stream) : launch_box2d_tile<double, 1, ADJ>(a, stream);
+    return (al && a.nx % 4 == 0) ? launch_box2d_tile<float, 4, ADJ>(a, stream) : launch_box2d_tile<float, 1, ADJ>(a, stream);
 }
 
 // w: 27 gather weights indexed (ox+1) + 3(oy+1) + 9(oz+1) (already mirrored for the adjoint)

@@ -50,8 +50,12 @@ def test_box_adjoint_and_primal(sadj, shape, functor, dtype):
     sadj.set_option("stencil1d.functor", functor)
     try:
         _box_case(sadj, shape, dtype, ndim, torch)
+        if ndim == 2:                                   # the strip march as well as the default tile form
+            sadj.set_option("wave2d.variant", 1)
+            _box_case(sadj, shape, dtype, ndim, torch)
     finally:
         sadj.set_option("stencil1d.functor", 0)
+        sadj.set_option("wave2d.variant", 0)
 
 
 def _box_case(sadj, shape, dtype, ndim, torch):
@@ -128,7 +132,9 @@ def test_box_on_drawn_shapes(sadj, case):
     shape = tuple(int(rng.integers(3, hi)) for hi in ((60, 400) if ndim == 2 else (40, 90, 260)))
     zchunk = int(rng.choice([0, 0, 6, 17]))
     sadj.set_option("wave3d.zchunk", zchunk)
+    sadj.set_option("wave2d.variant", int(rng.integers(0, 2)))
     try:
         _box_case(sadj, shape, dtype, ndim, torch)
     finally:
         sadj.set_option("wave3d.zchunk", 0)
+        sadj.set_option("wave2d.variant", 0)
