@@ -225,6 +225,32 @@ def test_wave2d_full_size(sadj):
         assert_close(to_host(ub), want, scale + np.abs(d["u_bar"]), np.float64, "wave2d 8192^2 variant %d" % variant)
 
 
+def test_wave2d_full_size_primal_and_both_adjoint_outputs(sadj):
+    """8192^2 in the default (tile) form: the primal and the adjoint with u_prev_bar, every element."""
+    d = inputs.config_inputs("wave2d")
+    shape = d["c"].shape
+    m = interior_mask(shape, 1)
+    u_prev_bar0 = inputs.uniform(3, "u_prev_bar", shape, -1, 1)
+    ub, upb = to_gpu(d["u_bar"]), to_gpu(u_prev_bar0)
+    sadj.sadj_adjoint_wave2d(to_gpu(d["c"]), to_gpu(d["r_bar"]), ub, upb)
+    _sync()
+    want, wantp, scale = oracle.wave_adjoint(d["c"], d["r_bar"], d["u_bar"], 1, u_prev_bar=u_prev_bar0, want_scale=True)
+    assert_close(to_host(ub), want, scale + np.abs(d["u_bar"]), np.float64, "wave2d 8192^2 with u_prev_bar")
+    assert_close(to_host(upb), wantp, np.abs(u_prev_bar0) + np.abs(d["r_bar"]), np.float64, "wave2d 8192^2 u_prev_bar")
+    assert np.array_equal(to_host(upb)[~m], u_prev_bar0[~m])
+    del ub, upb, want, wantp, scale
+    u = inputs.uniform(4, "u", shape, -1, 1)
+    u_prev = inputs.uniform(5, "u_prev", shape, -1, 1)
+    r0 = inputs.uniform(6, "aux", shape, -1, 1)
+    r = to_gpu(r0)
+    sadj.sadj_primal_wave2d(to_gpu(u), to_gpu(u_prev), to_gpu(d["c"]), r)
+    _sync()
+    got = to_host(r)
+    wantr = oracle.wave_primal(u, u_prev, d["c"], 1, r_init=r0)
+    assert np.array_equal(got[~m], r0[~m])
+    assert_close(got[m], wantr[m], wave_primal_scale(u, u_prev, d["c"], 1)[m], np.float64, "wave2d 8192^2 primal")
+
+
 # ------------------------------------------------------------------ graph capture
 def test_calls_can_be_captured_in_a_hip_graph_and_replayed(sadj):
     """The entry points only enqueue kernels on the given stream (no allocation, no
