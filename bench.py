@@ -170,6 +170,8 @@ def main():
     ap.add_argument("--settle-cap", type=int, default=300,
                     help="upper limit of launches in the settle phase before each timed leg (0 = no settle phase)")
     ap.add_argument("--size", type=int, default=512, help="grid edge of the headline workload")
+    ap.add_argument("--size2d", type=int, default=8192, help="grid edge of the 2-D workloads (views of the 3-D arrays: "
+                    "size2d^2 may not exceed size^3)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed region run one plain device copy of a whole array (the known-size "
                          "reference that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -244,7 +246,10 @@ def main():
     def f32set():
         return get("f32", lambda: (c.float(), rb.float(), ub.float()))
 
-    s2 = (8192, 8192)
+    s2 = (args.size2d, args.size2d)
+    if s2[0] * s2[1] > N or s2[0] < 3:
+        print("bench.py: --size2d %d does not fit the %d^3 arrays" % (args.size2d, n), file=sys.stderr)
+        sys.exit(2)
     nb = 1 << 24
     n1 = 4096
 
@@ -428,7 +433,7 @@ def main():
     # ---------------------------------------------------------------- headline
     out = {"metric": METRIC, "unit": "Gpoints/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
-           "size": n}
+           "size": n, "size2d": args.size2d}
     if args.only is None or args.only == HEADLINE:
         t = timer.time_calls(lambda: sadj.sadj_adjoint_wave3d(R, c, rb, ub), args.steps, args.warmup)
         alg_bytes = wave_adjoint_bytes(shape, R, 8)

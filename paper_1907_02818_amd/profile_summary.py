@@ -94,7 +94,8 @@ def summarise(workload, d):
     if workload in js.get("others", {}):            # bench.py times the further workloads with a quarter of the steps
         steps, warmup = max(5, steps // 4), max(3, warmup // 4)
     flag_steps, flag_warmup = js["steps"], js["warmup"]
-    only = "--only %s " % workload + ("--size %d " % js["size"] if js.get("size", 512) != 512 else "")
+    only = ("--only %s " % workload + ("--size %d " % js["size"] if js.get("size", 512) != 512 else "")
+            + ("--size2d %d " % js["size2d"] if js.get("size2d", 8192) != 8192 else ""))
     cmd_stats = ("rocprofv3 --kernel-trace --stats -d DIR/stats -o p --output-format csv -- python3 bench.py "
                  + only + "--steps %d --warmup %d --no-cpu-baseline" % (flag_steps, flag_warmup))
     cmd_pmc = ("rocprofv3 --pmc %s --kernel-trace -d DIR/%s -o p --output-format csv -- python3 bench.py "
@@ -224,9 +225,12 @@ def main(argv):
     stats_txt, pmc_txt = summarise(workload, d)
     out = os.path.join(ROOT, "profiles")
     os.makedirs(out, exist_ok=True)
-    size = _bench_json(os.path.join(d, "stats.json")).get("size", 512)
+    js = _bench_json(os.path.join(d, "stats.json"))
+    size, size2d = js.get("size", 512), js.get("size2d", 8192)
     if size != 512:
         workload += "_%d" % size                       # 3-D workloads at another grid edge (bench.py --size)
+    if size2d != 8192 and "2d" in workload:
+        workload += "_%d" % size2d                     # 2-D workloads at another grid edge (bench.py --size2d)
     with open(os.path.join(out, workload + "_stats.txt"), "w") as fh:
         fh.write(stats_txt)
     with open(os.path.join(out, workload + "_pmc.txt"), "w") as fh:
