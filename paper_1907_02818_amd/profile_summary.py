@@ -175,8 +175,19 @@ def summarise(workload, d):
             if r["Kernel_Name"] == kname:
                 acc.setdefault(r["Counter_Name"], []).append(float(r["Counter_Value"]))
         if acc:
-            lines += ["", "further counters of the same kernel (own run, mean per dispatch): "
-                      + ", ".join("%s %.0f" % (k, statistics.mean(v)) for k, v in sorted(acc.items()))]
+            m = {k: statistics.mean(v) for k, v in acc.items()}
+            lines += ["", "further counters of the same kernel (a run of its own, mean per dispatch):",
+                      "  rocprofv3 --pmc " + " ".join(sorted(m)) + " --kernel-trace -d DIR/sq -o p --output-format csv -- python3 bench.py "
+                      + only + "--steps 5 --warmup 2 --settle-cap 0 --no-cpu-baseline",
+                      "  " + ", ".join("%s %.4g" % (k, v) for k, v in sorted(m.items()))]
+            if m.get("SQ_WAVE_CYCLES") and "SQ_WAIT_INST_ANY" in m:
+                lines.append("  wave-cycles spent waiting for an instruction to complete: %.0f %%"
+                             % (100 * m["SQ_WAIT_INST_ANY"] / m["SQ_WAVE_CYCLES"]))
+            if m.get("SQ_ACTIVE_INST_LDS") and "SQ_LDS_BANK_CONFLICT" in m:
+                lines.append("  LDS bank-conflict cycles per active LDS cycle: %.3f"
+                             % (m["SQ_LDS_BANK_CONFLICT"] / m["SQ_ACTIVE_INST_LDS"]))
+            if m.get("SQ_INSTS_VALU") and m.get("SQ_INSTS_LDS"):
+                lines.append("  vector ALU instructions per LDS instruction: %.1f" % (m["SQ_INSTS_VALU"] / m["SQ_INSTS_LDS"]))
     pmc_txt = "\n".join(lines) + "\n"
     return stats_txt, pmc_txt
 
