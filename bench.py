@@ -434,6 +434,9 @@ def main():
     out = {"metric": METRIC, "unit": "Gpoints/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
            "size": n, "size2d": args.size2d}
+    props = torch.cuda.get_device_properties(dev)
+    out["device"] = {"name": props.name, "compute_units": props.multi_processor_count,
+                     "memory_GiB": round(props.total_memory / 2 ** 30, 1), "library": sadj.version()}
     if args.only is None or args.only == HEADLINE:
         t = timer.time_calls(lambda: sadj.sadj_adjoint_wave3d(R, c, rb, ub), args.steps, args.warmup)
         alg_bytes = wave_adjoint_bytes(shape, R, 8)
