@@ -554,6 +554,15 @@ def main():
                   lambda: sadj.sadj_primal_wave3d(1, a2, a3, cw, a1), N3, 8 * N3 + 24 * interior_points(s3, 1),
                   {"seconds_best": 0.897188, "hardware": "Xeon E5-2650 v4, 12 threads",
                    "seconds_best_other": 0.843320, "hardware_other": "Xeon Phi 7210, 32 threads"})
+        # reverse sweep of a time loop of such steps (the paper notes that solvers take many, Section 4): 25 steps per
+        # call, one kernel per step, then with pairs of steps fused (step 0 alone, then 12 pairs)
+        a4 = torch.empty_like(a1)
+        ks3, step3 = 25, 16 * interior_points(s3, 1) + 24 * N3
+        add("paper_wave3d_7pt_1000^3_f64_adjoint_steps_per_step", lambda: sadj.sadj_adjoint_wave3d_steps(1, ks3, cw, a1, a2, a3),
+            N3 * ks3, ks3 * step3, "f64", per=ks3)
+        add("paper_wave3d_7pt_1000^3_f64_adjoint_steps_fused_per_step",
+            lambda: sadj.sadj_adjoint_wave3d_steps_fused(1, ks3, cw, a1, a2, a3, a4), N3 * ks3, ks3 * step3, "f64", per=ks3)
+        del a4
         ub1d, rb1d, ubar1d, r1d = (t.reshape(-1) for t in (a1, a2, a3, cw))
         add_paper("paper_burgers1d_1e9_f64_adjoint",
                   lambda: sadj.sadj_adjoint_burgers1d(0.1, 0.05, ub1d, rb1d, ubar1d), N3, 32 * N3,
