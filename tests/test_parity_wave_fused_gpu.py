@@ -56,6 +56,23 @@ def test_fused_sweep_is_exact_on_dyadic_data(sadj, shape, nsteps):
             k, nsteps, shape, int(np.sum(got[k] != want[k])))
 
 
+@pytest.mark.parametrize("zchunk", [1, 2, 3, 8, 37])
+@pytest.mark.parametrize("shape,nsteps", [((2500, 9, 20), 7), ((64, 300, 2100), 5), ((23, 40, 66), 6)])
+def test_fused_sweep_is_exact_for_any_cut_along_z(sadj, shape, nsteps, zchunk):
+    """Tall grids cut into hundreds of z-chunks, chunks shorter than the pipeline of the two-stage
+    march, planes wide enough for the banded tile numbering: same bits as the oracle (dyadic data)."""
+    c = _dyadic(inputs.uniform(1, "c", shape, 0, 1), 4, 0.0, 1.0)
+    lams = [_dyadic(4 * x, 1, -4, 4) for x in _lams(shape, 2, np.float64)]
+    want = oracle.wave_adjoint_steps(c, *lams, 1, nsteps)
+    sadj.set_option("wave3d.zchunk", zchunk)
+    try:
+        got = _run_fused(sadj, 1, nsteps, c, lams, np.float64)
+    finally:
+        sadj.set_option("wave3d.zchunk", 0)
+    for k in (nsteps % 3, (nsteps + 1) % 3):
+        assert np.array_equal(got[k], want[k])
+
+
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
 @pytest.mark.parametrize("shape,nsteps", [((21, 37, 150), 5), ((21, 37, 150), 12), ((40, 35, 264), 8), ((9, 70, 132), 13),
                                           ((3, 3, 4), 9), ((6, 33, 1000), 6)])
