@@ -511,7 +511,7 @@ def main():
     if args.remainder_study:
         # Section 3.3.4's alternatives on the GPU: 0 guarded only where needed (default),
         # 1 guarded everywhere ("zero padding"), 2 core and remainder as separate dispatches
-        for rad in (4, 1):
+        for rad in (4, 3, 2, 1):
             for strat in (0, 1, 2):
                 sadj.set_option("wave3d.remainder", strat)
                 add("remainder_strategy%d_r%d_f64_adjoint" % (strat, rad),

@@ -84,7 +84,7 @@ def test_adjoint_tile_variants(sadj, radius, variant):
 
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
-@pytest.mark.parametrize("radius", [1, 4])
+@pytest.mark.parametrize("radius", [1, 2, 3, 4])
 def test_remainder_strategies_agree(sadj, radius, dtype):
     """Section 3.3.4 names several treatments of the remainder (disjoint nests, guarded
     statements, zero padding).  The library's three strategies must match the oracle and,
