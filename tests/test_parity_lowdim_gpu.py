@@ -251,6 +251,17 @@ def test_wave2d_full_size_primal_and_both_adjoint_outputs(sadj):
     assert_close(got[m], wantr[m], wave_primal_scale(u, u_prev, d["c"], 1)[m], np.float64, "wave2d 8192^2 primal")
 
 
+def test_wave2d_full_size_fp32(sadj):
+    """8192^2 in fp32 (four cells per lane, 128-cell tiles), every element."""
+    d = inputs.config_inputs("wave2d")
+    c, rb, ub0 = (d[k].astype(np.float32) for k in ("c", "r_bar", "u_bar"))
+    ub = to_gpu(ub0)
+    sadj.sadj_adjoint_wave2d(to_gpu(c), to_gpu(rb), ub)
+    _sync()
+    want, _, scale = oracle.wave_adjoint(c, rb, ub0, 1, want_scale=True)
+    assert_close(to_host(ub), want, scale + np.abs(ub0.astype(np.float64)), np.float32, "wave2d 8192^2 fp32")
+
+
 # ------------------------------------------------------------------ graph capture
 def test_calls_can_be_captured_in_a_hip_graph_and_replayed(sadj):
     """The entry points only enqueue kernels on the given stream (no allocation, no
